@@ -1,0 +1,177 @@
+/*
+ * CPU oracle (test infrastructure): the arithmetic definitions.
+ * Zig-zag order, 8x8 DCT pair, JFIF colour transforms, quality-scaled
+ * quantisation tables, and resize + centre crop + normalize.
+ * Everything is the textbook definition evaluated in double precision.
+ */
+#include "oracle.h"
+#include <math.h>
+#include <stdlib.h>
+
+/* T.81 Figure A.6.  Diagonal d = v+u runs 0..14; odd diagonals are walked
+ * with v increasing (towards the lower left), even ones with v decreasing. */
+void oracle_zigzag_pos(int k, int *v, int *u)
+{
+    int n = 0;
+    for (int d = 0; d <= 14; d++) {
+        int vlo = d > 7 ? d - 7 : 0;
+        int vhi = d < 7 ? d : 7;
+        int len = vhi - vlo + 1;
+        if (k < n + len) {
+            int i = k - n;
+            int vv = (d & 1) ? vlo + i : vhi - i;
+            *v = vv;
+            *u = d - vv;
+            return;
+        }
+        n += len;
+    }
+    *v = *u = -1;
+}
+
+static double dct_scale(int i) { return i == 0 ? sqrt(0.5) : 1.0; }
+
+/* cos((2i+1) k pi/16) for i,k = 0..7: the 64 distinct cosine factors of A.3.3 */
+static void cosine_factors(double ct[8][8])
+{
+    const double pi = acos(-1.0);
+    for (int i = 0; i < 8; i++)
+        for (int k = 0; k < 8; k++) ct[i][k] = cos((2 * i + 1) * k * pi / 16.0);
+}
+
+/* T.81 A.3.3:  s(y,x) = 1/4 sum_u sum_v C(u) C(v) S(v,u)
+ *                         cos((2x+1) u pi/16) cos((2y+1) v pi/16)          */
+void oracle_idct8x8(const double F[64], double f[64])
+{
+    double ct[8][8];
+    cosine_factors(ct);
+    for (int y = 0; y < 8; y++)
+        for (int x = 0; x < 8; x++) {
+            double s = 0.0;
+            for (int v = 0; v < 8; v++)
+                for (int u = 0; u < 8; u++)
+                    s += dct_scale(u) * dct_scale(v) * F[v * 8 + u] * ct[x][u] * ct[y][v];
+            f[y * 8 + x] = 0.25 * s;
+        }
+}
+
+/* T.81 A.3.3:  S(v,u) = 1/4 C(u) C(v) sum_x sum_y s(y,x) cos(..) cos(..)   */
+void oracle_fdct8x8(const double f[64], double F[64])
+{
+    double ct[8][8];
+    cosine_factors(ct);
+    for (int v = 0; v < 8; v++)
+        for (int u = 0; u < 8; u++) {
+            double s = 0.0;
+            for (int y = 0; y < 8; y++)
+                for (int x = 0; x < 8; x++) s += f[y * 8 + x] * ct[x][u] * ct[y][v];
+            F[v * 8 + u] = 0.25 * dct_scale(u) * dct_scale(v) * s;
+        }
+}
+
+static uint8_t round_clamp_u8(double v)
+{
+    double r = floor(v + 0.5);
+    if (r < 0.0) r = 0.0;
+    if (r > 255.0) r = 255.0;
+    return (uint8_t)r;
+}
+
+/* JFIF (ITU-R BT.601 full range) inverse transform.                        */
+void oracle_ycc_to_rgb(int y, int cb, int cr, uint8_t rgb[3])
+{
+    double Y = y, Cb = cb - 128.0, Cr = cr - 128.0;
+    rgb[0] = round_clamp_u8(Y + 1.402 * Cr);
+    rgb[1] = round_clamp_u8(Y - 0.344136 * Cb - 0.714136 * Cr);
+    rgb[2] = round_clamp_u8(Y + 1.772 * Cb);
+}
+
+/* JFIF forward transform.                                                  */
+void oracle_rgb_to_ycc(int r, int g, int b, uint8_t ycc[3])
+{
+    double R = r, G = g, B = b;
+    ycc[0] = round_clamp_u8(0.299 * R + 0.587 * G + 0.114 * B);
+    ycc[1] = round_clamp_u8(-0.168736 * R - 0.331264 * G + 0.5 * B + 128.0);
+    ycc[2] = round_clamp_u8(0.5 * R - 0.418688 * G - 0.081312 * B + 128.0);
+}
+
+/* T.81 Annex K, Tables K.1 (luminance) and K.2 (chrominance), row-major.   */
+static const uint8_t k1_luma[64] = {
+    16, 11, 10, 16, 24,  40,  51,  61,
+    12, 12, 14, 19, 26,  58,  60,  55,
+    14, 13, 16, 24, 40,  57,  69,  56,
+    14, 17, 22, 29, 51,  87,  80,  62,
+    18, 22, 37, 56, 68,  109, 103, 77,
+    24, 35, 55, 64, 81,  104, 113, 92,
+    49, 64, 78, 87, 103, 121, 120, 101,
+    72, 92, 95, 98, 112, 100, 103, 99};
+static const uint8_t k2_chroma[64] = {
+    17, 18, 24, 47, 99, 99, 99, 99,
+    18, 21, 26, 66, 99, 99, 99, 99,
+    24, 26, 56, 99, 99, 99, 99, 99,
+    47, 66, 99, 99, 99, 99, 99, 99,
+    99, 99, 99, 99, 99, 99, 99, 99,
+    99, 99, 99, 99, 99, 99, 99, 99,
+    99, 99, 99, 99, 99, 99, 99, 99,
+    99, 99, 99, 99, 99, 99, 99, 99};
+
+void oracle_quant_table(int quality, int chroma, uint16_t q[64])
+{
+    if (quality < 1) quality = 1;
+    if (quality > 100) quality = 100;
+    int s = quality < 50 ? 5000 / quality : 200 - 2 * quality;
+    const uint8_t *base = chroma ? k2_chroma : k1_luma;
+    for (int i = 0; i < 64; i++) {
+        int v = (base[i] * s + 50) / 100;
+        if (v < 1) v = 1;
+        if (v > 255) v = 255;
+        q[i] = (uint16_t)v;
+    }
+}
+
+void oracle_resized_size(int w, int h, int s, int *ow, int *oh)
+{
+    if (s <= 0) { *ow = w; *oh = h; return; }
+    if (w <= h) {
+        *ow = s;
+        *oh = (int)(((int64_t)s * h) / w);
+    } else {
+        *oh = s;
+        *ow = (int)(((int64_t)s * w) / h);
+    }
+}
+
+static int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+int oracle_preprocess(const uint8_t *rgb, int w, int h, int resize_short,
+                      int crop_h, int crop_w, const double mean[3], const double std[3],
+                      double *out)
+{
+    if (!rgb || !out || w < 1 || h < 1 || crop_h < 1 || crop_w < 1) return ORACLE_E_ARG;
+    int ow, oh;
+    oracle_resized_size(w, h, resize_short, &ow, &oh);
+    if (crop_w > ow || crop_h > oh) return ORACLE_E_ARG;
+    for (int c = 0; c < 3; c++)
+        if (!(std[c] > 0.0)) return ORACLE_E_ARG;
+    int top = (oh - crop_h) / 2, left = (ow - crop_w) / 2;
+    double scale_x = (double)w / (double)ow, scale_y = (double)h / (double)oh;
+    for (int c = 0; c < 3; c++)
+        for (int y = 0; y < crop_h; y++)
+            for (int x = 0; x < crop_w; x++) {
+                /* centre of output pixel mapped into source pixel units */
+                double sx = (x + left + 0.5) * scale_x - 0.5;
+                double sy = (y + top + 0.5) * scale_y - 0.5;
+                int x0 = (int)floor(sx), y0 = (int)floor(sy);
+                double fx = sx - x0, fy = sy - y0;
+                int xa = clampi(x0, 0, w - 1), xb = clampi(x0 + 1, 0, w - 1);
+                int ya = clampi(y0, 0, h - 1), yb = clampi(y0 + 1, 0, h - 1);
+                double p00 = rgb[((size_t)ya * w + xa) * 3 + c];
+                double p01 = rgb[((size_t)ya * w + xb) * 3 + c];
+                double p10 = rgb[((size_t)yb * w + xa) * 3 + c];
+                double p11 = rgb[((size_t)yb * w + xb) * 3 + c];
+                double v = (1.0 - fy) * ((1.0 - fx) * p00 + fx * p01) +
+                           fy * ((1.0 - fx) * p10 + fx * p11);
+                out[((size_t)c * crop_h + y) * crop_w + x] = (v / 255.0 - mean[c]) / std[c];
+            }
+    return ORACLE_OK;
+}
