@@ -29,7 +29,16 @@ void oracle_zigzag_pos(int k, int *v, int *u)
     *v = *u = -1;
 }
 
-static double dct_scale(int i) { return i == 0 ? sqrt(0.5) : 1.0; }
+/* C(u) C(v) of A.3.3 with C(0) = 1/sqrt(2), C(k>0) = 1.  The product is formed
+ * exactly (C(0)^2 = 1/2) so that a block holding only a DC term reconstructs to
+ * exactly DC/8 and the half-way cases of the final rounding fall where the
+ * definition puts them.                                                     */
+static double dct_scale2(int u, int v)
+{
+    if (u == 0 && v == 0) return 0.5;
+    if (u == 0 || v == 0) return sqrt(0.5);
+    return 1.0;
+}
 
 /* cos((2i+1) k pi/16) for i,k = 0..7: the 64 distinct cosine factors of A.3.3 */
 static void cosine_factors(double ct[8][8])
@@ -50,7 +59,7 @@ void oracle_idct8x8(const double F[64], double f[64])
             double s = 0.0;
             for (int v = 0; v < 8; v++)
                 for (int u = 0; u < 8; u++)
-                    s += dct_scale(u) * dct_scale(v) * F[v * 8 + u] * ct[x][u] * ct[y][v];
+                    s += dct_scale2(u, v) * F[v * 8 + u] * ct[x][u] * ct[y][v];
             f[y * 8 + x] = 0.25 * s;
         }
 }
@@ -65,7 +74,7 @@ void oracle_fdct8x8(const double f[64], double F[64])
             double s = 0.0;
             for (int y = 0; y < 8; y++)
                 for (int x = 0; x < 8; x++) s += f[y * 8 + x] * ct[x][u] * ct[y][v];
-            F[v * 8 + u] = 0.25 * dct_scale(u) * dct_scale(v) * s;
+            F[v * 8 + u] = 0.25 * dct_scale2(u, v) * s;
         }
 }
 

@@ -285,8 +285,26 @@ def test_all_eob_blocks_and_dc_only_blocks_decode_to_constant_blocks():
         dcq = int(coef[b, 0]) * int(q[0])
         expect = min(255, max(0, (dcq + 4) // 8 + 128))  # floor(DC*Q/8 + 0.5) + 128
         assert (block == expect).all()
-    # exact ties DC*Q = 4 (mod 8) round up
     assert int(q[0]) == 8 and rgb[0, 8, 0] == 129 and rgb[0, 16, 0] == 127
+
+
+def test_dc_only_ties_round_half_up_for_both_signs():
+    # DC*Q = 4 (mod 8) puts the sample exactly half way between two integers:
+    # floor(DC*Q/8 + 0.5) must go up for positive and for negative values alike
+    q = np.full(64, 4, dtype=np.uint16)          # DC*Q = 4*DC: a tie for every odd DC
+    dcs = [1, -1, 3, -3, 9, -9, 35, -35, 101, -101, 7, -7]
+    coef = np.zeros((12, 64), dtype=np.int16)
+    coef[:, 0] = dcs
+    data = oracle.write_jpeg(coef, 32, 24, MODE_GRAY, q, q)
+    _, rgb, _ = oracle.decode(data, want_coef=False)
+    for b, dc in enumerate(dcs):
+        by, bx = divmod(b, 4)
+        expect = min(255, max(0, (4 * dc + 4) // 8 + 128))
+        assert (rgb[by * 8:by * 8 + 8, bx * 8:bx * 8 + 8] == expect).all(), (dc, expect)
+    F = np.zeros((8, 8))
+    for dc in (-36.0, 36.0, -4.0, 1020.0):
+        F[0, 0] = dc
+        assert (oracle.idct8x8(F) == dc / 8.0).all()   # exactly, not approximately
 
 
 # ---------------------------------------------------------------- independent codec (Pillow)
