@@ -1,0 +1,199 @@
+/*
+ * prep -- batched JPEG -> model-input tensor preprocessing on one AMD Instinct
+ * MI355X (gfx950).
+ *
+ * The library computes the "data preprocessing" stage of an inference server
+ * for vision models as PREBA states it (section 2.3, item 1; the Decode,
+ * Resize, Crop and Normalize functional units of the image CU in section 4.2,
+ * Figure 11(a) and Table 1): every image of a batch is decoded from a JPEG
+ * bitstream to RGB, resized, cropped to the model's input size and normalized.
+ * The paper fixes nothing below that level; this library reads it as
+ *   decode    : ITU-T T.81 baseline sequential DCT, Huffman coded, 8 bit,
+ *               1 or 3 components in one interleaved scan, sampling gray /
+ *               4:4:4 / 4:2:0, optional restart intervals; chroma upsampled by
+ *               sample replication; JFIF YCbCr -> RGB; samples and RGB values
+ *               rounded half up and clamped to 0..255;
+ *   resize    : short side -> resize_short, long side floor(resize_short *
+ *               long / short); bilinear, pixel centres at half-integers,
+ *               per-axis scale in/out, taps clamped at the border, no
+ *               prefilter, no intermediate rounding;
+ *   crop      : centre window crop_h x crop_w, origin floor(margin / 2);
+ *   normalize : (v / 255 - mean[c]) / std[c];
+ *   output    : planar NCHW, RGB channel order, fp32 or fp16.
+ *
+ * All entry points are plain C.  "HOST" pointers are ordinary process memory,
+ * "DEVICE" pointers are HIP device memory of the handle's GPU.  A handle may be
+ * used by one thread and one stream at a time; use several handles for
+ * concurrent streams.  Every function returns PREP_OK (0) or a negative
+ * PREP_E_* code and never throws, aborts or prints.
+ */
+#ifndef PREP_H
+#define PREP_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    PREP_OK = 0,
+    PREP_E_INVALID_ARG = -1, /* null pointer, n out of range, bad params            */
+    PREP_E_TOO_LARGE = -2,   /* batch exceeds what prep_create reserved             */
+    PREP_E_HIP = -3,         /* a HIP runtime call failed                           */
+    PREP_E_UNSUPPORTED = -4, /* per image: valid JPEG outside the supported subset  */
+    PREP_E_CORRUPT = -5,     /* per image: stream violates the JPEG syntax          */
+    PREP_E_NOMEM = -6        /* host or device allocation failed in prep_create     */
+};
+
+enum { PREP_F32 = 0, PREP_F16 = 1 };
+enum { PREP_SAMPLING_444 = 0, PREP_SAMPLING_420 = 1, PREP_SAMPLING_GRAY = 2 };
+
+typedef struct prep_handle prep_handle;
+
+/* Capacity of a handle; all device and pinned host memory is reserved here. */
+typedef struct {
+    int32_t device;               /* HIP device ordinal                              */
+    int32_t max_batch;            /* largest n of one call                           */
+    int32_t max_width, max_height; /* largest single image                          */
+    uint64_t max_bitstream_bytes; /* largest sum of file sizes of one call           */
+    uint64_t max_total_pixels;    /* largest sum of width*height of one call;
+                                     0 = max_batch * max_width * max_height         */
+    uint32_t flags;               /* reserved, must be 0                             */
+} prep_config;
+
+/* Resize / crop / normalize parameters, the same for every image of a call. */
+typedef struct {
+    int32_t resize_short;  /* target length of the short side; 0 = keep the size    */
+    int32_t crop_h, crop_w;
+    int32_t out_dtype;     /* PREP_F32 or PREP_F16                                  */
+    float mean[3], std[3]; /* on the 0..1 pixel scale, R, G, B                      */
+} prep_params;
+
+/* What the host marker parser learns about one file (T.81 Annex B). */
+typedef struct {
+    int32_t status;            /* PREP_OK, PREP_E_UNSUPPORTED or PREP_E_CORRUPT     */
+    int32_t width, height;
+    int32_t sampling;          /* PREP_SAMPLING_*                                   */
+    int32_t mcu_cols, mcu_rows;
+    int32_t blocks_per_mcu;    /* 1, 3 or 6                                         */
+    int32_t restart_interval;  /* MCUs per restart interval, 0 = none               */
+    int32_t n_intervals;       /* restart-interval work descriptors of this image   */
+    int32_t reserved;
+    uint64_t entropy_offset;   /* first entropy-coded byte, from the file start     */
+    uint64_t entropy_bytes;    /* up to, not including, the EOI marker              */
+} prep_image_info;
+
+/* One restart-interval work descriptor: the unit of independent entropy
+ * decoding (T.81 E.2.4).  The parser knows which MCUs an interval covers; where
+ * its bytes begin inside the entropy-coded segment is found on the GPU.       */
+typedef struct {
+    int32_t image;      /* index into the batch                                     */
+    int32_t first_mcu;  /* first MCU of the interval, raster order                  */
+    int32_t n_mcu;      /* MCUs in the interval                                     */
+    int32_t rst_index;  /* n of the RSTn marker that precedes it, -1 for the first  */
+} prep_interval_desc;
+
+/* Reserve a handle's memory on cfg->device.  *out is NULL on failure.         */
+int prep_create(prep_handle **out, const prep_config *cfg);
+
+/* Release everything the handle owns (synchronises the device first).         */
+int prep_destroy(prep_handle *h);
+
+/*
+ * The whole path for one batch (section 2.3 item 1 / section 4.2): parse, copy
+ * to the GPU, entropy-decode, reconstruct RGB, resize + crop + normalize.
+ *   bitstreams HOST   n files back to back
+ *   offsets    HOST   n+1 entries; file i is bytes [offsets[i], offsets[i+1])
+ *   out        DEVICE n*3*crop_h*crop_w elements of params->out_dtype, NCHW;
+ *              must stay valid until `stream` has run the enqueued work
+ *   stream     a hipStream_t (NULL = the default stream)
+ * The call copies what it needs from the host buffers before it returns and
+ * returns as soon as the GPU work is enqueued on `stream`.  Whole-call errors
+ * (INVALID_ARG, TOO_LARGE, HIP) enqueue nothing.  A file that cannot be decoded
+ * does not fail the call: its status is reported by prep_get_status and its
+ * slab of `out` is filled with zeros.
+ */
+int prep_decode_resize_batch(prep_handle *h, const uint8_t *bitstreams, const uint64_t *offsets,
+                             int32_t n, const prep_params *params, void *out, void *stream);
+
+/*
+ * Same computation for a batch whose bytes already lie in device memory:
+ * `bitstreams_device` (DEVICE) holds the same bytes as `bitstreams` (HOST).  The
+ * host copy is read only up to each file's start-of-scan header (a few hundred
+ * bytes per file); the entropy-coded data is read on the GPU alone and is not
+ * copied.  `bitstreams_device` must stay valid until `stream` has run the work.
+ */
+int prep_decode_resize_batch_resident(prep_handle *h, const uint8_t *bitstreams,
+                                      const uint8_t *bitstreams_device, const uint64_t *offsets,
+                                      int32_t n, const prep_params *params, void *out,
+                                      void *stream);
+
+/* Wait for the handle's last call and fetch one status per image (HOST, n
+ * entries of the last call): PREP_OK, PREP_E_UNSUPPORTED or PREP_E_CORRUPT.   */
+int prep_get_status(prep_handle *h, int32_t *per_image_status, int32_t n);
+
+/* Text for a PREP_* code (static storage).                                    */
+const char *prep_strerror(int code);
+
+/* ---- host-only pieces (no GPU needed) ---------------------------------- */
+
+/* The marker/table parser alone (T.81 Annex B): fills info[i] for each file. */
+int prep_parse_headers(const uint8_t *bitstreams, const uint64_t *offsets, int32_t n,
+                       prep_image_info *info);
+
+/* Restart-interval work descriptors of a parsed batch, image after image.
+ * Writes at most cap entries and returns the total number (>= 0).             */
+int64_t prep_interval_descriptors(const prep_image_info *info, int32_t n,
+                                  prep_interval_desc *desc, int64_t cap);
+
+/* ---- single stages, for checking each against its own definition ---------- */
+
+/*
+ * Resize + centre crop + normalize alone (the Resize, Crop and Normalize units
+ * of Table 1) on RGB images the caller supplies.
+ *   rgb      DEVICE  interleaved 8-bit RGB images; image i starts at byte
+ *            rgb_offsets[i], rows are pitches[i] bytes apart
+ *   rgb_offsets, widths, heights, pitches   HOST, n entries each
+ */
+int prep_resize_normalize(prep_handle *h, const uint8_t *rgb, const uint64_t *rgb_offsets,
+                          const int32_t *widths, const int32_t *heights, const int32_t *pitches,
+                          int32_t n, const prep_params *params, void *out, void *stream);
+
+/*
+ * Dequantise + inverse DCT + chroma upsampling + colour conversion (the second
+ * half of the Decode unit), then resize/crop/normalize, from coefficients the
+ * caller supplies instead of the entropy decoder's: the files' headers give
+ * geometry and quantisation tables.
+ *   coefficients HOST  for each image in turn, its blocks in scan order, 64
+ *                int16 per block in zig-zag order with absolute DC values
+ */
+int prep_reconstruct_from_coefficients(prep_handle *h, const uint8_t *bitstreams,
+                                       const uint64_t *offsets, int32_t n,
+                                       const int16_t *coefficients, uint64_t n_coefficients,
+                                       const prep_params *params, void *out, void *stream);
+
+/* ---- checkpoints of the last call, copied to the host (these synchronise) - */
+
+/* Entropy decoder output of image `image`: blocks in scan order (MCU by MCU;
+ * in a 4:2:0 MCU Y00 Y01 Y10 Y11 Cb Cr), 64 int16 per block in zig-zag order,
+ * DC values absolute.  `cap` counts int16 entries; returns the number written
+ * (blocks*64) or a negative code.                                             */
+int64_t prep_debug_last_coefficients(prep_handle *h, int32_t image, int16_t *host_out,
+                                     uint64_t cap);
+
+/* Decoded RGB of image `image`: height*width*3 bytes, interleaved, tightly
+ * packed.  Returns the number of bytes written or a negative code.            */
+int64_t prep_debug_last_rgb(prep_handle *h, int32_t image, uint8_t *host_out_hwc, uint64_t cap);
+
+/* Duration in milliseconds of each GPU stage of the handle's last call, taken
+ * with events on the call's stream (synchronises): [0] restart-marker scan,
+ * [1] entropy decode, [2] reconstruct RGB, [3] resize/crop/normalize.
+ * Only filled when the handle was told to time stages (prep_set_timing).      */
+int prep_last_stage_ms(prep_handle *h, float ms[4]);
+int prep_set_timing(prep_handle *h, int32_t enabled);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

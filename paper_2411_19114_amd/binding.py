@@ -1,0 +1,241 @@
+"""ctypes marshalling for libprep.so.  Same names as the C ABI, no arithmetic."""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_CSRC = os.path.join(_HERE, "csrc")
+_SOURCES = ["entropy.hip", "reconstruct.hip", "resize.hip", "api.cpp", "parser.cpp"]
+
+OK, E_INVALID_ARG, E_TOO_LARGE, E_HIP, E_UNSUPPORTED, E_CORRUPT, E_NOMEM = 0, -1, -2, -3, -4, -5, -6
+F32, F16 = 0, 1
+
+
+def lib_path():
+    return os.path.join(_HERE, "libprep.so")
+
+
+def build(verbose=False):
+    """Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-o", lib_path()] + [os.path.join(_CSRC, s) for s in _SOURCES]
+    r = subprocess.run(cmd, capture_output=not verbose, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + (r.stderr or ""))
+    return lib_path()
+
+
+class PrepError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+        self.code = code
+
+
+class Config(C.Structure):
+    _fields_ = [("device", C.c_int32), ("max_batch", C.c_int32), ("max_width", C.c_int32),
+                ("max_height", C.c_int32), ("max_bitstream_bytes", C.c_uint64),
+                ("max_total_pixels", C.c_uint64), ("flags", C.c_uint32)]
+
+
+class Params(C.Structure):
+    _fields_ = [("resize_short", C.c_int32), ("crop_h", C.c_int32), ("crop_w", C.c_int32),
+                ("out_dtype", C.c_int32), ("mean", C.c_float * 3), ("std", C.c_float * 3)]
+
+
+class ImageInfo(C.Structure):
+    _fields_ = [("status", C.c_int32), ("width", C.c_int32), ("height", C.c_int32),
+                ("sampling", C.c_int32), ("mcu_cols", C.c_int32), ("mcu_rows", C.c_int32),
+                ("blocks_per_mcu", C.c_int32), ("restart_interval", C.c_int32),
+                ("n_intervals", C.c_int32), ("reserved", C.c_int32),
+                ("entropy_offset", C.c_uint64), ("entropy_bytes", C.c_uint64)]
+
+
+class IntervalDesc(C.Structure):
+    _fields_ = [("image", C.c_int32), ("first_mcu", C.c_int32), ("n_mcu", C.c_int32),
+                ("rst_index", C.c_int32)]
+
+
+EXPORTS = [
+    "prep_create", "prep_destroy", "prep_decode_resize_batch", "prep_decode_resize_batch_resident",
+    "prep_get_status", "prep_strerror", "prep_parse_headers", "prep_interval_descriptors",
+    "prep_resize_normalize", "prep_reconstruct_from_coefficients", "prep_debug_last_coefficients",
+    "prep_debug_last_rgb", "prep_last_stage_ms", "prep_set_timing",
+]
+
+_lib = None
+
+
+def lib():
+    """Load libprep.so; there is no fallback when it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(lib_path()):
+            raise RuntimeError(f"{lib_path()} is not built: run __graft_entry__.build() "
+                               "(hipcc --offload-arch=gfx950)")
+        L = C.CDLL(lib_path())
+        vp, u8p, u64p, i32p = C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int32)
+        L.prep_create.argtypes = [C.POINTER(vp), C.POINTER(Config)]
+        L.prep_destroy.argtypes = [vp]
+        L.prep_decode_resize_batch.argtypes = [vp, u8p, u64p, C.c_int32, C.POINTER(Params), vp, vp]
+        L.prep_decode_resize_batch_resident.argtypes = [vp, u8p, vp, u64p, C.c_int32,
+                                                        C.POINTER(Params), vp, vp]
+        L.prep_get_status.argtypes = [vp, i32p, C.c_int32]
+        L.prep_strerror.argtypes = [C.c_int]
+        L.prep_strerror.restype = C.c_char_p
+        L.prep_parse_headers.argtypes = [u8p, u64p, C.c_int32, C.POINTER(ImageInfo)]
+        L.prep_interval_descriptors.argtypes = [C.POINTER(ImageInfo), C.c_int32,
+                                                C.POINTER(IntervalDesc), C.c_int64]
+        L.prep_interval_descriptors.restype = C.c_int64
+        L.prep_resize_normalize.argtypes = [vp, vp, u64p, i32p, i32p, i32p, C.c_int32,
+                                            C.POINTER(Params), vp, vp]
+        L.prep_reconstruct_from_coefficients.argtypes = [vp, u8p, u64p, C.c_int32, vp, C.c_uint64,
+                                                         C.POINTER(Params), vp, vp]
+        L.prep_debug_last_coefficients.argtypes = [vp, C.c_int32, vp, C.c_uint64]
+        L.prep_debug_last_coefficients.restype = C.c_int64
+        L.prep_debug_last_rgb.argtypes = [vp, C.c_int32, vp, C.c_uint64]
+        L.prep_debug_last_rgb.restype = C.c_int64
+        L.prep_last_stage_ms.argtypes = [vp, C.POINTER(C.c_float)]
+        L.prep_set_timing.argtypes = [vp, C.c_int32]
+        _lib = L
+    return _lib
+
+
+def strerror(code):
+    return lib().prep_strerror(int(code)).decode()
+
+
+def _check(rc, what):
+    if rc != OK:
+        raise PrepError(rc, what)
+
+
+def _u8(a):
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    return a, a.ctypes.data
+
+
+def _u64(a):
+    a = np.ascontiguousarray(a, dtype=np.uint64)
+    return a, a.ctypes.data_as(C.POINTER(C.c_uint64))
+
+
+def make_params(resize_short, crop_h, crop_w, out_dtype, mean, std):
+    p = Params()
+    p.resize_short, p.crop_h, p.crop_w = int(resize_short), int(crop_h), int(crop_w)
+    p.out_dtype = {"f32": F32, "f16": F16}.get(out_dtype, out_dtype)
+    p.mean[:] = [float(m) for m in mean]
+    p.std[:] = [float(s) for s in std]
+    return p
+
+
+def parse_headers(bitstreams, offsets):
+    """prep_parse_headers: host marker parser only -> list of ImageInfo."""
+    b, bp = _u8(bitstreams)
+    o, op = _u64(offsets)
+    n = len(o) - 1
+    info = (ImageInfo * max(n, 1))()
+    _check(lib().prep_parse_headers(bp, op, n, info), "prep_parse_headers")
+    return list(info)[:n]
+
+
+def interval_descriptors(infos):
+    """prep_interval_descriptors -> list of IntervalDesc."""
+    n = len(infos)
+    arr = (ImageInfo * max(n, 1))(*infos)
+    total = lib().prep_interval_descriptors(arr, n, None, 0)
+    if total < 0:
+        raise PrepError(int(total), "prep_interval_descriptors")
+    desc = (IntervalDesc * max(total, 1))()
+    lib().prep_interval_descriptors(arr, n, desc, total)
+    return list(desc)[:total]
+
+
+class Preprocessor:
+    """Owns one prep_handle.  Device pointers are plain integers (tensor.data_ptr())."""
+
+    def __init__(self, device=0, max_batch=256, max_width=640, max_height=640,
+                 max_bitstream_bytes=64 << 20, max_total_pixels=0):
+        self._h = C.c_void_p()
+        cfg = Config(device, max_batch, max_width, max_height, max_bitstream_bytes,
+                     max_total_pixels, 0)
+        _check(lib().prep_create(C.byref(self._h), C.byref(cfg)), "prep_create")
+
+    def close(self):
+        if self._h:
+            lib().prep_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def decode_resize_batch(self, bitstreams, offsets, params, out_ptr, stream=0):
+        b, bp = _u8(bitstreams)
+        o, op = _u64(offsets)
+        _check(lib().prep_decode_resize_batch(self._h, bp, op, len(o) - 1, C.byref(params),
+                                              C.c_void_p(out_ptr), C.c_void_p(stream)),
+               "prep_decode_resize_batch")
+
+    def decode_resize_batch_resident(self, bitstreams, bitstreams_device_ptr, offsets, params,
+                                     out_ptr, stream=0):
+        b, bp = _u8(bitstreams)
+        o, op = _u64(offsets)
+        _check(lib().prep_decode_resize_batch_resident(
+            self._h, bp, C.c_void_p(bitstreams_device_ptr), op, len(o) - 1, C.byref(params),
+            C.c_void_p(out_ptr), C.c_void_p(stream)), "prep_decode_resize_batch_resident")
+
+    def get_status(self, n):
+        st = (C.c_int32 * max(n, 1))()
+        _check(lib().prep_get_status(self._h, st, n), "prep_get_status")
+        return list(st)[:n]
+
+    def resize_normalize(self, rgb_ptr, rgb_offsets, widths, heights, pitches, params, out_ptr,
+                         stream=0):
+        o, op = _u64(rgb_offsets)
+        w = np.ascontiguousarray(widths, dtype=np.int32)
+        h = np.ascontiguousarray(heights, dtype=np.int32)
+        p = np.ascontiguousarray(pitches, dtype=np.int32)
+        i32p = C.POINTER(C.c_int32)
+        _check(lib().prep_resize_normalize(
+            self._h, C.c_void_p(rgb_ptr), op, w.ctypes.data_as(i32p), h.ctypes.data_as(i32p),
+            p.ctypes.data_as(i32p), len(w), C.byref(params), C.c_void_p(out_ptr),
+            C.c_void_p(stream)), "prep_resize_normalize")
+
+    def reconstruct_from_coefficients(self, bitstreams, offsets, coefficients, params, out_ptr,
+                                      stream=0):
+        b, bp = _u8(bitstreams)
+        o, op = _u64(offsets)
+        c = np.ascontiguousarray(coefficients, dtype=np.int16)
+        _check(lib().prep_reconstruct_from_coefficients(
+            self._h, bp, op, len(o) - 1, c.ctypes.data, c.size, C.byref(params),
+            C.c_void_p(out_ptr), C.c_void_p(stream)), "prep_reconstruct_from_coefficients")
+
+    def debug_last_coefficients(self, image, n_blocks):
+        out = np.empty((n_blocks, 64), dtype=np.int16)
+        n = lib().prep_debug_last_coefficients(self._h, image, out.ctypes.data, out.size)
+        if n < 0:
+            raise PrepError(int(n), "prep_debug_last_coefficients")
+        assert n == out.size
+        return out
+
+    def debug_last_rgb(self, image, height, width):
+        out = np.empty((height, width, 3), dtype=np.uint8)
+        n = lib().prep_debug_last_rgb(self._h, image, out.ctypes.data, out.size)
+        if n < 0:
+            raise PrepError(int(n), "prep_debug_last_rgb")
+        assert n == out.size
+        return out
+
+    def set_timing(self, enabled):
+        _check(lib().prep_set_timing(self._h, int(bool(enabled))), "prep_set_timing")
+
+    def last_stage_ms(self):
+        ms = (C.c_float * 4)()
+        _check(lib().prep_last_stage_ms(self._h, ms), "prep_last_stage_ms")
+        return list(ms)

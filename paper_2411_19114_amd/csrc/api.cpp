@@ -1,0 +1,506 @@
+// C ABI of libprep: handle, workspace, host-side batch planning and the launch
+// sequence  parse -> (copy) -> restart-marker scan -> entropy decode ->
+// reconstruct RGB -> resize/crop/normalize  (PREBA section 2.3 item 1, 4.2).
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/prep.h"
+#include "kernels.h"
+#include "parser.h"
+#include "prep_internal.h"
+
+using namespace prep;
+
+namespace {
+
+constexpr int kSlots = 2;            // pinned staging is double buffered
+constexpr size_t kBitsPad = 256;     // readable slack after the last file
+constexpr size_t kRgbAlign = 256;
+
+struct Slot {
+    uint8_t *h_bits = nullptr;
+    ImageRec *h_recs = nullptr;
+    ResizeRec *h_rr = nullptr;
+    int32_t *h_status = nullptr;
+    hipEvent_t done = nullptr;
+    bool pending = false;
+};
+
+struct Plan {                         // what one call will run
+    uint32_t n_windows = 0;
+    uint32_t n_groups = 0;
+    uint64_t n_blocks = 0;
+    uint64_t rgb_bytes = 0;
+};
+
+}  // namespace
+
+struct prep_handle {
+    prep_config cfg{};
+    uint64_t cap_blocks = 0, cap_rgb = 0, cap_windows = 0, cap_bits = 0;
+    uint8_t *d_bits = nullptr;
+    int16_t *d_coef = nullptr;
+    uint8_t *d_rgb = nullptr;
+    ImageRec *d_recs = nullptr;
+    ResizeRec *d_rr = nullptr;
+    int32_t *d_status = nullptr;
+    uint32_t *d_win_count = nullptr, *d_win_first = nullptr;
+    Slot slot[kSlots];
+    int next_slot = 0;
+    hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    bool timing = false, timed_last = false;
+    // last call
+    int32_t last_n = 0;
+    hipStream_t last_stream = nullptr;
+    std::vector<ParsedImage> parsed;
+    std::vector<ImageRec> recs;
+    std::vector<ResizeRec> rr;
+};
+
+namespace {
+
+#define HIP_TRY(expr)                       \
+    do {                                    \
+        if ((expr) != hipSuccess) {         \
+            (void)hipGetLastError();        \
+            return PREP_E_HIP;              \
+        }                                   \
+    } while (0)
+
+bool params_ok(const prep_params *p)
+{
+    if (!p) return false;
+    if (p->resize_short < 0 || p->resize_short > 65535) return false;
+    if (p->crop_h < 1 || p->crop_w < 1 || p->crop_h > 65535 || p->crop_w > 65535) return false;
+    if (p->out_dtype != PREP_F32 && p->out_dtype != PREP_F16) return false;
+    for (int c = 0; c < 3; c++)
+        if (!(p->std[c] > 0.0f) || !isfinite(p->std[c]) || !isfinite(p->mean[c])) return false;
+    return true;
+}
+
+// Resized size: the short side becomes s, the long side floor(s * long / short).
+void resized_size(int w, int h, int s, int *ow, int *oh)
+{
+    if (s <= 0) { *ow = w; *oh = h; return; }
+    if (w <= h) { *ow = s; *oh = (int)(((int64_t)s * h) / w); }
+    else { *oh = s; *ow = (int)(((int64_t)s * w) / h); }
+}
+
+// Mapping constants of one image; false when the crop does not fit.
+bool make_resize_rec(int w, int h, const prep_params *p, uint64_t src_off, uint32_t pitch,
+                     ResizeRec *r)
+{
+    int ow, oh;
+    resized_size(w, h, p->resize_short, &ow, &oh);
+    if (p->crop_w > ow || p->crop_h > oh) return false;
+    const int top = (oh - p->crop_h) / 2, left = (ow - p->crop_w) / 2;
+    const double sx = (double)w / (double)ow, sy = (double)h / (double)oh;
+    r->scale_x = (float)sx;
+    r->scale_y = (float)sy;
+    r->off_x = (float)((left + 0.5) * sx - 0.5);
+    r->off_y = (float)((top + 0.5) * sy - 0.5);
+    r->src_w = w;
+    r->src_h = h;
+    r->src_pitch = pitch;
+    r->pad_ = 0;
+    r->src_off = src_off;
+    return true;
+}
+
+// Parse every file and lay the batch out in the workspace.
+int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int32_t n,
+               const prep_params *params, Plan *plan)
+{
+    h->parsed.resize((size_t)n);
+    h->recs.resize((size_t)n);
+    h->rr.resize((size_t)n);
+    Plan P;
+    for (int32_t i = 0; i < n; i++) {
+        if (offsets[i + 1] < offsets[i]) return PREP_E_INVALID_ARG;
+        const uint64_t len = offsets[i + 1] - offsets[i];
+        ParsedImage &pi = h->parsed[(size_t)i];
+        parse_image(bits + offsets[i], len, &pi);
+        prep_image_info &I = pi.info;
+        ImageRec &R = h->recs[(size_t)i];
+        memset(&R, 0, sizeof R);
+        ResizeRec &Z = h->rr[(size_t)i];
+        memset(&Z, 0, sizeof Z);
+        if (I.status == PREP_OK && (I.width > h->cfg.max_width || I.height > h->cfg.max_height))
+            return PREP_E_TOO_LARGE;
+        R.file_off = offsets[i];
+        R.window0 = P.n_windows;
+        R.group0 = P.n_groups;
+        R.coef_block0 = (uint32_t)P.n_blocks;
+        R.rgb_off = P.rgb_bytes;
+        R.status = I.status;
+        R.n_windows = 1;
+        R.groups_per_row = 1;
+        if (I.status == PREP_OK) {
+            const int hs = I.sampling == PREP_SAMPLING_420 ? 2 : 1;
+            R.entropy_rel = (uint32_t)I.entropy_offset;
+            R.entropy_len = (uint32_t)I.entropy_bytes;
+            R.n_blocks = (uint32_t)((uint64_t)I.mcu_cols * I.mcu_rows * I.blocks_per_mcu);
+            R.n_windows = (uint32_t)((I.entropy_bytes + kWindowBytes - 1) / kWindowBytes);
+            if (R.n_windows == 0) R.n_windows = 1;
+            R.rgb_pitch = (uint32_t)I.mcu_cols * 8u * hs * 3u;
+            const int per = recon_mcus_per_group(I.sampling);
+            R.groups_per_row = (uint32_t)((I.mcu_cols + per - 1) / per);
+            for (int t = 0; t < 4; t++) { R.dht_off[t] = pi.dht_off[t]; R.dht_nval[t] = pi.dht_nval[t]; }
+            for (int c = 0; c < 3; c++) R.dqt_off[c] = pi.dqt_off[c];
+            R.width = (uint16_t)I.width;
+            R.height = (uint16_t)I.height;
+            R.mcu_cols = (uint16_t)I.mcu_cols;
+            R.mcu_rows = (uint16_t)I.mcu_rows;
+            R.restart_interval = (uint16_t)I.restart_interval;
+            R.sampling = (uint8_t)I.sampling;
+            R.blocks_per_mcu = (uint8_t)I.blocks_per_mcu;
+            if (!make_resize_rec(I.width, I.height, params, R.rgb_off, R.rgb_pitch, &Z)) {
+                // the crop window does not fit this image after resizing
+                I.status = R.status = PREP_E_UNSUPPORTED;
+            }
+        }
+        if (R.status == PREP_OK) {
+            const uint64_t rows = (uint64_t)R.mcu_rows * 8u * (R.sampling == PREP_SAMPLING_420 ? 2 : 1);
+            P.n_blocks += R.n_blocks;
+            P.rgb_bytes += ((uint64_t)R.rgb_pitch * rows + kRgbAlign - 1) / kRgbAlign * kRgbAlign;
+            P.n_groups += R.groups_per_row * R.mcu_rows;
+        }
+        P.n_windows += R.n_windows;
+    }
+    if (P.n_blocks > h->cap_blocks || P.rgb_bytes > h->cap_rgb || P.n_windows > h->cap_windows)
+        return PREP_E_TOO_LARGE;
+    *plan = P;
+    return PREP_OK;
+}
+
+int take_slot(prep_handle *h, Slot **out)
+{
+    Slot &s = h->slot[h->next_slot];
+    h->next_slot = (h->next_slot + 1) % kSlots;
+    if (s.pending) {
+        HIP_TRY(hipEventSynchronize(s.done));
+        s.pending = false;
+    }
+    *out = &s;
+    return PREP_OK;
+}
+
+int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
+              const uint64_t *offsets, int32_t n, const prep_params *params, void *out,
+              hipStream_t stream, const int16_t *coef_host, uint64_t n_coef)
+{
+    if (!h || !bits_host || !offsets || !out || n < 0 || !params_ok(params)) return PREP_E_INVALID_ARG;
+    if (n > h->cfg.max_batch) return PREP_E_TOO_LARGE;
+    h->last_n = 0;
+    if (n == 0) return PREP_OK;
+    const uint64_t total = offsets[n] - offsets[0];
+    if (offsets[n] < offsets[0] || total > h->cfg.max_bitstream_bytes) return PREP_E_TOO_LARGE;
+    HIP_TRY(hipSetDevice(h->cfg.device));
+    Plan P;
+    // offsets are taken relative to the first file so that a batch may start anywhere
+    const uint8_t *base_host = bits_host + offsets[0];
+    std::vector<uint64_t> rel((size_t)n + 1);
+    for (int32_t i = 0; i <= n; i++) {
+        if (offsets[i] < offsets[0]) return PREP_E_INVALID_ARG;
+        rel[(size_t)i] = offsets[i] - offsets[0];
+    }
+    int rc = plan_batch(h, base_host, rel.data(), n, params, &P);
+    if (rc != PREP_OK) return rc;
+    if (coef_host && n_coef != P.n_blocks * 64) return PREP_E_INVALID_ARG;
+
+    Slot *s;
+    rc = take_slot(h, &s);
+    if (rc != PREP_OK) return rc;
+    memcpy(s->h_recs, h->recs.data(), sizeof(ImageRec) * (size_t)n);
+    memcpy(s->h_rr, h->rr.data(), sizeof(ResizeRec) * (size_t)n);
+    const uint8_t *d_bits = bits_dev ? bits_dev + offsets[0] : h->d_bits;
+    if (!bits_dev) {
+        memcpy(s->h_bits, base_host, total);
+        HIP_TRY(hipMemcpyAsync(h->d_bits, s->h_bits, total, hipMemcpyHostToDevice, stream));
+    }
+    HIP_TRY(hipMemcpyAsync(h->d_recs, s->h_recs, sizeof(ImageRec) * (size_t)n, hipMemcpyHostToDevice, stream));
+    HIP_TRY(hipMemcpyAsync(h->d_rr, s->h_rr, sizeof(ResizeRec) * (size_t)n, hipMemcpyHostToDevice, stream));
+    const bool timing = h->timing;
+    if (timing) HIP_TRY(hipEventRecord(h->ev[0], stream));
+    if (coef_host) {
+        for (int32_t i = 0; i < n; i++) s->h_status[i] = h->recs[(size_t)i].status;
+        HIP_TRY(hipMemcpyAsync(h->d_status, s->h_status, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice, stream));
+        if (P.n_blocks)
+            HIP_TRY(hipMemcpyAsync(h->d_coef, coef_host, P.n_blocks * 128, hipMemcpyHostToDevice, stream));
+        if (timing) { HIP_TRY(hipEventRecord(h->ev[1], stream)); HIP_TRY(hipEventRecord(h->ev[2], stream)); }
+    } else {
+        if (P.n_blocks) HIP_TRY(hipMemsetAsync(h->d_coef, 0, P.n_blocks * 128, stream));
+        launch_scan_restart_markers(d_bits, h->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
+                                    h->d_status, stream);
+        if (timing) HIP_TRY(hipEventRecord(h->ev[1], stream));
+        launch_decode_entropy(d_bits, h->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
+                              h->d_coef, h->d_status, stream);
+        if (timing) HIP_TRY(hipEventRecord(h->ev[2], stream));
+    }
+    launch_reconstruct(d_bits, h->d_recs, n, P.n_groups, h->d_coef, h->d_rgb, stream);
+    if (timing) HIP_TRY(hipEventRecord(h->ev[3], stream));
+    launch_resize_normalize(h->d_rgb, h->d_rr, h->d_status, n, params->crop_h, params->crop_w,
+                            params->out_dtype, params->mean, params->std, out, stream);
+    if (timing) HIP_TRY(hipEventRecord(h->ev[4], stream));
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(s->done, stream));
+    s->pending = true;
+    h->timed_last = timing;
+    h->last_n = n;
+    h->last_stream = stream;
+    return PREP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int prep_create(prep_handle **out, const prep_config *cfg)
+{
+    if (!out) return PREP_E_INVALID_ARG;
+    *out = nullptr;
+    if (!cfg || cfg->max_batch < 1 || cfg->max_batch > 65535 || cfg->max_width < 1 ||
+        cfg->max_height < 1 || cfg->max_width > 65535 || cfg->max_height > 65535 ||
+        cfg->max_bitstream_bytes < 1 || cfg->max_bitstream_bytes > 0x7FFF0000ull || cfg->flags != 0)
+        return PREP_E_INVALID_ARG;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) {
+        (void)hipGetLastError();
+        return PREP_E_HIP;
+    }
+    prep_handle *h = new (std::nothrow) prep_handle;
+    if (!h) return PREP_E_NOMEM;
+    h->cfg = *cfg;
+    const uint64_t n = (uint64_t)cfg->max_batch;
+    const uint64_t wh = (uint64_t)cfg->max_width * cfg->max_height;
+    uint64_t px = cfg->max_total_pixels ? cfg->max_total_pixels : n * wh;
+    if (px > n * wh) px = n * wh;
+    // padded to whole 16x16 MCUs an image of w x h has at most (w+15)(h+15) pixels
+    const uint64_t padded = px + 15ull * n * ((uint64_t)cfg->max_width + cfg->max_height) + 225ull * n;
+    h->cap_blocks = padded * 3 / 64 + 6 * n;       // 4:4:4 worst case: 3 blocks per 64 pixels
+    h->cap_rgb = padded * 3 + kRgbAlign * n;
+    h->cap_windows = cfg->max_bitstream_bytes / kWindowBytes + n + 1;
+    h->cap_bits = cfg->max_bitstream_bytes + kBitsPad;
+    if (h->cap_blocks > 0xFFFFFFFFull) { delete h; return PREP_E_TOO_LARGE; }
+
+    bool ok = hipSetDevice(cfg->device) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_bits, h->cap_bits) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_coef, h->cap_blocks * 128) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_rgb, h->cap_rgb) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_recs, sizeof(ImageRec) * n) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_rr, sizeof(ResizeRec) * n) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_status, sizeof(int32_t) * n) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_win_count, sizeof(uint32_t) * h->cap_windows) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_win_first, sizeof(uint32_t) * h->cap_windows) == hipSuccess;
+    for (int i = 0; ok && i < kSlots; i++) {
+        Slot &s = h->slot[i];
+        ok = ok && hipHostMalloc((void **)&s.h_bits, h->cap_bits, hipHostMallocDefault) == hipSuccess;
+        ok = ok && hipHostMalloc((void **)&s.h_recs, sizeof(ImageRec) * n, hipHostMallocDefault) == hipSuccess;
+        ok = ok && hipHostMalloc((void **)&s.h_rr, sizeof(ResizeRec) * n, hipHostMallocDefault) == hipSuccess;
+        ok = ok && hipHostMalloc((void **)&s.h_status, sizeof(int32_t) * n, hipHostMallocDefault) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&s.done, hipEventDisableTiming) == hipSuccess;
+    }
+    for (int i = 0; ok && i < 5; i++) ok = hipEventCreate(&h->ev[i]) == hipSuccess;
+    if (ok) ok = hipMemset(h->d_status, 0, sizeof(int32_t) * n) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        prep_destroy(h);
+        return PREP_E_NOMEM;
+    }
+    *out = h;
+    return PREP_OK;
+}
+
+int prep_destroy(prep_handle *h)
+{
+    if (!h) return PREP_E_INVALID_ARG;
+    (void)hipSetDevice(h->cfg.device);
+    (void)hipDeviceSynchronize();
+    (void)hipFree(h->d_bits);
+    (void)hipFree(h->d_coef);
+    (void)hipFree(h->d_rgb);
+    (void)hipFree(h->d_recs);
+    (void)hipFree(h->d_rr);
+    (void)hipFree(h->d_status);
+    (void)hipFree(h->d_win_count);
+    (void)hipFree(h->d_win_first);
+    for (int i = 0; i < kSlots; i++) {
+        Slot &s = h->slot[i];
+        if (s.h_bits) (void)hipHostFree(s.h_bits);
+        if (s.h_recs) (void)hipHostFree(s.h_recs);
+        if (s.h_rr) (void)hipHostFree(s.h_rr);
+        if (s.h_status) (void)hipHostFree(s.h_status);
+        if (s.done) (void)hipEventDestroy(s.done);
+    }
+    for (int i = 0; i < 5; i++)
+        if (h->ev[i]) (void)hipEventDestroy(h->ev[i]);
+    (void)hipGetLastError();
+    delete h;
+    return PREP_OK;
+}
+
+int prep_decode_resize_batch(prep_handle *h, const uint8_t *bitstreams, const uint64_t *offsets,
+                             int32_t n, const prep_params *params, void *out, void *stream)
+{
+    return run_batch(h, bitstreams, nullptr, offsets, n, params, out, (hipStream_t)stream, nullptr, 0);
+}
+
+int prep_decode_resize_batch_resident(prep_handle *h, const uint8_t *bitstreams,
+                                      const uint8_t *bitstreams_device, const uint64_t *offsets,
+                                      int32_t n, const prep_params *params, void *out, void *stream)
+{
+    if (!bitstreams_device) return PREP_E_INVALID_ARG;
+    return run_batch(h, bitstreams, bitstreams_device, offsets, n, params, out, (hipStream_t)stream,
+                     nullptr, 0);
+}
+
+int prep_reconstruct_from_coefficients(prep_handle *h, const uint8_t *bitstreams,
+                                       const uint64_t *offsets, int32_t n,
+                                       const int16_t *coefficients, uint64_t n_coefficients,
+                                       const prep_params *params, void *out, void *stream)
+{
+    if (!coefficients) return PREP_E_INVALID_ARG;
+    int rc = run_batch(h, bitstreams, nullptr, offsets, n, params, out, (hipStream_t)stream,
+                       coefficients, n_coefficients);
+    // the coefficients were copied from pageable memory: make sure the copy is over
+    if (rc == PREP_OK && hipStreamSynchronize((hipStream_t)stream) != hipSuccess) rc = PREP_E_HIP;
+    return rc;
+}
+
+int prep_get_status(prep_handle *h, int32_t *per_image_status, int32_t n)
+{
+    if (!h || !per_image_status || n < 0 || n > h->last_n) return PREP_E_INVALID_ARG;
+    if (n == 0) return PREP_OK;
+    HIP_TRY(hipSetDevice(h->cfg.device));
+    HIP_TRY(hipStreamSynchronize(h->last_stream));
+    HIP_TRY(hipMemcpy(per_image_status, h->d_status, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToHost));
+    for (int32_t i = 0; i < n; i++)
+        if (h->recs[(size_t)i].status != PREP_OK) per_image_status[i] = h->recs[(size_t)i].status;
+    return PREP_OK;
+}
+
+const char *prep_strerror(int code)
+{
+    switch (code) {
+    case PREP_OK: return "ok";
+    case PREP_E_INVALID_ARG: return "invalid argument";
+    case PREP_E_TOO_LARGE: return "batch exceeds the capacity the handle was created with";
+    case PREP_E_HIP: return "HIP runtime call failed";
+    case PREP_E_UNSUPPORTED: return "JPEG outside the supported baseline subset";
+    case PREP_E_CORRUPT: return "corrupt JPEG stream";
+    case PREP_E_NOMEM: return "out of memory";
+    default: return "unknown error code";
+    }
+}
+
+int prep_parse_headers(const uint8_t *bitstreams, const uint64_t *offsets, int32_t n,
+                       prep_image_info *info)
+{
+    if (!bitstreams || !offsets || !info || n < 0) return PREP_E_INVALID_ARG;
+    for (int32_t i = 0; i < n; i++) {
+        if (offsets[i + 1] < offsets[i]) return PREP_E_INVALID_ARG;
+        ParsedImage p;
+        parse_image(bitstreams + offsets[i], offsets[i + 1] - offsets[i], &p);
+        info[i] = p.info;
+    }
+    return PREP_OK;
+}
+
+int64_t prep_interval_descriptors(const prep_image_info *info, int32_t n, prep_interval_desc *desc,
+                                  int64_t cap)
+{
+    if (!info || n < 0 || cap < 0 || (cap > 0 && !desc)) return PREP_E_INVALID_ARG;
+    int64_t k = 0;
+    for (int32_t i = 0; i < n; i++) {
+        if (info[i].status != PREP_OK) continue;
+        const int64_t nmcu = (int64_t)info[i].mcu_cols * info[i].mcu_rows;
+        const int64_t ri = info[i].restart_interval > 0 ? info[i].restart_interval : nmcu;
+        for (int64_t m = 0, j = 0; m < nmcu; m += ri, j++, k++) {
+            if (k < cap) {
+                desc[k].image = i;
+                desc[k].first_mcu = (int32_t)m;
+                desc[k].n_mcu = (int32_t)(nmcu - m < ri ? nmcu - m : ri);
+                desc[k].rst_index = j == 0 ? -1 : (int32_t)((j - 1) & 7);
+            }
+        }
+    }
+    return k;
+}
+
+int prep_resize_normalize(prep_handle *h, const uint8_t *rgb, const uint64_t *rgb_offsets,
+                          const int32_t *widths, const int32_t *heights, const int32_t *pitches,
+                          int32_t n, const prep_params *params, void *out, void *stream)
+{
+    if (!h || !rgb || !rgb_offsets || !widths || !heights || !pitches || !out || n < 0 ||
+        !params_ok(params))
+        return PREP_E_INVALID_ARG;
+    if (n > h->cfg.max_batch) return PREP_E_TOO_LARGE;
+    if (n == 0) return PREP_OK;
+    HIP_TRY(hipSetDevice(h->cfg.device));
+    Slot *s;
+    int rc = take_slot(h, &s);
+    if (rc != PREP_OK) return rc;
+    for (int32_t i = 0; i < n; i++) {
+        if (widths[i] < 1 || heights[i] < 1 || pitches[i] < widths[i] * 3) return PREP_E_INVALID_ARG;
+        if (!make_resize_rec(widths[i], heights[i], params, rgb_offsets[i], (uint32_t)pitches[i], &s->h_rr[i]))
+            return PREP_E_INVALID_ARG;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipMemcpyAsync(h->d_rr, s->h_rr, sizeof(ResizeRec) * (size_t)n, hipMemcpyHostToDevice, st));
+    launch_resize_normalize(rgb, h->d_rr, nullptr, n, params->crop_h, params->crop_w,
+                            params->out_dtype, params->mean, params->std, out, st);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(s->done, st));
+    s->pending = true;
+    return PREP_OK;
+}
+
+int64_t prep_debug_last_coefficients(prep_handle *h, int32_t image, int16_t *host_out, uint64_t cap)
+{
+    if (!h || !host_out || image < 0 || image >= h->last_n) return PREP_E_INVALID_ARG;
+    const ImageRec &R = h->recs[(size_t)image];
+    if (R.status != PREP_OK) return R.status;
+    const uint64_t count = (uint64_t)R.n_blocks * 64;
+    if (cap < count) return PREP_E_INVALID_ARG;
+    HIP_TRY(hipSetDevice(h->cfg.device));
+    HIP_TRY(hipStreamSynchronize(h->last_stream));
+    HIP_TRY(hipMemcpy(host_out, h->d_coef + (size_t)R.coef_block0 * 64, count * 2, hipMemcpyDeviceToHost));
+    return (int64_t)count;
+}
+
+int64_t prep_debug_last_rgb(prep_handle *h, int32_t image, uint8_t *host_out_hwc, uint64_t cap)
+{
+    if (!h || !host_out_hwc || image < 0 || image >= h->last_n) return PREP_E_INVALID_ARG;
+    const ImageRec &R = h->recs[(size_t)image];
+    if (R.status != PREP_OK) return R.status;
+    const uint64_t row = (uint64_t)R.width * 3, count = row * R.height;
+    if (cap < count) return PREP_E_INVALID_ARG;
+    HIP_TRY(hipSetDevice(h->cfg.device));
+    HIP_TRY(hipStreamSynchronize(h->last_stream));
+    HIP_TRY(hipMemcpy2D(host_out_hwc, row, h->d_rgb + R.rgb_off, R.rgb_pitch, row, R.height,
+                        hipMemcpyDeviceToHost));
+    return (int64_t)count;
+}
+
+int prep_set_timing(prep_handle *h, int32_t enabled)
+{
+    if (!h) return PREP_E_INVALID_ARG;
+    h->timing = enabled != 0;
+    return PREP_OK;
+}
+
+int prep_last_stage_ms(prep_handle *h, float ms[4])
+{
+    if (!h || !ms || !h->timed_last || h->last_n == 0) return PREP_E_INVALID_ARG;
+    HIP_TRY(hipSetDevice(h->cfg.device));
+    HIP_TRY(hipEventSynchronize(h->ev[4]));
+    for (int i = 0; i < 4; i++) HIP_TRY(hipEventElapsedTime(&ms[i], h->ev[i], h->ev[i + 1]));
+    return PREP_OK;
+}
+
+}  // extern "C"

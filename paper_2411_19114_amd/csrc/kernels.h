@@ -1,0 +1,28 @@
+// Launchers of libprep's HIP kernels (one translation unit per stage).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "prep_internal.h"
+
+namespace prep {
+
+// entropy.hip
+void launch_scan_restart_markers(const uint8_t *bits, const ImageRec *recs, int n_images,
+                                 uint32_t n_windows, uint32_t *win_count, uint32_t *win_first,
+                                 int32_t *status, hipStream_t stream);
+void launch_decode_entropy(const uint8_t *bits, const ImageRec *recs, int n_images,
+                           uint32_t n_windows, const uint32_t *win_count, const uint32_t *win_first,
+                           int16_t *coef, int32_t *status, hipStream_t stream);
+
+// reconstruct.hip
+void launch_reconstruct(const uint8_t *bits, const ImageRec *recs, int n_images, uint32_t n_groups,
+                        const int16_t *coef, uint8_t *rgb, hipStream_t stream);
+
+// resize.hip
+void launch_resize_normalize(const uint8_t *rgb, const ResizeRec *rr, const int32_t *status,
+                             int n_images, int crop_h, int crop_w, int out_dtype,
+                             const float mean[3], const float std[3], void *out,
+                             hipStream_t stream);
+
+}  // namespace prep

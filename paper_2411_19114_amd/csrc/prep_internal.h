@@ -1,0 +1,65 @@
+// Shared between the host code and the HIP kernels of libprep: plain-old-data
+// records that travel to the GPU and the launch geometry constants.
+#pragma once
+#include <stdint.h>
+
+namespace prep {
+
+// ---- entropy decoder geometry -------------------------------------------
+// One workgroup owns a contiguous run of restart intervals of one image and
+// decodes it chunk by chunk.  A chunk is kChunkRaw raw bytes staged into LDS
+// with stuffing and markers removed; each lane then owns one subsequence of
+// kSubseqBytes clean bytes.
+constexpr int kDecodeThreads = 256;
+constexpr int kSubseqBytes = 64;                            // clean bytes per lane
+constexpr int kChunkRaw = kDecodeThreads * kSubseqBytes;    // raw bytes staged per chunk
+constexpr int kChunkTail = 16;                              // bytes a non-final chunk keeps back
+constexpr int kWindowBytes = 12288;                         // raw bytes between workgroup starts
+constexpr int kLutBits = 10;                                // first-level Huffman lookup width
+
+// ---- reconstruction geometry ----------------------------------------------
+// One workgroup turns kReconBlocks 8x8 blocks (a run of MCUs of one MCU row)
+// into RGB pixels: 5 MCUs of 4:2:0, 10 of 4:4:4, 32 of grayscale.
+constexpr int kReconThreads = 256;
+constexpr int kReconBlocks = 32;
+inline constexpr int recon_mcus_per_group(int sampling) { return sampling == 1 ? 5 : sampling == 0 ? 10 : 32; }
+
+// Per-image record, written by the host parser (T.81 Annex B) and read by
+// every kernel.  file_off is the byte offset of the file in the device copy of
+// the batch's bitstreams; entropy_rel, dht_off and dqt_off count from there.
+struct ImageRec {
+    uint64_t file_off;      // first byte (SOI) of this file
+    uint64_t rgb_off;       // this image's RGB plane in the workspace (bytes)
+    uint32_t entropy_rel;   // first entropy-coded byte
+    uint32_t entropy_len;   // bytes up to the EOI marker
+    uint32_t coef_block0;   // first block of this image in the coefficient workspace
+    uint32_t n_blocks;      // mcu_cols * mcu_rows * blocks_per_mcu
+    uint32_t window0;       // first decode window (= workgroup) of this image
+    uint32_t n_windows;
+    uint32_t rgb_pitch;     // bytes between RGB rows (covers the whole MCU grid)
+    uint32_t group0;        // first reconstruction workgroup of this image
+    uint32_t groups_per_row;  // reconstruction workgroups per MCU row
+    uint32_t dht_off[4];    // offset of BITS[16] of: DC luma, AC luma, DC chroma, AC chroma
+    uint32_t dht_nval[4];   // number of HUFFVAL bytes that follow the 16 BITS bytes
+    uint32_t dqt_off[3];    // offset of the 64 zig-zag ordered table bytes per component
+    uint16_t width, height;
+    uint16_t mcu_cols, mcu_rows;
+    uint16_t restart_interval;  // MCUs, 0 = none
+    uint8_t sampling;           // PREP_SAMPLING_*
+    uint8_t blocks_per_mcu;
+    int32_t status;             // host verdict; kernels skip images that are not PREP_OK
+};
+static_assert(sizeof(ImageRec) % 8 == 0, "ImageRec must keep 8-byte alignment in arrays");
+
+// Resize/crop/normalize geometry of one image, computed on the host in double
+// precision so that every lane uses identical mapping constants.
+struct ResizeRec {
+    float scale_x, scale_y;   // source pixels per output pixel
+    float off_x, off_y;       // source coordinate of output pixel (0,0)
+    int32_t src_w, src_h;
+    uint32_t src_pitch;
+    uint32_t pad_;
+    uint64_t src_off;         // byte offset of the source image
+};
+
+}  // namespace prep

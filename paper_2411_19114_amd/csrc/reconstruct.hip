@@ -1,0 +1,218 @@
+// Dequantise + 8x8 inverse DCT + chroma upsampling + YCbCr->RGB, fused (gfx950).
+//
+// The second half of the "Decode" functional unit (PREBA section 4.2, Table 1):
+// T.81 A.3.4 (dequantisation, zig-zag), A.3.3 (IDCT), A.3.1 (level shift),
+// sample replication for subsampled chroma, JFIF colour transform.  One
+// workgroup handles a run of MCUs of one MCU row: coefficients are read once
+// (128 B per block), everything else lives in LDS, and RGB leaves as aligned
+// 32-bit stores covering the whole MCU grid (the row pitch includes padding).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/prep.h"
+#include "kernels.h"
+#include "prep_internal.h"
+
+namespace prep {
+
+namespace {
+
+constexpr int kTileStride = 9;               // floats per tile row: spreads rows over LDS banks
+constexpr int kTileSize = 8 * kTileStride;   // one 8x8 block
+constexpr int kLumaPitch = 256;              // bytes per row of the luma sample plane
+constexpr int kChromaPitch = 96;
+
+// zig-zag position k -> natural index v*8+u (T.81 Figure A.6), found by walking
+// the anti-diagonals alternately down-left and up-right
+struct ZigZag {
+    uint8_t nat[64];
+    constexpr ZigZag() : nat()
+    {
+        int v = 0, u = 0;
+        for (int k = 0; k < 64; k++) {
+            nat[k] = (uint8_t)(v * 8 + u);
+            if (((v + u) & 1) == 0) {          // moving up-right
+                if (u == 7) v++;
+                else if (v == 0) u++;
+                else { v--; u++; }
+            } else {                           // moving down-left
+                if (v == 7) u++;
+                else if (u == 0) v++;
+                else { v++; u--; }
+            }
+        }
+    }
+};
+__device__ const ZigZag kZigZag{};
+
+// 8-point inverse DCT with basis m(x,0) = 1, m(x,u) = sqrt(2) cos((2x+1) u pi/16):
+// the 2-D result still needs a factor 1/8.  Even and odd frequencies are summed
+// separately because the odd basis is antisymmetric about the centre.
+__device__ inline void idct8(const float F[8], float out[8])
+{
+    constexpr float c1 = 1.3870398453221475f, c2 = 1.3065629648763766f, c3 = 1.1758756024193588f,
+                    c5 = 0.7856949583871022f, c6 = 0.5411961001461970f, c7 = 0.2758993792829431f;
+    const float a = F[0] + F[4], b = F[0] - F[4];
+    const float e0 = a + (c2 * F[2] + c6 * F[6]);
+    const float e3 = a - (c2 * F[2] + c6 * F[6]);
+    const float e1 = b + (c6 * F[2] - c2 * F[6]);
+    const float e2 = b - (c6 * F[2] - c2 * F[6]);
+    const float o0 = c1 * F[1] + c3 * F[3] + c5 * F[5] + c7 * F[7];
+    const float o1 = c3 * F[1] - c7 * F[3] - c1 * F[5] - c5 * F[7];
+    const float o2 = c5 * F[1] - c1 * F[3] + c7 * F[5] + c3 * F[7];
+    const float o3 = c7 * F[1] - c5 * F[3] + c3 * F[5] - c1 * F[7];
+    out[0] = e0 + o0; out[7] = e0 - o0;
+    out[1] = e1 + o1; out[6] = e1 - o1;
+    out[2] = e2 + o2; out[5] = e2 - o2;
+    out[3] = e3 + o3; out[4] = e3 - o3;
+}
+
+__device__ inline uint32_t round_clamp_u8(double v)
+{
+    double r = floor(v + 0.5);
+    r = r < 0.0 ? 0.0 : (r > 255.0 ? 255.0 : r);
+    return (uint32_t)r;
+}
+
+template <typename F>
+__device__ inline int find_image_by(int n, uint32_t x, F key)
+{
+    int lo = 0, hi = n - 1;
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (key(mid) <= x) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+}  // namespace
+
+__global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
+    const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
+    const int16_t *__restrict__ coef_all, uint8_t *__restrict__ rgb_all)
+{
+    __shared__ float tile[kReconBlocks * kTileSize];
+    __shared__ float qf[3][64];
+    __shared__ uint32_t luma[16 * kLumaPitch / 4];
+    __shared__ uint32_t chroma[2][8 * kChromaPitch / 4];
+
+    const int tid = threadIdx.x;
+    const uint32_t wg = blockIdx.x;
+    const int img = find_image_by(n_images, wg, [&](int i) { return recs[i].group0; });
+    const ImageRec &R = recs[img];
+    if (R.status != PREP_OK) return;
+    const uint32_t gi = wg - R.group0;
+    const uint32_t mrow = gi / R.groups_per_row, gcol = gi % R.groups_per_row;
+    if (mrow >= R.mcu_rows) return;
+    const int sampling = R.sampling;
+    const int bpm = R.blocks_per_mcu;
+    const int hs = sampling == PREP_SAMPLING_420 ? 2 : 1;  // luma blocks per MCU per axis
+    const int n_luma = hs * hs;
+    const int per_group = recon_mcus_per_group(sampling);
+    const uint32_t mcu_x0 = gcol * per_group;
+    const int gcount = min(per_group, (int)R.mcu_cols - (int)mcu_x0);
+    const int n_blk = gcount * bpm;  // <= kReconBlocks
+
+    const uint8_t *file = bits + R.file_off;
+    if (tid < 192) qf[tid >> 6][tid & 63] = (float)file[R.dqt_off[tid >> 6] + (tid & 63)];
+    __syncthreads();
+
+    const int b = tid >> 3, l = tid & 7;
+    const bool have = b < n_blk;
+    const int mcu = have ? b / bpm : 0, blk = have ? b % bpm : 0;
+    const int comp = blk < n_luma ? 0 : blk - n_luma + 1;
+    float *T = tile + b * kTileSize;
+
+    // ---- dequantise, undo the zig-zag (A.3.4) ------------------------------------
+    if (have) {
+        const size_t gb = (size_t)R.coef_block0 +
+                          ((size_t)mrow * R.mcu_cols + mcu_x0 + mcu) * bpm + blk;
+        const uint4 raw = *reinterpret_cast<const uint4 *>(coef_all + gb * 64 + l * 8);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const int k = l * 8 + j;
+            const int c = (int)(int16_t)(w[j >> 1] >> (16 * (j & 1)));
+            const int nat = kZigZag.nat[k];
+            T[(nat >> 3) * kTileStride + (nat & 7)] = (float)c * qf[comp][k];
+        }
+    }
+    __syncthreads();
+    // ---- columns: lane l transforms column u = l ------------------------------------
+    if (have) {
+        float F[8], o[8];
+#pragma unroll
+        for (int v = 0; v < 8; v++) F[v] = T[v * kTileStride + l];
+        idct8(F, o);
+#pragma unroll
+        for (int y = 0; y < 8; y++) T[y * kTileStride + l] = o[y];
+    }
+    __syncthreads();
+    // ---- rows: lane l transforms row y = l, level shift, round, clamp (A.3.1) ---------
+    if (have) {
+        float F[8], o[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) F[u] = T[l * kTileStride + u];
+        idct8(F, o);
+        uint32_t pk[2] = {0, 0};
+#pragma unroll
+        for (int x = 0; x < 8; x++) {
+            float s = floorf(o[x] * 0.125f + 0.5f) + 128.0f;
+            s = s < 0.0f ? 0.0f : (s > 255.0f ? 255.0f : s);
+            pk[x >> 2] |= (uint32_t)s << (8 * (x & 3));
+        }
+        if (comp == 0) {
+            const int bx = blk & (hs - 1), by = hs == 2 ? blk >> 1 : 0;
+            const int row = by * 8 + l, col = (mcu * hs + bx) * 8;
+            luma[(row * kLumaPitch + col) / 4] = pk[0];
+            luma[(row * kLumaPitch + col) / 4 + 1] = pk[1];
+        } else {
+            chroma[comp - 1][(l * kChromaPitch + mcu * 8) / 4] = pk[0];
+            chroma[comp - 1][(l * kChromaPitch + mcu * 8) / 4 + 1] = pk[1];
+        }
+    }
+    __syncthreads();
+    // ---- colour: 4 pixels (12 bytes) per item ------------------------------------------
+    const int rows = 8 * hs, width = gcount * 8 * hs, quads = width >> 2;
+    const int items = rows * quads;
+    const uint8_t *lum8 = reinterpret_cast<const uint8_t *>(luma);
+    const uint8_t *cb8 = reinterpret_cast<const uint8_t *>(chroma[0]);
+    const uint8_t *cr8 = reinterpret_cast<const uint8_t *>(chroma[1]);
+    uint8_t *dst0 = rgb_all + R.rgb_off + (size_t)mrow * rows * R.rgb_pitch +
+                    (size_t)mcu_x0 * 8 * hs * 3;
+    const int cshift = hs - 1;
+    for (int it = tid; it < items; it += kReconThreads) {
+        const int row = it / quads, x = (it - row * quads) * 4;
+        uint32_t out[3] = {0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const uint32_t Y = lum8[row * kLumaPitch + x + j];
+            uint32_t r = Y, gch = Y, bl = Y;
+            if (sampling != PREP_SAMPLING_GRAY) {
+                const int ci = (row >> cshift) * kChromaPitch + ((x + j) >> cshift);
+                const double cb = (double)cb8[ci] - 128.0, cr = (double)cr8[ci] - 128.0;
+                r = round_clamp_u8((double)Y + 1.402 * cr);
+                gch = round_clamp_u8((double)Y - 0.344136 * cb - 0.714136 * cr);
+                bl = round_clamp_u8((double)Y + 1.772 * cb);
+            }
+            const int o = j * 3;
+            out[o >> 2] |= r << (8 * (o & 3));
+            out[(o + 1) >> 2] |= gch << (8 * ((o + 1) & 3));
+            out[(o + 2) >> 2] |= bl << (8 * ((o + 2) & 3));
+        }
+        uint32_t *d = reinterpret_cast<uint32_t *>(dst0 + (size_t)row * R.rgb_pitch + x * 3);
+        d[0] = out[0];
+        d[1] = out[1];
+        d[2] = out[2];
+    }
+}
+
+void launch_reconstruct(const uint8_t *bits, const ImageRec *recs, int n_images, uint32_t n_groups,
+                        const int16_t *coef, uint8_t *rgb, hipStream_t stream)
+{
+    if (n_groups == 0) return;
+    hipLaunchKernelGGL(reconstruct_rgb, dim3(n_groups), dim3(kReconThreads), 0, stream, bits, recs,
+                       n_images, coef, rgb);
+}
+
+}  // namespace prep
