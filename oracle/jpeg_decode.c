@@ -225,9 +225,15 @@ static int receive_extend(bitreader *br, int t)
     return v < (1 << (t - 1)) ? v - (1 << t) + 1 : v;
 }
 
+/* A.3.3 + level shift (A.3.1): nearest integer, half-way cases up, clamped to 8 bits.
+ * Cosine products that are rational in exact arithmetic (C(0)^2 = 1/2,
+ * C(0) cos(pi/4) = 1/2, ...) can put a sample exactly half way; evaluated in
+ * double they land within ~1e-12 of it, on either side.  Values closer than
+ * ORACLE_TIE_EPS below a half-way point are therefore taken to be half way.    */
+#define ORACLE_TIE_EPS (1.0 / 1048576.0)
 static uint8_t clamp_sample(double v)
 {
-    double r = floor(v + 0.5) + 128.0;
+    double r = floor(v + 0.5 + ORACLE_TIE_EPS) + 128.0;
     if (r < 0.0) r = 0.0;
     if (r > 255.0) r = 255.0;
     return (uint8_t)r;

@@ -307,6 +307,28 @@ def test_dc_only_ties_round_half_up_for_both_signs():
         assert (oracle.idct8x8(F) == dc / 8.0).all()   # exactly, not approximately
 
 
+def test_structured_ties_of_dc_plus_one_cosine_term_round_up():
+    # only F(0,0) and F(v=0,u=4) non-zero: the definition gives (F00 +- F04)/8 exactly, with
+    # the sign of cos((2x+1) pi/4); many of these samples sit exactly half way
+    q = np.ones(64, dtype=np.uint16)
+    k04 = [k for k in range(64) if oracle.zigzag_pos(k) == (0, 4)][0]
+    cases = [(12, 8), (-12, 8), (100, -24), (4, 0), (-44, 16), (36, -8), (-4, 40), (20, 24)]
+    coef = np.zeros((len(cases), 64), dtype=np.int16)
+    for b, (f00, f04) in enumerate(cases):
+        coef[b, 0], coef[b, k04] = f00, f04
+    data = oracle.write_jpeg(coef, 8 * len(cases), 8, MODE_GRAY, q, q)
+    _, rgb, _ = oracle.decode(data, want_coef=False)
+    sign = np.array([1, -1, -1, 1, 1, -1, -1, 1])
+    n_ties = 0
+    for b, (f00, f04) in enumerate(cases):
+        num = f00 + sign * f04                      # sample * 8, exact integers
+        expect = np.clip((num + 4) // 8 + 128, 0, 255)   # floor(num/8 + 1/2) + 128
+        n_ties += int((num % 8 == 4).sum())
+        block = rgb[:, 8 * b:8 * b + 8, 0]
+        assert (block == expect[None, :]).all(), (f00, f04)
+    assert n_ties >= 16
+
+
 # ---------------------------------------------------------------- independent codec (Pillow)
 
 def _pil_decode(data):
