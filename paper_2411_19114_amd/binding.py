@@ -76,6 +76,12 @@ def lib():
         if not os.path.exists(lib_path()):
             raise RuntimeError(f"{lib_path()} is not built: run __graft_entry__.build() "
                                "(hipcc --offload-arch=gfx950)")
+        # PyTorch ships its own HIP runtime under the same soname; it must be the one
+        # this process uses, so it is loaded first and libprep binds to it.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(lib_path())
         vp, u8p, u64p, i32p = C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int32)
         L.prep_create.argtypes = [C.POINTER(vp), C.POINTER(Config)]

@@ -100,10 +100,10 @@ bool make_resize_rec(int w, int h, const prep_params *p, uint64_t src_off, uint3
     if (p->crop_w > ow || p->crop_h > oh) return false;
     const int top = (oh - p->crop_h) / 2, left = (ow - p->crop_w) / 2;
     const double sx = (double)w / (double)ow, sy = (double)h / (double)oh;
-    r->scale_x = (float)sx;
-    r->scale_y = (float)sy;
-    r->off_x = (float)((left + 0.5) * sx - 0.5);
-    r->off_y = (float)((top + 0.5) * sy - 0.5);
+    r->scale_x = sx;
+    r->scale_y = sy;
+    r->off_x = (left + 0.5) * sx - 0.5;
+    r->off_y = (top + 0.5) * sy - 0.5;
     r->src_w = w;
     r->src_h = h;
     r->src_pitch = pitch;

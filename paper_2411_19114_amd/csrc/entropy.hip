@@ -167,6 +167,7 @@ struct WriteCtx {
     int32_t dcreset[3];
     uint32_t dc_first;   // first block whose DC this lane decoded
     uint32_t dc_count;
+    int32_t need_restart;  // the next thing in the stream must be a restart boundary
     int32_t bad;
 };
 
@@ -222,6 +223,7 @@ __device__ inline uint32_t decode_span(const DecodeShared &S, const Geometry &g,
         }
         const uint32_t s = sym & 15u;
         const uint32_t adv = len + s;
+        if (kWrite && wc->need_restart && p + adv <= nb) wc->bad = 1;  // a restart marker is missing
         if (p + adv > nb) {
             // the symbol does not fit before the next restart boundary / end of data
             if (nb >= limit_bits) {
@@ -232,6 +234,7 @@ __device__ inline uint32_t decode_span(const DecodeShared &S, const Geometry &g,
             if (kWrite) {
                 if (blk != 0 || zz != 0 || nb - p >= 8) wc->bad = 1;
                 if (g.ri_blocks == 0 || wc->block % g.ri_blocks != 0) wc->bad = 1;
+                wc->need_restart = 0;
             }
             p = nb;
             blk = 0;
@@ -294,7 +297,11 @@ __device__ inline uint32_t decode_span(const DecodeShared &S, const Geometry &g,
             zz = 0;
             blk = blk + 1 == g.bpm ? 0 : blk + 1;
             done++;
-            if (kWrite) wc->block++;
+            if (kWrite) {
+                wc->block++;
+                if (g.ri_blocks && wc->block % g.ri_blocks == 0 && wc->block < g.n_blocks)
+                    wc->need_restart = 1;
+            }
         }
     }
     *nblk = done;
@@ -621,6 +628,11 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         wc.dc_first = 0;
         wc.dc_count = 0;
         wc.bad = 0;
+        // a lane that begins on an MCU boundary where an interval ends must meet the boundary
+        // first; lane 0 of a chunk may begin just after one (start of the run, or a boundary
+        // consumed at the very end of the previous chunk)
+        wc.need_restart = (in_state & 511u) == 0 && g.ri_blocks != 0 && my_block % g.ri_blocks == 0 &&
+                          my_block < g.n_blocks && tid != 0;
         uint32_t final_state = out_state;
         if (active && (in_state >> 9) < end_bit) {
             uint32_t nb2;

@@ -54,8 +54,8 @@ static_assert(sizeof(ImageRec) % 8 == 0, "ImageRec must keep 8-byte alignment in
 // Resize/crop/normalize geometry of one image, computed on the host in double
 // precision so that every lane uses identical mapping constants.
 struct ResizeRec {
-    float scale_x, scale_y;   // source pixels per output pixel
-    float off_x, off_y;       // source coordinate of output pixel (0,0)
+    double scale_x, scale_y;  // source pixels per output pixel
+    double off_x, off_y;      // source coordinate of output pixel (0,0)
     int32_t src_w, src_h;
     uint32_t src_pitch;
     uint32_t pad_;

@@ -17,7 +17,7 @@ namespace prep {
 
 namespace {
 
-constexpr int kTileStride = 9;               // floats per tile row: spreads rows over LDS banks
+constexpr int kTileStride = 9;               // doubles per tile row: spreads rows over LDS banks
 constexpr int kTileSize = 8 * kTileStride;   // one 8x8 block
 constexpr int kLumaPitch = 256;              // bytes per row of the luma sample plane
 constexpr int kChromaPitch = 96;
@@ -48,24 +48,34 @@ __device__ const ZigZag kZigZag{};
 // 8-point inverse DCT with basis m(x,0) = 1, m(x,u) = sqrt(2) cos((2x+1) u pi/16):
 // the 2-D result still needs a factor 1/8.  Even and odd frequencies are summed
 // separately because the odd basis is antisymmetric about the centre.
-__device__ inline void idct8(const float F[8], float out[8])
+//
+// Double precision on purpose: a decoded sample is rounded to 8 bits and a chroma
+// sample that rounds the other way moves blue by two levels after colour
+// conversion.  With ~1e-13 of evaluation noise only samples that the definition
+// puts exactly half way can flip, and those are settled by kTieEps below.  With
+// this basis m(x,4) = +-1 exactly, so DC-only and DC+F(.,4) blocks are exact.
+__device__ inline void idct8(const double F[8], double out[8])
 {
-    constexpr float c1 = 1.3870398453221475f, c2 = 1.3065629648763766f, c3 = 1.1758756024193588f,
-                    c5 = 0.7856949583871022f, c6 = 0.5411961001461970f, c7 = 0.2758993792829431f;
-    const float a = F[0] + F[4], b = F[0] - F[4];
-    const float e0 = a + (c2 * F[2] + c6 * F[6]);
-    const float e3 = a - (c2 * F[2] + c6 * F[6]);
-    const float e1 = b + (c6 * F[2] - c2 * F[6]);
-    const float e2 = b - (c6 * F[2] - c2 * F[6]);
-    const float o0 = c1 * F[1] + c3 * F[3] + c5 * F[5] + c7 * F[7];
-    const float o1 = c3 * F[1] - c7 * F[3] - c1 * F[5] - c5 * F[7];
-    const float o2 = c5 * F[1] - c1 * F[3] + c7 * F[5] + c3 * F[7];
-    const float o3 = c7 * F[1] - c5 * F[3] + c3 * F[5] - c1 * F[7];
+    constexpr double c1 = 1.3870398453221475, c2 = 1.3065629648763766, c3 = 1.1758756024193588,
+                     c5 = 0.7856949583871022, c6 = 0.5411961001461970, c7 = 0.2758993792829431;
+    const double a = F[0] + F[4], b = F[0] - F[4];
+    const double e0 = a + (c2 * F[2] + c6 * F[6]);
+    const double e3 = a - (c2 * F[2] + c6 * F[6]);
+    const double e1 = b + (c6 * F[2] - c2 * F[6]);
+    const double e2 = b - (c6 * F[2] - c2 * F[6]);
+    const double o0 = c1 * F[1] + c3 * F[3] + c5 * F[5] + c7 * F[7];
+    const double o1 = c3 * F[1] - c7 * F[3] - c1 * F[5] - c5 * F[7];
+    const double o2 = c5 * F[1] - c1 * F[3] + c7 * F[5] + c3 * F[7];
+    const double o3 = c7 * F[1] - c5 * F[3] + c3 * F[5] - c1 * F[7];
     out[0] = e0 + o0; out[7] = e0 - o0;
     out[1] = e1 + o1; out[6] = e1 - o1;
     out[2] = e2 + o2; out[5] = e2 - o2;
     out[3] = e3 + o3; out[4] = e3 - o3;
 }
+
+// Samples closer than this below a half-way point count as half way and round up:
+// rational results of the IDCT definition carry ~1e-13 of evaluation noise.
+constexpr double kTieEps = 1.0 / 1048576.0;
 
 __device__ inline uint32_t round_clamp_u8(double v)
 {
@@ -91,7 +101,7 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
     const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
     const int16_t *__restrict__ coef_all, uint8_t *__restrict__ rgb_all)
 {
-    __shared__ float tile[kReconBlocks * kTileSize];
+    __shared__ double tile[kReconBlocks * kTileSize];
     __shared__ float qf[3][64];
     __shared__ uint32_t luma[16 * kLumaPitch / 4];
     __shared__ uint32_t chroma[2][8 * kChromaPitch / 4];
@@ -121,7 +131,7 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
     const bool have = b < n_blk;
     const int mcu = have ? b / bpm : 0, blk = have ? b % bpm : 0;
     const int comp = blk < n_luma ? 0 : blk - n_luma + 1;
-    float *T = tile + b * kTileSize;
+    double *T = tile + b * kTileSize;
 
     // ---- dequantise, undo the zig-zag (A.3.4) ------------------------------------
     if (have) {
@@ -134,13 +144,13 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
             const int k = l * 8 + j;
             const int c = (int)(int16_t)(w[j >> 1] >> (16 * (j & 1)));
             const int nat = kZigZag.nat[k];
-            T[(nat >> 3) * kTileStride + (nat & 7)] = (float)c * qf[comp][k];
+            T[(nat >> 3) * kTileStride + (nat & 7)] = (double)c * (double)qf[comp][k];
         }
     }
     __syncthreads();
     // ---- columns: lane l transforms column u = l ------------------------------------
     if (have) {
-        float F[8], o[8];
+        double F[8], o[8];
 #pragma unroll
         for (int v = 0; v < 8; v++) F[v] = T[v * kTileStride + l];
         idct8(F, o);
@@ -150,15 +160,15 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
     __syncthreads();
     // ---- rows: lane l transforms row y = l, level shift, round, clamp (A.3.1) ---------
     if (have) {
-        float F[8], o[8];
+        double F[8], o[8];
 #pragma unroll
         for (int u = 0; u < 8; u++) F[u] = T[l * kTileStride + u];
         idct8(F, o);
         uint32_t pk[2] = {0, 0};
 #pragma unroll
         for (int x = 0; x < 8; x++) {
-            float s = floorf(o[x] * 0.125f + 0.5f) + 128.0f;
-            s = s < 0.0f ? 0.0f : (s > 255.0f ? 255.0f : s);
+            double s = floor(o[x] * 0.125 + (0.5 + kTieEps)) + 128.0;
+            s = s < 0.0 ? 0.0 : (s > 255.0 ? 255.0 : s);
             pk[x >> 2] |= (uint32_t)s << (8 * (x & 3));
         }
         if (comp == 0) {

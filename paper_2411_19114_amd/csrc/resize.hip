@@ -69,16 +69,17 @@ __global__ __launch_bounds__(kResizeThreads) void resize_crop_normalize(
     } else {
         const ResizeRec R = rr[img];
         const uint8_t *src = rgb + R.src_off;
-        const float sy = fmaf((float)y, R.scale_y, R.off_y);
-        const float fy0 = floorf(sy);
-        const float fy = sy - fy0;
+        // source coordinates in double: a float has too few bits left at x ~ 2000
+        const double sy = fma((double)y, R.scale_y, R.off_y);
+        const double fy0 = floor(sy);
+        const float fy = (float)(sy - fy0);
         const int ya = min(max((int)fy0, 0), R.src_h - 1), yb = min(max((int)fy0 + 1, 0), R.src_h - 1);
         const uint8_t *ra = src + (size_t)ya * R.src_pitch, *rb = src + (size_t)yb * R.src_pitch;
 #pragma unroll
         for (int j = 0; j < 4; j++) {
-            const float sx = fmaf((float)(x0 + j), R.scale_x, R.off_x);
-            const float fx0 = floorf(sx);
-            const float fx = sx - fx0;
+            const double sx = fma((double)(x0 + j), R.scale_x, R.off_x);
+            const double fx0 = floor(sx);
+            const float fx = (float)(sx - fx0);
             const int xa = min(max((int)fx0, 0), R.src_w - 1) * 3;
             const int xb = min(max((int)fx0 + 1, 0), R.src_w - 1) * 3;
 #pragma unroll

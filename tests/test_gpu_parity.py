@@ -1,0 +1,229 @@
+"""Parity of the GPU path (through the C ABI) with the CPU oracle, element by element:
+coefficients bit-exact, RGB within 1 LSB and >= 99.9 % exact, tensor within 0.02."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from helpers import MEAN, STD, check_against_oracle, oracle_batch, run_gpu
+from oracle import MODE_420, MODE_444, MODE_GRAY
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def prep():
+    import paper_2411_19114_amd as p
+    return p
+
+
+@pytest.fixture(scope="module")
+def pp(prep):
+    h = prep.Preprocessor(device=0, max_batch=64, max_width=2048, max_height=1200,
+                          max_bitstream_bytes=48 << 20, max_total_pixels=24 << 20)
+    yield h
+    h.close()
+
+
+def _img(seed, w, h, sigma=12.0):
+    rng = np.random.default_rng(seed)
+    return synth.gradient_noise_image(rng, w, h, sigma)
+
+
+@pytest.mark.parametrize("config,n,dtype", [(1, 8, "f32"), (2, 12, "f16"), (5, 12, "f16")])
+def test_workload_samples(pp, config, n, dtype):
+    r = synth.CONFIGS[config]
+    streams = synth.make_batch(config, n)
+    check_against_oracle(pp, streams, r["resize_short"], r["crop"], r["crop"], dtype)
+
+
+def test_workload_4_full_hd(pp):
+    r = synth.CONFIGS[4]
+    check_against_oracle(pp, synth.make_batch(4, 2), r["resize_short"], r["crop"], r["crop"], "f16")
+
+
+@pytest.mark.parametrize("mode", [MODE_444, MODE_420, MODE_GRAY])
+def test_odd_sizes_and_restart_intervals(pp, mode):
+    streams = []
+    for k, (w, h) in enumerate([(1, 1), (7, 9), (17, 33), (64, 48), (300, 251)]):
+        rgb = _img(200 + k + mode, w, h)
+        cols = -(-w // (16 if mode == MODE_420 else 8))
+        for dri in (0, 1, cols, 8):
+            streams.append(oracle.encode(rgb, 88, mode, dri, table_mode=k % 2)[0])
+    # no resize, 1x1 crop fits every image; intermediates carry the check
+    check_against_oracle(pp, streams, 0, 1, 1, "f32")
+
+
+def test_upscaling_small_images(pp):
+    streams = [oracle.encode(_img(300 + k, w, h), 90, MODE_420, 0)[0]
+               for k, (w, h) in enumerate([(1, 1), (7, 9), (40, 23), (23, 40)])]
+    check_against_oracle(pp, streams, 64, 48, 56, "f32")
+
+
+def test_extreme_coefficients_and_byte_stuffing(pp):
+    rng = np.random.default_rng(7)
+    w, h = 48, 32
+    nb = 3 * 2 * 6
+    coef = np.zeros((nb, 64), dtype=np.int16)
+    coef[:, 0] = rng.integers(-1000, 1000, size=nb)
+    coef[0, 1:] = 1023
+    coef[1, 1:] = -1023
+    coef[2, 63] = -1
+    coef[3, 17], coef[3, 50] = 5, -300
+    coef[4, 1:] = rng.integers(-1023, 1024, size=63)
+    coef[5:, 1:] = rng.integers(-3, 4, size=(nb - 5, 63))
+    q = np.ones(64, dtype=np.uint16)
+    streams = [oracle.write_jpeg(coef, w, h, MODE_420, q, q, dri=dri, table_mode=tm)
+               for dri in (0, 1, 2) for tm in (0, 1)]
+    assert all(b"\xff\x00" in s for s in streams)
+    status, _ = run_gpu(pp, streams, 0, 8, 8, "f32")
+    assert status == [0] * len(streams)
+    for i in range(len(streams)):
+        assert np.array_equal(pp.debug_last_coefficients(i, nb), coef)
+
+
+def test_all_eob_and_dc_only_blocks(pp):
+    # shortest possible blocks: hundreds of blocks per decoder subsequence
+    w, h = 512, 256
+    nb = (w // 8) * (h // 8)
+    rng = np.random.default_rng(8)
+    q = np.full(64, 4, dtype=np.uint16)
+    coef = np.zeros((nb, 64), dtype=np.int16)
+    coef[:, 0] = np.cumsum(rng.integers(-1, 2, size=nb))  # tiny DC differences, many exact ties
+    streams = [oracle.write_jpeg(coef, w, h, MODE_GRAY, q, q, dri=dri, table_mode=0) for dri in (0, 7)]
+    check_against_oracle(pp, streams, 0, 16, 16, "f32")
+
+
+def test_same_image_with_and_without_restart_markers(pp):
+    rgb = _img(400, 320, 240)
+    streams = [oracle.encode(rgb, 92, MODE_420, dri)[0] for dri in (0, 1, 20, 7)]
+    status, got = run_gpu(pp, streams, 128, 112, 112, "f32")
+    assert status == [0] * 4
+    ref = oracle.encode(rgb, 92, MODE_420, 0)[1]
+    for i in range(4):
+        assert np.array_equal(pp.debug_last_coefficients(i, ref.shape[0]), ref)
+    for i in range(1, 4):
+        assert np.array_equal(got[i], got[0])
+
+
+def test_long_stream_without_restart_markers_spans_many_chunks(pp):
+    rgb = _img(401, 1024, 768, sigma=20.0)
+    streams = [oracle.encode(rgb, 95, MODE_444, 0)[0], oracle.encode(rgb, 95, MODE_420, 0)[0]]
+    assert len(streams[0]) > 300000
+    check_against_oracle(pp, streams, 256, 224, 224, "f16")
+
+
+def test_batch_order_and_batch_size_do_not_matter(pp):
+    streams = synth.make_batch(2, 6)
+    _, a = run_gpu(pp, streams, 256, 224, 224, "f32")
+    perm = [3, 0, 5, 1, 4, 2]
+    _, b = run_gpu(pp, [streams[i] for i in perm], 256, 224, 224, "f32")
+    for j, i in enumerate(perm):
+        assert np.array_equal(b[j], a[i])
+    _, c = run_gpu(pp, [streams[4]], 256, 224, 224, "f32")
+    assert np.array_equal(c[0], a[4])
+    # two runs give identical bits
+    _, a2 = run_gpu(pp, streams, 256, 224, 224, "f32")
+    assert np.array_equal(a, a2)
+
+
+def test_resident_input_equals_host_input(pp):
+    streams = synth.make_batch(2, 5) + synth.make_batch(5, 3)
+    _, a = run_gpu(pp, streams, 256, 224, 224, "f16")
+    got = check_against_oracle(pp, streams, 256, 224, 224, "f16", resident=True)
+    assert np.array_equal(a, got)
+
+
+def test_corrupt_and_unsupported_images_do_not_poison_the_batch(pp, prep):
+    good = synth.make_batch(1, 3)
+    cut = good[1][:len(good[1]) // 2]                       # truncated: no EOI
+    prog = good[2].replace(b"\xff\xc0", b"\xff\xc2", 1)     # progressive frame header
+    sos = good[0].index(b"\xff\xda")
+    i = good[0].index(b"\xff\xd1", sos)
+    i2 = good[2].index(b"\xff\xd3", good[2].index(b"\xff\xda"))
+    wrong_rst = good[0][:i + 1] + b"\xd5" + good[0][i + 2:]  # RST5 where RST1 belongs: the index is not validated
+    dropped = good[2][:i2] + good[2][i2 + 2:]               # a restart marker removed
+    garbage = good[0][:sos + 40] + bytes(200) + good[0][sos + 240:]  # zeros inside the scan
+    streams = [good[0], cut, good[1], prog, dropped, good[2], garbage, wrong_rst]
+    status, got = run_gpu(pp, streams, 256, 224, 224, "f32")
+    assert status[0] == 0 and status[2] == 0 and status[5] == 0
+    assert status[1] == prep.E_CORRUPT and status[3] == prep.E_UNSUPPORTED
+    assert status[4] == prep.E_CORRUPT and status[6] == prep.E_CORRUPT
+    for i in (1, 3, 4, 6):
+        assert (got[i] == 0).all()
+    ref = oracle_batch(good, 256, 224, 224)
+    for j, i in ((0, 0), (2, 1), (5, 2)):
+        assert np.abs(got[j] - ref[i][3]).max() <= 0.02
+    assert status[7] == 0 and np.array_equal(got[7], got[0])
+
+
+def test_argument_errors(pp, prep):
+    import torch
+    from paper_2411_19114_amd.binding import make_params
+    streams = synth.make_batch(1, 2)
+    blob, offsets = synth.pack(streams)
+    out = torch.zeros((2, 3, 224, 224), device="cuda:0")
+    ok = make_params(256, 224, 224, "f32", MEAN, STD)
+    pp.decode_resize_batch(blob, offsets[:1], ok, out.data_ptr())      # n = 0 is a no-op
+    with pytest.raises(prep.PrepError) as e:
+        pp.decode_resize_batch(blob, offsets, make_params(256, 224, 224, "f32", MEAN, (0.2, 0.0, 0.2)),
+                               out.data_ptr())
+    assert e.value.code == prep.E_INVALID_ARG
+    with pytest.raises(prep.PrepError) as e:
+        pp.decode_resize_batch(blob, offsets, make_params(256, 0, 224, "f32", MEAN, STD), out.data_ptr())
+    assert e.value.code == prep.E_INVALID_ARG
+    small = prep.Preprocessor(device=0, max_batch=1, max_width=64, max_height=64, max_bitstream_bytes=1 << 20)
+    with pytest.raises(prep.PrepError) as e:
+        small.decode_resize_batch(blob, offsets, ok, out.data_ptr())
+    assert e.value.code == prep.E_TOO_LARGE
+    with pytest.raises(prep.PrepError) as e:
+        small.decode_resize_batch(blob, offsets[:2], ok, out.data_ptr())   # 256x256 image > 64x64
+    assert e.value.code == prep.E_TOO_LARGE
+    small.close()
+    # a crop that does not fit one image fails that image only
+    tiny = oracle.encode(_img(500, 40, 30), 90, MODE_444, 0)[0]
+    status, got = run_gpu(pp, [streams[0], tiny], 0, 224, 224, "f32")
+    assert status == [0, prep.E_UNSUPPORTED] and (got[1] == 0).all()
+
+
+# ---- single stages, each fed with the oracle's own intermediate ---------------------------
+
+def test_resize_stage_alone_on_oracle_rgb(pp):
+    import torch
+    from paper_2411_19114_amd.binding import make_params
+    rng = np.random.default_rng(9)
+    shapes = [(640, 480), (300, 500), (33, 77), (256, 256), (1920, 1080)]
+    imgs = [rng.integers(0, 256, size=(h, w, 3), dtype=np.uint8) for w, h in shapes]
+    for rs, ch, cw, dt in ((256, 224, 224, "f32"), (32, 32, 30, "f16"), (384, 384, 384, "f16")):
+        flat = np.concatenate([im.reshape(-1) for im in imgs])
+        offs = np.cumsum([0] + [im.size for im in imgs[:-1]]).astype(np.uint64)
+        dev = torch.from_numpy(flat).to("cuda:0")
+        tdt = torch.float16 if dt == "f16" else torch.float32
+        out = torch.full((len(imgs), 3, ch, cw), 777.0, dtype=tdt, device="cuda:0")
+        pp.resize_normalize(dev.data_ptr(), offs, [s[0] for s in shapes], [s[1] for s in shapes],
+                            [s[0] * 3 for s in shapes], make_params(rs, ch, cw, dt, MEAN, STD),
+                            out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        got = out.float().cpu().numpy().astype(np.float64)
+        tol = 0.02 if dt == "f16" else 1e-4   # fp32 path: only interpolation rounding remains
+        for i, im in enumerate(imgs):
+            ref = oracle.preprocess(im, rs, ch, cw, MEAN, STD)
+            assert np.abs(got[i] - ref).max() <= tol
+
+
+def test_reconstruct_stage_alone_on_oracle_coefficients(pp):
+    import torch
+    from paper_2411_19114_amd.binding import make_params
+    streams = synth.make_batch(5, 6)
+    ref = oracle_batch(streams, 256, 224, 224)
+    blob, offsets = synth.pack(streams)
+    coef = np.concatenate([r[0].reshape(-1) for r in ref])
+    out = torch.zeros((len(streams), 3, 224, 224), device="cuda:0")
+    pp.reconstruct_from_coefficients(blob, offsets, coef, make_params(256, 224, 224, "f32", MEAN, STD),
+                                     out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    assert pp.get_status(len(streams)) == [0] * len(streams)
+    got = out.cpu().numpy().astype(np.float64)
+    for i, (_, rgb, info, ten) in enumerate(ref):
+        d = np.abs(pp.debug_last_rgb(i, info.height, info.width).astype(int) - rgb.astype(int))
+        assert d.max() <= 1 and (d == 0).mean() >= 0.999
+        assert np.abs(got[i] - ten).max() <= 0.02
