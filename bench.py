@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Throughput of the whole JPEG -> normalized tensor path on one MI355X.
+
+One step = one call of prep_decode_resize_batch_resident on one batch of a synthetic
+workload (default: workload 2, 256 images of 300..640 x 250..500 pixels, 4:2:0, quality
+90, restart interval 8 MCUs) whose bitstreams already lie in HBM: host marker parsing,
+restart-marker scan, entropy decode, RGB reconstruction and resize/crop/normalize.
+Prints ONE JSON line with images/s, the roofline of the dominant kernel, the other
+stages, and the CPU oracle timed on the host cores of the same machine.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "images/sec JPEG→224² normalized tensor on 1 MI355X; % HBM/VALU roofline"
+
+# chip figures used for the rooflines
+HBM_PEAK_GBS = 8000.0
+# plain 32-bit integer vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
+INT_ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# essential integer operations of decoding one Huffman symbol by the serial definition
+# (peek, table lookup, split length/symbol, two buffer shifts, position update, receive
+#  bits, two for sign extension, run/zig-zag update, end-of-block test, address, store,
+#  refill share): see DESIGN.md, "entropy decode roofline"
+OPS_PER_SYMBOL = 16
+
+WORKLOAD_NAMES = {
+    1: "workload 1: 64 x 256x256 4:2:0 q85, restart per MCU row, crop 224 fp32",
+    2: "workload 2: 256 x U[300,640]xU[250,500] 4:2:0 q90, restart interval 8 MCUs, resize 256 crop 224 fp16",
+    4: "workload 4: 64 x 1920x1080 4:2:0 q95, restart per MCU row, resize 384 crop 384 fp16",
+    5: "workload 5: 512 x 256x256 mixed 4:4:4/4:2:0/gray q50-95, no restart markers, crop 224 fp16",
+}
+
+
+def cpu_baseline(streams, pr, max_seconds=60.0):
+    """The oracle as it stands, on the host cores, over a bounded sample of the batch."""
+    import oracle
+    cores = min(16, len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count())
+
+    def one(s):
+        oracle.decode_preprocess(s, pr["resize_short"], pr["crop_h"], pr["crop_w"], pr["mean"], pr["std"])
+        return oracle.jpeg_info(s)
+
+    # probe one image to bound the sample to roughly 20 s of CPU work
+    t0 = time.perf_counter()
+    one(streams[0])
+    per = time.perf_counter() - t0
+    n = int(max(cores, min(len(streams), 20.0 / max(per, 1e-4))))
+    n = min(n, len(streams))
+    sample = streams[:n]
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(cores) as ex:
+        list(ex.map(one, sample))
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "images/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {n} images of the batch, one image per task, {cores} threads, "
+                      f"{dt:.2f} s wall"}
+
+
+def symbols_in(streams, limit=64):
+    """Coded symbols per compressed byte, from the oracle's decode statistics on a sample
+    (part of the cpu_baseline leg); used to scale the entropy decoder's algorithmic work."""
+    import oracle
+    sym = byt = 0
+    for s in streams[:limit]:
+        _, _, info = oracle.decode(s, want_coef=True, want_rgb=False)
+        sym += info.symbols
+        byt += info.entropy_bytes
+    return sym / max(byt, 1)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--host-input", action="store_true",
+                    help="time prep_decode_resize_batch (bitstreams start in host memory)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (images are independent; a second GPU "
+              "would take a share of the batch with no exchange step); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2411_19114_amd as prep
+    import synth
+    from paper_2411_19114_amd.binding import make_params
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    if not os.path.exists(prep.lib_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+
+    cfg = args.workload
+    t0 = time.perf_counter()
+    streams = synth.make_batch(cfg)
+    gen_s = time.perf_counter() - t0
+    n = len(streams)
+    blob, offsets = synth.pack(streams)
+    pr = synth.params_of(cfg)
+    params = make_params(pr["resize_short"], pr["crop_h"], pr["crop_w"], pr["out_dtype"], pr["mean"], pr["std"])
+    infos = prep.parse_headers(blob, offsets)
+    assert all(i.status == 0 for i in infos)
+    max_w, max_h = max(i.width for i in infos), max(i.height for i in infos)
+    pixels = sum(i.width * i.height for i in infos)
+    entropy_bytes = sum(i.entropy_bytes for i in infos)
+    blocks = sum(i.mcu_cols * i.mcu_rows * i.blocks_per_mcu for i in infos)
+
+    dev = torch.device("cuda:0")
+    pp = prep.Preprocessor(device=0, max_batch=n, max_width=max_w, max_height=max_h,
+                           max_bitstream_bytes=int(offsets[-1]), max_total_pixels=pixels)
+    dt = torch.float16 if pr["out_dtype"] == "f16" else torch.float32
+    out = torch.empty((n, 3, pr["crop_h"], pr["crop_w"]), dtype=dt, device=dev)
+    dev_bits = torch.from_numpy(blob).to(dev)
+    stream = torch.cuda.Stream(device=dev)
+    sp = stream.cuda_stream
+
+    def step():
+        if args.host_input:
+            pp.decode_resize_batch(blob, offsets, params, out.data_ptr(), sp)
+        else:
+            pp.decode_resize_batch_resident(blob, dev_bits.data_ptr(), offsets, params, out.data_ptr(), sp)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    status = pp.get_status(n)
+    assert status == [0] * n, "a workload image failed to decode"
+
+    pp.set_timing(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    k = min(args.steps, 256)
+    stage = np.array([pp.stage_ms(i) for i in range(k)]).mean(axis=0)  # ms: scan, decode, recon, resize
+    pp.set_timing(False)
+
+    ms_per_step = wall / args.steps * 1e3
+    value = n * args.steps / wall
+
+    # ---- algorithmic work per launch ------------------------------------------------------
+    esz = 2 if pr["out_dtype"] == "f16" else 4
+    out_bytes = n * 3 * pr["crop_h"] * pr["crop_w"] * esz
+    # source footprint of the crop: the window of each image that the outputs map back to
+    foot = 0
+    for i in infos:
+        s = pr["resize_short"]
+        if s:
+            ow, oh = (s, s * i.height // i.width) if i.width <= i.height else (s * i.width // i.height, s)
+        else:
+            ow, oh = i.width, i.height
+        foot += int(round(pr["crop_w"] * i.width / ow)) * int(round(pr["crop_h"] * i.height / oh)) * 3
+    padded_rgb = sum(i.mcu_cols * i.mcu_rows * (256 if i.sampling == 1 else 64) * 3 for i in infos)
+    work = {
+        "scan": ("hbm", entropy_bytes + blocks * 128),          # read stream once + clear coefficients
+        "reconstruct": ("hbm", blocks * 128 + padded_rgb),       # coefficients in, RGB out
+        "resize": ("hbm", foot + out_bytes),                     # crop footprint in, tensor out
+    }
+    cpu = None
+    sym_per_byte = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(streams, pr)
+        sym_per_byte = symbols_in(streams)
+    stages = []
+    names = ["scan", "decode", "reconstruct", "resize"]
+    kernels = ["scan_restart_markers (+ clearing coefficients)", "decode_entropy", "reconstruct_rgb",
+               "resize_crop_normalize"]
+    for j, name in enumerate(names):
+        ms = float(stage[j])
+        if name == "decode":
+            if sym_per_byte is None:
+                stages.append({"stage": name, "kernel": kernels[j], "ms": ms, "bound": "alu"})
+                continue
+            ops = sym_per_byte * entropy_bytes * OPS_PER_SYMBOL
+            ach = ops / (ms * 1e-3) / 1e12
+            stages.append({"stage": name, "kernel": kernels[j], "ms": ms, "bound": "alu",
+                           "achieved": ach, "peak": INT_ALU_PEAK_TOPS, "unit": "TOP/s",
+                           "frac": ach / INT_ALU_PEAK_TOPS, "traffic": None,
+                           "symbols_per_launch": sym_per_byte * entropy_bytes,
+                           "compressed_GB_per_s": entropy_bytes / (ms * 1e-3) / 1e9})
+        else:
+            b = work[name][1]
+            ach = b / (ms * 1e-3) / 1e9
+            stages.append({"stage": name, "kernel": kernels[j], "ms": ms, "bound": "hbm",
+                           "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                           "algorithmic_bytes": b})
+    dominant = max(stages, key=lambda s: s["ms"])
+    roofline = {k: dominant.get(k) for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
+    roofline["kernel"] = dominant["kernel"]
+    roofline["avg_launch_ms"] = dominant["ms"]
+
+    result = {
+        "metric": METRIC, "value": value, "unit": "images/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32 entropy decode, f64 IDCT, f32 resize -> " + pr["out_dtype"] + " output",
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[cfg], "batch": n,
+                   "input": "host memory" if args.host_input else "resident in HBM",
+                   "compressed_bytes": int(offsets[-1]), "pixels": int(pixels),
+                   "sha256": synth.sha256_of(streams), "input_generation_s": round(gen_s, 2)},
+        "roofline": roofline,
+        "stages": stages,
+        "gpu_ms_per_step": float(stage.sum()),
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result))
+    pp.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -186,12 +186,15 @@ int64_t prep_debug_last_coefficients(prep_handle *h, int32_t image, int16_t *hos
  * packed.  Returns the number of bytes written or a negative code.            */
 int64_t prep_debug_last_rgb(prep_handle *h, int32_t image, uint8_t *host_out_hwc, uint64_t cap);
 
-/* Duration in milliseconds of each GPU stage of the handle's last call, taken
- * with events on the call's stream (synchronises): [0] restart-marker scan,
- * [1] entropy decode, [2] reconstruct RGB, [3] resize/crop/normalize.
- * Only filled when the handle was told to time stages (prep_set_timing).      */
-int prep_last_stage_ms(prep_handle *h, float ms[4]);
+/* Stage timing.  While enabled, every batch call brackets its GPU stages with
+ * events on the call's stream (calls that enqueue no decode are not counted).
+ * prep_stage_ms waits for the call made `calls_back` timed calls ago (0 = the
+ * last one; at most the last 256 are kept) and returns the milliseconds of
+ * [0] restart-marker scan (with clearing the coefficient workspace), [1] entropy
+ * decode, [2] reconstruct RGB, [3] resize/crop/normalize.  prep_set_timing
+ * forgets earlier timings.                                                    */
 int prep_set_timing(prep_handle *h, int32_t enabled);
+int prep_stage_ms(prep_handle *h, int32_t calls_back, float ms[4]);
 
 #ifdef __cplusplus
 }

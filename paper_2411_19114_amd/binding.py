@@ -63,7 +63,7 @@ EXPORTS = [
     "prep_create", "prep_destroy", "prep_decode_resize_batch", "prep_decode_resize_batch_resident",
     "prep_get_status", "prep_strerror", "prep_parse_headers", "prep_interval_descriptors",
     "prep_resize_normalize", "prep_reconstruct_from_coefficients", "prep_debug_last_coefficients",
-    "prep_debug_last_rgb", "prep_last_stage_ms", "prep_set_timing",
+    "prep_debug_last_rgb", "prep_stage_ms", "prep_set_timing",
 ]
 
 _lib = None
@@ -104,7 +104,7 @@ def lib():
         L.prep_debug_last_coefficients.restype = C.c_int64
         L.prep_debug_last_rgb.argtypes = [vp, C.c_int32, vp, C.c_uint64]
         L.prep_debug_last_rgb.restype = C.c_int64
-        L.prep_last_stage_ms.argtypes = [vp, C.POINTER(C.c_float)]
+        L.prep_stage_ms.argtypes = [vp, C.c_int32, C.POINTER(C.c_float)]
         L.prep_set_timing.argtypes = [vp, C.c_int32]
         _lib = L
     return _lib
@@ -241,7 +241,7 @@ class Preprocessor:
     def set_timing(self, enabled):
         _check(lib().prep_set_timing(self._h, int(bool(enabled))), "prep_set_timing")
 
-    def last_stage_ms(self):
+    def stage_ms(self, calls_back=0):
         ms = (C.c_float * 4)()
-        _check(lib().prep_last_stage_ms(self._h, ms), "prep_last_stage_ms")
+        _check(lib().prep_stage_ms(self._h, calls_back, ms), "prep_stage_ms")
         return list(ms)

@@ -21,6 +21,7 @@ namespace {
 constexpr int kSlots = 2;            // pinned staging is double buffered
 constexpr size_t kBitsPad = 256;     // readable slack after the last file
 constexpr size_t kRgbAlign = 256;
+constexpr int kTimedCalls = 256;     // calls whose stage events are kept
 
 struct Slot {
     uint8_t *h_bits = nullptr;
@@ -52,8 +53,10 @@ struct prep_handle {
     uint32_t *d_win_count = nullptr, *d_win_first = nullptr;
     Slot slot[kSlots];
     int next_slot = 0;
-    hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
-    bool timing = false, timed_last = false;
+    // stage timing: one set of 5 events per call, kept for the last kTimedCalls calls
+    std::vector<hipEvent_t> ev;
+    bool timing = false;
+    uint64_t timed_calls = 0;
     // last call
     int32_t last_n = 0;
     hipStream_t last_stream = nullptr;
@@ -226,31 +229,32 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
     HIP_TRY(hipMemcpyAsync(h->d_recs, s->h_recs, sizeof(ImageRec) * (size_t)n, hipMemcpyHostToDevice, stream));
     HIP_TRY(hipMemcpyAsync(h->d_rr, s->h_rr, sizeof(ResizeRec) * (size_t)n, hipMemcpyHostToDevice, stream));
     const bool timing = h->timing;
-    if (timing) HIP_TRY(hipEventRecord(h->ev[0], stream));
+    hipEvent_t *ev = timing ? &h->ev[(size_t)(h->timed_calls % kTimedCalls) * 5] : nullptr;
+    if (timing) HIP_TRY(hipEventRecord(ev[0], stream));
     if (coef_host) {
         for (int32_t i = 0; i < n; i++) s->h_status[i] = h->recs[(size_t)i].status;
         HIP_TRY(hipMemcpyAsync(h->d_status, s->h_status, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice, stream));
         if (P.n_blocks)
             HIP_TRY(hipMemcpyAsync(h->d_coef, coef_host, P.n_blocks * 128, hipMemcpyHostToDevice, stream));
-        if (timing) { HIP_TRY(hipEventRecord(h->ev[1], stream)); HIP_TRY(hipEventRecord(h->ev[2], stream)); }
+        if (timing) { HIP_TRY(hipEventRecord(ev[1], stream)); HIP_TRY(hipEventRecord(ev[2], stream)); }
     } else {
         if (P.n_blocks) HIP_TRY(hipMemsetAsync(h->d_coef, 0, P.n_blocks * 128, stream));
         launch_scan_restart_markers(d_bits, h->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
                                     h->d_status, stream);
-        if (timing) HIP_TRY(hipEventRecord(h->ev[1], stream));
+        if (timing) HIP_TRY(hipEventRecord(ev[1], stream));
         launch_decode_entropy(d_bits, h->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
                               h->d_coef, h->d_status, stream);
-        if (timing) HIP_TRY(hipEventRecord(h->ev[2], stream));
+        if (timing) HIP_TRY(hipEventRecord(ev[2], stream));
     }
     launch_reconstruct(d_bits, h->d_recs, n, P.n_groups, h->d_coef, h->d_rgb, stream);
-    if (timing) HIP_TRY(hipEventRecord(h->ev[3], stream));
+    if (timing) HIP_TRY(hipEventRecord(ev[3], stream));
     launch_resize_normalize(h->d_rgb, h->d_rr, h->d_status, n, params->crop_h, params->crop_w,
                             params->out_dtype, params->mean, params->std, out, stream);
-    if (timing) HIP_TRY(hipEventRecord(h->ev[4], stream));
+    if (timing) HIP_TRY(hipEventRecord(ev[4], stream));
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(s->done, stream));
     s->pending = true;
-    h->timed_last = timing;
+    if (timing) h->timed_calls++;
     h->last_n = n;
     h->last_stream = stream;
     return PREP_OK;
@@ -305,7 +309,8 @@ int prep_create(prep_handle **out, const prep_config *cfg)
         ok = ok && hipHostMalloc((void **)&s.h_status, sizeof(int32_t) * n, hipHostMallocDefault) == hipSuccess;
         ok = ok && hipEventCreateWithFlags(&s.done, hipEventDisableTiming) == hipSuccess;
     }
-    for (int i = 0; ok && i < 5; i++) ok = hipEventCreate(&h->ev[i]) == hipSuccess;
+    h->ev.assign((size_t)kTimedCalls * 5, nullptr);
+    for (size_t i = 0; ok && i < h->ev.size(); i++) ok = hipEventCreate(&h->ev[i]) == hipSuccess;
     if (ok) ok = hipMemset(h->d_status, 0, sizeof(int32_t) * n) == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
@@ -337,8 +342,8 @@ int prep_destroy(prep_handle *h)
         if (s.h_status) (void)hipHostFree(s.h_status);
         if (s.done) (void)hipEventDestroy(s.done);
     }
-    for (int i = 0; i < 5; i++)
-        if (h->ev[i]) (void)hipEventDestroy(h->ev[i]);
+    for (hipEvent_t e : h->ev)
+        if (e) (void)hipEventDestroy(e);
     (void)hipGetLastError();
     delete h;
     return PREP_OK;
@@ -491,15 +496,19 @@ int prep_set_timing(prep_handle *h, int32_t enabled)
 {
     if (!h) return PREP_E_INVALID_ARG;
     h->timing = enabled != 0;
+    h->timed_calls = 0;
     return PREP_OK;
 }
 
-int prep_last_stage_ms(prep_handle *h, float ms[4])
+int prep_stage_ms(prep_handle *h, int32_t calls_back, float ms[4])
 {
-    if (!h || !ms || !h->timed_last || h->last_n == 0) return PREP_E_INVALID_ARG;
+    if (!h || !ms || calls_back < 0 || calls_back >= kTimedCalls ||
+        (uint64_t)calls_back >= h->timed_calls)
+        return PREP_E_INVALID_ARG;
+    const hipEvent_t *ev = &h->ev[(size_t)((h->timed_calls - 1 - (uint64_t)calls_back) % kTimedCalls) * 5];
     HIP_TRY(hipSetDevice(h->cfg.device));
-    HIP_TRY(hipEventSynchronize(h->ev[4]));
-    for (int i = 0; i < 4; i++) HIP_TRY(hipEventElapsedTime(&ms[i], h->ev[i], h->ev[i + 1]));
+    HIP_TRY(hipEventSynchronize(ev[4]));
+    for (int i = 0; i < 4; i++) HIP_TRY(hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]));
     return PREP_OK;
 }
 
