@@ -2,24 +2,24 @@
 //
 // The first half of the "Decode" functional unit (PREBA section 4.2, Table 1).
 // The FPGA decodes one stream serially per compute unit; here one workgroup owns
-// a run of whole restart intervals (T.81 E.2.4) of one image and decodes it with
-// all of its lanes by self-synchronisation:
+// a run of whole restart intervals (T.81 E.2.4) of one image:
 //
 //   1. scan_restart_markers counts the RSTn markers in fixed windows of every
 //      image's entropy-coded segment, so that a workgroup starting at the first
 //      marker of its window knows which restart interval (hence which MCU) it
 //      starts at, without any serial pass over the stream.
 //   2. decode_entropy stages a chunk of the stream in LDS with byte stuffing
-//      (FF 00) and markers removed, gives every lane one fixed-size subsequence,
-//      and lets each lane decode from a guessed state (code-word boundary, block
-//      0 of an MCU, DC coefficient).  Lane j then re-decodes from the end state
-//      lane j-1 reached, until no end state changes.  Lane 0 starts from a known
-//      state, so the fixed point is the sequential decode, exactly.  Restart
-//      boundaries inside the chunk are hard synchronisation points.
-//   3. A prefix sum of the blocks each lane completed gives every lane its
-//      absolute block index; a last pass decodes once more from the now-true
-//      start states and writes the coefficients; DC differences are turned into
-//      absolute values with a segmented scan over the lanes.
+//      (FF 00) and markers removed and the interval starts marked, then decodes
+//      it in one of two ways:
+//      - short intervals: one lane per restart interval, a single sequential pass
+//        that writes coefficients directly (start state and MCU index are known);
+//      - long intervals or none: every lane takes a fixed-size subsequence and
+//        decodes from a guessed state (code-word boundary, block 0 of an MCU, DC
+//        coefficient); lane j then re-decodes from the end state lane j-1 reached
+//        until no end state changes.  Lane 0 starts from a known state, so the
+//        fixed point is the sequential decode, exactly.  A prefix sum of completed
+//        blocks gives every lane its block index, a last pass writes coefficients,
+//        and a segmented scan turns DC differences into absolute values.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -34,27 +34,45 @@ namespace {
 constexpr int kT = kDecodeThreads;
 constexpr int kCleanWords = kChunkRaw / 4 + 8;      // destuffed stream + zero tail
 constexpr int kMaskWords = kChunkRaw / 32 + 2;      // one bit per clean byte
+constexpr int kSubEntries = 512;                    // second-level lookup entries per table
+constexpr int kMaxBoundaries = 1024;                // listed interval starts per chunk
+constexpr uint32_t kShortInterval = 1024;           // mean clean bytes up to which a lane takes a whole interval
 constexpr uint32_t kNoMarker = 0xFFFFFFFFu;
 constexpr uint32_t kSubBits = kSubseqBytes * 8;
-static_assert(kSubseqBytes == 64, "one 64-bit keep mask per lane");
+static_assert(kSubseqBytes == 64 && kT == 256, "one 64-bit keep mask per lane, 256 HUFFVAL bytes");
 
-struct HuffTable {
-    uint16_t lut[1 << kLutBits];   // (length << 8) | symbol for codes up to kLutBits bits, else 0
-    int32_t first[17];             // first code of each length
-    int32_t count[17];             // BITS
-    int32_t valptr[17];            // index of the first symbol of each length
-    uint8_t huffval[256];
+// Lookup entry of a Huffman code (16 bits):
+//   bit 15     valid
+//   bit 14     a coefficient is stored (DC, or AC with a non-zero size)
+//   bits 13..8 zig-zag advance - 1 (DC 1, AC run+1, ZRL 16, EOB 64)
+//   bits 7..4  number of appended bits
+//   bits 3..0  code length - 1
+// A first-level entry that is not valid is 0 (no such code), kUseLoop, or a
+// reference to a second-level block: bits 14..11 = extra index bits (1..6),
+// bits 10..0 = offset into the table's second-level pool.
+constexpr uint32_t kValid = 0x8000u, kStore = 0x4000u, kUseLoop = 0x7FFFu;
+constexpr uint32_t kInvalidEntry = kValid | (63u << 8) | 15u;  // 16 bits, ends the block
+
+struct HuffTables {
+    uint16_t lut[4 << kLutBits];     // first level, indexed by the next kLutBits bits
+    uint16_t sub[4 * kSubEntries];   // second level
+    int32_t first[4][17];            // first code of each length
+    int32_t count[4][17];            // BITS
+    int32_t valptr[4][17];           // index of the first symbol of each length
+    uint8_t huffval[4][256];
+    uint32_t sub_used[4];
 };
 
 struct DecodeShared {
-    uint32_t clean[kCleanWords];   // big-endian packed: bit 31 of a word is the earliest bit
-    uint32_t bmask[kMaskWords];    // bit q set: a restart interval begins at clean byte q
+    uint32_t clean[kCleanWords];     // big-endian packed: bit 31 of a word is the earliest bit
+    uint32_t bmask[kMaskWords];      // bit q set: a restart interval begins at clean byte q
     uint32_t next_boundary[kT + 1];  // first interval start at or after the lane's subsequence
-    HuffTable tab[4];              // DC luma, AC luma, DC chroma, AC chroma
-    unsigned long long keep[kT];   // which of the lane's 64 raw bytes survived destuffing
-    uint32_t keep_off[kT + 1];     // clean offset of the lane's first surviving byte
-    uint32_t state[kT];            // end state of every subsequence
-    uint32_t scan_a[kT / 64 + 1];  // per-wave totals for workgroup scans
+    uint16_t bpos[kMaxBoundaries];   // interval starts of the chunk in order (clean byte offsets)
+    HuffTables tab;                  // DC luma, AC luma, DC chroma, AC chroma
+    unsigned long long keep[kT];     // which of the lane's 64 raw bytes survived destuffing
+    uint32_t keep_off[kT + 1];       // clean offset of the lane's first surviving byte
+    uint32_t state[kT];              // end state of every subsequence
+    uint32_t scan_a[kT / 64 + 1];    // per-wave totals for workgroup scans
     int32_t dc_val[3][kT / 64 + 1];
     int32_t dc_flag[3][kT / 64 + 1];
     uint32_t bcast[8];
@@ -117,7 +135,6 @@ __device__ inline int32_t block_seg_excl_scan(int32_t v, int32_t f, int32_t carr
     __syncthreads();
     if (lane == 63) { wave_val[wave] = iv; wave_flag[wave] = ifl; }
     __syncthreads();
-    // carry into this wave
     int32_t cv = carry_in, all_v = carry_in;
 #pragma unroll
     for (int w = 0; w < kT / 64; w++) {
@@ -127,11 +144,120 @@ __device__ inline int32_t block_seg_excl_scan(int32_t v, int32_t f, int32_t carr
         all_v = nv;
     }
     *carry_out = all_v;
-    // exclusive value for this lane: inclusive of the previous lane
     int32_t pv = __shfl_up(iv, 1, 64);
     int32_t pf = __shfl_up(ifl, 1, 64);
     if (lane == 0) return cv;
     return pf ? pv : cv + pv;
+}
+
+// ---- Huffman tables (T.81 Annex C) --------------------------------------------
+
+// canonical search among the code lengths lo..hi for the code that starts `peek16`
+__device__ inline bool canonical_lookup(const HuffTables &T, int t, uint32_t peek16, int lo, int hi,
+                                        uint32_t *len, uint32_t *sym)
+{
+    for (int l = lo; l <= hi; l++) {
+        const int32_t c = (int32_t)(peek16 >> (16 - l)) - T.first[t][l];
+        if (c >= 0 && c < T.count[t][l]) {
+            *len = (uint32_t)l;
+            *sym = T.huffval[t][(T.valptr[t][l] + c) & 255];
+            return true;
+        }
+    }
+    return false;
+}
+
+__device__ inline uint32_t make_entry(bool ac, uint32_t sym, uint32_t len)
+{
+    uint32_t s = sym & 15u, inc, store;
+    if (!ac) {
+        if (sym > 11u) return 0u;  // no such DC category in baseline
+        inc = 1;
+        store = 1;
+    } else if (s == 0) {
+        inc = (sym >> 4) == 15u ? 16u : 64u;  // ZRL, otherwise end of block
+        store = 0;
+    } else {
+        inc = (sym >> 4) + 1u;
+        store = 1;
+    }
+    return kValid | (store << 14) | ((inc - 1u) << 8) | (s << 4) | (len - 1u);
+}
+
+__device__ inline void build_tables(HuffTables &T, const uint8_t *file, const ImageRec &R)
+{
+    const int tid = threadIdx.x;
+    if (tid < 4) {
+        const uint8_t *b = file + R.dht_off[tid];
+        int32_t code = 0, k = 0;
+        T.first[tid][0] = T.count[tid][0] = T.valptr[tid][0] = 0;
+        for (int l = 1; l <= 16; l++) {
+            const int32_t c = b[l - 1];
+            T.first[tid][l] = code;
+            T.count[tid][l] = c;
+            T.valptr[tid][l] = k;
+            code = (code + c) << 1;
+            k += c;
+        }
+        T.sub_used[tid] = 0;
+    }
+    for (int t = 0; t < 4; t++) {
+        const uint32_t nval = min(R.dht_nval[t], 256u);
+        T.huffval[t][tid] = (uint32_t)tid < nval ? file[R.dht_off[t] + 16 + tid] : 0;
+    }
+    for (int i = tid; i < 4 * kSubEntries; i += kT) T.sub[i] = 0;
+    __syncthreads();
+    // first level
+    for (int t = 0; t < 4; t++) {
+        for (int x = tid; x < (1 << kLutBits); x += kT) {
+            uint32_t e = 0, len, sym;
+            if (canonical_lookup(T, t, (uint32_t)x << (16 - kLutBits), 1, kLutBits, &len, &sym)) {
+                e = make_entry(t & 1, sym, len);
+            } else {
+                // is x the beginning of longer codes?  Codes of one length are consecutive.
+                int maxl = 0;
+                for (int l = kLutBits + 1; l <= 16; l++) {
+                    const int32_t c = T.count[t][l];
+                    if (c == 0) continue;
+                    const int32_t lo = T.first[t][l] >> (l - kLutBits);
+                    const int32_t hi = (T.first[t][l] + c - 1) >> (l - kLutBits);
+                    if (x >= lo && x <= hi) maxl = l;
+                }
+                if (maxl) {
+                    const uint32_t nb = (uint32_t)(maxl - kLutBits), size = 1u << nb;
+                    const uint32_t off = atomicAdd(&T.sub_used[t], size);
+                    if (off + size <= (uint32_t)kSubEntries) {
+                        e = (nb << 11) | off;
+                        // leave a note for the second-level pass: which prefix owns these entries
+                        for (uint32_t i = 0; i < size; i++)
+                            T.sub[t * kSubEntries + off + i] = (uint16_t)((nb << 11) | (uint32_t)x);
+                    } else {
+                        e = kUseLoop;
+                    }
+                }
+            }
+            T.lut[(t << kLutBits) + x] = (uint16_t)e;
+        }
+    }
+    __syncthreads();
+    // second level: entry i of a block with nb extra bits covers prefix:i:anything
+    for (int t = 0; t < 4; t++) {
+        const uint32_t used = min(T.sub_used[t], (uint32_t)kSubEntries);
+        for (uint32_t i = tid; i < used; i += kT) {
+            const uint32_t note = T.sub[t * kSubEntries + i];
+            uint32_t e = 0;
+            if (note) {
+                const uint32_t nb = note >> 11, x = note & ((1u << kLutBits) - 1u);
+                const uint32_t off = T.lut[(t << kLutBits) + x] & 0x7FFu;
+                const uint32_t peek = (x << (16 - kLutBits)) | ((i - off) << (16 - kLutBits - nb));
+                uint32_t len, sym;
+                if (canonical_lookup(T, t, peek, kLutBits + 1, kLutBits + (int)nb, &len, &sym))
+                    e = make_entry(t & 1, sym, len);
+            }
+            T.sub[t * kSubEntries + i] = (uint16_t)e;
+        }
+    }
+    __syncthreads();
 }
 
 // ---- bit-level decoding ------------------------------------------------------
@@ -151,7 +277,7 @@ __device__ inline uint32_t comp_of_block(const Geometry &g, uint32_t blk_in_mcu)
 // first interval start at or after clean byte q (in bits), limit if none
 __device__ inline uint32_t boundary_from(const DecodeShared &S, uint32_t q, uint32_t limit_bits)
 {
-    uint32_t j = q >> 6;
+    const uint32_t j = q >> 6;
     if (j >= (uint32_t)kT) return limit_bits;
     unsigned long long m = ((unsigned long long)S.bmask[2 * j + 1] << 32) | S.bmask[2 * j];
     m >>= (q & 63);
@@ -160,11 +286,14 @@ __device__ inline uint32_t boundary_from(const DecodeShared &S, uint32_t q, uint
     return r < limit_bits ? r : limit_bits;
 }
 
+// Per-lane state of a writing pass.  Only scalar members and no indexing by a run-time
+// value: the struct must stay in registers (a private-memory copy would make every
+// iteration of the decode loop wait for its coefficient stores).
 struct WriteCtx {
     int16_t *coef;       // this image's first block
     uint32_t block;      // absolute index of the block being decoded
-    int32_t dcsum[3];    // running DC per component since the lane began or the last reset
-    int32_t dcreset[3];
+    int32_t dc0, dc1, dc2;  // running DC per component since the lane began or the last reset
+    int32_t rs0, rs1, rs2;  // whether that component's prediction was reset in this lane
     uint32_t dc_first;   // first block whose DC this lane decoded
     uint32_t dc_count;
     int32_t need_restart;  // the next thing in the stream must be a restart boundary
@@ -174,54 +303,136 @@ struct WriteCtx {
 __device__ inline bool first_of_interval(const Geometry &g, uint32_t block)
 {
     // the first block of each component in the first MCU of an interval restarts DC prediction
-    uint32_t r = g.ri_blocks ? block % g.ri_blocks : block;
+    const uint32_t r = g.ri_blocks ? block % g.ri_blocks : block;
     return r == 0 || (r >= g.n_luma && r < g.bpm);
+}
+
+// The part of a lookup that is rare: codes longer than the first level covers.
+__device__ inline uint32_t resolve_long_code(const HuffTables &T, uint32_t e, uint32_t tsel, uint32_t hi)
+{
+    if (e == kUseLoop) {
+        uint32_t len, sym;
+        return canonical_lookup(T, (int)tsel, hi >> 16, kLutBits + 1, 16, &len, &sym)
+                   ? make_entry(tsel & 1u, sym, len) : 0u;
+    }
+    if (e == 0) return 0u;
+    const uint32_t nbits = e >> 11;
+    return T.sub[tsel * kSubEntries + (e & 0x7FFu) + ((hi << kLutBits) >> (32 - nbits))];
 }
 
 // Decode from packed state `st` until the bit position reaches end_bit.
 // limit_bits = end of the staged data.  Returns the end state; *nblk = blocks completed.
+//
+// The loop body is one symbol: look the next bits up, (write mode) extract the value and
+// store it, shift the bit buffer, advance the zig-zag position.  A symbol is at most 31 bits
+// long, so symbols that begin more than 31 bits before the next restart boundary are
+// decoded by a fast loop that cannot meet it; the careful step below deals with
+// boundaries, the end of the data and the checks a writing pass makes there.
 template <bool kWrite>
-__device__ inline uint32_t decode_span(const DecodeShared &S, const Geometry &g, uint32_t st,
-                                       uint32_t end_bit, uint32_t limit_bits, uint32_t *nblk,
-                                       WriteCtx *wc)
+__device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geometry &g, uint32_t st,
+                                                uint32_t end_bit, uint32_t limit_bits, uint32_t *nblk,
+                                                WriteCtx *wc)
 {
     uint32_t p = st >> 9, blk = (st >> 6) & 7u, zz = st & 63u;
     uint32_t done = 0;
-    uint32_t widx = p >> 5;
-    uint64_t acc;
-    int cnt;
+    // bit buffer: the next `cnt` bits of the stream are the top bits of hi:lo
+    uint32_t hi, lo, widx, next;
+    uint32_t cnt;
     auto reload = [&]() {
         widx = p >> 5;
-        uint32_t w0 = S.clean[min(widx, (uint32_t)kCleanWords - 1)];
-        uint32_t w1 = S.clean[min(widx + 1, (uint32_t)kCleanWords - 1)];
-        acc = (((uint64_t)w0 << 32) | w1) << (p & 31);
-        cnt = 64 - (int)(p & 31);
-        widx += 2;
+        const uint32_t w0 = S.clean[min(widx, (uint32_t)kCleanWords - 1)];
+        const uint32_t w1 = S.clean[min(widx + 1, (uint32_t)kCleanWords - 1)];
+        const uint32_t sh = p & 31u;
+        hi = sh ? (w0 << sh) | (w1 >> (32 - sh)) : w0;
+        lo = w1 << sh;
+        cnt = 64 - sh;
+        widx = min(widx + 2, (uint32_t)kCleanWords - 1);
+        next = S.clean[widx];
+    };
+    // consume adv (1..31) bits; when fewer than 32 remain the next word moves in
+    auto consume = [&](uint32_t adv) {
+        hi = __builtin_amdgcn_alignbit(hi, lo, 32 - adv);
+        lo <<= adv;
+        cnt -= adv;
+        p += adv;
+        const bool refill = cnt < 32;
+        hi |= refill ? next >> cnt : 0u;
+        lo = refill ? (next << 1) << (31 - cnt) : lo;
+        cnt += refill ? 32u : 0u;
+        widx = min(widx + (refill ? 1u : 0u), (uint32_t)kCleanWords - 1);
+        next = S.clean[widx];
+    };
+    // position of the current block inside its restart interval (write mode)
+    uint32_t iv_pos = 0;
+    if (kWrite) iv_pos = g.ri_blocks ? wc->block % g.ri_blocks : wc->block;
+    auto block_done = [&]() {
+        zz = 0;
+        blk = blk + 1 == g.bpm ? 0 : blk + 1;
+        done++;
+        if (kWrite) {
+            wc->block++;
+            iv_pos++;
+            if (g.ri_blocks && iv_pos == g.ri_blocks) {
+                iv_pos = 0;
+                if (wc->block < g.n_blocks) wc->need_restart = 1;
+            }
+        }
+    };
+    // store the coefficient of entry e (write mode); `after` = buffer past the code word
+    auto store = [&](uint32_t e, uint32_t len, uint32_t s) {
+        // appended bits (T.81 F.2.2.4 RECEIVE) and sign extension (F.2.2.1 EXTEND)
+        const uint32_t after = __builtin_amdgcn_alignbit(hi, lo, 32 - len);
+        const uint32_t extra = (after >> 1) >> (31 - s);
+        const int32_t val = ((int32_t)after < 0 || s == 0) ? (int32_t)extra
+                                                            : (int32_t)extra - (int32_t)((1u << s) - 1u);
+        const uint32_t k = zz + ((e >> 8) & 63u);
+        if (wc->block >= g.n_blocks || k > 63u) {
+            wc->bad = 1;
+        } else if (k == 0) {
+            const uint32_t c = comp_of_block(g, blk);
+            // the first block of each component in the first MCU of an interval restarts prediction
+            const bool rst = iv_pos == 0 || (iv_pos >= g.n_luma && iv_pos < g.bpm);
+            const int32_t run = (rst ? 0 : (c == 0 ? wc->dc0 : c == 1 ? wc->dc1 : wc->dc2)) + val;
+            if (c == 0) { wc->dc0 = run; wc->rs0 |= rst; }
+            else if (c == 1) { wc->dc1 = run; wc->rs1 |= rst; }
+            else { wc->dc2 = run; wc->rs2 |= rst; }
+            wc->coef[wc->block * 64u] = (int16_t)run;
+            if (wc->dc_count == 0) wc->dc_first = wc->block;
+            wc->dc_count++;
+        } else {
+            wc->coef[wc->block * 64u + k] = (int16_t)val;
+        }
     };
     reload();
     uint32_t nb = boundary_from(S, (p + 7) >> 3, limit_bits);
     while (p < end_bit) {
-        const bool dc = zz == 0;
-        const HuffTable &T = S.tab[(blk >= g.n_luma ? 2u : 0u) + (dc ? 0u : 1u)];
-        uint32_t e = T.lut[(uint32_t)(acc >> (64 - kLutBits))];
-        uint32_t len = e >> 8, sym = e & 255u;
-        bool found = true;
-        if (len == 0) {  // code longer than the first-level table, or no code at all
-            const uint32_t peek = (uint32_t)(acc >> 48);
-            len = 16;
-            sym = 0;
-            found = false;
-            for (int l = kLutBits + 1; l <= 16; l++) {
-                int32_t c = (int32_t)(peek >> (16 - l)) - T.first[l];
-                if (c >= 0 && c < T.count[l]) {
-                    len = l;
-                    sym = T.huffval[(T.valptr[l] + c) & 255];
-                    found = true;
-                    break;
+        // ---- fast loop: symbols that end before the next boundary whatever their length ----
+        const uint32_t fast_end = min(end_bit, nb >= 31u ? nb - 31u : 0u);
+        if (kWrite && wc->need_restart && p < fast_end) wc->bad = 1;  // a restart marker is missing
+        while (p < fast_end) {
+            const uint32_t tsel = (blk >= g.n_luma ? 2u : 0u) | (zz ? 1u : 0u);
+            uint32_t e = S.tab.lut[(tsel << kLutBits) + (hi >> (32 - kLutBits))];
+            if (!(e & kValid)) {
+                e = resolve_long_code(S.tab, e, tsel, hi);
+                if (!(e & kValid)) {
+                    if (kWrite) wc->bad = 1;  // bits that are no code word
+                    e = kInvalidEntry;
                 }
             }
+            const uint32_t len = (e & 15u) + 1u, s = (e >> 4) & 15u;
+            if (kWrite && (e & kStore)) store(e, len, s);
+            consume(len + s);
+            zz += ((e >> 8) & 63u) + 1u;
+            if (zz >= 64u) block_done();
         }
-        const uint32_t s = sym & 15u;
+        if (p >= end_bit) break;
+        // ---- one careful step near a boundary or the end of the data -----------------------
+        const uint32_t tsel = (blk >= g.n_luma ? 2u : 0u) | (zz ? 1u : 0u);
+        uint32_t e = S.tab.lut[(tsel << kLutBits) + (hi >> (32 - kLutBits))];
+        if (!(e & kValid)) e = resolve_long_code(S.tab, e, tsel, hi);
+        const bool found = (e & kValid) != 0;
+        if (!found) e = kInvalidEntry;
+        const uint32_t len = (e & 15u) + 1u, s = (e >> 4) & 15u;
         const uint32_t adv = len + s;
         if (kWrite && wc->need_restart && p + adv <= nb) wc->bad = 1;  // a restart marker is missing
         if (p + adv > nb) {
@@ -232,8 +443,7 @@ __device__ inline uint32_t decode_span(const DecodeShared &S, const Geometry &g,
                 break;
             }
             if (kWrite) {
-                if (blk != 0 || zz != 0 || nb - p >= 8) wc->bad = 1;
-                if (g.ri_blocks == 0 || wc->block % g.ri_blocks != 0) wc->bad = 1;
+                if (blk != 0 || zz != 0 || nb - p >= 8 || iv_pos != 0 || g.ri_blocks == 0) wc->bad = 1;
                 wc->need_restart = 0;
             }
             p = nb;
@@ -243,66 +453,13 @@ __device__ inline uint32_t decode_span(const DecodeShared &S, const Geometry &g,
             nb = boundary_from(S, (p >> 3) + 1, limit_bits);
             continue;
         }
-        if (kWrite && !found) wc->bad = 1;  // bits that are no code word (padding is met above)
-        // appended bits (T.81 F.2.2.4 RECEIVE) and sign extension (F.2.2.1 EXTEND)
-        const uint32_t after = (uint32_t)((acc << len) >> 32);
-        const uint32_t extra = s ? after >> (32 - s) : 0u;
-        const int32_t val = s ? ((extra >> (s - 1)) ? (int32_t)extra
-                                                    : (int32_t)extra - (int32_t)((1u << s) - 1u))
-                              : 0;
-        acc <<= adv;
-        cnt -= (int)adv;
-        p += adv;
-        if (cnt < 32) {
-            uint32_t w = S.clean[min(widx, (uint32_t)kCleanWords - 1)];
-            widx++;
-            acc |= (uint64_t)w << (32 - cnt);
-            cnt += 32;
+        if (kWrite) {
+            if (!found) wc->bad = 1;  // bits that are no code word (padding is met above)
+            if (e & kStore) store(e, len, s);
         }
-        if (dc) {
-            if (kWrite) {
-                if (sym > 11) wc->bad = 1;
-                if (wc->block < g.n_blocks) {
-                    const uint32_t c = comp_of_block(g, blk);
-                    if (first_of_interval(g, wc->block)) {
-                        wc->dcsum[c] = val;
-                        wc->dcreset[c] = 1;
-                    } else {
-                        wc->dcsum[c] += val;
-                    }
-                    wc->coef[(size_t)wc->block * 64] = (int16_t)wc->dcsum[c];
-                    if (wc->dc_count == 0) wc->dc_first = wc->block;
-                    wc->dc_count++;
-                } else {
-                    wc->bad = 1;
-                }
-            }
-            zz = 1;
-        } else {
-            const uint32_t r = sym >> 4;
-            if (s == 0) {
-                zz = (r == 15) ? zz + 16 : 64;  // ZRL or end of block
-            } else {
-                zz += r;
-                if (zz < 64) {
-                    if (kWrite && wc->block < g.n_blocks)
-                        wc->coef[(size_t)wc->block * 64 + zz] = (int16_t)val;
-                } else if (kWrite) {
-                    wc->bad = 1;
-                }
-                zz++;
-            }
-        }
-        if (zz >= 64) {
-            zz = 0;
-            blk = blk + 1 == g.bpm ? 0 : blk + 1;
-            done++;
-            if (kWrite) {
-                wc->block++;
-                if (g.ri_blocks && wc->block % g.ri_blocks == 0 && wc->block < g.n_blocks)
-                    wc->need_restart = 1;
-            }
-        }
+        consume(adv);
+        zz += ((e >> 8) & 63u) + 1u;
+        if (zz >= 64u) block_done();
     }
     *nblk = done;
     return pack_state(p, blk, zz);
@@ -320,6 +477,35 @@ __device__ inline int find_image(int n, uint32_t x, F key)
         if (key(mid) <= x) lo = mid; else hi = mid - 1;
     }
     return lo;
+}
+
+// Which raw bytes of one 16-byte piece are entropy-coded data (keep) and which are the
+// code byte of an RSTn marker (bound).  prev = the byte before the piece, next = the byte
+// after it.  Bytes outside [cs, ce) are neither.  A byte after FF is stuffing or a marker
+// code; FF itself is data only before 00.
+__device__ inline void classify16(const uint4 v, uint32_t prev, uint32_t nextb, int32_t plo,
+                                  int32_t cs, int32_t ce, uint32_t *keep, uint32_t *bound,
+                                  uint32_t *last, int32_t *bad)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t k = 0, b = 0;
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        const uint32_t cur = (w[i >> 2] >> (8 * (i & 3))) & 255u;
+        const uint32_t nxt = i < 15 ? (w[(i + 1) >> 2] >> (8 * ((i + 1) & 3))) & 255u : nextb;
+        const int32_t pos = plo + i;
+        const bool inside = pos >= cs && pos < ce;
+        const bool kp = cur == 0xFFu ? nxt == 0u : prev != 0xFFu;
+        if (inside && kp) k |= 1u << i;
+        if (inside && prev == 0xFFu && cur != 0u) {
+            if (cur >= 0xD0u && cur <= 0xD7u) b |= 1u << i;
+            else if (cur != 0xFFu) *bad = 1;  // a marker that may not occur inside a scan
+        }
+        prev = cur;
+    }
+    *keep = k;
+    *bound = b;
+    *last = prev;
 }
 
 }  // namespace
@@ -453,41 +639,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         return;
     }
 
-    // ---- Huffman tables into LDS (T.81 Annex C) ---------------------------------
     const uint8_t *file = bits + R.file_off;
-    if (tid < 4) {
-        const uint8_t *b = file + R.dht_off[tid];
-        HuffTable &T = S.tab[tid];
-        int32_t code = 0, k = 0;
-        T.first[0] = T.count[0] = T.valptr[0] = 0;
-        for (int l = 1; l <= 16; l++) {
-            int32_t c = b[l - 1];
-            T.first[l] = code;
-            T.count[l] = c;
-            T.valptr[l] = k;
-            code = (code + c) << 1;
-            k += c;
-        }
-    }
-    for (int t = 0; t < 4; t++) {
-        const uint32_t nval = min(R.dht_nval[t], 256u);
-        S.tab[t].huffval[tid] = (uint32_t)tid < nval ? file[R.dht_off[t] + 16 + tid] : 0;
-    }
-    __syncthreads();
-    for (int t = 0; t < 4; t++) {
-        HuffTable &T = S.tab[t];
-        for (int x = tid; x < (1 << kLutBits); x += kT) {
-            uint32_t e = 0;
-            for (int l = 1; l <= kLutBits; l++) {
-                int32_t c = (x >> (kLutBits - l)) - T.first[l];
-                if (c >= 0 && c < T.count[l]) {
-                    e = ((uint32_t)l << 8) | T.huffval[(T.valptr[l] + c) & 255];
-                    break;
-                }
-            }
-            T.lut[x] = (uint16_t)e;
-        }
-    }
+    build_tables(S.tab, file, R);
 
     const uint8_t *seg = file + R.entropy_rel;
     int16_t *coef = coef_all + (size_t)R.coef_block0 * 64;
@@ -501,7 +654,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     int32_t dc_carry[3] = {0, 0, 0};
     int32_t bad = 0;
 
-    const uint32_t max_chunks = (range_hi - range_lo) / (kChunkRaw / 4) + 2;
+    const uint32_t max_chunks = (range_hi - range_lo) / 64u + 2;
     for (uint32_t iter = 0; iter < max_chunks && cs < rhi; iter++) {
         // ---- stage: destuff raw bytes [cs, ce) into S.clean --------------------------
         // lanes own 64-byte pieces of the 16-byte aligned span that contains cs
@@ -513,57 +666,63 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         for (int i = tid; i < kCleanWords; i += kT) S.clean[i] = 0;
         for (int i = tid; i < kMaskWords; i += kT) S.bmask[i] = 0;
         const int32_t my_lo = a0 + tid * 64;  // raw offset of my first byte
+        const uint4 *src = reinterpret_cast<const uint4 *>(seg + my_lo);
         unsigned long long keep = 0, bound = 0;
-        uint32_t raw[16];
         {
-            const uint4 *src = reinterpret_cast<const uint4 *>(seg + my_lo);
-#pragma unroll
-            for (int k = 0; k < 4; k++) {
-                uint4 v = make_uint4(0, 0, 0, 0);
-                // load a 16-byte piece only if it overlaps [cs, ce]: the byte at ce (the FF
-                // of the marker that ends the run) is looked at, not consumed
-                const int32_t plo = my_lo + 16 * k;
-                if (plo + 16 > cs && plo <= ce) v = src[k];
-                raw[4 * k + 0] = v.x; raw[4 * k + 1] = v.y; raw[4 * k + 2] = v.z; raw[4 * k + 3] = v.w;
-            }
-        }
-        {
-            // byte before my piece and byte after it, for the FF xx pairs that straddle;
-            // past the segment comes the FF of the EOI marker
-            uint32_t prev = 0, nextb = 0xFFu;
+            // the byte before my piece and the byte after each 16-byte part, for the FF xx
+            // pairs that straddle; past the segment comes the FF of the EOI marker
+            uint32_t prev = 0;
             if (my_lo > cs && my_lo <= ce) prev = load_byte(seg + my_lo - 1);
-            if (my_lo + 64 < seg_len && my_lo + 64 > cs && my_lo + 64 <= ce) nextb = load_byte(seg + my_lo + 64);
-#pragma unroll
-            for (int i = 0; i < 64; i++) {
-                const uint32_t cur = (raw[i >> 2] >> (8 * (i & 3))) & 255u;
-                const uint32_t nxt = i < 63 ? (raw[(i + 1) >> 2] >> (8 * ((i + 1) & 3))) & 255u : nextb;
-                const int32_t pos = my_lo + i;
-                const bool inside = pos >= cs && pos < ce;
-                // a byte after FF is stuffing or a marker code; FF itself is data only before 00
-                const bool k = cur == 0xFFu ? nxt == 0u : prev != 0xFFu;
-                if (inside && k) keep |= 1ull << i;
-                if (inside && prev == 0xFFu && cur != 0u) {
-                    if (cur >= 0xD0u && cur <= 0xD7u) bound |= 1ull << i;
-                    else if (cur != 0xFFu) bad = 1;  // a marker that may not occur inside a scan
+            for (int k = 0; k < 4; k++) {
+                const int32_t plo = my_lo + 16 * k;
+                uint32_t kp = 0, bd = 0;
+                // a part is looked at only if it overlaps [cs, ce]: the byte at ce (the FF of
+                // the marker that ends the run) is examined, not consumed
+                if (plo + 16 > cs && plo <= ce) {
+                    const uint4 v = src[k];
+                    uint32_t nextb = 0xFFu;
+                    if (plo + 16 < seg_len && plo + 16 <= ce) nextb = load_byte(seg + plo + 16);
+                    classify16(v, prev, nextb, plo, cs, ce, &kp, &bd, &prev, &bad);
+                } else {
+                    prev = 0;
                 }
-                prev = cur;
+                keep |= (unsigned long long)kp << (16 * k);
+                bound |= (unsigned long long)bd << (16 * k);
             }
         }
-        uint32_t clean_len;
-        const uint32_t my_off = block_excl_scan((uint32_t)__popcll(keep), S.scan_a, &clean_len);
+        // clean offsets (low half) and boundary ranks (high half) in one scan
+        uint32_t totals;
+        const uint32_t my_pre = block_excl_scan((uint32_t)__popcll(keep) | ((uint32_t)__popcll(bound) << 16),
+                                                S.scan_a, &totals);
+        const uint32_t clean_len = totals & 0xFFFFu, nbnd = totals >> 16;
+        const uint32_t my_off = my_pre & 0xFFFFu;
         S.keep[tid] = keep;
         S.keep_off[tid] = my_off;
         if (tid == 0) S.keep_off[kT] = clean_len;
         __syncthreads();  // zero fill done before bytes are written
         {
             uint8_t *cb = reinterpret_cast<uint8_t *>(S.clean);
-            uint32_t o = my_off;
+            uint32_t o = my_off, rank = my_pre >> 16;
+            for (int k = 0; k < 4; k++) {
+                const uint32_t kp = (uint32_t)(keep >> (16 * k)) & 0xFFFFu;
+                const uint32_t bd = (uint32_t)(bound >> (16 * k)) & 0xFFFFu;
+                if ((kp | bd) == 0) continue;
+                const uint4 v = src[k];
+                const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int i = 0; i < 64; i++) {
-                if ((bound >> i) & 1ull) atomicOr(&S.bmask[o >> 5], 1u << (o & 31));
-                if ((keep >> i) & 1ull) {
-                    cb[o ^ 3u] = (uint8_t)((raw[i >> 2] >> (8 * (i & 3))) & 255u);
-                    o++;
+                for (int i = 0; i < 16; i++) {
+                    if ((bd >> i) & 1u) {
+                        atomicOr(&S.bmask[o >> 5], 1u << (o & 31));
+                        if (rank < (uint32_t)kMaxBoundaries) S.bpos[rank] = (uint16_t)o;
+                        // raw offset just after the last marker of the chunk: where a chunk of
+                        // whole intervals would resume
+                        if (rank + 1 == nbnd) S.bcast[2] = (uint32_t)(my_lo + 16 * k + i + 1);
+                        rank++;
+                    }
+                    if ((kp >> i) & 1u) {
+                        cb[o ^ 3u] = (uint8_t)((wv[i >> 2] >> (8 * (i & 3))) & 255u);
+                        o++;
+                    }
                 }
             }
         }
@@ -572,7 +731,6 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             // first interval start at or after each lane's subsequence: suffix minimum
             unsigned long long m = ((unsigned long long)S.bmask[2 * tid + 1] << 32) | S.bmask[2 * tid];
             uint32_t mine = m ? (uint32_t)tid * 64u + (uint32_t)__builtin_ctzll(m) : kNoMarker;
-            // suffix min inside the wave, then across waves
             const int lane = tid & 63, wave = tid >> 6;
             for (int d = 1; d < 64; d <<= 1) {
                 uint32_t o = __shfl_down(mine, d, 64);
@@ -588,6 +746,51 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         __syncthreads();
 
         const uint32_t limit_bits = clean_len * 8u;
+        WriteCtx wc;
+        wc.coef = coef;
+        wc.bad = 0;
+
+        // ---- short intervals: one lane per restart interval, one pass -----------------
+        // Intervals 0..n_iv-1 of the chunk end inside it: the first runs from the chunk's
+        // start state to the first listed start, interval k > 0 between listed starts k-1
+        // and k, and in the last chunk one more runs to the end of the data.
+        const uint32_t n_iv = last ? nbnd + 1 : nbnd;
+        if (g.ri_blocks != 0 && n_iv >= 1 && nbnd <= (uint32_t)kMaxBoundaries &&
+            clean_len <= kShortInterval * (nbnd + 1)) {
+            const uint32_t rem0 = g.ri_blocks - block_base % g.ri_blocks;  // blocks left in interval 0
+            // consecutive intervals go to different waves so that every SIMD gets some
+            const uint32_t slot = ((uint32_t)tid & 63u) * (kT / 64) + ((uint32_t)tid >> 6);
+            for (uint32_t k = slot; k < n_iv; k += kT) {
+                const uint32_t start = k ? pack_state((uint32_t)S.bpos[k - 1] * 8u, 0, 0) : st0;
+                const uint32_t end_bit = k < nbnd ? (uint32_t)S.bpos[k] * 8u : limit_bits;
+                const uint32_t blk0 = k ? block_base + rem0 + (k - 1) * g.ri_blocks : block_base;
+                const uint32_t want = min(k ? g.ri_blocks : rem0, block_end > blk0 ? block_end - blk0 : 0u);
+                wc.block = blk0;
+                wc.dc0 = k ? 0 : dc_carry[0];
+                wc.dc1 = k ? 0 : dc_carry[1];
+                wc.dc2 = k ? 0 : dc_carry[2];
+                wc.rs0 = wc.rs1 = wc.rs2 = 0;
+                wc.dc_first = 0;
+                wc.dc_count = 0;
+                wc.need_restart = 0;
+                uint32_t got;
+                const uint32_t fin = decode_span<true>(S, g, start, end_bit, limit_bits, &got, &wc);
+                // the interval must end on its boundary, between MCUs, with all its blocks
+                if (got != want || (fin & 511u) != 0 || (fin >> 9) != end_bit) wc.bad = 1;
+            }
+            bad |= wc.bad;
+            block_base = min(block_base + rem0 + (n_iv - 1) * g.ri_blocks, block_end);
+            st0 = pack_state(0, 0, 0);
+            dc_carry[0] = dc_carry[1] = dc_carry[2] = 0;
+            if (last) { cs = rhi; break; }
+            __syncthreads();
+            const int32_t next_cs = (int32_t)S.bcast[2];
+            if (next_cs <= cs || next_cs > rhi) { bad = 1; cs = rhi; break; }
+            cs = next_cs;
+            continue;
+        }
+
+        // ---- long intervals: speculative subsequences ------------------------------------
         // a chunk that is not the last keeps a tail back so that no symbol straddles its end
         const uint32_t own_bits = last ? limit_bits
                                        : (clean_len > (uint32_t)kChunkTail ? (clean_len - kChunkTail) * 8u : 0u);
@@ -595,7 +798,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         const bool active = (uint32_t)tid < nsub;
         const uint32_t end_bit = min(((uint32_t)tid + 1u) * kSubBits, own_bits);
 
-        // ---- synchronise: iterate end states to their fixed point ---------------------
+        // synchronise: iterate end states to their fixed point
         uint32_t in_state = tid == 0 ? st0 : pack_state((uint32_t)tid * kSubBits, 0, 0);
         uint32_t out_state = in_state, nblk = 0;
         if (active) out_state = decode_span<false>(S, g, in_state, end_bit, limit_bits, &nblk, nullptr);
@@ -603,7 +806,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         for (uint32_t round = 0; round <= nsub; round++) {
             __syncthreads();
             int changed = 0;
-            uint32_t prev_state = tid > 0 ? S.state[tid - 1] : st0;
+            const uint32_t prev_state = tid > 0 ? S.state[tid - 1] : st0;
             __syncthreads();
             if (active && tid > 0 && prev_state != in_state) {
                 in_state = prev_state;
@@ -617,17 +820,14 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             if (!__syncthreads_or(changed)) break;
         }
 
-        // ---- write: decode once more from the true states -----------------------------
+        // write: decode once more from the true states
         uint32_t total_blocks;
         const uint32_t my_block = block_base + block_excl_scan(active ? nblk : 0u, S.scan_a, &total_blocks);
-        WriteCtx wc;
-        wc.coef = coef;
         wc.block = my_block;
-        wc.dcsum[0] = wc.dcsum[1] = wc.dcsum[2] = 0;
-        wc.dcreset[0] = wc.dcreset[1] = wc.dcreset[2] = 0;
+        wc.dc0 = wc.dc1 = wc.dc2 = 0;
+        wc.rs0 = wc.rs1 = wc.rs2 = 0;
         wc.dc_first = 0;
         wc.dc_count = 0;
-        wc.bad = 0;
         // a lane that begins on an MCU boundary where an interval ends must meet the boundary
         // first; lane 0 of a chunk may begin just after one (start of the run, or a boundary
         // consumed at the very end of the previous chunk)
@@ -642,29 +842,28 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         bad |= wc.bad;
         // DC differences -> absolute values (T.81 F.2.2.1): carry each component's
         // running value across lanes, restarting where an interval begins
-        int32_t carry[3];
-#pragma unroll
-        for (int c = 0; c < 3; c++) {
-            int32_t out_c;
-            carry[c] = block_seg_excl_scan(wc.dcsum[c], wc.dcreset[c], dc_carry[c], S.dc_val[c],
-                                           S.dc_flag[c], &out_c);
-            dc_carry[c] = out_c;
-        }
+        int32_t out_c;
+        int32_t cy0 = block_seg_excl_scan(wc.dc0, wc.rs0, dc_carry[0], S.dc_val[0], S.dc_flag[0], &out_c);
+        dc_carry[0] = out_c;
+        int32_t cy1 = block_seg_excl_scan(wc.dc1, wc.rs1, dc_carry[1], S.dc_val[1], S.dc_flag[1], &out_c);
+        dc_carry[1] = out_c;
+        int32_t cy2 = block_seg_excl_scan(wc.dc2, wc.rs2, dc_carry[2], S.dc_val[2], S.dc_flag[2], &out_c);
+        dc_carry[2] = out_c;
         for (uint32_t i = 0; i < wc.dc_count; i++) {
             const uint32_t b = wc.dc_first + i;
             if (b >= g.n_blocks) break;
             const uint32_t c = comp_of_block(g, b % g.bpm);
-            if (first_of_interval(g, b)) carry[c] = 0;
-            if (carry[c] == 0 && carry[0] == 0 && carry[1] == 0 && carry[2] == 0) break;
-            if (carry[c] != 0) coef[(size_t)b * 64] = (int16_t)(coef[(size_t)b * 64] + carry[c]);
+            if (first_of_interval(g, b)) {
+                if (c == 0) cy0 = 0; else if (c == 1) cy1 = 0; else cy2 = 0;
+            }
+            if ((cy0 | cy1 | cy2) == 0) break;
+            const int32_t cy = c == 0 ? cy0 : c == 1 ? cy1 : cy2;
+            if (cy != 0) coef[(size_t)b * 64] = (int16_t)(coef[(size_t)b * 64] + cy);
         }
 
-        // ---- carry the true end state into the next chunk -----------------------------
+        // carry the true end state into the next chunk
         __syncthreads();
-        if (tid == 0) {
-            const uint32_t fs = nsub ? S.state[nsub - 1] : st0;
-            S.bcast[0] = fs;
-        }
+        if (tid == 0) S.bcast[0] = nsub ? S.state[nsub - 1] : st0;
         __syncthreads();
         const uint32_t fs = S.bcast[0];
         block_base += total_blocks;
@@ -680,7 +879,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         }
         if (S.keep_off[tid] <= qc && qc < S.keep_off[tid] + (uint32_t)__popcll(S.keep[tid])) {
             unsigned long long m = S.keep[tid];
-            uint32_t skip = qc - S.keep_off[tid];
+            const uint32_t skip = qc - S.keep_off[tid];
             for (uint32_t i = 0; i < skip; i++) m &= m - 1;  // drop the lowest set bits
             S.bcast[1] = (uint32_t)(a0 + tid * 64 + (int32_t)__builtin_ctzll(m));
         }

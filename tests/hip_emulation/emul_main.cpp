@@ -78,9 +78,9 @@ int main(int argc, char **argv)
             }
         }
         fwrite(&nc, 8, 1, o);
-        fwrite(coef.data(), 2, (size_t)nc, o);
+        if (nc) fwrite(coef.data(), 2, (size_t)nc, o);
         fwrite(&nr, 8, 1, o);
-        fwrite(rgb.data(), 1, (size_t)nr, o);
+        if (nr) fwrite(rgb.data(), 1, (size_t)nr, o);
     }
     fwrite(out.data(), 1, out.size() - 16, o);
     fclose(o);

@@ -25,6 +25,7 @@
 #define __constant__
 #define __shared__ static
 #define __launch_bounds__(...)
+#define __forceinline__ inline
 
 struct dim3 {
     unsigned x, y, z;
@@ -117,11 +118,17 @@ template <typename T>
 inline T __shfl_xor(T v, int d, int = 64) { return hip_emul::shuffle(v, [d](int l) { return l ^ d; }); }
 
 inline uint32_t atomicOr(uint32_t *p, uint32_t v) { return __atomic_fetch_or(p, v, __ATOMIC_SEQ_CST); }
+inline uint32_t atomicAdd(uint32_t *p, uint32_t v) { return __atomic_fetch_add(p, v, __ATOMIC_SEQ_CST); }
 inline int32_t atomicMin(int32_t *p, int32_t v)
 {
     int32_t old = __atomic_load_n(p, __ATOMIC_SEQ_CST);
     while (old > v && !__atomic_compare_exchange_n(p, &old, v, false, __ATOMIC_SEQ_CST, __ATOMIC_SEQ_CST)) {}
     return old;
+}
+// ({hi,lo} >> (shift & 31)) truncated to 32 bits, as V_ALIGNBIT_B32 computes it
+inline uint32_t __builtin_amdgcn_alignbit(uint32_t hi, uint32_t lo, uint32_t shift)
+{
+    return (uint32_t)(((((uint64_t)hi) << 32) | lo) >> (shift & 31u));
 }
 inline int __popcll(unsigned long long v) { return __builtin_popcountll(v); }
 

@@ -1,0 +1,70 @@
+"""Host logic and kernel indexing, checked without a GPU: the library's sources are compiled
+by g++ against a CPU stand-in for HIP (one OS thread per lane, AddressSanitizer and UBSan
+on) and run end to end through the C ABI.  The product never uses this build; the GPU
+parity tests are the ones marked `gpu`."""
+import numpy as np
+import pytest
+
+import emul
+import oracle
+import synth
+from oracle import MODE_420, MODE_444, MODE_GRAY
+
+MEAN, STD = synth.IMAGENET_MEAN, synth.IMAGENET_STD
+
+
+def _img(seed, w, h, sigma=12.0):
+    return synth.gradient_noise_image(np.random.default_rng(seed), w, h, sigma)
+
+
+def _check(streams, rs, ch, cw, dt, expect_status=None):
+    per, ten = emul.run(streams, rs, ch, cw, dt, MEAN, STD)
+    for i, s in enumerate(streams):
+        status, coef, rgb = per[i]
+        if expect_status and expect_status[i] != 0:
+            assert status == expect_status[i]
+            assert (ten[i] == 0).all()
+            continue
+        assert status == 0, f"image {i}: status {status}"
+        c0, r0, info = oracle.decode(s)
+        assert np.array_equal(coef, c0), f"image {i}: coefficients differ"
+        d = np.abs(rgb.reshape(r0.shape).astype(int) - r0.astype(int))
+        assert d.max() <= 1 and (d == 0).mean() >= 0.999, f"image {i}: rgb"
+        ref = oracle.preprocess(r0, rs, ch, cw, MEAN, STD)
+        assert np.abs(ten[i].astype(np.float64) - ref).max() <= 0.02, f"image {i}: tensor"
+
+
+def test_modes_restart_intervals_and_odd_sizes():
+    streams = []
+    for k, (w, h) in enumerate([(1, 1), (17, 33), (70, 45)]):
+        for mode in (MODE_444, MODE_420, MODE_GRAY):
+            cols = -(-w // (16 if mode == MODE_420 else 8))
+            for dri in (0, 1, cols):
+                streams.append(oracle.encode(_img(10 + k, w, h), 88, mode, dri, table_mode=k % 2)[0])
+    _check(streams, 0, 1, 1, "f32")
+
+
+def test_pillow_streams_of_workloads_1_and_5():
+    streams = [synth.make_image(1, 5)[0], synth.make_image(5, 0)[0], synth.make_image(5, 1)[0],
+               synth.make_image(5, 2)[0]]
+    _check(streams, 256, 224, 224, "f16")
+
+
+def test_long_intervals_and_many_chunks():
+    rgb = _img(20, 480, 320, sigma=25.0)
+    streams = [oracle.encode(rgb, 95, MODE_444, 0)[0],        # ~150 KB without markers
+               oracle.encode(rgb, 95, MODE_420, 30)[0],       # one interval per MCU row, > 1 KB each
+               oracle.encode(rgb, 95, MODE_420, 3)[0]]        # short intervals over many windows
+    assert len(streams[0]) > 100000
+    _check(streams, 128, 112, 120, "f32")
+
+
+def test_broken_streams_are_reported_and_zero_filled():
+    good = [oracle.encode(_img(30 + k, 64, 48), 85, MODE_420, 2)[0] for k in range(3)]
+    sos = good[0].index(b"\xff\xda")
+    i = good[0].index(b"\xff\xd1", sos)
+    streams = [good[0], good[1][:len(good[1]) // 2], good[2],
+               good[0].replace(b"\xff\xc0", b"\xff\xc2", 1),
+               good[0][:i - 1] + good[0][i + 2:],
+               good[0][:sos + 30] + bytes(60) + good[0][sos + 90:]]
+    _check(streams, 32, 24, 24, "f32", expect_status=[0, -5, 0, -4, -5, -5])
