@@ -34,7 +34,7 @@ namespace {
 constexpr int kT = kDecodeThreads;
 constexpr int kCleanWords = kChunkRaw / 4 + 8;      // destuffed stream + zero tail
 constexpr int kMaskWords = kChunkRaw / 32 + 2;      // one bit per clean byte
-constexpr int kSubEntries = 512;                    // second-level lookup entries per table
+constexpr int kSubEntries = 256;                    // second-level lookup entries per table
 constexpr int kMaxBoundaries = 1024;                // listed interval starts per chunk
 constexpr uint32_t kShortInterval = 1024;           // mean clean bytes up to which a lane takes a whole interval
 constexpr uint32_t kNoMarker = 0xFFFFFFFFu;
@@ -42,16 +42,15 @@ constexpr uint32_t kSubBits = kSubseqBytes * 8;
 static_assert(kSubseqBytes == 64 && kT == 256, "one 64-bit keep mask per lane, 256 HUFFVAL bytes");
 
 // Lookup entry of a Huffman code (16 bits):
-//   bit 15     valid
-//   bit 14     a coefficient is stored (DC, or AC with a non-zero size)
-//   bits 13..8 zig-zag advance - 1 (DC 1, AC run+1, ZRL 16, EOB 64)
-//   bits 7..4  number of appended bits
-//   bits 3..0  code length - 1
-// A first-level entry that is not valid is 0 (no such code), kUseLoop, or a
-// reference to a second-level block: bits 14..11 = extra index bits (1..6),
-// bits 10..0 = offset into the table's second-level pool.
-constexpr uint32_t kValid = 0x8000u, kStore = 0x4000u, kUseLoop = 0x7FFFu;
-constexpr uint32_t kInvalidEntry = kValid | (63u << 8) | 15u;  // 16 bits, ends the block
+//   bits 15..11 code length + number of appended bits (1..31); 0 = not a code entry
+//   bit 10      a coefficient is stored (DC, or AC with a non-zero size)
+//   bits 9..4   zig-zag advance - 1 (DC 1, AC run+1, ZRL 16, EOB 64)
+//   bits 3..0   number of appended bits
+// A first-level entry that is not a code entry is 0 (no such code), kUseLoop, or a
+// reference to a second-level block: bits 10..8 = extra index bits (1..6),
+// bits 7..0 = offset into the table's second-level pool.
+constexpr uint32_t kStore = 0x0400u, kUseLoop = 0x07FFu;
+constexpr uint32_t kInvalidEntry = (16u << 11) | (63u << 4);  // 16 bits, ends the block
 
 struct HuffTables {
     uint16_t lut[4 << kLutBits];     // first level, indexed by the next kLutBits bits
@@ -181,7 +180,7 @@ __device__ inline uint32_t make_entry(bool ac, uint32_t sym, uint32_t len)
         inc = (sym >> 4) + 1u;
         store = 1;
     }
-    return kValid | (store << 14) | ((inc - 1u) << 8) | (s << 4) | (len - 1u);
+    return ((len + s) << 11) | (store << 10) | ((inc - 1u) << 4) | s;
 }
 
 __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const ImageRec &R)
@@ -227,7 +226,7 @@ __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const Im
                     const uint32_t nb = (uint32_t)(maxl - kLutBits), size = 1u << nb;
                     const uint32_t off = atomicAdd(&T.sub_used[t], size);
                     if (off + size <= (uint32_t)kSubEntries) {
-                        e = (nb << 11) | off;
+                        e = (nb << 8) | off;
                         // leave a note for the second-level pass: which prefix owns these entries
                         for (uint32_t i = 0; i < size; i++)
                             T.sub[t * kSubEntries + off + i] = (uint16_t)((nb << 11) | (uint32_t)x);
@@ -248,7 +247,7 @@ __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const Im
             uint32_t e = 0;
             if (note) {
                 const uint32_t nb = note >> 11, x = note & ((1u << kLutBits) - 1u);
-                const uint32_t off = T.lut[(t << kLutBits) + x] & 0x7FFu;
+                const uint32_t off = T.lut[(t << kLutBits) + x] & 0xFFu;
                 const uint32_t peek = (x << (16 - kLutBits)) | ((i - off) << (16 - kLutBits - nb));
                 uint32_t len, sym;
                 if (canonical_lookup(T, t, peek, kLutBits + 1, kLutBits + (int)nb, &len, &sym))
@@ -290,12 +289,8 @@ __device__ inline uint32_t boundary_from(const DecodeShared &S, uint32_t q, uint
 // value: the struct must stay in registers (a private-memory copy would make every
 // iteration of the decode loop wait for its coefficient stores).
 struct WriteCtx {
-    int16_t *coef;       // this image's first block
-    uint32_t block;      // absolute index of the block being decoded
-    int32_t dc0, dc1, dc2;  // running DC per component since the lane began or the last reset
-    int32_t rs0, rs1, rs2;  // whether that component's prediction was reset in this lane
-    uint32_t dc_first;   // first block whose DC this lane decoded
-    uint32_t dc_count;
+    int16_t *coef;         // this image's first block
+    uint32_t block;        // absolute index of the block being decoded
     int32_t need_restart;  // the next thing in the stream must be a restart boundary
     int32_t bad;
 };
@@ -307,27 +302,61 @@ __device__ inline bool first_of_interval(const Geometry &g, uint32_t block)
     return r == 0 || (r >= g.n_luma && r < g.bpm);
 }
 
-// The part of a lookup that is rare: codes longer than the first level covers.
-__device__ inline uint32_t resolve_long_code(const HuffTables &T, uint32_t e, uint32_t tsel, uint32_t hi)
+// The rarest part of a lookup: a table whose second level did not fit its pool.  Out of
+// line so that the decode loops stay short.
+__device__ __attribute__((noinline)) uint32_t lookup_by_search(const HuffTables &T, uint32_t tsel,
+                                                               uint32_t win)
 {
-    if (e == kUseLoop) {
-        uint32_t len, sym;
-        return canonical_lookup(T, (int)tsel, hi >> 16, kLutBits + 1, 16, &len, &sym)
-                   ? make_entry(tsel & 1u, sym, len) : 0u;
-    }
-    if (e == 0) return 0u;
-    const uint32_t nbits = e >> 11;
-    return T.sub[tsel * kSubEntries + (e & 0x7FFu) + ((hi << kLutBits) >> (32 - nbits))];
+    uint32_t len, sym;
+    return canonical_lookup(T, (int)tsel, win >> 16, kLutBits + 1, 16, &len, &sym)
+               ? make_entry(tsel & 1u, sym, len) : 0u;
+}
+
+// Codes longer than the first level covers: e is the first-level entry (not a code entry),
+// win = the next 32 bits of the stream.  Returns a code entry or 0.
+__device__ __forceinline__ uint32_t resolve_long_code(const HuffTables &T, uint32_t e, uint32_t tsel,
+                                                      uint32_t win)
+{
+    if (__builtin_expect(e == kUseLoop, 0)) return lookup_by_search(T, tsel, win);
+    // e = 0 (no such code) reads entry 0 of the pool with a zero index: harmless, and the
+    // result is discarded
+    const uint32_t nbits = e >> 8;
+    const uint32_t idx = nbits ? (win << kLutBits) >> (32 - nbits) : 0u;
+    const uint32_t r = T.sub[tsel * kSubEntries + (e & 0xFFu) + idx];
+    return e ? r : 0u;
+}
+
+// The next 32 bits of the staged stream at bit position p (two LDS words and a shift).
+__device__ __forceinline__ uint32_t window32(const DecodeShared &S, uint32_t p)
+{
+    const uint32_t w = min(p >> 5, (uint32_t)kCleanWords - 2);
+    const unsigned long long pair = ((unsigned long long)S.clean[w] << 32) | S.clean[w + 1];
+    return (uint32_t)(pair >> (32 - (p & 31u)));
+}
+
+// value of a stored coefficient: appended bits (T.81 F.2.2.4 RECEIVE) and sign extension
+// (F.2.2.1 EXTEND); adv = code length + s
+__device__ __forceinline__ int32_t coefficient_value(uint32_t win, uint32_t adv, uint32_t s)
+{
+    const uint32_t after = win << (adv - s);
+    const uint32_t extra = (after >> 1) >> (31 - s);
+    return ((int32_t)after < 0 || s == 0) ? (int32_t)extra : (int32_t)extra - (int32_t)((1u << s) - 1u);
 }
 
 // Decode from packed state `st` until the bit position reaches end_bit.
 // limit_bits = end of the staged data.  Returns the end state; *nblk = blocks completed.
 //
-// The loop body is one symbol: look the next bits up, (write mode) extract the value and
-// store it, shift the bit buffer, advance the zig-zag position.  A symbol is at most 31 bits
-// long, so symbols that begin more than 31 bits before the next restart boundary are
-// decoded by a fast loop that cannot meet it; the careful step below deals with
-// boundaries, the end of the data and the checks a writing pass makes there.
+// One iteration = one symbol: fetch the next 32 bits, look them up, (write mode) extract
+// the value and store it, advance position and zig-zag index.  The state carried from one
+// symbol to the next is the bit position, block-in-MCU and zig-zag index only.  A writing
+// pass stores DC *differences*; dc_prefix() turns them into values afterwards.
+//
+// A lone wave issues about one instruction every five cycles and pays a fetch bubble for
+// every taken branch, so the loop is kept short and straight: a symbol is at most 31 bits
+// long, hence symbols that begin more than 31 bits before the next restart boundary are
+// decoded by a fast loop that cannot meet it, with everything rare (long codes, boundaries,
+// end of data, the checks of a writing pass at a boundary) left out of line or to the
+// careful step after it.
 template <bool kWrite>
 __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geometry &g, uint32_t st,
                                                 uint32_t end_bit, uint32_t limit_bits, uint32_t *nblk,
@@ -335,106 +364,75 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
 {
     uint32_t p = st >> 9, blk = (st >> 6) & 7u, zz = st & 63u;
     uint32_t done = 0;
-    // bit buffer: the next `cnt` bits of the stream are the top bits of hi:lo
-    uint32_t hi, lo, widx, next;
-    uint32_t cnt;
-    auto reload = [&]() {
-        widx = p >> 5;
-        const uint32_t w0 = S.clean[min(widx, (uint32_t)kCleanWords - 1)];
-        const uint32_t w1 = S.clean[min(widx + 1, (uint32_t)kCleanWords - 1)];
-        const uint32_t sh = p & 31u;
-        hi = sh ? (w0 << sh) | (w1 >> (32 - sh)) : w0;
-        lo = w1 << sh;
-        cnt = 64 - sh;
-        widx = min(widx + 2, (uint32_t)kCleanWords - 1);
-        next = S.clean[widx];
-    };
-    // consume adv (1..31) bits; when fewer than 32 remain the next word moves in
-    auto consume = [&](uint32_t adv) {
-        hi = __builtin_amdgcn_alignbit(hi, lo, 32 - adv);
-        lo <<= adv;
-        cnt -= adv;
-        p += adv;
-        const bool refill = cnt < 32;
-        hi |= refill ? next >> cnt : 0u;
-        lo = refill ? (next << 1) << (31 - cnt) : lo;
-        cnt += refill ? 32u : 0u;
-        widx = min(widx + (refill ? 1u : 0u), (uint32_t)kCleanWords - 1);
-        next = S.clean[widx];
-    };
-    // position of the current block inside its restart interval (write mode)
-    uint32_t iv_pos = 0;
-    if (kWrite) iv_pos = g.ri_blocks ? wc->block % g.ri_blocks : wc->block;
-    auto block_done = [&]() {
-        zz = 0;
-        blk = blk + 1 == g.bpm ? 0 : blk + 1;
-        done++;
-        if (kWrite) {
-            wc->block++;
-            iv_pos++;
-            if (g.ri_blocks && iv_pos == g.ri_blocks) {
-                iv_pos = 0;
-                if (wc->block < g.n_blocks) wc->need_restart = 1;
-            }
-        }
-    };
-    // store the coefficient of entry e (write mode); `after` = buffer past the code word
-    auto store = [&](uint32_t e, uint32_t len, uint32_t s) {
-        // appended bits (T.81 F.2.2.4 RECEIVE) and sign extension (F.2.2.1 EXTEND)
-        const uint32_t after = __builtin_amdgcn_alignbit(hi, lo, 32 - len);
-        const uint32_t extra = (after >> 1) >> (31 - s);
-        const int32_t val = ((int32_t)after < 0 || s == 0) ? (int32_t)extra
-                                                            : (int32_t)extra - (int32_t)((1u << s) - 1u);
-        const uint32_t k = zz + ((e >> 8) & 63u);
-        if (wc->block >= g.n_blocks || k > 63u) {
-            wc->bad = 1;
-        } else if (k == 0) {
-            const uint32_t c = comp_of_block(g, blk);
-            // the first block of each component in the first MCU of an interval restarts prediction
-            const bool rst = iv_pos == 0 || (iv_pos >= g.n_luma && iv_pos < g.bpm);
-            const int32_t run = (rst ? 0 : (c == 0 ? wc->dc0 : c == 1 ? wc->dc1 : wc->dc2)) + val;
-            if (c == 0) { wc->dc0 = run; wc->rs0 |= rst; }
-            else if (c == 1) { wc->dc1 = run; wc->rs1 |= rst; }
-            else { wc->dc2 = run; wc->rs2 |= rst; }
-            wc->coef[wc->block * 64u] = (int16_t)run;
-            if (wc->dc_count == 0) wc->dc_first = wc->block;
-            wc->dc_count++;
-        } else {
-            wc->coef[wc->block * 64u + k] = (int16_t)val;
-        }
-    };
-    reload();
+    // write mode: position of the current block inside its restart interval, its first
+    // coefficient, one past the image's last coefficient
+    uint32_t iv_pos = 0, boff = 0, bend = 0;
+    if (kWrite) {
+        iv_pos = g.ri_blocks ? wc->block % g.ri_blocks : wc->block;
+        boff = wc->block * 64u;
+        bend = g.n_blocks * 64u;
+    }
     uint32_t nb = boundary_from(S, (p + 7) >> 3, limit_bits);
+    const uint16_t *lut = S.tab.lut;
+    const uint32_t chroma_tb = 2u << kLutBits, ac_bit = 1u << kLutBits;
     while (p < end_bit) {
-        // ---- fast loop: symbols that end before the next boundary whatever their length ----
+        // ---- fast loop ------------------------------------------------------------------
         const uint32_t fast_end = min(end_bit, nb >= 31u ? nb - 31u : 0u);
-        if (kWrite && wc->need_restart && p < fast_end) wc->bad = 1;  // a restart marker is missing
-        while (p < fast_end) {
-            const uint32_t tsel = (blk >= g.n_luma ? 2u : 0u) | (zz ? 1u : 0u);
-            uint32_t e = S.tab.lut[(tsel << kLutBits) + (hi >> (32 - kLutBits))];
-            if (!(e & kValid)) {
-                e = resolve_long_code(S.tab, e, tsel, hi);
-                if (!(e & kValid)) {
-                    if (kWrite) wc->bad = 1;  // bits that are no code word
-                    e = kInvalidEntry;
+        if (p < fast_end) {
+            // tb: first entry of the current table (DC luma 0, AC luma 1024, DC chroma 2048, AC 3072)
+            uint32_t tb = (blk >= g.n_luma ? chroma_tb : 0u) | (zz ? ac_bit : 0u);
+            int32_t bad = kWrite ? wc->need_restart : 0;  // data where a restart marker had to come
+            do {
+                const uint32_t win = window32(S, p);
+                uint32_t e = lut[tb + (win >> (32 - kLutBits))];
+                if (__builtin_expect((e >> 11) == 0, 0)) {
+                    e = resolve_long_code(S.tab, e, tb >> kLutBits, win);
+                    if ((e >> 11) == 0) {
+                        bad = 1;  // bits that are no code word
+                        e = kInvalidEntry;
+                    }
                 }
+                const uint32_t adv = e >> 11;
+                const uint32_t k = zz + ((e >> 4) & 63u);  // index of a stored coefficient
+                if (kWrite) {
+                    const bool st_ok = (e & kStore) != 0 && k < 64u && boff < bend;
+                    if (st_ok) wc->coef[boff + k] = (int16_t)coefficient_value(win, adv, e & 15u);
+                    bad |= (e & kStore) != 0 && !st_ok;
+                }
+                p += adv;
+                const bool endb = k >= 63u;  // zz = k + 1 reaches 64
+                const uint32_t blk1 = blk + 1u == g.bpm ? 0u : blk + 1u;
+                zz = endb ? 0u : k + 1u;
+                blk = endb ? blk1 : blk;
+                done += endb ? 1u : 0u;
+                tb = endb ? (blk1 >= g.n_luma ? chroma_tb : 0u) : tb | ac_bit;
+                if (kWrite) {
+                    boff += endb ? 64u : 0u;
+                    iv_pos += endb ? 1u : 0u;
+                    // after the last block of an interval only a restart boundary may follow,
+                    // and the fast loop is never that close to one
+                    const bool wrap = g.ri_blocks != 0 && iv_pos == g.ri_blocks;
+                    iv_pos = wrap ? 0u : iv_pos;
+                    bad |= wrap && boff < bend && p < fast_end;
+                    wc->need_restart = wrap && boff < bend;
+                }
+            } while (p < fast_end);
+            if (kWrite) {
+                wc->bad |= bad;
+                wc->block = boff >> 6;
             }
-            const uint32_t len = (e & 15u) + 1u, s = (e >> 4) & 15u;
-            if (kWrite && (e & kStore)) store(e, len, s);
-            consume(len + s);
-            zz += ((e >> 8) & 63u) + 1u;
-            if (zz >= 64u) block_done();
+            if (p >= end_bit) break;
         }
-        if (p >= end_bit) break;
         // ---- one careful step near a boundary or the end of the data -----------------------
+        const uint32_t win = window32(S, p);
         const uint32_t tsel = (blk >= g.n_luma ? 2u : 0u) | (zz ? 1u : 0u);
-        uint32_t e = S.tab.lut[(tsel << kLutBits) + (hi >> (32 - kLutBits))];
-        if (!(e & kValid)) e = resolve_long_code(S.tab, e, tsel, hi);
-        const bool found = (e & kValid) != 0;
-        if (!found) e = kInvalidEntry;
-        const uint32_t len = (e & 15u) + 1u, s = (e >> 4) & 15u;
-        const uint32_t adv = len + s;
-        if (kWrite && wc->need_restart && p + adv <= nb) wc->bad = 1;  // a restart marker is missing
+        uint32_t e = lut[(tsel << kLutBits) + (win >> (32 - kLutBits))];
+        bool found = true;
+        if ((e >> 11) == 0) {
+            e = resolve_long_code(S.tab, e, tsel, win);
+            if ((e >> 11) == 0) { found = false; e = kInvalidEntry; }
+        }
+        const uint32_t adv = e >> 11;
         if (p + adv > nb) {
             // the symbol does not fit before the next restart boundary / end of data
             if (nb >= limit_bits) {
@@ -449,20 +447,77 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
             p = nb;
             blk = 0;
             zz = 0;
-            reload();
             nb = boundary_from(S, (p >> 3) + 1, limit_bits);
             continue;
         }
+        const uint32_t k = zz + ((e >> 4) & 63u);
         if (kWrite) {
-            if (!found) wc->bad = 1;  // bits that are no code word (padding is met above)
-            if (e & kStore) store(e, len, s);
+            // bits that are no code word, or data where a restart marker had to come
+            if (!found || wc->need_restart) wc->bad = 1;
+            if (e & kStore) {
+                if (k < 64u && boff < bend) wc->coef[boff + k] = (int16_t)coefficient_value(win, adv, e & 15u);
+                else wc->bad = 1;
+            }
         }
-        consume(adv);
-        zz += ((e >> 8) & 63u) + 1u;
-        if (zz >= 64u) block_done();
+        p += adv;
+        zz = k + 1u;
+        if (zz >= 64u) {
+            zz = 0;
+            blk = blk + 1 == g.bpm ? 0 : blk + 1;
+            done++;
+            if (kWrite) {
+                boff += 64u;
+                wc->block = boff >> 6;
+                iv_pos++;
+                if (g.ri_blocks && iv_pos == g.ri_blocks) {
+                    iv_pos = 0;
+                    if (boff < bend) wc->need_restart = 1;
+                }
+            }
+        }
     }
     *nblk = done;
     return pack_state(p, blk, zz);
+}
+
+// DC differences -> DC values (T.81 F.2.2.1) for blocks [lo, hi) of the image, by the whole
+// workgroup: each lane takes a contiguous run of blocks, sums its differences per component
+// (a sum restarts where a restart interval begins), a segmented scan over the lanes carries
+// the running values in, and a second walk writes them.  carry[] = running value of each
+// component before block lo; on return, after block hi - 1.  All lanes must call.
+__device__ inline void dc_prefix(DecodeShared &S, const Geometry &g, int16_t *coef, uint32_t lo,
+                                 uint32_t hi, int32_t carry[3])
+{
+    __syncthreads();  // the coefficient stores of every lane are done and visible
+    const uint32_t n = hi > lo ? hi - lo : 0u;
+    const uint32_t per = (n + kT - 1) / kT;
+    const uint32_t a = min(lo + threadIdx.x * per, hi), b = min(a + per, hi);
+    int32_t s0 = 0, s1 = 0, s2 = 0, r0 = 0, r1 = 0, r2 = 0;
+    for (uint32_t i = a; i < b; i++) {
+        const int32_t d = coef[(size_t)i * 64];
+        const uint32_t c = comp_of_block(g, i % g.bpm);
+        const bool rst = first_of_interval(g, i);
+        if (c == 0) { s0 = (rst ? 0 : s0) + d; r0 |= rst; }
+        else if (c == 1) { s1 = (rst ? 0 : s1) + d; r1 |= rst; }
+        else { s2 = (rst ? 0 : s2) + d; r2 |= rst; }
+    }
+    int32_t out;
+    int32_t c0 = block_seg_excl_scan(s0, r0, carry[0], S.dc_val[0], S.dc_flag[0], &out);
+    carry[0] = out;
+    int32_t c1 = block_seg_excl_scan(s1, r1, carry[1], S.dc_val[1], S.dc_flag[1], &out);
+    carry[1] = out;
+    int32_t c2 = block_seg_excl_scan(s2, r2, carry[2], S.dc_val[2], S.dc_flag[2], &out);
+    carry[2] = out;
+    for (uint32_t i = a; i < b; i++) {
+        const int32_t d = coef[(size_t)i * 64];
+        const uint32_t c = comp_of_block(g, i % g.bpm);
+        const bool rst = first_of_interval(g, i);
+        int32_t v;
+        if (c == 0) { c0 = (rst ? 0 : c0) + d; v = c0; }
+        else if (c == 1) { c1 = (rst ? 0 : c1) + d; v = c1; }
+        else { c2 = (rst ? 0 : c2) + d; v = c2; }
+        coef[(size_t)i * 64] = (int16_t)v;
+    }
 }
 
 __device__ inline uint32_t load_byte(const uint8_t *p) { return *p; }
@@ -766,12 +821,6 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
                 const uint32_t blk0 = k ? block_base + rem0 + (k - 1) * g.ri_blocks : block_base;
                 const uint32_t want = min(k ? g.ri_blocks : rem0, block_end > blk0 ? block_end - blk0 : 0u);
                 wc.block = blk0;
-                wc.dc0 = k ? 0 : dc_carry[0];
-                wc.dc1 = k ? 0 : dc_carry[1];
-                wc.dc2 = k ? 0 : dc_carry[2];
-                wc.rs0 = wc.rs1 = wc.rs2 = 0;
-                wc.dc_first = 0;
-                wc.dc_count = 0;
                 wc.need_restart = 0;
                 uint32_t got;
                 const uint32_t fin = decode_span<true>(S, g, start, end_bit, limit_bits, &got, &wc);
@@ -779,7 +828,12 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
                 if (got != want || (fin & 511u) != 0 || (fin >> 9) != end_bit) wc.bad = 1;
             }
             bad |= wc.bad;
-            block_base = min(block_base + rem0 + (n_iv - 1) * g.ri_blocks, block_end);
+            {
+                // DC values of the blocks whose DC was decoded here (the chunk may begin inside a block)
+                const uint32_t dc_lo = block_base + ((st0 & 63u) ? 1u : 0u);
+                block_base = min(block_base + rem0 + (n_iv - 1) * g.ri_blocks, block_end);
+                dc_prefix(S, g, coef, dc_lo, min(block_base, g.n_blocks), dc_carry);
+            }
             st0 = pack_state(0, 0, 0);
             dc_carry[0] = dc_carry[1] = dc_carry[2] = 0;
             if (last) { cs = rhi; break; }
@@ -824,10 +878,6 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         uint32_t total_blocks;
         const uint32_t my_block = block_base + block_excl_scan(active ? nblk : 0u, S.scan_a, &total_blocks);
         wc.block = my_block;
-        wc.dc0 = wc.dc1 = wc.dc2 = 0;
-        wc.rs0 = wc.rs1 = wc.rs2 = 0;
-        wc.dc_first = 0;
-        wc.dc_count = 0;
         // a lane that begins on an MCU boundary where an interval ends must meet the boundary
         // first; lane 0 of a chunk may begin just after one (start of the run, or a boundary
         // consumed at the very end of the previous chunk)
@@ -840,32 +890,19 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             if (final_state != out_state || nb2 != nblk) wc.bad = 1;
         }
         bad |= wc.bad;
-        // DC differences -> absolute values (T.81 F.2.2.1): carry each component's
-        // running value across lanes, restarting where an interval begins
-        int32_t out_c;
-        int32_t cy0 = block_seg_excl_scan(wc.dc0, wc.rs0, dc_carry[0], S.dc_val[0], S.dc_flag[0], &out_c);
-        dc_carry[0] = out_c;
-        int32_t cy1 = block_seg_excl_scan(wc.dc1, wc.rs1, dc_carry[1], S.dc_val[1], S.dc_flag[1], &out_c);
-        dc_carry[1] = out_c;
-        int32_t cy2 = block_seg_excl_scan(wc.dc2, wc.rs2, dc_carry[2], S.dc_val[2], S.dc_flag[2], &out_c);
-        dc_carry[2] = out_c;
-        for (uint32_t i = 0; i < wc.dc_count; i++) {
-            const uint32_t b = wc.dc_first + i;
-            if (b >= g.n_blocks) break;
-            const uint32_t c = comp_of_block(g, b % g.bpm);
-            if (first_of_interval(g, b)) {
-                if (c == 0) cy0 = 0; else if (c == 1) cy1 = 0; else cy2 = 0;
-            }
-            if ((cy0 | cy1 | cy2) == 0) break;
-            const int32_t cy = c == 0 ? cy0 : c == 1 ? cy1 : cy2;
-            if (cy != 0) coef[(size_t)b * 64] = (int16_t)(coef[(size_t)b * 64] + cy);
-        }
-
-        // carry the true end state into the next chunk
         __syncthreads();
         if (tid == 0) S.bcast[0] = nsub ? S.state[nsub - 1] : st0;
         __syncthreads();
         const uint32_t fs = S.bcast[0];
+        {
+            // DC values of the blocks whose DC was decoded in this chunk: it may begin inside
+            // a block (DC decoded earlier) and end inside one (DC decoded here)
+            const uint32_t dc_lo = block_base + ((st0 & 63u) ? 1u : 0u);
+            const uint32_t dc_hi = block_base + total_blocks + ((fs & 63u) ? 1u : 0u);
+            dc_prefix(S, g, coef, dc_lo, min(dc_hi, g.n_blocks), dc_carry);
+        }
+
+        // carry the true end state into the next chunk
         block_base += total_blocks;
         if (last) { cs = rhi; st0 = fs; break; }
         // raw position of the clean byte the end state points into
