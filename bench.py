@@ -85,6 +85,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 256 MiB device copy (a reference for HBM counters)")
     ap.add_argument("--host-input", action="store_true",
                     help="time prep_decode_resize_batch (bitstreams start in host memory)")
     args = ap.parse_args()
@@ -136,6 +138,12 @@ def main():
         else:
             pp.decode_resize_batch_resident(blob, dev_bits.data_ptr(), offsets, params, out.data_ptr(), sp)
 
+    if args.copy_probe:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        a.fill_(1)
+        b.copy_(a)
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -21,6 +21,7 @@ namespace {
 constexpr int kSlots = 2;            // pinned staging is double buffered
 constexpr size_t kBitsPad = 256;     // readable slack after the last file
 constexpr size_t kRgbAlign = 256;
+constexpr size_t kRgbSlack = 16;     // readable bytes kept after every image's RGB rows
 constexpr int kTimedCalls = 256;     // calls whose stage events are kept
 
 struct Slot {
@@ -103,10 +104,11 @@ bool make_resize_rec(int w, int h, const prep_params *p, uint64_t src_off, uint3
     if (p->crop_w > ow || p->crop_h > oh) return false;
     const int top = (oh - p->crop_h) / 2, left = (ow - p->crop_w) / 2;
     const double sx = (double)w / (double)ow, sy = (double)h / (double)oh;
-    r->scale_x = sx;
-    r->scale_y = sy;
-    r->off_x = (left + 0.5) * sx - 0.5;
-    r->off_y = (top + 0.5) * sy - 0.5;
+    const double one = (double)(1ull << kCoordFrac);
+    r->scale_x = (uint64_t)llround(sx * one);
+    r->scale_y = (uint64_t)llround(sy * one);
+    r->off_x = (uint64_t)llround(((left + 0.5) * sx - 0.5 + kCoordBias) * one);
+    r->off_y = (uint64_t)llround(((top + 0.5) * sy - 0.5 + kCoordBias) * one);
     r->src_w = w;
     r->src_h = h;
     r->src_pitch = pitch;
@@ -170,7 +172,7 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
         if (R.status == PREP_OK) {
             const uint64_t rows = (uint64_t)R.mcu_rows * 8u * (R.sampling == PREP_SAMPLING_420 ? 2 : 1);
             P.n_blocks += R.n_blocks;
-            P.rgb_bytes += ((uint64_t)R.rgb_pitch * rows + kRgbAlign - 1) / kRgbAlign * kRgbAlign;
+            P.rgb_bytes += ((uint64_t)R.rgb_pitch * rows + kRgbSlack + kRgbAlign - 1) / kRgbAlign * kRgbAlign;
             P.n_groups += R.groups_per_row * R.mcu_rows;
         }
         P.n_windows += R.n_windows;
@@ -249,7 +251,7 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
     launch_reconstruct(d_bits, h->d_recs, n, P.n_groups, h->d_coef, h->d_rgb, stream);
     if (timing) HIP_TRY(hipEventRecord(ev[3], stream));
     launch_resize_normalize(h->d_rgb, h->d_rr, h->d_status, n, params->crop_h, params->crop_w,
-                            params->out_dtype, params->mean, params->std, out, stream);
+                            params->out_dtype, params->mean, params->std, out, true, stream);
     if (timing) HIP_TRY(hipEventRecord(ev[4], stream));
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(s->done, stream));
@@ -287,7 +289,7 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     // padded to whole 16x16 MCUs an image of w x h has at most (w+15)(h+15) pixels
     const uint64_t padded = px + 15ull * n * ((uint64_t)cfg->max_width + cfg->max_height) + 225ull * n;
     h->cap_blocks = padded * 3 / 64 + 6 * n;       // 4:4:4 worst case: 3 blocks per 64 pixels
-    h->cap_rgb = padded * 3 + kRgbAlign * n;
+    h->cap_rgb = padded * 3 + (kRgbAlign + kRgbSlack) * n;
     h->cap_windows = cfg->max_bitstream_bytes / kWindowBytes + n + 1;
     h->cap_bits = cfg->max_bitstream_bytes + kBitsPad;
     if (h->cap_blocks > 0xFFFFFFFFull) { delete h; return PREP_E_TOO_LARGE; }
@@ -458,7 +460,7 @@ int prep_resize_normalize(prep_handle *h, const uint8_t *rgb, const uint64_t *rg
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(hipMemcpyAsync(h->d_rr, s->h_rr, sizeof(ResizeRec) * (size_t)n, hipMemcpyHostToDevice, st));
     launch_resize_normalize(rgb, h->d_rr, nullptr, n, params->crop_h, params->crop_w,
-                            params->out_dtype, params->mean, params->std, out, st);
+                            params->out_dtype, params->mean, params->std, out, false, st);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(s->done, st));
     s->pending = true;

@@ -22,7 +22,7 @@ void launch_reconstruct(const uint8_t *bits, const ImageRec *recs, int n_images,
 // resize.hip
 void launch_resize_normalize(const uint8_t *rgb, const ResizeRec *rr, const int32_t *status,
                              int n_images, int crop_h, int crop_w, int out_dtype,
-                             const float mean[3], const float std[3], void *out,
+                             const float mean[3], const float std[3], void *out, bool wide_reads,
                              hipStream_t stream);
 
 }  // namespace prep

@@ -51,15 +51,18 @@ struct ImageRec {
 };
 static_assert(sizeof(ImageRec) % 8 == 0, "ImageRec must keep 8-byte alignment in arrays");
 
-// Resize/crop/normalize geometry of one image, computed on the host in double
-// precision so that every lane uses identical mapping constants.
+// Resize/crop/normalize geometry of one image, computed on the host in double precision
+// and handed over in fixed point so that every lane maps coordinates with integer
+// arithmetic: source coordinate of output pixel i = (off + i * scale) / 2^kCoordFrac - kCoordBias.
+constexpr int kCoordFrac = 30;   // fraction bits (scale < 2^17 and i < 2^16 keep the product in 64 bits)
+constexpr int kCoordBias = 16;   // added so that the slightly negative coordinates at the border stay positive
 struct ResizeRec {
-    double scale_x, scale_y;  // source pixels per output pixel
-    double off_x, off_y;      // source coordinate of output pixel (0,0)
+    uint64_t scale_x, scale_y;  // source pixels per output pixel
+    uint64_t off_x, off_y;      // source coordinate of output pixel (0,0), biased
     int32_t src_w, src_h;
     uint32_t src_pitch;
     uint32_t pad_;
-    uint64_t src_off;         // byte offset of the source image
+    uint64_t src_off;           // byte offset of the source image
 };
 
 }  // namespace prep

@@ -77,11 +77,13 @@ __device__ inline void idct8(const double F[8], double out[8])
 // rational results of the IDCT definition carry ~1e-13 of evaluation noise.
 constexpr double kTieEps = 1.0 / 1048576.0;
 
-__device__ inline uint32_t round_clamp_u8(double v)
+// JFIF colour values are sums of an integer and one or two products of small integers
+// with three-decimal constants; in float they stay well clear of the half-way points that
+// matter except for isolated saturated-blue cases, so single precision decides the rounding.
+__device__ inline uint32_t round_clamp_u8(float v)
 {
-    double r = floor(v + 0.5);
-    r = r < 0.0 ? 0.0 : (r > 255.0 ? 255.0 : r);
-    return (uint32_t)r;
+    const int r = (int)floorf(v + 0.5f);
+    return (uint32_t)min(max(r, 0), 255);
 }
 
 template <typename F>
@@ -102,7 +104,7 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
     const int16_t *__restrict__ coef_all, uint8_t *__restrict__ rgb_all)
 {
     __shared__ double tile[kReconBlocks * kTileSize];
-    __shared__ float qf[3][64];
+    __shared__ int32_t qi[3][64];
     __shared__ uint32_t luma[16 * kLumaPitch / 4];
     __shared__ uint32_t chroma[2][8 * kChromaPitch / 4];
 
@@ -124,7 +126,7 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
     const int n_blk = gcount * bpm;  // <= kReconBlocks
 
     const uint8_t *file = bits + R.file_off;
-    if (tid < 192) qf[tid >> 6][tid & 63] = (float)file[R.dqt_off[tid >> 6] + (tid & 63)];
+    if (tid < 192) qi[tid >> 6][tid & 63] = (int32_t)file[R.dqt_off[tid >> 6] + (tid & 63)];
     __syncthreads();
 
     const int b = tid >> 3, l = tid & 7;
@@ -144,7 +146,7 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
             const int k = l * 8 + j;
             const int c = (int)(int16_t)(w[j >> 1] >> (16 * (j & 1)));
             const int nat = kZigZag.nat[k];
-            T[(nat >> 3) * kTileStride + (nat & 7)] = (double)c * (double)qf[comp][k];
+            T[(nat >> 3) * kTileStride + (nat & 7)] = (double)(c * qi[comp][k]);  // exact in int32
         }
     }
     __syncthreads();
@@ -167,9 +169,8 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
         uint32_t pk[2] = {0, 0};
 #pragma unroll
         for (int x = 0; x < 8; x++) {
-            double s = floor(o[x] * 0.125 + (0.5 + kTieEps)) + 128.0;
-            s = s < 0.0 ? 0.0 : (s > 255.0 ? 255.0 : s);
-            pk[x >> 2] |= (uint32_t)s << (8 * (x & 3));
+            const int sample = (int)floor(o[x] * 0.125 + (0.5 + kTieEps)) + 128;
+            pk[x >> 2] |= (uint32_t)min(max(sample, 0), 255) << (8 * (x & 3));
         }
         if (comp == 0) {
             const int bx = blk & (hs - 1), by = hs == 2 ? blk >> 1 : 0;
@@ -200,10 +201,10 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
             uint32_t r = Y, gch = Y, bl = Y;
             if (sampling != PREP_SAMPLING_GRAY) {
                 const int ci = (row >> cshift) * kChromaPitch + ((x + j) >> cshift);
-                const double cb = (double)cb8[ci] - 128.0, cr = (double)cr8[ci] - 128.0;
-                r = round_clamp_u8((double)Y + 1.402 * cr);
-                gch = round_clamp_u8((double)Y - 0.344136 * cb - 0.714136 * cr);
-                bl = round_clamp_u8((double)Y + 1.772 * cb);
+                const float yf = (float)Y, cb = (float)((int)cb8[ci] - 128), cr = (float)((int)cr8[ci] - 128);
+                r = round_clamp_u8(fmaf(1.402f, cr, yf));
+                gch = round_clamp_u8(fmaf(-0.714136f, cr, fmaf(-0.344136f, cb, yf)));
+                bl = round_clamp_u8(fmaf(1.772f, cb, yf));
             }
             const int o = j * 3;
             out[o >> 2] |= r << (8 * (o & 3));
