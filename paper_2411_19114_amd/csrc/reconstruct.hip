@@ -99,28 +99,30 @@ __device__ inline int find_image_by(int n, uint32_t x, F key)
 
 }  // namespace
 
-__global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
-    const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
-    const int16_t *__restrict__ coef_all, uint8_t *__restrict__ rgb_all)
-{
-    __shared__ double tile[kReconBlocks * kTileSize];
-    __shared__ int32_t qi[3][64];
-    __shared__ uint32_t luma[16 * kLumaPitch / 4];
-    __shared__ uint32_t chroma[2][8 * kChromaPitch / 4];
+struct ReconShared {
+    double tile[kReconBlocks * kTileSize];
+    int32_t qi[3][64];
+    uint32_t luma[16 * kLumaPitch / 4];
+    uint32_t chroma[2][8 * kChromaPitch / 4];
+};
 
+// The work of one workgroup, with the sampling mode a compile-time constant so that every
+// block / pixel index is divided by constants.
+template <int sampling>
+__device__ __forceinline__ void reconstruct_group(ReconShared &S, const uint8_t *__restrict__ bits,
+                                                  const ImageRec &R, uint32_t mrow, uint32_t gcol,
+                                                  const int16_t *__restrict__ coef_all,
+                                                  uint8_t *__restrict__ rgb_all)
+{
+    double *tile = S.tile;
+    int32_t (*qi)[64] = S.qi;
+    uint32_t *luma = S.luma;
+    uint32_t (*chroma)[8 * kChromaPitch / 4] = S.chroma;
     const int tid = threadIdx.x;
-    const uint32_t wg = blockIdx.x;
-    const int img = find_image_by(n_images, wg, [&](int i) { return recs[i].group0; });
-    const ImageRec &R = recs[img];
-    if (R.status != PREP_OK) return;
-    const uint32_t gi = wg - R.group0;
-    const uint32_t mrow = gi / R.groups_per_row, gcol = gi % R.groups_per_row;
-    if (mrow >= R.mcu_rows) return;
-    const int sampling = R.sampling;
-    const int bpm = R.blocks_per_mcu;
-    const int hs = sampling == PREP_SAMPLING_420 ? 2 : 1;  // luma blocks per MCU per axis
-    const int n_luma = hs * hs;
-    const int per_group = recon_mcus_per_group(sampling);
+    constexpr int bpm = sampling == PREP_SAMPLING_420 ? 6 : sampling == PREP_SAMPLING_444 ? 3 : 1;
+    constexpr int hs = sampling == PREP_SAMPLING_420 ? 2 : 1;  // luma blocks per MCU per axis
+    constexpr int n_luma = hs * hs;
+    constexpr int per_group = recon_mcus_per_group(sampling);
     const uint32_t mcu_x0 = gcol * per_group;
     const int gcount = min(per_group, (int)R.mcu_cols - (int)mcu_x0);
     const int n_blk = gcount * bpm;  // <= kReconBlocks
@@ -216,6 +218,26 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
         d[1] = out[1];
         d[2] = out[2];
     }
+}
+
+__global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
+    const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
+    const int16_t *__restrict__ coef_all, uint8_t *__restrict__ rgb_all)
+{
+    __shared__ ReconShared S;
+    const uint32_t wg = blockIdx.x;
+    const int img = find_image_by(n_images, wg, [&](int i) { return recs[i].group0; });
+    const ImageRec &R = recs[img];
+    if (R.status != PREP_OK) return;
+    const uint32_t gi = wg - R.group0;
+    const uint32_t mrow = gi / R.groups_per_row, gcol = gi % R.groups_per_row;
+    if (mrow >= R.mcu_rows) return;
+    if (R.sampling == PREP_SAMPLING_420)
+        reconstruct_group<PREP_SAMPLING_420>(S, bits, R, mrow, gcol, coef_all, rgb_all);
+    else if (R.sampling == PREP_SAMPLING_444)
+        reconstruct_group<PREP_SAMPLING_444>(S, bits, R, mrow, gcol, coef_all, rgb_all);
+    else
+        reconstruct_group<PREP_SAMPLING_GRAY>(S, bits, R, mrow, gcol, coef_all, rgb_all);
 }
 
 void launch_reconstruct(const uint8_t *bits, const ImageRec *recs, int n_images, uint32_t n_groups,
