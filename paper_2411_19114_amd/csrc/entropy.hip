@@ -1,8 +1,11 @@
 // GPU Huffman entropy decoder for baseline JPEG (T.81 F.2.2), gfx950.
 //
 // The first half of the "Decode" functional unit (PREBA section 4.2, Table 1).
-// The FPGA decodes one stream serially per compute unit; here one workgroup owns
-// a run of whole restart intervals (T.81 E.2.4) of one image:
+// The FPGA decodes one stream serially per compute unit; here one workgroup of a
+// single wave owns a run of whole restart intervals (T.81 E.2.4) of one image.  A
+// decoding lane is bound by the latency of its own dependent instruction chain, so
+// the work is arranged to put as many busy lanes as possible into each wave and one
+// wave on each SIMD, rather than spreading a chunk's lanes over several waves:
 //
 //   1. scan_restart_markers counts the RSTn markers in fixed windows of every
 //      image's entropy-coded segment, so that a workgroup starting at the first
@@ -32,18 +35,16 @@ namespace prep {
 namespace {
 
 constexpr int kT = kDecodeThreads;
-constexpr int kCleanWords = kChunkRaw / 4 + 8;      // destuffed stream + zero tail
+constexpr int kCleanWords = kChunkRaw / 4 + kDecodeThreads + 16;  // destuffed stream, one pad word per lane, zero tail
 constexpr int kMaskWords = kChunkRaw / 32 + 2;      // one bit per clean byte
 constexpr int kSubEntries = 256;                    // second-level lookup entries per table
 constexpr int kMaxBoundaries = 1024;                // listed interval starts per chunk
-constexpr uint32_t kShortInterval = 1024;           // mean clean bytes up to which a lane takes a whole interval
 constexpr uint32_t kNoMarker = 0xFFFFFFFFu;
-constexpr uint32_t kSubBits = kSubseqBytes * 8;
-static_assert(kSubseqBytes == 64 && kT == 256, "one 64-bit keep mask per lane, 256 HUFFVAL bytes");
+static_assert(kT == 64, "the workgroup is one wave: scans and state exchange use lane shuffles only");
 
 // Lookup entry of a Huffman code (16 bits):
 //   bits 15..11 code length + number of appended bits (1..31); 0 = not a code entry
-//   bit 10      a coefficient is stored (DC, or AC with a non-zero size)
+//   bit 10      the symbol's coefficient index must lie inside the block (all but EOB)
 //   bits 9..4   zig-zag advance - 1 (DC 1, AC run+1, ZRL 16, EOB 64)
 //   bits 3..0   number of appended bits
 // A first-level entry that is not a code entry is 0 (no such code), kUseLoop, or a
@@ -53,7 +54,7 @@ constexpr uint32_t kStore = 0x0400u, kUseLoop = 0x07FFu;
 constexpr uint32_t kInvalidEntry = (16u << 11) | (63u << 4);  // 16 bits, ends the block
 
 struct HuffTables {
-    uint16_t lut[4 << kLutBits];     // first level, indexed by the next kLutBits bits
+    alignas(8) uint16_t lut[4 << kLutBits];  // first level, indexed by the next kLutBits bits
     uint16_t sub[4 * kSubEntries];   // second level
     int32_t first[4][17];            // first code of each length
     int32_t count[4][17];            // BITS
@@ -63,17 +64,17 @@ struct HuffTables {
 };
 
 struct DecodeShared {
-    uint32_t clean[kCleanWords];     // big-endian packed: bit 31 of a word is the earliest bit
+    // The destuffed stream, big-endian packed (bit 31 of a word is the earliest bit), with one
+    // unused word after every sub_bytes / 4 words: lanes that read at similar offsets of their
+    // subsequences then hit different LDS banks instead of all the same one.
+    uint32_t clean[kCleanWords];
     uint32_t bmask[kMaskWords];      // bit q set: a restart interval begins at clean byte q
-    uint32_t next_boundary[kT + 1];  // first interval start at or after the lane's subsequence
+    uint32_t next_boundary[kChunkPieces + 1];  // first interval start at or after each 64-byte clean piece
     uint16_t bpos[kMaxBoundaries];   // interval starts of the chunk in order (clean byte offsets)
     HuffTables tab;                  // DC luma, AC luma, DC chroma, AC chroma
-    unsigned long long keep[kT];     // which of the lane's 64 raw bytes survived destuffing
-    uint32_t keep_off[kT + 1];       // clean offset of the lane's first surviving byte
-    uint32_t state[kT];              // end state of every subsequence
-    uint32_t scan_a[kT / 64 + 1];    // per-wave totals for workgroup scans
-    int32_t dc_val[3][kT / 64 + 1];
-    int32_t dc_flag[3][kT / 64 + 1];
+    unsigned long long keep[kChunkPieces];   // which bytes of each 64-byte raw piece survived destuffing
+    unsigned long long bound[kChunkPieces];  // which are the code byte of an RSTn marker
+    uint32_t keep_off[kChunkPieces];         // clean offset of the piece's first surviving byte
     uint32_t bcast[8];
 };
 
@@ -82,7 +83,7 @@ __device__ inline uint32_t pack_state(uint32_t p, uint32_t blk, uint32_t zz)
     return (p << 9) | (blk << 6) | zz;
 }
 
-// ---- workgroup-wide helpers (kT threads, wave64) ---------------------------
+// ---- wave-wide helpers ---------------------------------------------------------
 
 __device__ inline uint32_t wave_incl_scan(uint32_t v)
 {
@@ -95,32 +96,26 @@ __device__ inline uint32_t wave_incl_scan(uint32_t v)
     return v;
 }
 
-// exclusive prefix sum over the workgroup; *total receives the sum
-__device__ inline uint32_t block_excl_scan(uint32_t v, uint32_t *wave_tot, uint32_t *total)
+// exclusive prefix sum over the wave; *total receives the sum
+__device__ inline uint32_t wave_excl_scan(uint32_t v, uint32_t *total)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t inc = wave_incl_scan(v);
-    __syncthreads();
-    if (lane == 63) wave_tot[wave] = inc;
-    __syncthreads();
-    uint32_t base = 0, tot = 0;
+    const uint32_t inc = wave_incl_scan(v);
+    *total = __shfl(inc, 63, 64);
+    return inc - v;
+}
+
+__device__ inline uint32_t wave_sum(uint32_t v)
+{
 #pragma unroll
-    for (int w = 0; w < kT / 64; w++) {
-        uint32_t t = wave_tot[w];
-        if (w < wave) base += t;
-        tot += t;
-    }
-    *total = tot;
-    return base + inc - v;
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
 }
 
 // Segmented running sum (value, reset flag): a reset discards what came before.
 // Returns the value carried INTO this lane (exclusive); carry_in seeds lane 0.
-__device__ inline int32_t block_seg_excl_scan(int32_t v, int32_t f, int32_t carry_in,
-                                              int32_t *wave_val, int32_t *wave_flag,
-                                              int32_t *carry_out)
+__device__ inline int32_t wave_seg_excl_scan(int32_t v, int32_t f, int32_t carry_in, int32_t *carry_out)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
     int32_t iv = v, ifl = f;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -131,22 +126,12 @@ __device__ inline int32_t block_seg_excl_scan(int32_t v, int32_t f, int32_t carr
             ifl |= of;
         }
     }
-    __syncthreads();
-    if (lane == 63) { wave_val[wave] = iv; wave_flag[wave] = ifl; }
-    __syncthreads();
-    int32_t cv = carry_in, all_v = carry_in;
-#pragma unroll
-    for (int w = 0; w < kT / 64; w++) {
-        int32_t wv = wave_val[w], wf = wave_flag[w];
-        int32_t nv = wf ? wv : all_v + wv;
-        if (w < wave) cv = nv;
-        all_v = nv;
-    }
-    *carry_out = all_v;
-    int32_t pv = __shfl_up(iv, 1, 64);
-    int32_t pf = __shfl_up(ifl, 1, 64);
-    if (lane == 0) return cv;
-    return pf ? pv : cv + pv;
+    const int32_t lv = __shfl(iv, 63, 64), lf = __shfl(ifl, 63, 64);
+    *carry_out = lf ? lv : carry_in + lv;
+    const int32_t pv = __shfl_up(iv, 1, 64);
+    const int32_t pf = __shfl_up(ifl, 1, 64);
+    if (lane == 0) return carry_in;
+    return pf ? pv : carry_in + pv;
 }
 
 // ---- Huffman tables (T.81 Annex C) --------------------------------------------
@@ -174,8 +159,9 @@ __device__ inline uint32_t make_entry(bool ac, uint32_t sym, uint32_t len)
         inc = 1;
         store = 1;
     } else if (s == 0) {
-        inc = (sym >> 4) == 15u ? 16u : 64u;  // ZRL, otherwise end of block
-        store = 0;
+        const bool zrl = (sym >> 4) == 15u;
+        inc = zrl ? 16u : 64u;  // ZRL, otherwise end of block
+        store = zrl ? 1u : 0u;
     } else {
         inc = (sym >> 4) + 1u;
         store = 1;
@@ -183,15 +169,24 @@ __device__ inline uint32_t make_entry(bool ac, uint32_t sym, uint32_t len)
     return ((len + s) << 11) | (store << 10) | ((inc - 1u) << 4) | s;
 }
 
+// The first level is filled code by code: canonical codes of one table are consecutive when
+// left-aligned, so the code of length len with value c owns the 2^(kLutBits-len) entries that
+// begin with it.  Entries above the last code of at most kLutBits bits begin longer codes (or
+// nothing): each such prefix gets a block of the second-level pool sized for the longest
+// code that shares it.
 __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const ImageRec &R)
 {
     const int tid = threadIdx.x;
     if (tid < 4) {
         const uint8_t *b = file + R.dht_off[tid];
+        int32_t bits[16];
+#pragma unroll
+        for (int l = 0; l < 16; l++) bits[l] = b[l];
         int32_t code = 0, k = 0;
         T.first[tid][0] = T.count[tid][0] = T.valptr[tid][0] = 0;
+#pragma unroll
         for (int l = 1; l <= 16; l++) {
-            const int32_t c = b[l - 1];
+            const int32_t c = bits[l - 1];
             T.first[tid][l] = code;
             T.count[tid][l] = c;
             T.valptr[tid][l] = k;
@@ -202,37 +197,52 @@ __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const Im
     }
     for (int t = 0; t < 4; t++) {
         const uint32_t nval = min(R.dht_nval[t], 256u);
-        T.huffval[t][tid] = (uint32_t)tid < nval ? file[R.dht_off[t] + 16 + tid] : 0;
+#pragma unroll
+        for (uint32_t i = tid; i < 256u; i += kT) T.huffval[t][i] = i < nval ? file[R.dht_off[t] + 16 + i] : 0;
     }
     for (int i = tid; i < 4 * kSubEntries; i += kT) T.sub[i] = 0;
     __syncthreads();
-    // first level
     for (int t = 0; t < 4; t++) {
-        for (int x = tid; x < (1 << kLutBits); x += kT) {
-            uint32_t e = 0, len, sym;
-            if (canonical_lookup(T, t, (uint32_t)x << (16 - kLutBits), 1, kLutBits, &len, &sym)) {
-                e = make_entry(t & 1, sym, len);
+        // codes of at most kLutBits bits: one lane per code
+        const int32_t n_short = min(T.valptr[t][kLutBits] + T.count[t][kLutBits], 256);
+        for (int32_t i = tid; i < n_short; i += kT) {
+            int l = 1;
+            while (l < kLutBits && T.valptr[t][l] + T.count[t][l] <= i) l++;
+            const uint32_t c = (uint32_t)(T.first[t][l] + (i - T.valptr[t][l]));
+            const uint32_t e = make_entry(t & 1, T.huffval[t][i], (uint32_t)l);
+            const uint32_t span = 1u << (kLutBits - l), base = c << (kLutBits - l);
+            if (base + span > (1u << kLutBits)) continue;  // not a prefix code; the parser refuses these
+            uint16_t *dst = &T.lut[(t << kLutBits) + base];
+            if (span >= 4u) {
+                const unsigned long long four = 0x0001000100010001ull * e;
+                for (uint32_t j = 0; j < span; j += 4) *reinterpret_cast<unsigned long long *>(dst + j) = four;
             } else {
-                // is x the beginning of longer codes?  Codes of one length are consecutive.
-                int maxl = 0;
-                for (int l = kLutBits + 1; l <= 16; l++) {
-                    const int32_t c = T.count[t][l];
-                    if (c == 0) continue;
-                    const int32_t lo = T.first[t][l] >> (l - kLutBits);
-                    const int32_t hi = (T.first[t][l] + c - 1) >> (l - kLutBits);
-                    if (x >= lo && x <= hi) maxl = l;
-                }
-                if (maxl) {
-                    const uint32_t nb = (uint32_t)(maxl - kLutBits), size = 1u << nb;
-                    const uint32_t off = atomicAdd(&T.sub_used[t], size);
-                    if (off + size <= (uint32_t)kSubEntries) {
-                        e = (nb << 8) | off;
-                        // leave a note for the second-level pass: which prefix owns these entries
-                        for (uint32_t i = 0; i < size; i++)
-                            T.sub[t * kSubEntries + off + i] = (uint16_t)((nb << 11) | (uint32_t)x);
-                    } else {
-                        e = kUseLoop;
-                    }
+                for (uint32_t j = 0; j < span; j++) dst[j] = (uint16_t)e;
+            }
+        }
+        // the rest of the first level: beginnings of longer codes, or of none
+        const uint32_t x_lo = min((uint32_t)(T.first[t][kLutBits] + T.count[t][kLutBits]), 1u << kLutBits);
+        for (uint32_t x = x_lo + tid; x < (1u << kLutBits); x += kT) {
+            uint32_t e = 0;
+            // codes of one length are consecutive: which lengths have a code that begins with x?
+            int maxl = 0;
+            for (int l = kLutBits + 1; l <= 16; l++) {
+                const int32_t c = T.count[t][l];
+                if (c == 0) continue;
+                const int32_t lo = T.first[t][l] >> (l - kLutBits);
+                const int32_t hi = (T.first[t][l] + c - 1) >> (l - kLutBits);
+                if ((int32_t)x >= lo && (int32_t)x <= hi) maxl = l;
+            }
+            if (maxl) {
+                const uint32_t nb = (uint32_t)(maxl - kLutBits), size = 1u << nb;
+                const uint32_t off = atomicAdd(&T.sub_used[t], size);
+                if (off + size <= (uint32_t)kSubEntries) {
+                    e = (nb << 8) | off;
+                    // leave a note for the second-level pass: which prefix owns these entries
+                    for (uint32_t i = 0; i < size; i++)
+                        T.sub[t * kSubEntries + off + i] = (uint16_t)((nb << 11) | x);
+                } else {
+                    e = kUseLoop;
                 }
             }
             T.lut[(t << kLutBits) + x] = (uint16_t)e;
@@ -262,6 +272,7 @@ __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const Im
 // ---- bit-level decoding ------------------------------------------------------
 
 struct Geometry {
+    uint32_t pad_shift;  // log2 of the words between pad words of the staged stream
     uint32_t bpm;        // blocks per MCU
     uint32_t n_luma;     // luma blocks per MCU (blocks >= n_luma use the chroma tables)
     uint32_t ri_blocks;  // blocks per restart interval, 0 = none
@@ -277,7 +288,7 @@ __device__ inline uint32_t comp_of_block(const Geometry &g, uint32_t blk_in_mcu)
 __device__ inline uint32_t boundary_from(const DecodeShared &S, uint32_t q, uint32_t limit_bits)
 {
     const uint32_t j = q >> 6;
-    if (j >= (uint32_t)kT) return limit_bits;
+    if (j >= (uint32_t)kChunkPieces) return limit_bits;
     unsigned long long m = ((unsigned long long)S.bmask[2 * j + 1] << 32) | S.bmask[2 * j];
     m >>= (q & 63);
     uint32_t r = m ? q + (uint32_t)__builtin_ctzll(m) : S.next_boundary[j + 1];
@@ -291,16 +302,9 @@ __device__ inline uint32_t boundary_from(const DecodeShared &S, uint32_t q, uint
 struct WriteCtx {
     int16_t *coef;         // this image's first block
     uint32_t block;        // absolute index of the block being decoded
-    int32_t need_restart;  // the next thing in the stream must be a restart boundary
+    int32_t iv_rem;        // blocks left before a restart boundary has to come (0: it comes next)
     int32_t bad;
 };
-
-__device__ inline bool first_of_interval(const Geometry &g, uint32_t block)
-{
-    // the first block of each component in the first MCU of an interval restarts DC prediction
-    const uint32_t r = g.ri_blocks ? block % g.ri_blocks : block;
-    return r == 0 || (r >= g.n_luma && r < g.bpm);
-}
 
 // The rarest part of a lookup: a table whose second level did not fit its pool.  Out of
 // line so that the decode loops stay short.
@@ -326,11 +330,18 @@ __device__ __forceinline__ uint32_t resolve_long_code(const HuffTables &T, uint3
     return e ? r : 0u;
 }
 
-// The next 32 bits of the staged stream at bit position p (two LDS words and a shift).
-__device__ __forceinline__ uint32_t window32(const DecodeShared &S, uint32_t p)
+// word w of the destuffed stream lives at this index of DecodeShared::clean
+__device__ __forceinline__ uint32_t clean_index(const Geometry &g, uint32_t w)
 {
-    const uint32_t w = min(p >> 5, (uint32_t)kCleanWords - 2);
-    const unsigned long long pair = ((unsigned long long)S.clean[w] << 32) | S.clean[w + 1];
+    return w + (w >> g.pad_shift);
+}
+
+// The next 32 bits of the staged stream at bit position p (two LDS words and a shift).
+__device__ __forceinline__ uint32_t window32(const DecodeShared &S, const Geometry &g, uint32_t p)
+{
+    const uint32_t w = min(p >> 5, (uint32_t)(kChunkRaw / 4 + 8));
+    const unsigned long long pair = ((unsigned long long)S.clean[clean_index(g, w)] << 32) |
+                                    S.clean[clean_index(g, w + 1)];
     return (uint32_t)(pair >> (32 - (p & 31u)));
 }
 
@@ -364,13 +375,14 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
 {
     uint32_t p = st >> 9, blk = (st >> 6) & 7u, zz = st & 63u;
     uint32_t done = 0;
-    // write mode: position of the current block inside its restart interval, its first
-    // coefficient, one past the image's last coefficient
-    uint32_t iv_pos = 0, boff = 0, bend = 0;
+    // write mode: first coefficient of the current block, the image's last coefficient,
+    // blocks left in the restart interval
+    uint32_t boff = 0, last = 0;
+    int32_t iv_rem = 0;
     if (kWrite) {
-        iv_pos = g.ri_blocks ? wc->block % g.ri_blocks : wc->block;
         boff = wc->block * 64u;
-        bend = g.n_blocks * 64u;
+        last = g.n_blocks * 64u - 1u;
+        iv_rem = wc->iv_rem;
     }
     uint32_t nb = boundary_from(S, (p + 7) >> 3, limit_bits);
     const uint16_t *lut = S.tab.lut;
@@ -381,25 +393,47 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
         if (p < fast_end) {
             // tb: first entry of the current table (DC luma 0, AC luma 1024, DC chroma 2048, AC 3072)
             uint32_t tb = (blk >= g.n_luma ? chroma_tb : 0u) | (zz ? ac_bit : 0u);
-            int32_t bad = kWrite ? wc->need_restart : 0;  // data where a restart marker had to come
+            // what a writing pass has to refuse is gathered without branches: no_code = bits
+            // that are no code word; bit 6 of over = a coefficient index past its block; sign
+            // of late = a symbol where a restart marker had to come
+            int32_t no_code = 0, late = 0;
+            uint32_t over = 0;
+            // the stream words that hold bit p, the one after, and the one after that, kept in
+            // registers: a symbol is shorter than a word, so at most one new word is needed
+            // per symbol, and it is fetched one symbol ahead of its use
+            uint32_t w = p >> 5;
+            uint32_t hi = S.clean[clean_index(g, w)], lo = S.clean[clean_index(g, w + 1)];
+            uint32_t ahead = S.clean[clean_index(g, w + 2)];
             do {
-                const uint32_t win = window32(S, p);
+                const uint32_t win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
                 uint32_t e = lut[tb + (win >> (32 - kLutBits))];
                 if (__builtin_expect((e >> 11) == 0, 0)) {
                     e = resolve_long_code(S.tab, e, tb >> kLutBits, win);
                     if ((e >> 11) == 0) {
-                        bad = 1;  // bits that are no code word
+                        no_code = 1;
                         e = kInvalidEntry;
                     }
                 }
                 const uint32_t adv = e >> 11;
-                const uint32_t k = zz + ((e >> 4) & 63u);  // index of a stored coefficient
+                const uint32_t k = zz + ((e >> 4) & 63u);  // index of the symbol's coefficient
                 if (kWrite) {
-                    const bool st_ok = (e & kStore) != 0 && k < 64u && boff < bend;
-                    if (st_ok) wc->coef[boff + k] = (int16_t)coefficient_value(win, adv, e & 15u);
-                    bad |= (e & kStore) != 0 && !st_ok;
+                    // Every symbol stores.  ZRL and EOB carry no appended bits, so their value
+                    // is 0, and it lands on a coefficient that they declare to be zero: the
+                    // last of ZRL's sixteen, the last of the block for EOB.  A stream that runs
+                    // past the image keeps overwriting the image's last coefficient; the block
+                    // count then gives it away.
+                    wc->coef[min(boff + min(k, 63u), last)] = (int16_t)coefficient_value(win, adv, e & 15u);
+                    over |= (e >> 4) & k;
+                    late |= iv_rem - 1;
                 }
                 p += adv;
+                {
+                    const bool moved = (p >> 5) != w;
+                    hi = moved ? lo : hi;
+                    lo = moved ? ahead : lo;
+                    w += moved ? 1u : 0u;
+                    ahead = S.clean[clean_index(g, w + 2)];
+                }
                 const bool endb = k >= 63u;  // zz = k + 1 reaches 64
                 const uint32_t blk1 = blk + 1u == g.bpm ? 0u : blk + 1u;
                 zz = endb ? 0u : k + 1u;
@@ -408,23 +442,14 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                 tb = endb ? (blk1 >= g.n_luma ? chroma_tb : 0u) : tb | ac_bit;
                 if (kWrite) {
                     boff += endb ? 64u : 0u;
-                    iv_pos += endb ? 1u : 0u;
-                    // after the last block of an interval only a restart boundary may follow,
-                    // and the fast loop is never that close to one
-                    const bool wrap = g.ri_blocks != 0 && iv_pos == g.ri_blocks;
-                    iv_pos = wrap ? 0u : iv_pos;
-                    bad |= wrap && boff < bend && p < fast_end;
-                    wc->need_restart = wrap && boff < bend;
+                    iv_rem -= endb ? 1 : 0;
                 }
             } while (p < fast_end);
-            if (kWrite) {
-                wc->bad |= bad;
-                wc->block = boff >> 6;
-            }
+            if (kWrite) wc->bad |= no_code | (late < 0 ? 1 : 0) | (int32_t)((over >> 6) & 1u);
             if (p >= end_bit) break;
         }
         // ---- one careful step near a boundary or the end of the data -----------------------
-        const uint32_t win = window32(S, p);
+        const uint32_t win = window32(S, g, p);
         const uint32_t tsel = (blk >= g.n_luma ? 2u : 0u) | (zz ? 1u : 0u);
         uint32_t e = lut[(tsel << kLutBits) + (win >> (32 - kLutBits))];
         bool found = true;
@@ -441,8 +466,12 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                 break;
             }
             if (kWrite) {
-                if (blk != 0 || zz != 0 || nb - p >= 8 || iv_pos != 0 || g.ri_blocks == 0) wc->bad = 1;
-                wc->need_restart = 0;
+                // a boundary comes between MCUs, behind fewer than eight padding bits, and
+                // after a whole interval (or right where one has just begun)
+                if (blk != 0 || zz != 0 || nb - p >= 8 || g.ri_blocks == 0 ||
+                    (iv_rem != 0 && iv_rem != (int32_t)g.ri_blocks))
+                    wc->bad = 1;
+                iv_rem = (int32_t)g.ri_blocks;
             }
             p = nb;
             blk = 0;
@@ -453,9 +482,9 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
         const uint32_t k = zz + ((e >> 4) & 63u);
         if (kWrite) {
             // bits that are no code word, or data where a restart marker had to come
-            if (!found || wc->need_restart) wc->bad = 1;
+            if (!found || iv_rem <= 0) wc->bad = 1;
             if (e & kStore) {
-                if (k < 64u && boff < bend) wc->coef[boff + k] = (int16_t)coefficient_value(win, adv, e & 15u);
+                if (k < 64u && boff <= last) wc->coef[boff + k] = (int16_t)coefficient_value(win, adv, e & 15u);
                 else wc->bad = 1;
             }
         }
@@ -467,12 +496,7 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
             done++;
             if (kWrite) {
                 boff += 64u;
-                wc->block = boff >> 6;
-                iv_pos++;
-                if (g.ri_blocks && iv_pos == g.ri_blocks) {
-                    iv_pos = 0;
-                    if (boff < bend) wc->need_restart = 1;
-                }
+                iv_rem--;
             }
         }
     }
@@ -481,42 +505,83 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
 }
 
 // DC differences -> DC values (T.81 F.2.2.1) for blocks [lo, hi) of the image, by the whole
-// workgroup: each lane takes a contiguous run of blocks, sums its differences per component
-// (a sum restarts where a restart interval begins), a segmented scan over the lanes carries
-// the running values in, and a second walk writes them.  carry[] = running value of each
+// wave: each lane takes a contiguous run of blocks, sums its differences per component (a
+// sum restarts where a restart interval begins), a segmented scan over the lanes carries the
+// running values in, and a second walk writes them.  carry[] = running value of each
 // component before block lo; on return, after block hi - 1.  All lanes must call.
-__device__ inline void dc_prefix(DecodeShared &S, const Geometry &g, int16_t *coef, uint32_t lo,
-                                 uint32_t hi, int32_t carry[3])
+// Blocks are read eight at a time so that the loads do not wait for one another.
+struct DcWalk {
+    uint32_t in_mcu, in_iv;  // position of the block in its MCU and in its restart interval
+    __device__ inline void start(const Geometry &g, uint32_t block)
+    {
+        in_mcu = block % g.bpm;
+        in_iv = g.ri_blocks ? block % g.ri_blocks : block;
+    }
+    // the first block of each component in the first MCU of an interval restarts DC prediction
+    __device__ inline bool restarts(const Geometry &g) const
+    {
+        return in_iv == 0 || (in_iv >= g.n_luma && in_iv < g.bpm);
+    }
+    __device__ inline uint32_t comp(const Geometry &g) const { return comp_of_block(g, in_mcu); }
+    __device__ inline void next(const Geometry &g)
+    {
+        in_mcu = in_mcu + 1u == g.bpm ? 0u : in_mcu + 1u;
+        in_iv++;
+        if (g.ri_blocks && in_iv == g.ri_blocks) in_iv = 0;
+    }
+};
+
+__device__ inline void dc_prefix(const Geometry &g, int16_t *coef, uint32_t lo, uint32_t hi,
+                                 int32_t carry[3])
 {
     __syncthreads();  // the coefficient stores of every lane are done and visible
     const uint32_t n = hi > lo ? hi - lo : 0u;
     const uint32_t per = (n + kT - 1) / kT;
     const uint32_t a = min(lo + threadIdx.x * per, hi), b = min(a + per, hi);
     int32_t s0 = 0, s1 = 0, s2 = 0, r0 = 0, r1 = 0, r2 = 0;
-    for (uint32_t i = a; i < b; i++) {
-        const int32_t d = coef[(size_t)i * 64];
-        const uint32_t c = comp_of_block(g, i % g.bpm);
-        const bool rst = first_of_interval(g, i);
-        if (c == 0) { s0 = (rst ? 0 : s0) + d; r0 |= rst; }
-        else if (c == 1) { s1 = (rst ? 0 : s1) + d; r1 |= rst; }
-        else { s2 = (rst ? 0 : s2) + d; r2 |= rst; }
+    DcWalk wk;
+    wk.start(g, a);
+    for (uint32_t i = a; i < b; i += 8) {
+        int32_t d[8];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; u++) d[u] = coef[(size_t)min(i + u, b - 1) * 64];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; u++) {
+            if (i + u < b) {
+                const uint32_t c = wk.comp(g);
+                const bool rst = wk.restarts(g);
+                if (c == 0) { s0 = (rst ? 0 : s0) + d[u]; r0 |= rst; }
+                else if (c == 1) { s1 = (rst ? 0 : s1) + d[u]; r1 |= rst; }
+                else { s2 = (rst ? 0 : s2) + d[u]; r2 |= rst; }
+                wk.next(g);
+            }
+        }
     }
     int32_t out;
-    int32_t c0 = block_seg_excl_scan(s0, r0, carry[0], S.dc_val[0], S.dc_flag[0], &out);
+    int32_t c0 = wave_seg_excl_scan(s0, r0, carry[0], &out);
     carry[0] = out;
-    int32_t c1 = block_seg_excl_scan(s1, r1, carry[1], S.dc_val[1], S.dc_flag[1], &out);
+    int32_t c1 = wave_seg_excl_scan(s1, r1, carry[1], &out);
     carry[1] = out;
-    int32_t c2 = block_seg_excl_scan(s2, r2, carry[2], S.dc_val[2], S.dc_flag[2], &out);
+    int32_t c2 = wave_seg_excl_scan(s2, r2, carry[2], &out);
     carry[2] = out;
-    for (uint32_t i = a; i < b; i++) {
-        const int32_t d = coef[(size_t)i * 64];
-        const uint32_t c = comp_of_block(g, i % g.bpm);
-        const bool rst = first_of_interval(g, i);
-        int32_t v;
-        if (c == 0) { c0 = (rst ? 0 : c0) + d; v = c0; }
-        else if (c == 1) { c1 = (rst ? 0 : c1) + d; v = c1; }
-        else { c2 = (rst ? 0 : c2) + d; v = c2; }
-        coef[(size_t)i * 64] = (int16_t)v;
+    wk.start(g, a);
+    for (uint32_t i = a; i < b; i += 8) {
+        int32_t d[8];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; u++) d[u] = coef[(size_t)min(i + u, b - 1) * 64];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; u++) {
+            if (i + u < b) {
+                const uint32_t c = wk.comp(g);
+                const bool rst = wk.restarts(g);
+                int32_t v;
+                if (c == 0) { c0 = (rst ? 0 : c0) + d[u]; v = c0; }
+                else if (c == 1) { c1 = (rst ? 0 : c1) + d[u]; v = c1; }
+                else { c2 = (rst ? 0 : c2) + d[u]; v = c2; }
+                coef[(size_t)(i + u) * 64] = (int16_t)v;
+                wk.next(g);
+            }
+        }
     }
 }
 
@@ -566,7 +631,7 @@ __device__ inline void classify16(const uint4 v, uint32_t prev, uint32_t nextb, 
 }  // namespace
 
 // ---- kernel 1: restart markers per window -----------------------------------
-// window w of an image = raw bytes [w*kWindowBytes, (w+1)*kWindowBytes) of its
+// window w of an image = raw bytes [w*window_bytes, (w+1)*window_bytes) of its
 // entropy-coded segment.  cnt = RSTn markers whose FF byte lies in the window,
 // first = offset (from the segment start) of the first such FF byte.
 __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
@@ -574,7 +639,6 @@ __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
     uint32_t *__restrict__ win_count, uint32_t *__restrict__ win_first,
     int32_t *__restrict__ status)
 {
-    __shared__ uint32_t s_cnt[kT / 64], s_first[kT / 64];
     const uint32_t wg = blockIdx.x;
     const int img = find_image(n_images, wg, [&](int i) { return recs[i].window0; });
     const ImageRec &R = recs[img];
@@ -584,36 +648,35 @@ __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
     uint32_t cnt = 0, first = kNoMarker;
     if (R.status == PREP_OK && R.restart_interval != 0 && w < R.n_windows) {
         const uint8_t *seg = bits + R.file_off + R.entropy_rel;
-        const uint32_t lo = w * (uint32_t)kWindowBytes;
-        const uint32_t hi = min(lo + (uint32_t)kWindowBytes, R.entropy_len);
-        constexpr uint32_t per = kWindowBytes / kT;
-        uint32_t a = lo + threadIdx.x * per;
-        uint32_t b = min(a + per, hi);
-        if (a < b) {
-            uint32_t prev = load_byte(seg + a);
-            for (uint32_t i = a; i < b; i++) {
-                // the byte after the last one of the segment is the EOI marker's FF
-                uint32_t next = i + 1 < R.entropy_len ? load_byte(seg + i + 1) : 0xFFu;
-                if (prev == 0xFFu && next >= 0xD0u && next <= 0xD7u) {
+        const int32_t lo = (int32_t)(w * R.window_bytes);
+        const int32_t hi = (int32_t)min(w * R.window_bytes + R.window_bytes, R.entropy_len);
+        // 16-byte aligned parts that cover [lo, hi), dealt to the lanes in turn; a part that
+        // begins before lo reaches at most 15 bytes back, into the file's headers
+        const int32_t a0 = lo - (int32_t)((uintptr_t)(seg + lo) & 15u);
+        for (int32_t plo = a0 + 16 * (int32_t)threadIdx.x; plo < hi; plo += 16 * kT) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(seg + plo);
+            // the byte after the last one of the segment is the EOI marker's FF
+            const uint32_t after = load_byte(seg + min(plo + 16, (int32_t)R.entropy_len));
+            const uint32_t wv[5] = {v.x, v.y, v.z, v.w, after};
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const uint32_t cur = (wv[i >> 2] >> (8 * (i & 3))) & 255u;
+                const uint32_t nxt = (wv[(i + 1) >> 2] >> (8 * ((i + 1) & 3))) & 255u;
+                const int32_t pos = plo + i;
+                if (cur == 0xFFu && nxt >= 0xD0u && nxt <= 0xD7u && pos >= lo && pos < hi) {
                     cnt++;
-                    if (first == kNoMarker) first = i;
+                    first = min(first, (uint32_t)pos);
                 }
-                prev = next;
             }
         }
     }
-    // workgroup reduction
     for (int d = 32; d >= 1; d >>= 1) {
         cnt += __shfl_xor(cnt, d, 64);
         first = min(first, (uint32_t)__shfl_xor(first, d, 64));
     }
-    if ((threadIdx.x & 63) == 0) { s_cnt[threadIdx.x >> 6] = cnt; s_first[threadIdx.x >> 6] = first; }
-    __syncthreads();
     if (threadIdx.x == 0) {
-        uint32_t c = 0, f = kNoMarker;
-        for (int i = 0; i < kT / 64; i++) { c += s_cnt[i]; f = min(f, s_first[i]); }
-        win_count[wg] = c;
-        win_first[wg] = f;
+        win_count[wg] = cnt;
+        win_first[wg] = first;
     }
 }
 
@@ -630,8 +693,13 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     const ImageRec &R = recs[img];
     const uint32_t w = wg - R.window0;
     if (R.status != PREP_OK || w >= R.n_windows) return;
+    // clean bytes per lane, 64-byte pieces per lane, raw bytes per chunk
+    const uint32_t sub_bytes = R.sub_bytes, ppl = sub_bytes >> 6, sub_bits = sub_bytes * 8u;
+    const int32_t chunk_raw = (int32_t)(sub_bytes * kT);
+    if (sub_bytes != 64u && sub_bytes != 128u && sub_bytes != 256u) return;  // not a record of this library
 
     Geometry g;
+    g.pad_shift = sub_bytes == 64u ? 4u : sub_bytes == 128u ? 5u : 6u;
     g.bpm = R.blocks_per_mcu;
     g.n_luma = R.sampling == PREP_SAMPLING_420 ? 4u : 1u;
     g.ri_blocks = (uint32_t)R.restart_interval * g.bpm;
@@ -655,22 +723,6 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             uint32_t ow = __shfl_xor(next_w, d, 64), of = __shfl_xor(next_first, d, 64);
             if (ow < next_w) { next_w = ow; next_first = of; }
         }
-        if ((tid & 63) == 0) {
-            S.scan_a[tid >> 6] = before;
-            S.dc_val[0][tid >> 6] = (int32_t)next_w;
-            S.dc_val[1][tid >> 6] = (int32_t)next_first;
-        }
-        __syncthreads();
-        before = 0;
-        next_w = kNoMarker;
-        for (int i = 0; i < kT / 64; i++) {
-            before += S.scan_a[i];
-            if ((uint32_t)S.dc_val[0][i] < next_w) {
-                next_w = (uint32_t)S.dc_val[0][i];
-                next_first = (uint32_t)S.dc_val[1][i];
-            }
-        }
-        __syncthreads();
         if (w != 0) {
             range_lo = my_first + 2;
             block0 = (before + 1) * g.ri_blocks;  // markers before ours + ours = intervals done
@@ -680,12 +732,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             // markers up to and including the first one of window next_w
             uint32_t upto = 0;
             for (uint32_t i = tid; i < next_w; i += kT) upto += wc[i];
-            for (int d = 32; d >= 1; d >>= 1) upto += __shfl_xor(upto, d, 64);
-            if ((tid & 63) == 0) S.scan_a[tid >> 6] = upto;
-            __syncthreads();
-            upto = 0;
-            for (int i = 0; i < kT / 64; i++) upto += S.scan_a[i];
-            __syncthreads();
+            upto = wave_sum(upto);
             block_end = (upto + 1) * g.ri_blocks;
         }
     }
@@ -712,91 +759,123 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     const uint32_t max_chunks = (range_hi - range_lo) / 64u + 2;
     for (uint32_t iter = 0; iter < max_chunks && cs < rhi; iter++) {
         // ---- stage: destuff raw bytes [cs, ce) into S.clean --------------------------
-        // lanes own 64-byte pieces of the 16-byte aligned span that contains cs
+        // each lane owns sub_bytes consecutive raw bytes of the 16-byte aligned span that
+        // contains cs, handled as 64-byte pieces of four 16-byte parts
         const int32_t mis = (int32_t)((uintptr_t)(seg + cs) & 15u);
         const int32_t a0 = cs - mis;
-        const int32_t ce = min(a0 + (int32_t)kChunkRaw, rhi);
+        const int32_t ce = min(a0 + chunk_raw, rhi);
         const bool last = ce == rhi;
         __syncthreads();
-        for (int i = tid; i < kCleanWords; i += kT) S.clean[i] = 0;
         for (int i = tid; i < kMaskWords; i += kT) S.bmask[i] = 0;
-        const int32_t my_lo = a0 + tid * 64;  // raw offset of my first byte
-        const uint4 *src = reinterpret_cast<const uint4 *>(seg + my_lo);
-        unsigned long long keep = 0, bound = 0;
+        const int32_t my_lo = a0 + tid * (int32_t)sub_bytes;  // raw offset of my first byte
+        // 16-byte parts are loaded whether or not they still overlap [cs, ce] (what lies
+        // outside is not looked at), from an address clamped to the part that holds ce, so
+        // that the loads of a piece do not wait for one another
+        const int32_t last_part = a0 + ((ce - a0) & ~15);
+        uint32_t n_keep = 0, n_bound = 0;
         {
-            // the byte before my piece and the byte after each 16-byte part, for the FF xx
+            // the byte before my bytes and the byte after each 16-byte part, for the FF xx
             // pairs that straddle; past the segment comes the FF of the EOI marker
             uint32_t prev = 0;
             if (my_lo > cs && my_lo <= ce) prev = load_byte(seg + my_lo - 1);
-            for (int k = 0; k < 4; k++) {
-                const int32_t plo = my_lo + 16 * k;
-                uint32_t kp = 0, bd = 0;
-                // a part is looked at only if it overlaps [cs, ce]: the byte at ce (the FF of
-                // the marker that ends the run) is examined, not consumed
-                if (plo + 16 > cs && plo <= ce) {
-                    const uint4 v = src[k];
-                    uint32_t nextb = 0xFFu;
-                    if (plo + 16 < seg_len && plo + 16 <= ce) nextb = load_byte(seg + plo + 16);
-                    classify16(v, prev, nextb, plo, cs, ce, &kp, &bd, &prev, &bad);
-                } else {
-                    prev = 0;
+            for (uint32_t j = 0; j < ppl; j++) {
+                const int32_t pj = my_lo + (int32_t)(64 * j);
+                uint4 v[4];
+#pragma unroll
+                for (int k = 0; k < 4; k++)
+                    v[k] = *reinterpret_cast<const uint4 *>(seg + min(pj + 16 * k, last_part));
+                const uint32_t after = load_byte(seg + min(pj + 64, ce));
+                unsigned long long keep = 0, bound = 0;
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const int32_t plo = pj + 16 * k;
+                    uint32_t kp = 0, bd = 0;
+                    // a part is looked at only if it overlaps [cs, ce]: the byte at ce (the FF
+                    // of the marker that ends the run) is examined, not consumed
+                    if (plo <= ce) {
+                        uint32_t nextb = k < 3 ? (v[(k + 1) & 3].x & 255u) : after;
+                        if (!(plo + 16 < seg_len && plo + 16 <= ce)) nextb = 0xFFu;
+                        classify16(v[k], prev, nextb, plo, cs, ce, &kp, &bd, &prev, &bad);
+                    } else {
+                        prev = 0;
+                    }
+                    keep |= (unsigned long long)kp << (16 * k);
+                    bound |= (unsigned long long)bd << (16 * k);
                 }
-                keep |= (unsigned long long)kp << (16 * k);
-                bound |= (unsigned long long)bd << (16 * k);
+                S.keep[tid * ppl + j] = keep;
+                S.bound[tid * ppl + j] = bound;
+                n_keep += (uint32_t)__popcll(keep);
+                n_bound += (uint32_t)__popcll(bound);
             }
         }
         // clean offsets (low half) and boundary ranks (high half) in one scan
         uint32_t totals;
-        const uint32_t my_pre = block_excl_scan((uint32_t)__popcll(keep) | ((uint32_t)__popcll(bound) << 16),
-                                                S.scan_a, &totals);
+        const uint32_t my_pre = wave_excl_scan(n_keep | (n_bound << 16), &totals);
         const uint32_t clean_len = totals & 0xFFFFu, nbnd = totals >> 16;
-        const uint32_t my_off = my_pre & 0xFFFFu;
-        S.keep[tid] = keep;
-        S.keep_off[tid] = my_off;
-        if (tid == 0) S.keep_off[kT] = clean_len;
+        // zeros behind the data: the last word is written byte by byte, and lookups near the
+        // end read up to eight words past it
+        if (tid < 12) S.clean[clean_index(g, (clean_len >> 2) + (uint32_t)tid)] = 0;
         __syncthreads();  // zero fill done before bytes are written
         {
             uint8_t *cb = reinterpret_cast<uint8_t *>(S.clean);
-            uint32_t o = my_off, rank = my_pre >> 16;
-            for (int k = 0; k < 4; k++) {
-                const uint32_t kp = (uint32_t)(keep >> (16 * k)) & 0xFFFFu;
-                const uint32_t bd = (uint32_t)(bound >> (16 * k)) & 0xFFFFu;
-                if ((kp | bd) == 0) continue;
-                const uint4 v = src[k];
-                const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+            uint32_t o = my_pre & 0xFFFFu, rank = my_pre >> 16;
+            for (uint32_t j = 0; j < ppl; j++) {
+                const unsigned long long keep = S.keep[tid * ppl + j], bound = S.bound[tid * ppl + j];
+                S.keep_off[tid * ppl + j] = o;
+                if ((keep | bound) == 0) continue;
+                const int32_t pj = my_lo + (int32_t)(64 * j);
+                uint4 v[4];
 #pragma unroll
-                for (int i = 0; i < 16; i++) {
-                    if ((bd >> i) & 1u) {
-                        atomicOr(&S.bmask[o >> 5], 1u << (o & 31));
-                        if (rank < (uint32_t)kMaxBoundaries) S.bpos[rank] = (uint16_t)o;
-                        // raw offset just after the last marker of the chunk: where a chunk of
-                        // whole intervals would resume
-                        if (rank + 1 == nbnd) S.bcast[2] = (uint32_t)(my_lo + 16 * k + i + 1);
-                        rank++;
-                    }
-                    if ((kp >> i) & 1u) {
-                        cb[o ^ 3u] = (uint8_t)((wv[i >> 2] >> (8 * (i & 3))) & 255u);
-                        o++;
+                for (int k = 0; k < 4; k++)
+                    v[k] = *reinterpret_cast<const uint4 *>(seg + min(pj + 16 * k, last_part));
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const uint32_t kp = (uint32_t)(keep >> (16 * k)) & 0xFFFFu;
+                    const uint32_t bd = (uint32_t)(bound >> (16 * k)) & 0xFFFFu;
+                    if ((kp | bd) == 0) continue;
+                    const uint32_t wv[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+#pragma unroll
+                    for (int i = 0; i < 16; i++) {
+                        if ((bd >> i) & 1u) {
+                            atomicOr(&S.bmask[o >> 5], 1u << (o & 31));
+                            if (rank < (uint32_t)kMaxBoundaries) S.bpos[rank] = (uint16_t)o;
+                            // raw offset just after the last marker of the chunk: where a chunk
+                            // of whole intervals would resume
+                            if (rank + 1 == nbnd) S.bcast[2] = (uint32_t)(pj + 16 * k + i + 1);
+                            rank++;
+                        }
+                        if ((kp >> i) & 1u) {
+                            cb[(clean_index(g, o >> 2) << 2) | ((o & 3u) ^ 3u)] = (uint8_t)((wv[i >> 2] >> (8 * (i & 3))) & 255u);
+                            o++;
+                        }
                     }
                 }
             }
         }
         __syncthreads();
         {
-            // first interval start at or after each lane's subsequence: suffix minimum
-            unsigned long long m = ((unsigned long long)S.bmask[2 * tid + 1] << 32) | S.bmask[2 * tid];
-            uint32_t mine = m ? (uint32_t)tid * 64u + (uint32_t)__builtin_ctzll(m) : kNoMarker;
-            const int lane = tid & 63, wave = tid >> 6;
-            for (int d = 1; d < 64; d <<= 1) {
-                uint32_t o = __shfl_down(mine, d, 64);
-                if (lane + d < 64) mine = min(mine, o);
+            // first interval start at or after each 64-byte clean piece: suffix minimum over
+            // the pieces, four consecutive ones per lane
+            uint32_t mine[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const uint32_t pc = 4u * (uint32_t)tid + (uint32_t)i;
+                const unsigned long long m = ((unsigned long long)S.bmask[2 * pc + 1] << 32) | S.bmask[2 * pc];
+                mine[i] = m ? pc * 64u + (uint32_t)__builtin_ctzll(m) : kNoMarker;
             }
-            if (lane == 0) S.scan_a[wave] = mine;
-            __syncthreads();
-            uint32_t later = kNoMarker;
-            for (int ww = wave + 1; ww < kT / 64; ww++) later = min(later, S.scan_a[ww]);
-            S.next_boundary[tid] = min(mine, later);
-            if (tid == 0) S.next_boundary[kT] = kNoMarker;
+            mine[2] = min(mine[2], mine[3]);
+            mine[1] = min(mine[1], mine[2]);
+            mine[0] = min(mine[0], mine[1]);
+            uint32_t suffix = mine[0];  // becomes the minimum over this lane and all later ones
+            for (int d = 1; d < 64; d <<= 1) {
+                uint32_t o = __shfl_down(suffix, d, 64);
+                if (tid + d < 64) suffix = min(suffix, o);
+            }
+            uint32_t later = __shfl_down(suffix, 1, 64);
+            if (tid == 63) later = kNoMarker;
+#pragma unroll
+            for (int i = 0; i < 4; i++) S.next_boundary[4 * tid + i] = min(mine[i], later);
+            if (tid == 0) S.next_boundary[kChunkPieces] = kNoMarker;
         }
         __syncthreads();
 
@@ -813,15 +892,13 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         if (g.ri_blocks != 0 && n_iv >= 1 && nbnd <= (uint32_t)kMaxBoundaries &&
             clean_len <= kShortInterval * (nbnd + 1)) {
             const uint32_t rem0 = g.ri_blocks - block_base % g.ri_blocks;  // blocks left in interval 0
-            // consecutive intervals go to different waves so that every SIMD gets some
-            const uint32_t slot = ((uint32_t)tid & 63u) * (kT / 64) + ((uint32_t)tid >> 6);
-            for (uint32_t k = slot; k < n_iv; k += kT) {
+            for (uint32_t k = (uint32_t)tid; k < n_iv; k += kT) {
                 const uint32_t start = k ? pack_state((uint32_t)S.bpos[k - 1] * 8u, 0, 0) : st0;
                 const uint32_t end_bit = k < nbnd ? (uint32_t)S.bpos[k] * 8u : limit_bits;
                 const uint32_t blk0 = k ? block_base + rem0 + (k - 1) * g.ri_blocks : block_base;
                 const uint32_t want = min(k ? g.ri_blocks : rem0, block_end > blk0 ? block_end - blk0 : 0u);
                 wc.block = blk0;
-                wc.need_restart = 0;
+                wc.iv_rem = (int32_t)(k ? g.ri_blocks : rem0);
                 uint32_t got;
                 const uint32_t fin = decode_span<true>(S, g, start, end_bit, limit_bits, &got, &wc);
                 // the interval must end on its boundary, between MCUs, with all its blocks
@@ -832,7 +909,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
                 // DC values of the blocks whose DC was decoded here (the chunk may begin inside a block)
                 const uint32_t dc_lo = block_base + ((st0 & 63u) ? 1u : 0u);
                 block_base = min(block_base + rem0 + (n_iv - 1) * g.ri_blocks, block_end);
-                dc_prefix(S, g, coef, dc_lo, min(block_base, g.n_blocks), dc_carry);
+                dc_prefix(g, coef, dc_lo, min(block_base, g.n_blocks), dc_carry);
             }
             st0 = pack_state(0, 0, 0);
             dc_carry[0] = dc_carry[1] = dc_carry[2] = 0;
@@ -848,20 +925,18 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         // a chunk that is not the last keeps a tail back so that no symbol straddles its end
         const uint32_t own_bits = last ? limit_bits
                                        : (clean_len > (uint32_t)kChunkTail ? (clean_len - kChunkTail) * 8u : 0u);
-        const uint32_t nsub = (own_bits + kSubBits - 1) / kSubBits;  // <= kT
+        const uint32_t nsub = (own_bits + sub_bits - 1) / sub_bits;  // <= kT
         const bool active = (uint32_t)tid < nsub;
-        const uint32_t end_bit = min(((uint32_t)tid + 1u) * kSubBits, own_bits);
+        const uint32_t end_bit = min(((uint32_t)tid + 1u) * sub_bits, own_bits);
 
         // synchronise: iterate end states to their fixed point
-        uint32_t in_state = tid == 0 ? st0 : pack_state((uint32_t)tid * kSubBits, 0, 0);
+        uint32_t in_state = tid == 0 ? st0 : pack_state((uint32_t)tid * sub_bits, 0, 0);
         uint32_t out_state = in_state, nblk = 0;
         if (active) out_state = decode_span<false>(S, g, in_state, end_bit, limit_bits, &nblk, nullptr);
-        S.state[tid] = out_state;
         for (uint32_t round = 0; round <= nsub; round++) {
-            __syncthreads();
             int changed = 0;
-            const uint32_t prev_state = tid > 0 ? S.state[tid - 1] : st0;
-            __syncthreads();
+            uint32_t prev_state = __shfl_up(out_state, 1, 64);
+            if (tid == 0) prev_state = st0;
             if (active && tid > 0 && prev_state != in_state) {
                 in_state = prev_state;
                 uint32_t o = in_state;
@@ -869,20 +944,20 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
                 if ((in_state >> 9) < end_bit) o = decode_span<false>(S, g, in_state, end_bit, limit_bits, &nblk, nullptr);
                 else nblk = 0;
                 if (o != out_state) { out_state = o; changed = 1; }
-                S.state[tid] = out_state;
             }
             if (!__syncthreads_or(changed)) break;
         }
 
         // write: decode once more from the true states
         uint32_t total_blocks;
-        const uint32_t my_block = block_base + block_excl_scan(active ? nblk : 0u, S.scan_a, &total_blocks);
+        const uint32_t my_block = block_base + wave_excl_scan(active ? nblk : 0u, &total_blocks);
         wc.block = my_block;
         // a lane that begins on an MCU boundary where an interval ends must meet the boundary
         // first; lane 0 of a chunk may begin just after one (start of the run, or a boundary
         // consumed at the very end of the previous chunk)
-        wc.need_restart = (in_state & 511u) == 0 && g.ri_blocks != 0 && my_block % g.ri_blocks == 0 &&
-                          my_block < g.n_blocks && tid != 0;
+        const bool boundary_due = (in_state & 511u) == 0 && g.ri_blocks != 0 && my_block % g.ri_blocks == 0 &&
+                                  my_block < g.n_blocks && tid != 0;
+        wc.iv_rem = boundary_due ? 0 : g.ri_blocks ? (int32_t)(g.ri_blocks - my_block % g.ri_blocks) : 0x7FFFFFFF;
         uint32_t final_state = out_state;
         if (active && (in_state >> 9) < end_bit) {
             uint32_t nb2;
@@ -890,16 +965,14 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             if (final_state != out_state || nb2 != nblk) wc.bad = 1;
         }
         bad |= wc.bad;
-        __syncthreads();
-        if (tid == 0) S.bcast[0] = nsub ? S.state[nsub - 1] : st0;
-        __syncthreads();
-        const uint32_t fs = S.bcast[0];
+        // true end state of the chunk: that of its last subsequence
+        const uint32_t fs = nsub ? __shfl(out_state, (int)nsub - 1, 64) : st0;
         {
             // DC values of the blocks whose DC was decoded in this chunk: it may begin inside
             // a block (DC decoded earlier) and end inside one (DC decoded here)
             const uint32_t dc_lo = block_base + ((st0 & 63u) ? 1u : 0u);
             const uint32_t dc_hi = block_base + total_blocks + ((fs & 63u) ? 1u : 0u);
-            dc_prefix(S, g, coef, dc_lo, min(dc_hi, g.n_blocks), dc_carry);
+            dc_prefix(g, coef, dc_lo, min(dc_hi, g.n_blocks), dc_carry);
         }
 
         // carry the true end state into the next chunk
@@ -914,11 +987,16 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             cs = rhi;
             break;
         }
-        if (S.keep_off[tid] <= qc && qc < S.keep_off[tid] + (uint32_t)__popcll(S.keep[tid])) {
-            unsigned long long m = S.keep[tid];
-            const uint32_t skip = qc - S.keep_off[tid];
-            for (uint32_t i = 0; i < skip; i++) m &= m - 1;  // drop the lowest set bits
-            S.bcast[1] = (uint32_t)(a0 + tid * 64 + (int32_t)__builtin_ctzll(m));
+        if (tid == 0) S.bcast[1] = 0;
+        __syncthreads();
+        for (uint32_t j = 0; j < ppl; j++) {
+            const uint32_t off = S.keep_off[tid * ppl + j];
+            unsigned long long m = S.keep[tid * ppl + j];
+            if (off <= qc && qc < off + (uint32_t)__popcll(m)) {
+                const uint32_t skip = qc - off;
+                for (uint32_t i = 0; i < skip; i++) m &= m - 1;  // drop the lowest set bits
+                S.bcast[1] = (uint32_t)(my_lo + (int32_t)(64 * j) + (int32_t)__builtin_ctzll(m));
+            }
         }
         __syncthreads();
         const int32_t next_cs = (int32_t)S.bcast[1];

@@ -111,6 +111,8 @@ inline int __syncthreads_or(int p)
     return r;
 }
 template <typename T>
+inline T __shfl(T v, int src, int = 64) { return hip_emul::shuffle(v, [src](int) { return src; }); }
+template <typename T>
 inline T __shfl_up(T v, unsigned d, int = 64) { return hip_emul::shuffle(v, [d](int l) { return l - (int)d; }); }
 template <typename T>
 inline T __shfl_down(T v, unsigned d, int = 64) { return hip_emul::shuffle(v, [d](int l) { return l + (int)d; }); }
