@@ -150,9 +150,7 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
             R.entropy_rel = (uint32_t)I.entropy_offset;
             R.entropy_len = (uint32_t)I.entropy_bytes;
             R.n_blocks = (uint32_t)((uint64_t)I.mcu_cols * I.mcu_rows * I.blocks_per_mcu);
-            R.sub_bytes = subseq_bytes_for(I.entropy_bytes, (uint64_t)I.n_intervals);
-            R.window_bytes = window_bytes_for(R.sub_bytes);
-            R.n_windows = (uint32_t)((I.entropy_bytes + R.window_bytes - 1) / R.window_bytes);
+            R.n_windows = (uint32_t)((I.entropy_bytes + kWindowBytes - 1) / kWindowBytes);
             if (R.n_windows == 0) R.n_windows = 1;
             R.rgb_pitch = (uint32_t)I.mcu_cols * 8u * hs * 3u;
             const int per = recon_mcus_per_group(I.sampling);
@@ -292,7 +290,7 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     const uint64_t padded = px + 15ull * n * ((uint64_t)cfg->max_width + cfg->max_height) + 225ull * n;
     h->cap_blocks = padded * 3 / 64 + 6 * n;       // 4:4:4 worst case: 3 blocks per 64 pixels
     h->cap_rgb = padded * 3 + (kRgbAlign + kRgbSlack) * n;
-    h->cap_windows = cfg->max_bitstream_bytes / window_bytes_for(kMinSubseqBytes) + n + 1;
+    h->cap_windows = cfg->max_bitstream_bytes / kWindowBytes + n + 1;
     h->cap_bits = cfg->max_bitstream_bytes + kBitsPad;
     if (h->cap_blocks > 0xFFFFFFFFull) { delete h; return PREP_E_TOO_LARGE; }
 

@@ -1,11 +1,8 @@
 // GPU Huffman entropy decoder for baseline JPEG (T.81 F.2.2), gfx950.
 //
 // The first half of the "Decode" functional unit (PREBA section 4.2, Table 1).
-// The FPGA decodes one stream serially per compute unit; here one workgroup of a
-// single wave owns a run of whole restart intervals (T.81 E.2.4) of one image.  A
-// decoding lane is bound by the latency of its own dependent instruction chain, so
-// the work is arranged to put as many busy lanes as possible into each wave and one
-// wave on each SIMD, rather than spreading a chunk's lanes over several waves:
+// The FPGA decodes one stream serially per compute unit; here one workgroup owns
+// a run of whole restart intervals (T.81 E.2.4) of one image:
 //
 //   1. scan_restart_markers counts the RSTn markers in fixed windows of every
 //      image's entropy-coded segment, so that a workgroup starting at the first
@@ -35,12 +32,15 @@ namespace prep {
 namespace {
 
 constexpr int kT = kDecodeThreads;
-constexpr int kCleanWords = kChunkRaw / 4 + kDecodeThreads + 16;  // destuffed stream, one pad word per lane, zero tail
+constexpr int kPadShift = 4;                        // one pad word after every 16 words (= one subsequence)
+constexpr int kCleanWords = kChunkRaw / 4 + kT + 16;  // destuffed stream, pad words, zero tail
 constexpr int kMaskWords = kChunkRaw / 32 + 2;      // one bit per clean byte
 constexpr int kSubEntries = 256;                    // second-level lookup entries per table
 constexpr int kMaxBoundaries = 1024;                // listed interval starts per chunk
+constexpr uint32_t kShortInterval = 1024;           // mean clean bytes up to which a lane takes a whole interval
 constexpr uint32_t kNoMarker = 0xFFFFFFFFu;
-static_assert(kT == 64, "the workgroup is one wave: scans and state exchange use lane shuffles only");
+constexpr uint32_t kSubBits = kSubseqBytes * 8;
+static_assert(kSubseqBytes == 64 && (kSubseqBytes / 4) == (1 << kPadShift), "one 64-bit keep mask per lane");
 
 // Lookup entry of a Huffman code (16 bits):
 //   bits 15..11 code length + number of appended bits (1..31); 0 = not a code entry
@@ -65,16 +65,19 @@ struct HuffTables {
 
 struct DecodeShared {
     // The destuffed stream, big-endian packed (bit 31 of a word is the earliest bit), with one
-    // unused word after every sub_bytes / 4 words: lanes that read at similar offsets of their
+    // unused word after every 16 words: lanes that read at similar offsets of their
     // subsequences then hit different LDS banks instead of all the same one.
     uint32_t clean[kCleanWords];
     uint32_t bmask[kMaskWords];      // bit q set: a restart interval begins at clean byte q
-    uint32_t next_boundary[kChunkPieces + 1];  // first interval start at or after each 64-byte clean piece
+    uint32_t next_boundary[kT + 1];  // first interval start at or after the lane's subsequence
     uint16_t bpos[kMaxBoundaries];   // interval starts of the chunk in order (clean byte offsets)
     HuffTables tab;                  // DC luma, AC luma, DC chroma, AC chroma
-    unsigned long long keep[kChunkPieces];   // which bytes of each 64-byte raw piece survived destuffing
-    unsigned long long bound[kChunkPieces];  // which are the code byte of an RSTn marker
-    uint32_t keep_off[kChunkPieces];         // clean offset of the piece's first surviving byte
+    unsigned long long keep[kT];     // which of the lane's 64 raw bytes survived destuffing
+    uint32_t keep_off[kT + 1];       // clean offset of the lane's first surviving byte
+    uint32_t state[kT];              // end state of every subsequence
+    uint32_t scan_a[kT / 64 + 1];    // per-wave totals for workgroup scans
+    int32_t dc_val[kT / 64 + 1];
+    int32_t dc_flag[kT / 64 + 1];
     uint32_t bcast[8];
 };
 
@@ -83,7 +86,7 @@ __device__ inline uint32_t pack_state(uint32_t p, uint32_t blk, uint32_t zz)
     return (p << 9) | (blk << 6) | zz;
 }
 
-// ---- wave-wide helpers ---------------------------------------------------------
+// ---- workgroup-wide helpers (kT threads, wave64) ---------------------------
 
 __device__ inline uint32_t wave_incl_scan(uint32_t v)
 {
@@ -96,26 +99,46 @@ __device__ inline uint32_t wave_incl_scan(uint32_t v)
     return v;
 }
 
-// exclusive prefix sum over the wave; *total receives the sum
-__device__ inline uint32_t wave_excl_scan(uint32_t v, uint32_t *total)
+// exclusive prefix sum over the workgroup; *total receives the sum
+__device__ inline uint32_t block_excl_scan(uint32_t v, uint32_t *wave_tot, uint32_t *total)
 {
-    const uint32_t inc = wave_incl_scan(v);
-    *total = __shfl(inc, 63, 64);
-    return inc - v;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t inc = wave_incl_scan(v);
+    __syncthreads();
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kT / 64; w++) {
+        uint32_t t = wave_tot[w];
+        if (w < wave) base += t;
+        tot += t;
+    }
+    *total = tot;
+    return base + inc - v;
 }
 
-__device__ inline uint32_t wave_sum(uint32_t v)
+// sum over the workgroup
+__device__ inline uint32_t block_sum(uint32_t v, uint32_t *wave_tot)
 {
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-    return v;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) wave_tot[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint32_t tot = 0;
+#pragma unroll
+    for (int w = 0; w < kT / 64; w++) tot += wave_tot[w];
+    return tot;
 }
 
 // Segmented running sum (value, reset flag): a reset discards what came before.
 // Returns the value carried INTO this lane (exclusive); carry_in seeds lane 0.
-__device__ inline int32_t wave_seg_excl_scan(int32_t v, int32_t f, int32_t carry_in, int32_t *carry_out)
+__device__ inline int32_t block_seg_excl_scan(int32_t v, int32_t f, int32_t carry_in,
+                                              int32_t *wave_val, int32_t *wave_flag,
+                                              int32_t *carry_out)
 {
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int32_t iv = v, ifl = f;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -126,12 +149,22 @@ __device__ inline int32_t wave_seg_excl_scan(int32_t v, int32_t f, int32_t carry
             ifl |= of;
         }
     }
-    const int32_t lv = __shfl(iv, 63, 64), lf = __shfl(ifl, 63, 64);
-    *carry_out = lf ? lv : carry_in + lv;
-    const int32_t pv = __shfl_up(iv, 1, 64);
-    const int32_t pf = __shfl_up(ifl, 1, 64);
-    if (lane == 0) return carry_in;
-    return pf ? pv : carry_in + pv;
+    __syncthreads();
+    if (lane == 63) { wave_val[wave] = iv; wave_flag[wave] = ifl; }
+    __syncthreads();
+    int32_t cv = carry_in, all_v = carry_in;
+#pragma unroll
+    for (int w = 0; w < kT / 64; w++) {
+        int32_t wv = wave_val[w], wf = wave_flag[w];
+        int32_t nv = wf ? wv : all_v + wv;
+        if (w < wave) cv = nv;
+        all_v = nv;
+    }
+    *carry_out = all_v;
+    int32_t pv = __shfl_up(iv, 1, 64);
+    int32_t pf = __shfl_up(ifl, 1, 64);
+    if (lane == 0) return cv;
+    return pf ? pv : cv + pv;
 }
 
 // ---- Huffman tables (T.81 Annex C) --------------------------------------------
@@ -272,7 +305,6 @@ __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const Im
 // ---- bit-level decoding ------------------------------------------------------
 
 struct Geometry {
-    uint32_t pad_shift;  // log2 of the words between pad words of the staged stream
     uint32_t bpm;        // blocks per MCU
     uint32_t n_luma;     // luma blocks per MCU (blocks >= n_luma use the chroma tables)
     uint32_t ri_blocks;  // blocks per restart interval, 0 = none
@@ -288,7 +320,7 @@ __device__ inline uint32_t comp_of_block(const Geometry &g, uint32_t blk_in_mcu)
 __device__ inline uint32_t boundary_from(const DecodeShared &S, uint32_t q, uint32_t limit_bits)
 {
     const uint32_t j = q >> 6;
-    if (j >= (uint32_t)kChunkPieces) return limit_bits;
+    if (j >= (uint32_t)kT) return limit_bits;
     unsigned long long m = ((unsigned long long)S.bmask[2 * j + 1] << 32) | S.bmask[2 * j];
     m >>= (q & 63);
     uint32_t r = m ? q + (uint32_t)__builtin_ctzll(m) : S.next_boundary[j + 1];
@@ -331,17 +363,17 @@ __device__ __forceinline__ uint32_t resolve_long_code(const HuffTables &T, uint3
 }
 
 // word w of the destuffed stream lives at this index of DecodeShared::clean
-__device__ __forceinline__ uint32_t clean_index(const Geometry &g, uint32_t w)
+__device__ __forceinline__ uint32_t clean_index(uint32_t w)
 {
-    return w + (w >> g.pad_shift);
+    return w + (w >> kPadShift);
 }
 
 // The next 32 bits of the staged stream at bit position p (two LDS words and a shift).
 __device__ __forceinline__ uint32_t window32(const DecodeShared &S, const Geometry &g, uint32_t p)
 {
     const uint32_t w = min(p >> 5, (uint32_t)(kChunkRaw / 4 + 8));
-    const unsigned long long pair = ((unsigned long long)S.clean[clean_index(g, w)] << 32) |
-                                    S.clean[clean_index(g, w + 1)];
+    const unsigned long long pair = ((unsigned long long)S.clean[clean_index(w)] << 32) |
+                                    S.clean[clean_index(w + 1)];
     return (uint32_t)(pair >> (32 - (p & 31u)));
 }
 
@@ -356,22 +388,25 @@ __device__ __forceinline__ int32_t coefficient_value(uint32_t win, uint32_t adv,
 
 // Decode from packed state `st` until the bit position reaches end_bit.
 // limit_bits = end of the staged data.  Returns the end state; *nblk = blocks completed.
+// after_boundary: st.p is the first bit of a restart interval (the boundary there is behind
+// us, not ahead).
 //
-// One iteration = one symbol: fetch the next 32 bits, look them up, (write mode) extract
-// the value and store it, advance position and zig-zag index.  The state carried from one
-// symbol to the next is the bit position, block-in-MCU and zig-zag index only.  A writing
-// pass stores DC *differences*; dc_prefix() turns them into values afterwards.
+// One iteration = one symbol: take the next 32 bits, look them up, (write mode) extract the
+// value and store it, advance position and zig-zag index.  The state carried from one symbol
+// to the next is the bit position, block-in-MCU and zig-zag index only.  A writing pass
+// stores DC *differences*; dc_prefix() turns them into values afterwards.
 //
-// A lone wave issues about one instruction every five cycles and pays a fetch bubble for
-// every taken branch, so the loop is kept short and straight: a symbol is at most 31 bits
-// long, hence symbols that begin more than 31 bits before the next restart boundary are
-// decoded by a fast loop that cannot meet it, with everything rare (long codes, boundaries,
-// end of data, the checks of a writing pass at a boundary) left out of line or to the
-// careful step after it.
+// A lone wave issues a dependent instruction only every eight cycles or so and pays a fetch
+// bubble for every taken branch, and a lane that leaves the loop waits for the whole wave to
+// leave it.  So there is one loop, kept short and straight, that every lane stays in until
+// its span is done; the two rare events are branches off it that return to it: a code longer
+// than the first-level table covers, and a symbol that does not fit before the next restart
+// boundary or the end of the data (the bits there are padding, or belong to the next
+// interval), which is where the lane steps over the boundary.
 template <bool kWrite>
 __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geometry &g, uint32_t st,
-                                                uint32_t end_bit, uint32_t limit_bits, uint32_t *nblk,
-                                                WriteCtx *wc)
+                                                bool after_boundary, uint32_t end_bit,
+                                                uint32_t limit_bits, uint32_t *nblk, WriteCtx *wc)
 {
     uint32_t p = st >> 9, blk = (st >> 6) & 7u, zz = st & 63u;
     uint32_t done = 0;
@@ -384,37 +419,61 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
         last = g.n_blocks * 64u - 1u;
         iv_rem = wc->iv_rem;
     }
-    uint32_t nb = boundary_from(S, (p + 7) >> 3, limit_bits);
+    // next restart boundary ahead (bit position), limit_bits if none
+    uint32_t nb = boundary_from(S, after_boundary ? (p >> 3) + 1u : (p + 7u) >> 3, limit_bits);
     const uint16_t *lut = S.tab.lut;
     const uint32_t chroma_tb = 2u << kLutBits, ac_bit = 1u << kLutBits;
-    while (p < end_bit) {
-        // ---- fast loop ------------------------------------------------------------------
-        const uint32_t fast_end = min(end_bit, nb >= 31u ? nb - 31u : 0u);
-        if (p < fast_end) {
-            // tb: first entry of the current table (DC luma 0, AC luma 1024, DC chroma 2048, AC 3072)
-            uint32_t tb = (blk >= g.n_luma ? chroma_tb : 0u) | (zz ? ac_bit : 0u);
-            // what a writing pass has to refuse is gathered without branches: no_code = bits
-            // that are no code word; bit 6 of over = a coefficient index past its block; sign
-            // of late = a symbol where a restart marker had to come
-            int32_t no_code = 0, late = 0;
-            uint32_t over = 0;
-            // the stream words that hold bit p, the one after, and the one after that, kept in
-            // registers: a symbol is shorter than a word, so at most one new word is needed
-            // per symbol, and it is fetched one symbol ahead of its use
-            uint32_t w = p >> 5;
-            uint32_t hi = S.clean[clean_index(g, w)], lo = S.clean[clean_index(g, w + 1)];
-            uint32_t ahead = S.clean[clean_index(g, w + 2)];
-            do {
-                const uint32_t win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
-                uint32_t e = lut[tb + (win >> (32 - kLutBits))];
-                if (__builtin_expect((e >> 11) == 0, 0)) {
-                    e = resolve_long_code(S.tab, e, tb >> kLutBits, win);
-                    if ((e >> 11) == 0) {
-                        no_code = 1;
-                        e = kInvalidEntry;
-                    }
+    // tb: first entry of the current table (DC luma 0, AC luma 1024, DC chroma 2048, AC 3072)
+    uint32_t tb = (blk >= g.n_luma ? chroma_tb : 0u) | (zz ? ac_bit : 0u);
+    // what a writing pass has to refuse is gathered without branches: no_code = bits that are
+    // no code word; bit 6 of over = a coefficient index past its block; sign of late = a
+    // symbol where a restart marker had to come
+    int32_t no_code = 0, late = 0, broken = 0;
+    uint32_t over = 0;
+    // the stream words that hold bit p, the one after, and the one after that, kept in
+    // registers: a symbol is shorter than a word, so at most one new word is needed per
+    // symbol, and it is fetched one symbol ahead of its use
+    uint32_t w = p >> 5;
+    uint32_t hi = S.clean[clean_index(w)], lo = S.clean[clean_index(w + 1)];
+    uint32_t ahead = S.clean[clean_index(w + 2)];
+    if (p < end_bit) {
+        do {
+            const uint32_t win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
+            uint32_t e = lut[tb + (win >> (32 - kLutBits))];
+            int32_t unknown = 0;
+            if (__builtin_expect((e >> 11) == 0, 0)) {
+                e = resolve_long_code(S.tab, e, tb >> kLutBits, win);
+                if ((e >> 11) == 0) {
+                    unknown = 1;
+                    e = kInvalidEntry;
                 }
-                const uint32_t adv = e >> 11;
+            }
+            const uint32_t adv = e >> 11;
+            if (__builtin_expect(p + adv > nb, 0)) {
+                // the symbol does not fit before the next restart boundary / the end of the data
+                if (nb >= limit_bits) {
+                    if (kWrite && (blk != 0 || zz != 0 || limit_bits - p >= 8)) broken = 1;
+                    p = limit_bits;  // >= end_bit: the lane is done
+                } else {
+                    if (kWrite) {
+                        // a boundary comes between MCUs, behind fewer than eight padding bits,
+                        // and after a whole interval (or right where one has just begun)
+                        if (blk != 0 || zz != 0 || nb - p >= 8 || g.ri_blocks == 0 ||
+                            (iv_rem != 0 && iv_rem != (int32_t)g.ri_blocks))
+                            broken = 1;
+                        iv_rem = (int32_t)g.ri_blocks;
+                    }
+                    p = nb;
+                    blk = 0;
+                    zz = 0;
+                    tb = 0;
+                    nb = boundary_from(S, (p >> 3) + 1u, limit_bits);
+                    w = p >> 5;
+                    hi = S.clean[clean_index(w)];
+                    lo = S.clean[clean_index(w + 1)];
+                    ahead = S.clean[clean_index(w + 2)];
+                }
+            } else {
                 const uint32_t k = zz + ((e >> 4) & 63u);  // index of the symbol's coefficient
                 if (kWrite) {
                     // Every symbol stores.  ZRL and EOB carry no appended bits, so their value
@@ -423,6 +482,7 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                     // past the image keeps overwriting the image's last coefficient; the block
                     // count then gives it away.
                     wc->coef[min(boff + min(k, 63u), last)] = (int16_t)coefficient_value(win, adv, e & 15u);
+                    no_code |= unknown;
                     over |= (e >> 4) & k;
                     late |= iv_rem - 1;
                 }
@@ -432,7 +492,7 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                     hi = moved ? lo : hi;
                     lo = moved ? ahead : lo;
                     w += moved ? 1u : 0u;
-                    ahead = S.clean[clean_index(g, w + 2)];
+                    ahead = S.clean[clean_index(w + 2)];
                 }
                 const bool endb = k >= 63u;  // zz = k + 1 reaches 64
                 const uint32_t blk1 = blk + 1u == g.bpm ? 0u : blk + 1u;
@@ -444,68 +504,16 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                     boff += endb ? 64u : 0u;
                     iv_rem -= endb ? 1 : 0;
                 }
-            } while (p < fast_end);
-            if (kWrite) wc->bad |= no_code | (late < 0 ? 1 : 0) | (int32_t)((over >> 6) & 1u);
-            if (p >= end_bit) break;
-        }
-        // ---- one careful step near a boundary or the end of the data -----------------------
-        const uint32_t win = window32(S, g, p);
-        const uint32_t tsel = (blk >= g.n_luma ? 2u : 0u) | (zz ? 1u : 0u);
-        uint32_t e = lut[(tsel << kLutBits) + (win >> (32 - kLutBits))];
-        bool found = true;
-        if ((e >> 11) == 0) {
-            e = resolve_long_code(S.tab, e, tsel, win);
-            if ((e >> 11) == 0) { found = false; e = kInvalidEntry; }
-        }
-        const uint32_t adv = e >> 11;
-        if (p + adv > nb) {
-            // the symbol does not fit before the next restart boundary / end of data
-            if (nb >= limit_bits) {
-                if (kWrite && (blk != 0 || zz != 0 || limit_bits - p >= 8)) wc->bad = 1;
-                p = limit_bits;
-                break;
             }
-            if (kWrite) {
-                // a boundary comes between MCUs, behind fewer than eight padding bits, and
-                // after a whole interval (or right where one has just begun)
-                if (blk != 0 || zz != 0 || nb - p >= 8 || g.ri_blocks == 0 ||
-                    (iv_rem != 0 && iv_rem != (int32_t)g.ri_blocks))
-                    wc->bad = 1;
-                iv_rem = (int32_t)g.ri_blocks;
-            }
-            p = nb;
-            blk = 0;
-            zz = 0;
-            nb = boundary_from(S, (p >> 3) + 1, limit_bits);
-            continue;
-        }
-        const uint32_t k = zz + ((e >> 4) & 63u);
-        if (kWrite) {
-            // bits that are no code word, or data where a restart marker had to come
-            if (!found || iv_rem <= 0) wc->bad = 1;
-            if (e & kStore) {
-                if (k < 64u && boff <= last) wc->coef[boff + k] = (int16_t)coefficient_value(win, adv, e & 15u);
-                else wc->bad = 1;
-            }
-        }
-        p += adv;
-        zz = k + 1u;
-        if (zz >= 64u) {
-            zz = 0;
-            blk = blk + 1 == g.bpm ? 0 : blk + 1;
-            done++;
-            if (kWrite) {
-                boff += 64u;
-                iv_rem--;
-            }
-        }
+        } while (p < end_bit);
     }
+    if (kWrite) wc->bad |= broken | no_code | (late < 0 ? 1 : 0) | (int32_t)((over >> 6) & 1u);
     *nblk = done;
     return pack_state(p, blk, zz);
 }
 
 // DC differences -> DC values (T.81 F.2.2.1) for blocks [lo, hi) of the image, by the whole
-// wave: each lane takes a contiguous run of blocks, sums its differences per component (a
+// workgroup: each lane takes a contiguous run of blocks, sums its differences per component (a
 // sum restarts where a restart interval begins), a segmented scan over the lanes carries the
 // running values in, and a second walk writes them.  carry[] = running value of each
 // component before block lo; on return, after block hi - 1.  All lanes must call.
@@ -531,8 +539,8 @@ struct DcWalk {
     }
 };
 
-__device__ inline void dc_prefix(const Geometry &g, int16_t *coef, uint32_t lo, uint32_t hi,
-                                 int32_t carry[3])
+__device__ inline void dc_prefix(DecodeShared &S, const Geometry &g, int16_t *coef, uint32_t lo,
+                                 uint32_t hi, int32_t carry[3])
 {
     __syncthreads();  // the coefficient stores of every lane are done and visible
     const uint32_t n = hi > lo ? hi - lo : 0u;
@@ -558,11 +566,11 @@ __device__ inline void dc_prefix(const Geometry &g, int16_t *coef, uint32_t lo, 
         }
     }
     int32_t out;
-    int32_t c0 = wave_seg_excl_scan(s0, r0, carry[0], &out);
+    int32_t c0 = block_seg_excl_scan(s0, r0, carry[0], S.dc_val, S.dc_flag, &out);
     carry[0] = out;
-    int32_t c1 = wave_seg_excl_scan(s1, r1, carry[1], &out);
+    int32_t c1 = block_seg_excl_scan(s1, r1, carry[1], S.dc_val, S.dc_flag, &out);
     carry[1] = out;
-    int32_t c2 = wave_seg_excl_scan(s2, r2, carry[2], &out);
+    int32_t c2 = block_seg_excl_scan(s2, r2, carry[2], S.dc_val, S.dc_flag, &out);
     carry[2] = out;
     wk.start(g, a);
     for (uint32_t i = a; i < b; i += 8) {
@@ -631,7 +639,7 @@ __device__ inline void classify16(const uint4 v, uint32_t prev, uint32_t nextb, 
 }  // namespace
 
 // ---- kernel 1: restart markers per window -----------------------------------
-// window w of an image = raw bytes [w*window_bytes, (w+1)*window_bytes) of its
+// window w of an image = raw bytes [w*kWindowBytes, (w+1)*kWindowBytes) of its
 // entropy-coded segment.  cnt = RSTn markers whose FF byte lies in the window,
 // first = offset (from the segment start) of the first such FF byte.
 __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
@@ -639,6 +647,7 @@ __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
     uint32_t *__restrict__ win_count, uint32_t *__restrict__ win_first,
     int32_t *__restrict__ status)
 {
+    __shared__ uint32_t s_cnt[kT / 64], s_first[kT / 64];
     const uint32_t wg = blockIdx.x;
     const int img = find_image(n_images, wg, [&](int i) { return recs[i].window0; });
     const ImageRec &R = recs[img];
@@ -648,8 +657,8 @@ __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
     uint32_t cnt = 0, first = kNoMarker;
     if (R.status == PREP_OK && R.restart_interval != 0 && w < R.n_windows) {
         const uint8_t *seg = bits + R.file_off + R.entropy_rel;
-        const int32_t lo = (int32_t)(w * R.window_bytes);
-        const int32_t hi = (int32_t)min(w * R.window_bytes + R.window_bytes, R.entropy_len);
+        const int32_t lo = (int32_t)(w * (uint32_t)kWindowBytes);
+        const int32_t hi = (int32_t)min(w * (uint32_t)kWindowBytes + (uint32_t)kWindowBytes, R.entropy_len);
         // 16-byte aligned parts that cover [lo, hi), dealt to the lanes in turn; a part that
         // begins before lo reaches at most 15 bytes back, into the file's headers
         const int32_t a0 = lo - (int32_t)((uintptr_t)(seg + lo) & 15u);
@@ -670,13 +679,18 @@ __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
             }
         }
     }
+    // workgroup reduction
     for (int d = 32; d >= 1; d >>= 1) {
         cnt += __shfl_xor(cnt, d, 64);
         first = min(first, (uint32_t)__shfl_xor(first, d, 64));
     }
+    if ((threadIdx.x & 63) == 0) { s_cnt[threadIdx.x >> 6] = cnt; s_first[threadIdx.x >> 6] = first; }
+    __syncthreads();
     if (threadIdx.x == 0) {
-        win_count[wg] = cnt;
-        win_first[wg] = first;
+        uint32_t c = 0, f = kNoMarker;
+        for (int i = 0; i < kT / 64; i++) { c += s_cnt[i]; f = min(f, s_first[i]); }
+        win_count[wg] = c;
+        win_first[wg] = f;
     }
 }
 
@@ -693,13 +707,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     const ImageRec &R = recs[img];
     const uint32_t w = wg - R.window0;
     if (R.status != PREP_OK || w >= R.n_windows) return;
-    // clean bytes per lane, 64-byte pieces per lane, raw bytes per chunk
-    const uint32_t sub_bytes = R.sub_bytes, ppl = sub_bytes >> 6, sub_bits = sub_bytes * 8u;
-    const int32_t chunk_raw = (int32_t)(sub_bytes * kT);
-    if (sub_bytes != 64u && sub_bytes != 128u && sub_bytes != 256u) return;  // not a record of this library
 
     Geometry g;
-    g.pad_shift = sub_bytes == 64u ? 4u : sub_bytes == 128u ? 5u : 6u;
     g.bpm = R.blocks_per_mcu;
     g.n_luma = R.sampling == PREP_SAMPLING_420 ? 4u : 1u;
     g.ri_blocks = (uint32_t)R.restart_interval * g.bpm;
@@ -723,6 +732,22 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             uint32_t ow = __shfl_xor(next_w, d, 64), of = __shfl_xor(next_first, d, 64);
             if (ow < next_w) { next_w = ow; next_first = of; }
         }
+        if ((tid & 63) == 0) {
+            S.scan_a[tid >> 6] = before;
+            S.dc_val[tid >> 6] = (int32_t)next_w;
+            S.dc_flag[tid >> 6] = (int32_t)next_first;
+        }
+        __syncthreads();
+        before = 0;
+        next_w = kNoMarker;
+        for (int i = 0; i < kT / 64; i++) {
+            before += S.scan_a[i];
+            if ((uint32_t)S.dc_val[i] < next_w) {
+                next_w = (uint32_t)S.dc_val[i];
+                next_first = (uint32_t)S.dc_flag[i];
+            }
+        }
+        __syncthreads();
         if (w != 0) {
             range_lo = my_first + 2;
             block0 = (before + 1) * g.ri_blocks;  // markers before ours + ours = intervals done
@@ -732,7 +757,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             // markers up to and including the first one of window next_w
             uint32_t upto = 0;
             for (uint32_t i = tid; i < next_w; i += kT) upto += wc[i];
-            upto = wave_sum(upto);
+            upto = block_sum(upto, S.scan_a);
             block_end = (upto + 1) * g.ri_blocks;
         }
     }
@@ -759,123 +784,103 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     const uint32_t max_chunks = (range_hi - range_lo) / 64u + 2;
     for (uint32_t iter = 0; iter < max_chunks && cs < rhi; iter++) {
         // ---- stage: destuff raw bytes [cs, ce) into S.clean --------------------------
-        // each lane owns sub_bytes consecutive raw bytes of the 16-byte aligned span that
-        // contains cs, handled as 64-byte pieces of four 16-byte parts
+        // lanes own 64-byte pieces (four 16-byte parts) of the 16-byte aligned span that
+        // contains cs
         const int32_t mis = (int32_t)((uintptr_t)(seg + cs) & 15u);
         const int32_t a0 = cs - mis;
-        const int32_t ce = min(a0 + chunk_raw, rhi);
+        const int32_t ce = min(a0 + (int32_t)kChunkRaw, rhi);
         const bool last = ce == rhi;
         __syncthreads();
         for (int i = tid; i < kMaskWords; i += kT) S.bmask[i] = 0;
-        const int32_t my_lo = a0 + tid * (int32_t)sub_bytes;  // raw offset of my first byte
+        const int32_t my_lo = a0 + tid * 64;  // raw offset of my first byte
         // 16-byte parts are loaded whether or not they still overlap [cs, ce] (what lies
         // outside is not looked at), from an address clamped to the part that holds ce, so
-        // that the loads of a piece do not wait for one another
+        // that the loads of a piece do not wait for one another.  Such a load is aligned
+        // and holds at least one byte of the file, so it stays inside the file's last page.
         const int32_t last_part = a0 + ((ce - a0) & ~15);
-        uint32_t n_keep = 0, n_bound = 0;
+        uint4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; k++)
+            v[k] = *reinterpret_cast<const uint4 *>(seg + min(my_lo + 16 * k, last_part));
+        unsigned long long keep = 0, bound = 0;
         {
-            // the byte before my bytes and the byte after each 16-byte part, for the FF xx
+            // the byte before my piece and the byte after each 16-byte part, for the FF xx
             // pairs that straddle; past the segment comes the FF of the EOI marker
+            const uint32_t after = load_byte(seg + min(my_lo + 64, ce));
             uint32_t prev = 0;
             if (my_lo > cs && my_lo <= ce) prev = load_byte(seg + my_lo - 1);
-            for (uint32_t j = 0; j < ppl; j++) {
-                const int32_t pj = my_lo + (int32_t)(64 * j);
-                uint4 v[4];
 #pragma unroll
-                for (int k = 0; k < 4; k++)
-                    v[k] = *reinterpret_cast<const uint4 *>(seg + min(pj + 16 * k, last_part));
-                const uint32_t after = load_byte(seg + min(pj + 64, ce));
-                unsigned long long keep = 0, bound = 0;
-#pragma unroll
-                for (int k = 0; k < 4; k++) {
-                    const int32_t plo = pj + 16 * k;
-                    uint32_t kp = 0, bd = 0;
-                    // a part is looked at only if it overlaps [cs, ce]: the byte at ce (the FF
-                    // of the marker that ends the run) is examined, not consumed
-                    if (plo <= ce) {
-                        uint32_t nextb = k < 3 ? (v[(k + 1) & 3].x & 255u) : after;
-                        if (!(plo + 16 < seg_len && plo + 16 <= ce)) nextb = 0xFFu;
-                        classify16(v[k], prev, nextb, plo, cs, ce, &kp, &bd, &prev, &bad);
-                    } else {
-                        prev = 0;
-                    }
-                    keep |= (unsigned long long)kp << (16 * k);
-                    bound |= (unsigned long long)bd << (16 * k);
+            for (int k = 0; k < 4; k++) {
+                const int32_t plo = my_lo + 16 * k;
+                uint32_t kp = 0, bd = 0;
+                // a part is looked at only if it overlaps [cs, ce]: the byte at ce (the FF of
+                // the marker that ends the run) is examined, not consumed
+                if (plo <= ce) {
+                    uint32_t nextb = k < 3 ? (v[(k + 1) & 3].x & 255u) : after;
+                    if (!(plo + 16 < seg_len && plo + 16 <= ce)) nextb = 0xFFu;
+                    classify16(v[k], prev, nextb, plo, cs, ce, &kp, &bd, &prev, &bad);
+                } else {
+                    prev = 0;
                 }
-                S.keep[tid * ppl + j] = keep;
-                S.bound[tid * ppl + j] = bound;
-                n_keep += (uint32_t)__popcll(keep);
-                n_bound += (uint32_t)__popcll(bound);
+                keep |= (unsigned long long)kp << (16 * k);
+                bound |= (unsigned long long)bd << (16 * k);
             }
         }
         // clean offsets (low half) and boundary ranks (high half) in one scan
         uint32_t totals;
-        const uint32_t my_pre = wave_excl_scan(n_keep | (n_bound << 16), &totals);
+        const uint32_t my_pre = block_excl_scan((uint32_t)__popcll(keep) | ((uint32_t)__popcll(bound) << 16),
+                                                S.scan_a, &totals);
         const uint32_t clean_len = totals & 0xFFFFu, nbnd = totals >> 16;
+        const uint32_t my_off = my_pre & 0xFFFFu;
+        S.keep[tid] = keep;
+        S.keep_off[tid] = my_off;
+        if (tid == 0) S.keep_off[kT] = clean_len;
         // zeros behind the data: the last word is written byte by byte, and lookups near the
-        // end read up to eight words past it
-        if (tid < 12) S.clean[clean_index(g, (clean_len >> 2) + (uint32_t)tid)] = 0;
+        // end read a few words past it
+        if (tid < 12) S.clean[clean_index((clean_len >> 2) + (uint32_t)tid)] = 0;
         __syncthreads();  // zero fill done before bytes are written
         {
             uint8_t *cb = reinterpret_cast<uint8_t *>(S.clean);
-            uint32_t o = my_pre & 0xFFFFu, rank = my_pre >> 16;
-            for (uint32_t j = 0; j < ppl; j++) {
-                const unsigned long long keep = S.keep[tid * ppl + j], bound = S.bound[tid * ppl + j];
-                S.keep_off[tid * ppl + j] = o;
-                if ((keep | bound) == 0) continue;
-                const int32_t pj = my_lo + (int32_t)(64 * j);
-                uint4 v[4];
+            uint32_t o = my_off, rank = my_pre >> 16;
 #pragma unroll
-                for (int k = 0; k < 4; k++)
-                    v[k] = *reinterpret_cast<const uint4 *>(seg + min(pj + 16 * k, last_part));
+            for (int k = 0; k < 4; k++) {
+                const uint32_t kp = (uint32_t)(keep >> (16 * k)) & 0xFFFFu;
+                const uint32_t bd = (uint32_t)(bound >> (16 * k)) & 0xFFFFu;
+                if ((kp | bd) == 0) continue;
+                const uint32_t wv[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
 #pragma unroll
-                for (int k = 0; k < 4; k++) {
-                    const uint32_t kp = (uint32_t)(keep >> (16 * k)) & 0xFFFFu;
-                    const uint32_t bd = (uint32_t)(bound >> (16 * k)) & 0xFFFFu;
-                    if ((kp | bd) == 0) continue;
-                    const uint32_t wv[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
-#pragma unroll
-                    for (int i = 0; i < 16; i++) {
-                        if ((bd >> i) & 1u) {
-                            atomicOr(&S.bmask[o >> 5], 1u << (o & 31));
-                            if (rank < (uint32_t)kMaxBoundaries) S.bpos[rank] = (uint16_t)o;
-                            // raw offset just after the last marker of the chunk: where a chunk
-                            // of whole intervals would resume
-                            if (rank + 1 == nbnd) S.bcast[2] = (uint32_t)(pj + 16 * k + i + 1);
-                            rank++;
-                        }
-                        if ((kp >> i) & 1u) {
-                            cb[(clean_index(g, o >> 2) << 2) | ((o & 3u) ^ 3u)] = (uint8_t)((wv[i >> 2] >> (8 * (i & 3))) & 255u);
-                            o++;
-                        }
+                for (int i = 0; i < 16; i++) {
+                    if ((bd >> i) & 1u) {
+                        atomicOr(&S.bmask[o >> 5], 1u << (o & 31));
+                        if (rank < (uint32_t)kMaxBoundaries) S.bpos[rank] = (uint16_t)o;
+                        // raw offset just after the last marker of the chunk: where a chunk of
+                        // whole intervals would resume
+                        if (rank + 1 == nbnd) S.bcast[2] = (uint32_t)(my_lo + 16 * k + i + 1);
+                        rank++;
+                    }
+                    if ((kp >> i) & 1u) {
+                        cb[(clean_index(o >> 2) << 2) | ((o & 3u) ^ 3u)] = (uint8_t)((wv[i >> 2] >> (8 * (i & 3))) & 255u);
+                        o++;
                     }
                 }
             }
         }
         __syncthreads();
         {
-            // first interval start at or after each 64-byte clean piece: suffix minimum over
-            // the pieces, four consecutive ones per lane
-            uint32_t mine[4];
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const uint32_t pc = 4u * (uint32_t)tid + (uint32_t)i;
-                const unsigned long long m = ((unsigned long long)S.bmask[2 * pc + 1] << 32) | S.bmask[2 * pc];
-                mine[i] = m ? pc * 64u + (uint32_t)__builtin_ctzll(m) : kNoMarker;
-            }
-            mine[2] = min(mine[2], mine[3]);
-            mine[1] = min(mine[1], mine[2]);
-            mine[0] = min(mine[0], mine[1]);
-            uint32_t suffix = mine[0];  // becomes the minimum over this lane and all later ones
+            // first interval start at or after each lane's subsequence: suffix minimum
+            unsigned long long m = ((unsigned long long)S.bmask[2 * tid + 1] << 32) | S.bmask[2 * tid];
+            uint32_t mine = m ? (uint32_t)tid * 64u + (uint32_t)__builtin_ctzll(m) : kNoMarker;
+            const int lane = tid & 63, wave = tid >> 6;
             for (int d = 1; d < 64; d <<= 1) {
-                uint32_t o = __shfl_down(suffix, d, 64);
-                if (tid + d < 64) suffix = min(suffix, o);
+                uint32_t o = __shfl_down(mine, d, 64);
+                if (lane + d < 64) mine = min(mine, o);
             }
-            uint32_t later = __shfl_down(suffix, 1, 64);
-            if (tid == 63) later = kNoMarker;
-#pragma unroll
-            for (int i = 0; i < 4; i++) S.next_boundary[4 * tid + i] = min(mine[i], later);
-            if (tid == 0) S.next_boundary[kChunkPieces] = kNoMarker;
+            if (lane == 0) S.scan_a[wave] = mine;
+            __syncthreads();
+            uint32_t later = kNoMarker;
+            for (int ww = wave + 1; ww < kT / 64; ww++) later = min(later, S.scan_a[ww]);
+            S.next_boundary[tid] = min(mine, later);
+            if (tid == 0) S.next_boundary[kT] = kNoMarker;
         }
         __syncthreads();
 
@@ -887,7 +892,11 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         // ---- short intervals: one lane per restart interval, one pass -----------------
         // Intervals 0..n_iv-1 of the chunk end inside it: the first runs from the chunk's
         // start state to the first listed start, interval k > 0 between listed starts k-1
-        // and k, and in the last chunk one more runs to the end of the data.
+        // and k, and in the last chunk one more runs to the end of the data.  A decoding
+        // lane is bound by the latency of its own dependent instructions, and a wave takes
+        // as long as its slowest lane whatever the number of busy lanes: consecutive
+        // intervals go to consecutive lanes, so that they fill as few waves as possible and
+        // the other waves of the workgroup leave their SIMDs to other workgroups.
         const uint32_t n_iv = last ? nbnd + 1 : nbnd;
         if (g.ri_blocks != 0 && n_iv >= 1 && nbnd <= (uint32_t)kMaxBoundaries &&
             clean_len <= kShortInterval * (nbnd + 1)) {
@@ -900,7 +909,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
                 wc.block = blk0;
                 wc.iv_rem = (int32_t)(k ? g.ri_blocks : rem0);
                 uint32_t got;
-                const uint32_t fin = decode_span<true>(S, g, start, end_bit, limit_bits, &got, &wc);
+                const uint32_t fin = decode_span<true>(S, g, start, k != 0, end_bit, limit_bits, &got, &wc);
                 // the interval must end on its boundary, between MCUs, with all its blocks
                 if (got != want || (fin & 511u) != 0 || (fin >> 9) != end_bit) wc.bad = 1;
             }
@@ -909,7 +918,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
                 // DC values of the blocks whose DC was decoded here (the chunk may begin inside a block)
                 const uint32_t dc_lo = block_base + ((st0 & 63u) ? 1u : 0u);
                 block_base = min(block_base + rem0 + (n_iv - 1) * g.ri_blocks, block_end);
-                dc_prefix(g, coef, dc_lo, min(block_base, g.n_blocks), dc_carry);
+                dc_prefix(S, g, coef, dc_lo, min(block_base, g.n_blocks), dc_carry);
             }
             st0 = pack_state(0, 0, 0);
             dc_carry[0] = dc_carry[1] = dc_carry[2] = 0;
@@ -925,32 +934,35 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         // a chunk that is not the last keeps a tail back so that no symbol straddles its end
         const uint32_t own_bits = last ? limit_bits
                                        : (clean_len > (uint32_t)kChunkTail ? (clean_len - kChunkTail) * 8u : 0u);
-        const uint32_t nsub = (own_bits + sub_bits - 1) / sub_bits;  // <= kT
+        const uint32_t nsub = (own_bits + kSubBits - 1) / kSubBits;  // <= kT
         const bool active = (uint32_t)tid < nsub;
-        const uint32_t end_bit = min(((uint32_t)tid + 1u) * sub_bits, own_bits);
+        const uint32_t end_bit = min(((uint32_t)tid + 1u) * kSubBits, own_bits);
 
         // synchronise: iterate end states to their fixed point
-        uint32_t in_state = tid == 0 ? st0 : pack_state((uint32_t)tid * sub_bits, 0, 0);
+        uint32_t in_state = tid == 0 ? st0 : pack_state((uint32_t)tid * kSubBits, 0, 0);
         uint32_t out_state = in_state, nblk = 0;
-        if (active) out_state = decode_span<false>(S, g, in_state, end_bit, limit_bits, &nblk, nullptr);
+        if (active) out_state = decode_span<false>(S, g, in_state, false, end_bit, limit_bits, &nblk, nullptr);
+        S.state[tid] = out_state;
         for (uint32_t round = 0; round <= nsub; round++) {
+            __syncthreads();
             int changed = 0;
-            uint32_t prev_state = __shfl_up(out_state, 1, 64);
-            if (tid == 0) prev_state = st0;
+            const uint32_t prev_state = tid > 0 ? S.state[tid - 1] : st0;
+            __syncthreads();
             if (active && tid > 0 && prev_state != in_state) {
                 in_state = prev_state;
                 uint32_t o = in_state;
                 // a predecessor that already ran past my subsequence leaves me nothing to decode
-                if ((in_state >> 9) < end_bit) o = decode_span<false>(S, g, in_state, end_bit, limit_bits, &nblk, nullptr);
+                if ((in_state >> 9) < end_bit) o = decode_span<false>(S, g, in_state, false, end_bit, limit_bits, &nblk, nullptr);
                 else nblk = 0;
                 if (o != out_state) { out_state = o; changed = 1; }
+                S.state[tid] = out_state;
             }
             if (!__syncthreads_or(changed)) break;
         }
 
         // write: decode once more from the true states
         uint32_t total_blocks;
-        const uint32_t my_block = block_base + wave_excl_scan(active ? nblk : 0u, &total_blocks);
+        const uint32_t my_block = block_base + block_excl_scan(active ? nblk : 0u, S.scan_a, &total_blocks);
         wc.block = my_block;
         // a lane that begins on an MCU boundary where an interval ends must meet the boundary
         // first; lane 0 of a chunk may begin just after one (start of the run, or a boundary
@@ -961,18 +973,20 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         uint32_t final_state = out_state;
         if (active && (in_state >> 9) < end_bit) {
             uint32_t nb2;
-            final_state = decode_span<true>(S, g, in_state, end_bit, limit_bits, &nb2, &wc);
+            final_state = decode_span<true>(S, g, in_state, false, end_bit, limit_bits, &nb2, &wc);
             if (final_state != out_state || nb2 != nblk) wc.bad = 1;
         }
         bad |= wc.bad;
-        // true end state of the chunk: that of its last subsequence
-        const uint32_t fs = nsub ? __shfl(out_state, (int)nsub - 1, 64) : st0;
+        __syncthreads();
+        if (tid == 0) S.bcast[0] = nsub ? S.state[nsub - 1] : st0;
+        __syncthreads();
+        const uint32_t fs = S.bcast[0];  // true end state of the chunk
         {
             // DC values of the blocks whose DC was decoded in this chunk: it may begin inside
             // a block (DC decoded earlier) and end inside one (DC decoded here)
             const uint32_t dc_lo = block_base + ((st0 & 63u) ? 1u : 0u);
             const uint32_t dc_hi = block_base + total_blocks + ((fs & 63u) ? 1u : 0u);
-            dc_prefix(g, coef, dc_lo, min(dc_hi, g.n_blocks), dc_carry);
+            dc_prefix(S, g, coef, dc_lo, min(dc_hi, g.n_blocks), dc_carry);
         }
 
         // carry the true end state into the next chunk
@@ -989,14 +1003,11 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         }
         if (tid == 0) S.bcast[1] = 0;
         __syncthreads();
-        for (uint32_t j = 0; j < ppl; j++) {
-            const uint32_t off = S.keep_off[tid * ppl + j];
-            unsigned long long m = S.keep[tid * ppl + j];
-            if (off <= qc && qc < off + (uint32_t)__popcll(m)) {
-                const uint32_t skip = qc - off;
-                for (uint32_t i = 0; i < skip; i++) m &= m - 1;  // drop the lowest set bits
-                S.bcast[1] = (uint32_t)(my_lo + (int32_t)(64 * j) + (int32_t)__builtin_ctzll(m));
-            }
+        if (S.keep_off[tid] <= qc && qc < S.keep_off[tid] + (uint32_t)__popcll(S.keep[tid])) {
+            unsigned long long m = S.keep[tid];
+            const uint32_t skip = qc - S.keep_off[tid];
+            for (uint32_t i = 0; i < skip; i++) m &= m - 1;  // drop the lowest set bits
+            S.bcast[1] = (uint32_t)(my_lo + (int32_t)__builtin_ctzll(m));
         }
         __syncthreads();
         const int32_t next_cs = (int32_t)S.bcast[1];

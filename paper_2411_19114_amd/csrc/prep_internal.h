@@ -6,31 +6,16 @@
 namespace prep {
 
 // ---- entropy decoder geometry -------------------------------------------
-// One workgroup (a single wave) owns a contiguous run of restart intervals of one
-// image and decodes it chunk by chunk.  A chunk is 64 * sub_bytes raw bytes staged
-// into LDS with stuffing and markers removed; in the speculative regime each lane
-// owns one subsequence of sub_bytes clean bytes.  sub_bytes is chosen per image
-// (subseq_bytes_for): large enough that a small image is one chunk, and the
-// largest size where one lane takes a whole short restart interval, so that a
-// chunk holds as many intervals as possible.
-constexpr int kDecodeThreads = 64;
-constexpr int kMinSubseqBytes = 64, kMaxSubseqBytes = 256;  // clean bytes per lane
-constexpr int kChunkRaw = kDecodeThreads * kMaxSubseqBytes; // most raw bytes staged per chunk
-constexpr int kChunkPieces = kChunkRaw / 64;                // 64-byte pieces of a chunk
+// One workgroup owns a contiguous run of restart intervals of one image and
+// decodes it chunk by chunk.  A chunk is kChunkRaw raw bytes staged into LDS
+// with stuffing and markers removed; in the speculative regime each lane owns
+// one subsequence of kSubseqBytes clean bytes.
+constexpr int kDecodeThreads = 256;
+constexpr int kSubseqBytes = 64;                            // clean bytes per lane
+constexpr int kChunkRaw = kDecodeThreads * kSubseqBytes;    // raw bytes staged per chunk
 constexpr int kChunkTail = 16;                              // bytes a non-final chunk keeps back
+constexpr int kWindowBytes = 12288;                         // raw bytes between workgroup starts
 constexpr int kLutBits = 10;                                // first-level Huffman lookup width
-constexpr uint32_t kShortInterval = 1024;  // mean bytes up to which a lane takes a whole restart interval
-
-// clean bytes per lane for an image with this much entropy-coded data
-inline uint32_t subseq_bytes_for(uint64_t entropy_len, uint64_t n_intervals)
-{
-    if (n_intervals > 1 && entropy_len <= (uint64_t)kShortInterval * n_intervals) return kMaxSubseqBytes;
-    uint32_t b = kMinSubseqBytes;
-    while (b < (uint32_t)kMaxSubseqBytes && (uint64_t)b * kDecodeThreads < entropy_len) b *= 2;
-    return b;
-}
-// raw bytes between workgroup starts: three quarters of a chunk
-inline uint32_t window_bytes_for(uint32_t sub_bytes) { return 48u * sub_bytes; }
 
 // ---- reconstruction geometry ----------------------------------------------
 // One workgroup turns kReconBlocks 8x8 blocks (a run of MCUs of one MCU row)
@@ -51,8 +36,6 @@ struct ImageRec {
     uint32_t n_blocks;      // mcu_cols * mcu_rows * blocks_per_mcu
     uint32_t window0;       // first decode window (= workgroup) of this image
     uint32_t n_windows;
-    uint32_t window_bytes;  // raw bytes between workgroup starts (a multiple of 64)
-    uint32_t sub_bytes;     // clean bytes per lane of the entropy decoder: 64, 128 or 256
     uint32_t rgb_pitch;     // bytes between RGB rows (covers the whole MCU grid)
     uint32_t group0;        // first reconstruction workgroup of this image
     uint32_t groups_per_row;  // reconstruction workgroups per MCU row
