@@ -38,7 +38,9 @@ WORKLOAD_NAMES = {
     2: "workload 2: 256 x U[300,640]xU[250,500] 4:2:0 q90, restart interval 8 MCUs, resize 256 crop 224 fp16",
     4: "workload 4: 64 x 1920x1080 4:2:0 q95, restart per MCU row, resize 384 crop 384 fp16",
     5: "workload 5: 512 x 256x256 mixed 4:4:4/4:2:0/gray q50-95, no restart markers, crop 224 fp16",
+    3: "workload 3: 7 concurrent streams x batches of 8 from 512 x 256x256 4:2:0 q85, restart per MCU row, crop 224 fp32",
 }
+N_STREAMS, STREAM_BATCH = 7, 8
 
 
 def cpu_baseline(streams, pr, max_seconds=60.0):
@@ -78,12 +80,169 @@ def symbols_in(streams, limit=64):
     return sym / max(byt, 1)
 
 
+def algorithmic_bytes(infos, pr):
+    """Bytes each HBM-bound stage has to move for these images (rooflines)."""
+    esz = 2 if pr["out_dtype"] == "f16" else 4
+    n = len(infos)
+    out_bytes = n * 3 * pr["crop_h"] * pr["crop_w"] * esz
+    entropy_bytes = sum(i.entropy_bytes for i in infos)
+    blocks = sum(i.mcu_cols * i.mcu_rows * i.blocks_per_mcu for i in infos)
+    # source footprint of the crop: the window of each image that the outputs map back to
+    foot = 0
+    for i in infos:
+        s = pr["resize_short"]
+        if s:
+            ow, oh = (s, s * i.height // i.width) if i.width <= i.height else (s * i.width // i.height, s)
+        else:
+            ow, oh = i.width, i.height
+        foot += int(round(pr["crop_w"] * i.width / ow)) * int(round(pr["crop_h"] * i.height / oh)) * 3
+    padded_rgb = sum(i.mcu_cols * i.mcu_rows * (256 if i.sampling == 1 else 64) * 3 for i in infos)
+    return {
+        "scan": entropy_bytes + blocks * 128,           # read stream once + clear coefficients
+        "reconstruct": blocks * 128 + padded_rgb,       # coefficients in, RGB out
+        "resize": foot + out_bytes,                     # crop footprint in, tensor out
+    }, entropy_bytes
+
+
+def stage_report(stage_ms, work, entropy_bytes, sym_per_byte):
+    names = ["scan", "decode", "reconstruct", "resize"]
+    kernels = ["scan_restart_markers (+ clearing coefficients)", "decode_entropy", "reconstruct_rgb",
+               "resize_crop_normalize"]
+    stages = []
+    for j, name in enumerate(names):
+        ms = float(stage_ms[j])
+        if name == "decode":
+            if sym_per_byte is None:
+                stages.append({"stage": name, "kernel": kernels[j], "ms": ms, "bound": "alu"})
+                continue
+            ops = sym_per_byte * entropy_bytes * OPS_PER_SYMBOL
+            ach = ops / (ms * 1e-3) / 1e12
+            stages.append({"stage": name, "kernel": kernels[j], "ms": ms, "bound": "alu",
+                           "achieved": ach, "peak": INT_ALU_PEAK_TOPS, "unit": "TOP/s",
+                           "frac": ach / INT_ALU_PEAK_TOPS, "traffic": None,
+                           "symbols_per_launch": sym_per_byte * entropy_bytes,
+                           "compressed_GB_per_s": entropy_bytes / (ms * 1e-3) / 1e9})
+        else:
+            b = work[name]
+            ach = b / (ms * 1e-3) / 1e9
+            stages.append({"stage": name, "kernel": kernels[j], "ms": ms, "bound": "hbm",
+                           "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                           "algorithmic_bytes": b})
+    dominant = max(stages, key=lambda s: s["ms"])
+    roofline = {k: dominant.get(k) for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
+    roofline["kernel"] = dominant["kernel"]
+    roofline["avg_launch_ms"] = dominant["ms"]
+    return stages, roofline
+
+
+def run_streams(args, torch, prep, synth, make_params):
+    """Workload 3: N_STREAMS host threads, each with its own handle and HIP stream, decode
+    batches of STREAM_BATCH images back to back; one step = one batch on every stream.
+    Reports whole-job images/s and the distribution of per-batch latency (submit -> done)."""
+    import threading
+    t0 = time.perf_counter()
+    streams = synth.make_batch(3)
+    gen_s = time.perf_counter() - t0
+    blob, offsets = synth.pack(streams)
+    pr = synth.params_of(3)
+    params = make_params(pr["resize_short"], pr["crop_h"], pr["crop_w"], pr["out_dtype"], pr["mean"], pr["std"])
+    infos = prep.parse_headers(blob, offsets)
+    assert all(i.status == 0 for i in infos)
+    n_batches = len(streams) // STREAM_BATCH
+    dev = torch.device("cuda:0")
+    dev_bits = torch.from_numpy(blob).to(dev)
+    dt = torch.float16 if pr["out_dtype"] == "f16" else torch.float32
+    max_w, max_h = max(i.width for i in infos), max(i.height for i in infos)
+    max_bytes = max(int(offsets[(b + 1) * STREAM_BATCH] - offsets[b * STREAM_BATCH]) for b in range(n_batches))
+    pps, outs, hip_streams = [], [], []
+    for _ in range(N_STREAMS):
+        pps.append(prep.Preprocessor(device=0, max_batch=STREAM_BATCH, max_width=max_w, max_height=max_h,
+                                     max_bitstream_bytes=max_bytes))
+        outs.append(torch.empty((STREAM_BATCH, 3, pr["crop_h"], pr["crop_w"]), dtype=dt, device=dev))
+        hip_streams.append(torch.cuda.Stream(device=dev))
+    torch.cuda.synchronize()
+    lat = [[] for _ in range(N_STREAMS)]
+    span = [None] * N_STREAMS
+    gate = threading.Barrier(N_STREAMS)
+    errors = []
+
+    def worker(i):
+        try:
+            pp, out, hs = pps[i], outs[i], hip_streams[i]
+            b = i
+            for k in range(args.warmup + args.steps):
+                if k == args.warmup:
+                    if i == 0:
+                        pp.set_timing(True)
+                    gate.wait()
+                    span[i] = [time.perf_counter(), None]
+                o = offsets[b * STREAM_BATCH:(b + 1) * STREAM_BATCH + 1]
+                t = time.perf_counter()
+                pp.decode_resize_batch_resident(blob, dev_bits.data_ptr(), o, params, out.data_ptr(), hs.cuda_stream)
+                hs.synchronize()
+                if k >= args.warmup:
+                    lat[i].append(time.perf_counter() - t)
+                b = (b + N_STREAMS) % n_batches
+            span[i][1] = time.perf_counter()
+            assert pp.get_status(STREAM_BATCH) == [0] * STREAM_BATCH
+        except Exception as e:  # surfaced by the main thread
+            errors.append(repr(e))
+            try:
+                gate.abort()
+            except Exception:
+                pass
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(N_STREAMS)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    if errors:
+        print("bench.py: " + "; ".join(errors), file=sys.stderr)
+        sys.exit(1)
+    wall = max(s[1] for s in span) - min(s[0] for s in span)
+    images = N_STREAMS * args.steps * STREAM_BATCH
+    all_lat = np.sort(np.concatenate([np.array(l) for l in lat])) * 1e3
+    k = min(args.steps, 256)
+    stage = np.array([pps[0].stage_ms(i) for i in range(k)]).mean(axis=0)
+    pps[0].set_timing(False)
+    work, entropy_bytes = algorithmic_bytes(infos[:STREAM_BATCH], pr)
+    cpu = sym_per_byte = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(streams, pr)
+        sym_per_byte = symbols_in(streams)
+    stages, roofline = stage_report(stage, work, entropy_bytes, sym_per_byte)
+    result = {
+        "metric": METRIC, "value": images / wall, "unit": "images/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32 entropy decode, f64 IDCT, f32 resize -> " + pr["out_dtype"] + " output",
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[3], "streams": N_STREAMS, "batch": STREAM_BATCH,
+                   "input": "resident in HBM", "pool_images": len(streams),
+                   "sha256": synth.sha256_of(streams), "input_generation_s": round(gen_s, 2)},
+        "latency_ms": {"p50": float(np.percentile(all_lat, 50)), "p95": float(np.percentile(all_lat, 95)),
+                       "p99": float(np.percentile(all_lat, 99)), "max": float(all_lat[-1]),
+                       "what": "one batch of 8: call of the entry point until its stream is idle",
+                       "samples": int(all_lat.size)},
+        "roofline": roofline,
+        "stages": stages,
+        "stage_timing": "stream 0 only, one batch of 8 images per launch",
+        "gpu_ms_per_step": float(stage.sum()),
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result))
+    for pp in pps:
+        pp.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 4, 5])
+    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy (a reference for HBM counters)")
@@ -109,6 +268,9 @@ def main():
         __graft_entry__.build()
 
     cfg = args.workload
+    if cfg == 3:
+        run_streams(args, torch, prep, synth, make_params)
+        return
     t0 = time.perf_counter()
     streams = synth.make_batch(cfg)
     gen_s = time.perf_counter() - t0
@@ -165,56 +327,13 @@ def main():
     value = n * args.steps / wall
 
     # ---- algorithmic work per launch ------------------------------------------------------
-    esz = 2 if pr["out_dtype"] == "f16" else 4
-    out_bytes = n * 3 * pr["crop_h"] * pr["crop_w"] * esz
-    # source footprint of the crop: the window of each image that the outputs map back to
-    foot = 0
-    for i in infos:
-        s = pr["resize_short"]
-        if s:
-            ow, oh = (s, s * i.height // i.width) if i.width <= i.height else (s * i.width // i.height, s)
-        else:
-            ow, oh = i.width, i.height
-        foot += int(round(pr["crop_w"] * i.width / ow)) * int(round(pr["crop_h"] * i.height / oh)) * 3
-    padded_rgb = sum(i.mcu_cols * i.mcu_rows * (256 if i.sampling == 1 else 64) * 3 for i in infos)
-    work = {
-        "scan": ("hbm", entropy_bytes + blocks * 128),          # read stream once + clear coefficients
-        "reconstruct": ("hbm", blocks * 128 + padded_rgb),       # coefficients in, RGB out
-        "resize": ("hbm", foot + out_bytes),                     # crop footprint in, tensor out
-    }
+    work, entropy_bytes = algorithmic_bytes(infos, pr)
     cpu = None
     sym_per_byte = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(streams, pr)
         sym_per_byte = symbols_in(streams)
-    stages = []
-    names = ["scan", "decode", "reconstruct", "resize"]
-    kernels = ["scan_restart_markers (+ clearing coefficients)", "decode_entropy", "reconstruct_rgb",
-               "resize_crop_normalize"]
-    for j, name in enumerate(names):
-        ms = float(stage[j])
-        if name == "decode":
-            if sym_per_byte is None:
-                stages.append({"stage": name, "kernel": kernels[j], "ms": ms, "bound": "alu"})
-                continue
-            ops = sym_per_byte * entropy_bytes * OPS_PER_SYMBOL
-            ach = ops / (ms * 1e-3) / 1e12
-            stages.append({"stage": name, "kernel": kernels[j], "ms": ms, "bound": "alu",
-                           "achieved": ach, "peak": INT_ALU_PEAK_TOPS, "unit": "TOP/s",
-                           "frac": ach / INT_ALU_PEAK_TOPS, "traffic": None,
-                           "symbols_per_launch": sym_per_byte * entropy_bytes,
-                           "compressed_GB_per_s": entropy_bytes / (ms * 1e-3) / 1e9})
-        else:
-            b = work[name][1]
-            ach = b / (ms * 1e-3) / 1e9
-            stages.append({"stage": name, "kernel": kernels[j], "ms": ms, "bound": "hbm",
-                           "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                           "frac": ach / HBM_PEAK_GBS, "traffic": None,
-                           "algorithmic_bytes": b})
-    dominant = max(stages, key=lambda s: s["ms"])
-    roofline = {k: dominant.get(k) for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
-    roofline["kernel"] = dominant["kernel"]
-    roofline["avg_launch_ms"] = dominant["ms"]
+    stages, roofline = stage_report(stage, work, entropy_bytes, sym_per_byte)
 
     result = {
         "metric": METRIC, "value": value, "unit": "images/s", "n_gpus": 1,
