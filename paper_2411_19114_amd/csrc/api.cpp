@@ -222,13 +222,18 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
     rc = take_slot(h, &s);
     if (rc != PREP_OK) return rc;
     memcpy(s->h_recs, h->recs.data(), sizeof(ImageRec) * (size_t)n);
+    // the first reconstruction workgroup of every image, packed behind the records: the
+    // kernel finds its image by counting the entries that do not exceed its index
+    uint32_t *h_group0 = reinterpret_cast<uint32_t *>(s->h_recs + n);
+    for (int32_t i = 0; i < n; i++) h_group0[i] = h->recs[(size_t)i].group0;
     memcpy(s->h_rr, h->rr.data(), sizeof(ResizeRec) * (size_t)n);
     const uint8_t *d_bits = bits_dev ? bits_dev + offsets[0] : h->d_bits;
     if (!bits_dev) {
         memcpy(s->h_bits, base_host, total);
         HIP_TRY(hipMemcpyAsync(h->d_bits, s->h_bits, total, hipMemcpyHostToDevice, stream));
     }
-    HIP_TRY(hipMemcpyAsync(h->d_recs, s->h_recs, sizeof(ImageRec) * (size_t)n, hipMemcpyHostToDevice, stream));
+    HIP_TRY(hipMemcpyAsync(h->d_recs, s->h_recs, (sizeof(ImageRec) + sizeof(uint32_t)) * (size_t)n,
+                           hipMemcpyHostToDevice, stream));
     HIP_TRY(hipMemcpyAsync(h->d_rr, s->h_rr, sizeof(ResizeRec) * (size_t)n, hipMemcpyHostToDevice, stream));
     const bool timing = h->timing;
     hipEvent_t *ev = timing ? &h->ev[(size_t)(h->timed_calls % kTimedCalls) * 5] : nullptr;
@@ -248,7 +253,8 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
                               h->d_coef, h->d_status, stream);
         if (timing) HIP_TRY(hipEventRecord(ev[2], stream));
     }
-    launch_reconstruct(d_bits, h->d_recs, n, P.n_groups, h->d_coef, h->d_rgb, stream);
+    launch_reconstruct(d_bits, h->d_recs, reinterpret_cast<const uint32_t *>(h->d_recs + n), n, P.n_groups,
+                       h->d_coef, h->d_rgb, stream);
     if (timing) HIP_TRY(hipEventRecord(ev[3], stream));
     launch_resize_normalize(h->d_rgb, h->d_rr, h->d_status, n, params->crop_h, params->crop_w,
                             params->out_dtype, params->mean, params->std, out, true, stream);
@@ -298,7 +304,7 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     ok = ok && hipMalloc((void **)&h->d_bits, h->cap_bits) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_coef, h->cap_blocks * 128) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_rgb, h->cap_rgb) == hipSuccess;
-    ok = ok && hipMalloc((void **)&h->d_recs, sizeof(ImageRec) * n) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_recs, (sizeof(ImageRec) + sizeof(uint32_t)) * n) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_rr, sizeof(ResizeRec) * n) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_status, sizeof(int32_t) * n) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_win_count, sizeof(uint32_t) * h->cap_windows) == hipSuccess;
@@ -306,7 +312,7 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     for (int i = 0; ok && i < kSlots; i++) {
         Slot &s = h->slot[i];
         ok = ok && hipHostMalloc((void **)&s.h_bits, h->cap_bits, hipHostMallocDefault) == hipSuccess;
-        ok = ok && hipHostMalloc((void **)&s.h_recs, sizeof(ImageRec) * n, hipHostMallocDefault) == hipSuccess;
+        ok = ok && hipHostMalloc((void **)&s.h_recs, (sizeof(ImageRec) + sizeof(uint32_t)) * n, hipHostMallocDefault) == hipSuccess;
         ok = ok && hipHostMalloc((void **)&s.h_rr, sizeof(ResizeRec) * n, hipHostMallocDefault) == hipSuccess;
         ok = ok && hipHostMalloc((void **)&s.h_status, sizeof(int32_t) * n, hipHostMallocDefault) == hipSuccess;
         ok = ok && hipEventCreateWithFlags(&s.done, hipEventDisableTiming) == hipSuccess;

@@ -80,21 +80,39 @@ constexpr double kTieEps = 1.0 / 1048576.0;
 // JFIF colour values are sums of an integer and one or two products of small integers
 // with three-decimal constants; in float they stay well clear of the half-way points that
 // matter except for isolated saturated-blue cases, so single precision decides the rounding.
-__device__ inline uint32_t round_clamp_u8(float v)
+// v_half = value + 0.5.  Rounding half up is floor(v_half); the conversion truncates
+// instead, which differs only below zero, where both results clamp to 0.
+__device__ inline uint32_t round_clamp_u8(float v_half)
 {
-    const int r = (int)floorf(v + 0.5f);
-    return (uint32_t)min(max(r, 0), 255);
+    return (uint32_t)min(max((int)v_half, 0), 255);
 }
 
-template <typename F>
-__device__ inline int find_image_by(int n, uint32_t x, F key)
+// the three colour values of one pixel from its luma + 0.5 and the chroma terms of its
+// chroma sample, packed R | G << 8 | B << 16
+struct ChromaTerms {
+    float r, g, b;  // 1.402 Cr, -0.344136 Cb - 0.714136 Cr, 1.772 Cb (Cb, Cr less 128)
+};
+__device__ inline ChromaTerms chroma_terms(uint32_t cb_byte, uint32_t cr_byte)
 {
-    int lo = 0, hi = n - 1;
-    while (lo < hi) {
-        int mid = (lo + hi + 1) >> 1;
-        if (key(mid) <= x) lo = mid; else hi = mid - 1;
-    }
-    return lo;
+    const float cb = (float)((int)cb_byte - 128), cr = (float)((int)cr_byte - 128);
+    ChromaTerms t;
+    t.r = 1.402f * cr;
+    t.g = fmaf(-0.714136f, cr, -0.344136f * cb);
+    t.b = 1.772f * cb;
+    return t;
+}
+__device__ inline uint32_t rgb_of(uint32_t y_byte, const ChromaTerms &t)
+{
+    const float yh = (float)y_byte + 0.5f;
+    return round_clamp_u8(yh + t.r) | (round_clamp_u8(yh + t.g) << 8) | (round_clamp_u8(yh + t.b) << 16);
+}
+// four packed pixels -> twelve bytes R G B R G B ...
+__device__ inline void store_rgb4(uint8_t *dst, const uint32_t px[4])
+{
+    uint32_t *d = reinterpret_cast<uint32_t *>(dst);
+    d[0] = px[0] | (px[1] << 24);
+    d[1] = (px[1] >> 8) | (px[2] << 16);
+    d[2] = (px[2] >> 16) | (px[3] << 8);
 }
 
 }  // namespace
@@ -148,7 +166,7 @@ __device__ __forceinline__ void reconstruct_group(ReconShared &S, const uint8_t 
             const int k = l * 8 + j;
             const int c = (int)(int16_t)(w[j >> 1] >> (16 * (j & 1)));
             const int nat = kZigZag.nat[k];
-            T[(nat >> 3) * kTileStride + (nat & 7)] = (double)(c * qi[comp][k]);  // exact in int32
+            T[(nat >> 3) * kTileStride + (nat & 7)] = (double)__mul24(c, qi[comp][k]);  // 16 x 8 bits: exact
         }
     }
     __syncthreads();
@@ -171,7 +189,9 @@ __device__ __forceinline__ void reconstruct_group(ReconShared &S, const uint8_t 
         uint32_t pk[2] = {0, 0};
 #pragma unroll
         for (int x = 0; x < 8; x++) {
-            const int sample = (int)floor(o[x] * 0.125 + (0.5 + kTieEps)) + 128;
+            // level shift and round half up; truncation instead of floor differs only below
+            // zero, where both clamp to 0
+            const int sample = (int)fma(o[x], 0.125, 128.5 + kTieEps);
             pk[x >> 2] |= (uint32_t)min(max(sample, 0), 255) << (8 * (x & 3));
         }
         if (comp == 0) {
@@ -185,52 +205,76 @@ __device__ __forceinline__ void reconstruct_group(ReconShared &S, const uint8_t 
         }
     }
     __syncthreads();
-    // ---- colour: 4 pixels (12 bytes) per item ------------------------------------------
+    // ---- colour ---------------------------------------------------------------------------
     const int rows = 8 * hs, width = gcount * 8 * hs, quads = width >> 2;
-    const int items = rows * quads;
-    const uint8_t *lum8 = reinterpret_cast<const uint8_t *>(luma);
-    const uint8_t *cb8 = reinterpret_cast<const uint8_t *>(chroma[0]);
-    const uint8_t *cr8 = reinterpret_cast<const uint8_t *>(chroma[1]);
     uint8_t *dst0 = rgb_all + R.rgb_off + (size_t)mrow * rows * R.rgb_pitch +
                     (size_t)mcu_x0 * 8 * hs * 3;
-    const int cshift = hs - 1;
-    for (int it = tid; it < items; it += kReconThreads) {
-        const int row = it / quads, x = (it - row * quads) * 4;
-        uint32_t out[3] = {0, 0, 0};
+    if (sampling == PREP_SAMPLING_420) {
+        // an item is 4 x 2 pixels: two chroma samples serve it, so their terms are formed once
+        const int items = (rows >> 1) * quads;
+        const uint16_t *cb16 = reinterpret_cast<const uint16_t *>(chroma[0]);
+        const uint16_t *cr16 = reinterpret_cast<const uint16_t *>(chroma[1]);
+        for (int it = tid; it < items; it += kReconThreads) {
+            const int rp = it / quads, q = it - rp * quads;
+            const uint32_t cbp = cb16[(rp * kChromaPitch) / 2 + q], crp = cr16[(rp * kChromaPitch) / 2 + q];
+            const ChromaTerms t0 = chroma_terms(cbp & 255u, crp & 255u);
+            const ChromaTerms t1 = chroma_terms(cbp >> 8, crp >> 8);
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const uint32_t Y = lum8[row * kLumaPitch + x + j];
-            uint32_t r = Y, gch = Y, bl = Y;
-            if (sampling != PREP_SAMPLING_GRAY) {
-                const int ci = (row >> cshift) * kChromaPitch + ((x + j) >> cshift);
-                const float yf = (float)Y, cb = (float)((int)cb8[ci] - 128), cr = (float)((int)cr8[ci] - 128);
-                r = round_clamp_u8(fmaf(1.402f, cr, yf));
-                gch = round_clamp_u8(fmaf(-0.714136f, cr, fmaf(-0.344136f, cb, yf)));
-                bl = round_clamp_u8(fmaf(1.772f, cb, yf));
+            for (int r = 0; r < 2; r++) {
+                const int row = 2 * rp + r;
+                const uint32_t y4 = luma[(row * kLumaPitch) / 4 + q];
+                const uint32_t px[4] = {rgb_of(y4 & 255u, t0), rgb_of((y4 >> 8) & 255u, t0),
+                                        rgb_of((y4 >> 16) & 255u, t1), rgb_of(y4 >> 24, t1)};
+                store_rgb4(dst0 + (size_t)row * R.rgb_pitch + q * 12, px);
             }
-            const int o = j * 3;
-            out[o >> 2] |= r << (8 * (o & 3));
-            out[(o + 1) >> 2] |= gch << (8 * ((o + 1) & 3));
-            out[(o + 2) >> 2] |= bl << (8 * ((o + 2) & 3));
         }
-        uint32_t *d = reinterpret_cast<uint32_t *>(dst0 + (size_t)row * R.rgb_pitch + x * 3);
-        d[0] = out[0];
-        d[1] = out[1];
-        d[2] = out[2];
+    } else {
+        // an item is 4 pixels of one row
+        const int items = rows * quads;
+        for (int it = tid; it < items; it += kReconThreads) {
+            const int row = it / quads, q = it - row * quads;
+            const uint32_t y4 = luma[(row * kLumaPitch) / 4 + q];
+            uint32_t px[4];
+            if (sampling == PREP_SAMPLING_GRAY) {
+#pragma unroll
+                for (int j = 0; j < 4; j++) px[j] = ((y4 >> (8 * j)) & 255u) * 0x010101u;
+            } else {
+                const uint32_t cb4 = chroma[0][(row * kChromaPitch) / 4 + q];
+                const uint32_t cr4 = chroma[1][(row * kChromaPitch) / 4 + q];
+#pragma unroll
+                for (int j = 0; j < 4; j++)
+                    px[j] = rgb_of((y4 >> (8 * j)) & 255u,
+                                   chroma_terms((cb4 >> (8 * j)) & 255u, (cr4 >> (8 * j)) & 255u));
+            }
+            store_rgb4(dst0 + (size_t)row * R.rgb_pitch + q * 12, px);
+        }
     }
 }
 
+// group0[i] = first workgroup of image i (ascending).  The image of workgroup wg is the last
+// one whose entry does not exceed wg: every lane tests one entry and the hits are counted.
 __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
-    const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
-    const int16_t *__restrict__ coef_all, uint8_t *__restrict__ rgb_all)
+    const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs,
+    const uint32_t *__restrict__ group0, int n_images, const int16_t *__restrict__ coef_all,
+    uint8_t *__restrict__ rgb_all)
 {
     __shared__ ReconShared S;
+    __shared__ uint32_t s_hits[kReconThreads / 64];
     const uint32_t wg = blockIdx.x;
-    const int img = find_image_by(n_images, wg, [&](int i) { return recs[i].group0; });
-    const ImageRec &R = recs[img];
+    uint32_t hits = 0;
+    for (int base = 0; base < n_images; base += kReconThreads) {
+        const int i = base + (int)threadIdx.x;
+        hits += (uint32_t)__popcll(__ballot(i < n_images && group0[i] <= wg));
+    }
+    if ((threadIdx.x & 63) == 0) s_hits[threadIdx.x >> 6] = hits;
+    __syncthreads();
+    hits = 0;
+    for (int w = 0; w < kReconThreads / 64; w++) hits += s_hits[w];
+    if (hits == 0) return;
+    const ImageRec &R = recs[hits - 1];
     if (R.status != PREP_OK) return;
     const uint32_t gi = wg - R.group0;
-    const uint32_t mrow = gi / R.groups_per_row, gcol = gi % R.groups_per_row;
+    const uint32_t mrow = gi / R.groups_per_row, gcol = gi - mrow * R.groups_per_row;
     if (mrow >= R.mcu_rows) return;
     if (R.sampling == PREP_SAMPLING_420)
         reconstruct_group<PREP_SAMPLING_420>(S, bits, R, mrow, gcol, coef_all, rgb_all);
@@ -240,11 +284,11 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
         reconstruct_group<PREP_SAMPLING_GRAY>(S, bits, R, mrow, gcol, coef_all, rgb_all);
 }
 
-void launch_reconstruct(const uint8_t *bits, const ImageRec *recs, int n_images, uint32_t n_groups,
-                        const int16_t *coef, uint8_t *rgb, hipStream_t stream)
+void launch_reconstruct(const uint8_t *bits, const ImageRec *recs, const uint32_t *group0, int n_images,
+                        uint32_t n_groups, const int16_t *coef, uint8_t *rgb, hipStream_t stream)
 {
     if (n_groups == 0) return;
-    hipLaunchKernelGGL(reconstruct_rgb, dim3(n_groups), dim3(kReconThreads), 0, stream, bits, recs,
+    hipLaunchKernelGGL(reconstruct_rgb, dim3(n_groups), dim3(kReconThreads), 0, stream, bits, recs, group0,
                        n_images, coef, rgb);
 }
 

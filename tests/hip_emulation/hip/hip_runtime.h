@@ -110,6 +110,20 @@ inline int __syncthreads_or(int p)
     if (t.tid.x == 0) c.orflag[slot].store(0);
     return r;
 }
+// mask of the lanes of the wave whose predicate is true
+inline unsigned long long __ballot(int pred)
+{
+    hip_emul::ThreadState &t = hip_emul::tls;
+    const unsigned tid = t.tid.x, wave = tid >> 6;
+    hip_emul::BlockCtx &c = *t.ctx;
+    const unsigned wave_n = std::min(64u, c.nthreads - wave * 64);
+    c.xchg[tid] = pred ? 1 : 0;
+    c.wave_bar[wave]->arrive_and_wait();
+    unsigned long long m = 0;
+    for (unsigned l = 0; l < wave_n; l++) m |= (unsigned long long)(c.xchg[wave * 64 + l] & 1) << l;
+    c.wave_bar[wave]->arrive_and_wait();
+    return m;
+}
 template <typename T>
 inline T __shfl(T v, int src, int = 64) { return hip_emul::shuffle(v, [src](int) { return src; }); }
 template <typename T>
@@ -132,6 +146,7 @@ inline uint32_t __builtin_amdgcn_alignbit(uint32_t hi, uint32_t lo, uint32_t shi
 {
     return (uint32_t)(((((uint64_t)hi) << 32) | lo) >> (shift & 31u));
 }
+inline int __mul24(int a, int b) { return a * b; }
 inline int __popcll(unsigned long long v) { return __builtin_popcountll(v); }
 
 template <typename T> inline T min(T a, T b) { return b < a ? b : a; }
