@@ -119,10 +119,13 @@ int prep_decode_resize_batch(prep_handle *h, const uint8_t *bitstreams, const ui
 
 /*
  * Same computation for a batch whose bytes already lie in device memory:
- * `bitstreams_device` (DEVICE) holds the same bytes as `bitstreams` (HOST).  The
- * host copy is read only up to each file's start-of-scan header (a few hundred
- * bytes per file); the entropy-coded data is read on the GPU alone and is not
- * copied.  `bitstreams_device` must stay valid until `stream` has run the work.
+ * `bitstreams_device` (DEVICE) holds the same bytes as `bitstreams` (HOST).  Of
+ * the host copy only the headers up to each file's start-of-scan header (a few
+ * hundred bytes per file) and the bytes at its end (to find the EOI marker) are
+ * read; the entropy-coded data is read on the GPU alone and is not copied.
+ * `bitstreams_device` must stay valid until `stream` has run the work.  The
+ * kernels read it with aligned 16-byte loads that contain at least one byte of
+ * a file, so they stay inside the last page of the buffer whatever its size.
  */
 int prep_decode_resize_batch_resident(prep_handle *h, const uint8_t *bitstreams,
                                       const uint8_t *bitstreams_device, const uint64_t *offsets,
