@@ -245,9 +245,9 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
             HIP_TRY(hipMemcpyAsync(h->d_coef, coef_host, P.n_blocks * 128, hipMemcpyHostToDevice, stream));
         if (timing) { HIP_TRY(hipEventRecord(ev[1], stream)); HIP_TRY(hipEventRecord(ev[2], stream)); }
     } else {
-        if (P.n_blocks) HIP_TRY(hipMemsetAsync(h->d_coef, 0, P.n_blocks * 128, stream));
+        // the scan also clears the coefficients of the batch (P.n_windows >= n > 0)
         launch_scan_restart_markers(d_bits, h->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
-                                    h->d_status, stream);
+                                    h->d_status, h->d_coef, P.n_blocks, stream);
         if (timing) HIP_TRY(hipEventRecord(ev[1], stream));
         launch_decode_entropy(d_bits, h->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
                               h->d_coef, h->d_status, stream);

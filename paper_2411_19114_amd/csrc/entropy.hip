@@ -642,13 +642,29 @@ __device__ inline void classify16(const uint4 v, uint32_t prev, uint32_t nextb, 
 // window w of an image = raw bytes [w*kWindowBytes, (w+1)*kWindowBytes) of its
 // entropy-coded segment.  cnt = RSTn markers whose FF byte lies in the window,
 // first = offset (from the segment start) of the first such FF byte.
+// The workgroups also clear the coefficient workspace between them (the decoder stores only
+// the coefficients that symbols name): workgroup wg clears 16-byte units [wg, wg + 1) *
+// clear_per_wg of the clear_units that the batch uses.
 __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
     const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
     uint32_t *__restrict__ win_count, uint32_t *__restrict__ win_first,
-    int32_t *__restrict__ status)
+    int32_t *__restrict__ status, uint4 *__restrict__ clear, uint64_t clear_units,
+    uint64_t clear_per_wg)
 {
     __shared__ uint32_t s_cnt[kT / 64], s_first[kT / 64];
     const uint32_t wg = blockIdx.x;
+    {
+        const uint64_t lo = (uint64_t)wg * clear_per_wg;
+        const uint64_t hi = lo + clear_per_wg < clear_units ? lo + clear_per_wg : clear_units;
+        uint64_t i = lo + threadIdx.x;
+        for (; i + 3 * kT < hi; i += 4 * kT) {
+            clear[i] = make_uint4(0, 0, 0, 0);
+            clear[i + kT] = make_uint4(0, 0, 0, 0);
+            clear[i + 2 * kT] = make_uint4(0, 0, 0, 0);
+            clear[i + 3 * kT] = make_uint4(0, 0, 0, 0);
+        }
+        for (; i < hi; i += kT) clear[i] = make_uint4(0, 0, 0, 0);
+    }
     const int img = find_image(n_images, wg, [&](int i) { return recs[i].window0; });
     const ImageRec &R = recs[img];
     const uint32_t w = wg - R.window0;
@@ -1025,11 +1041,14 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
 
 void launch_scan_restart_markers(const uint8_t *bits, const ImageRec *recs, int n_images,
                                  uint32_t n_windows, uint32_t *win_count, uint32_t *win_first,
-                                 int32_t *status, hipStream_t stream)
+                                 int32_t *status, int16_t *coef, uint64_t n_blocks, hipStream_t stream)
 {
     if (n_windows == 0) return;
+    const uint64_t clear_units = n_blocks * 8;  // 128 bytes per block, 16 per unit
+    const uint64_t clear_per_wg = (clear_units + n_windows - 1) / n_windows;
     hipLaunchKernelGGL(scan_restart_markers, dim3(n_windows), dim3(kDecodeThreads), 0, stream, bits,
-                       recs, n_images, win_count, win_first, status);
+                       recs, n_images, win_count, win_first, status, reinterpret_cast<uint4 *>(coef),
+                       clear_units, clear_per_wg);
 }
 
 void launch_decode_entropy(const uint8_t *bits, const ImageRec *recs, int n_images,

@@ -10,7 +10,7 @@ namespace prep {
 // entropy.hip
 void launch_scan_restart_markers(const uint8_t *bits, const ImageRec *recs, int n_images,
                                  uint32_t n_windows, uint32_t *win_count, uint32_t *win_first,
-                                 int32_t *status, hipStream_t stream);
+                                 int32_t *status, int16_t *coef, uint64_t n_blocks, hipStream_t stream);
 void launch_decode_entropy(const uint8_t *bits, const ImageRec *recs, int n_images,
                            uint32_t n_windows, const uint32_t *win_count, const uint32_t *win_first,
                            int16_t *coef, int32_t *status, hipStream_t stream);
