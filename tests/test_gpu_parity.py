@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 import synth
-from helpers import MEAN, STD, check_against_oracle, oracle_batch, run_gpu
+from helpers import MEAN, STD, TENSOR_ABS_TOL, check_against_oracle, oracle_batch, run_gpu
 from oracle import MODE_420, MODE_444, MODE_GRAY
 
 pytestmark = pytest.mark.gpu
@@ -227,3 +227,62 @@ def test_reconstruct_stage_alone_on_oracle_coefficients(pp):
         d = np.abs(pp.debug_last_rgb(i, info.height, info.width).astype(int) - rgb.astype(int))
         assert d.max() <= 1 and (d == 0).mean() >= 0.999
         assert np.abs(got[i] - ten).max() <= 0.02
+
+
+def test_medium_restart_intervals_cross_subsequences(pp):
+    # intervals of a few KiB: the speculative pass meets restart boundaries inside its
+    # subsequences in most waves, for every sampling mode
+    streams = []
+    for k, mode in enumerate((MODE_444, MODE_420, MODE_GRAY)):
+        rgb = _img(500 + k, 640, 360, sigma=18.0)
+        cols = -(-640 // (16 if mode == MODE_420 else 8))
+        for dri in (cols // 2, cols, 3 * cols):
+            streams.append(oracle.encode(rgb, 93, mode, dri)[0])
+    check_against_oracle(pp, streams, 200, 160, 192, "f16")
+
+
+def test_concurrent_handles_and_streams(prep):
+    # the serving pattern of workload 3: several host threads, each with its own handle and
+    # stream, decode different batches at the same time
+    import threading
+    import torch
+    from paper_2411_19114_amd.binding import make_params
+    n_workers, per_batch, rounds = 4, 6, 3
+    pool = synth.make_batch(3, n_workers * per_batch)
+    blob, offsets = synth.pack(pool)
+    dev_bits = torch.from_numpy(blob).to("cuda:0")
+    torch.cuda.synchronize()
+    pr = synth.params_of(3)
+    params = make_params(pr["resize_short"], pr["crop_h"], pr["crop_w"], pr["out_dtype"], MEAN, STD)
+    ref = oracle_batch(pool, pr["resize_short"], pr["crop_h"], pr["crop_w"])
+    results, errors = [None] * n_workers, []
+
+    def worker(i):
+        try:
+            pp_i = prep.Preprocessor(device=0, max_batch=per_batch, max_width=256, max_height=256,
+                                     max_bitstream_bytes=1 << 20)
+            hs = torch.cuda.Stream(device="cuda:0")
+            out = torch.empty((per_batch, 3, pr["crop_h"], pr["crop_w"]), dtype=torch.float32, device="cuda:0")
+            o = offsets[i * per_batch:(i + 1) * per_batch + 1]
+            for _ in range(rounds):
+                out.fill_(777.0)
+                hs.wait_stream(torch.cuda.current_stream())
+                pp_i.decode_resize_batch_resident(blob, dev_bits.data_ptr(), o, params, out.data_ptr(),
+                                                  hs.cuda_stream)
+                hs.synchronize()
+                assert pp_i.get_status(per_batch) == [0] * per_batch
+            results[i] = out.cpu().numpy().astype(np.float64)
+            pp_i.close()
+        except Exception as e:  # reported by the main thread
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(n_workers)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for i in range(n_workers):
+        for j in range(per_batch):
+            err = np.abs(results[i][j] - ref[i * per_batch + j][3]).max()
+            assert err <= TENSOR_ABS_TOL, f"worker {i} image {j}: tensor off by {err}"
