@@ -6,7 +6,10 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
+#include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "../../include/prep.h"
@@ -36,6 +39,7 @@ struct Slot {
 struct Plan {                         // what one call will run
     uint32_t n_windows = 0;
     uint32_t n_groups = 0;
+    uint32_t n_tables = 0;     // distinct sets of Huffman tables (<= the handle's table slots)
     uint64_t n_blocks = 0;
     uint64_t rgb_bytes = 0;
 };
@@ -48,7 +52,11 @@ struct prep_handle {
     uint8_t *d_bits = nullptr;
     int16_t *d_coef = nullptr;
     uint8_t *d_rgb = nullptr;
-    ImageRec *d_recs = nullptr;
+    ImageRec *d_recs = nullptr;   // n records, then n first-group indices, then <= n table owners
+    uint8_t *d_tables = nullptr;  // table_slots expanded Huffman table sets
+    uint32_t table_slots = 0;
+    std::vector<uint32_t> table_rep;                      // image that owns each slot of this call
+    std::unordered_map<std::string, uint32_t> table_of;   // DHT bytes -> slot, per call
     ResizeRec *d_rr = nullptr;
     int32_t *d_status = nullptr;
     uint32_t *d_win_count = nullptr, *d_win_first = nullptr;
@@ -124,6 +132,8 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
     h->parsed.resize((size_t)n);
     h->recs.resize((size_t)n);
     h->rr.resize((size_t)n);
+    h->table_rep.clear();
+    h->table_of.clear();
     Plan P;
     for (int32_t i = 0; i < n; i++) {
         if (offsets[i + 1] < offsets[i]) return PREP_E_INVALID_ARG;
@@ -156,6 +166,23 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
             const int per = recon_mcus_per_group(I.sampling);
             R.groups_per_row = (uint32_t)((I.mcu_cols + per - 1) / per);
             for (int t = 0; t < 4; t++) { R.dht_off[t] = pi.dht_off[t]; R.dht_nval[t] = pi.dht_nval[t]; }
+            {
+                // images with the same four tables share one expanded copy
+                std::string key;
+                for (int t = 0; t < 4; t++)
+                    key.append(reinterpret_cast<const char *>(bits + offsets[i] + pi.dht_off[t]),
+                               16 + (size_t)std::min<uint32_t>(pi.dht_nval[t], 256u));
+                auto it = h->table_of.find(key);
+                if (it != h->table_of.end()) {
+                    R.table_slot = it->second;
+                } else if (h->table_rep.size() < h->table_slots) {
+                    R.table_slot = (uint32_t)h->table_rep.size();
+                    h->table_of.emplace(std::move(key), R.table_slot);
+                    h->table_rep.push_back((uint32_t)i);
+                } else {
+                    R.table_slot = kNoTableSlot;
+                }
+            }
             for (int c = 0; c < 3; c++) R.dqt_off[c] = pi.dqt_off[c];
             R.width = (uint16_t)I.width;
             R.height = (uint16_t)I.height;
@@ -177,6 +204,7 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
         }
         P.n_windows += R.n_windows;
     }
+    P.n_tables = (uint32_t)h->table_rep.size();
     if (P.n_blocks > h->cap_blocks || P.rgb_bytes > h->cap_rgb || P.n_windows > h->cap_windows)
         return PREP_E_TOO_LARGE;
     *plan = P;
@@ -226,13 +254,14 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
     // kernel finds its image by counting the entries that do not exceed its index
     uint32_t *h_group0 = reinterpret_cast<uint32_t *>(s->h_recs + n);
     for (int32_t i = 0; i < n; i++) h_group0[i] = h->recs[(size_t)i].group0;
+    for (uint32_t t = 0; t < P.n_tables; t++) h_group0[n + (int32_t)t] = h->table_rep[t];
     memcpy(s->h_rr, h->rr.data(), sizeof(ResizeRec) * (size_t)n);
     const uint8_t *d_bits = bits_dev ? bits_dev + offsets[0] : h->d_bits;
     if (!bits_dev) {
         memcpy(s->h_bits, base_host, total);
         HIP_TRY(hipMemcpyAsync(h->d_bits, s->h_bits, total, hipMemcpyHostToDevice, stream));
     }
-    HIP_TRY(hipMemcpyAsync(h->d_recs, s->h_recs, (sizeof(ImageRec) + sizeof(uint32_t)) * (size_t)n,
+    HIP_TRY(hipMemcpyAsync(h->d_recs, s->h_recs, (sizeof(ImageRec) + 2 * sizeof(uint32_t)) * (size_t)n,
                            hipMemcpyHostToDevice, stream));
     HIP_TRY(hipMemcpyAsync(h->d_rr, s->h_rr, sizeof(ResizeRec) * (size_t)n, hipMemcpyHostToDevice, stream));
     const bool timing = h->timing;
@@ -247,10 +276,12 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
     } else {
         // the scan also clears the coefficients of the batch (P.n_windows >= n > 0)
         launch_scan_restart_markers(d_bits, h->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
-                                    h->d_status, h->d_coef, P.n_blocks, stream);
+                                    h->d_status, h->d_coef, P.n_blocks,
+                                    reinterpret_cast<const uint32_t *>(h->d_recs + n) + n, P.n_tables,
+                                    h->d_tables, stream);
         if (timing) HIP_TRY(hipEventRecord(ev[1], stream));
         launch_decode_entropy(d_bits, h->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
-                              h->d_coef, h->d_status, stream);
+                              h->d_coef, h->d_status, h->d_tables, stream);
         if (timing) HIP_TRY(hipEventRecord(ev[2], stream));
     }
     launch_reconstruct(d_bits, h->d_recs, reinterpret_cast<const uint32_t *>(h->d_recs + n), n, P.n_groups,
@@ -304,7 +335,9 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     ok = ok && hipMalloc((void **)&h->d_bits, h->cap_bits) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_coef, h->cap_blocks * 128) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_rgb, h->cap_rgb) == hipSuccess;
-    ok = ok && hipMalloc((void **)&h->d_recs, (sizeof(ImageRec) + sizeof(uint32_t)) * n) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_recs, (sizeof(ImageRec) + 2 * sizeof(uint32_t)) * n) == hipSuccess;
+    h->table_slots = std::min<uint32_t>((uint32_t)n, kMaxTableSlots);
+    ok = ok && hipMalloc((void **)&h->d_tables, (size_t)h->table_slots * huff_tables_bytes()) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_rr, sizeof(ResizeRec) * n) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_status, sizeof(int32_t) * n) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_win_count, sizeof(uint32_t) * h->cap_windows) == hipSuccess;
@@ -312,7 +345,7 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     for (int i = 0; ok && i < kSlots; i++) {
         Slot &s = h->slot[i];
         ok = ok && hipHostMalloc((void **)&s.h_bits, h->cap_bits, hipHostMallocDefault) == hipSuccess;
-        ok = ok && hipHostMalloc((void **)&s.h_recs, (sizeof(ImageRec) + sizeof(uint32_t)) * n, hipHostMallocDefault) == hipSuccess;
+        ok = ok && hipHostMalloc((void **)&s.h_recs, (sizeof(ImageRec) + 2 * sizeof(uint32_t)) * n, hipHostMallocDefault) == hipSuccess;
         ok = ok && hipHostMalloc((void **)&s.h_rr, sizeof(ResizeRec) * n, hipHostMallocDefault) == hipSuccess;
         ok = ok && hipHostMalloc((void **)&s.h_status, sizeof(int32_t) * n, hipHostMallocDefault) == hipSuccess;
         ok = ok && hipEventCreateWithFlags(&s.done, hipEventDisableTiming) == hipSuccess;
@@ -338,6 +371,7 @@ int prep_destroy(prep_handle *h)
     (void)hipFree(h->d_coef);
     (void)hipFree(h->d_rgb);
     (void)hipFree(h->d_recs);
+    (void)hipFree(h->d_tables);
     (void)hipFree(h->d_rr);
     (void)hipFree(h->d_status);
     (void)hipFree(h->d_win_count);

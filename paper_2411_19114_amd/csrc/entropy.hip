@@ -21,6 +21,7 @@
 //        blocks gives every lane its block index, a last pass writes coefficients,
 //        and a segmented scan turns DC differences into absolute values.
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include "../../include/prep.h"
@@ -53,7 +54,7 @@ static_assert(kSubseqBytes == 64 && (kSubseqBytes / 4) == (1 << kPadShift), "one
 constexpr uint32_t kStore = 0x0400u, kUseLoop = 0x07FFu;
 constexpr uint32_t kInvalidEntry = (16u << 11) | (63u << 4);  // 16 bits, ends the block
 
-struct HuffTables {
+struct alignas(16) HuffTables {
     alignas(8) uint16_t lut[4 << kLutBits];  // first level, indexed by the next kLutBits bits
     uint16_t sub[4 * kSubEntries];   // second level
     int32_t first[4][17];            // first code of each length
@@ -207,10 +208,12 @@ __device__ inline uint32_t make_entry(bool ac, uint32_t sym, uint32_t len)
 // begin with it.  Entries above the last code of at most kLutBits bits begin longer codes (or
 // nothing): each such prefix gets a block of the second-level pool sized for the longest
 // code that shares it.
-__device__ inline void build_tables(HuffTables &T, const uint8_t *file, const ImageRec &R)
+// Expands tables t_lo .. t_hi-1 of the four (all lanes of the workgroup must call).
+__device__ inline void build_tables(HuffTables &T, const uint8_t *file, const ImageRec &R, int t_lo = 0,
+                                    int t_hi = 4)
 {
     const int tid = threadIdx.x;
-    if (tid < 4) {
+    if (tid >= t_lo && tid < t_hi) {
         const uint8_t *b = file + R.dht_off[tid];
         int32_t bits[16];
 #pragma unroll
@@ -228,14 +231,14 @@ __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const Im
         }
         T.sub_used[tid] = 0;
     }
-    for (int t = 0; t < 4; t++) {
+    for (int t = t_lo; t < t_hi; t++) {
         const uint32_t nval = min(R.dht_nval[t], 256u);
 #pragma unroll
         for (uint32_t i = tid; i < 256u; i += kT) T.huffval[t][i] = i < nval ? file[R.dht_off[t] + 16 + i] : 0;
     }
-    for (int i = tid; i < 4 * kSubEntries; i += kT) T.sub[i] = 0;
+    for (int i = t_lo * kSubEntries + tid; i < t_hi * kSubEntries; i += kT) T.sub[i] = 0;
     __syncthreads();
-    for (int t = 0; t < 4; t++) {
+    for (int t = t_lo; t < t_hi; t++) {
         // codes of at most kLutBits bits: one lane per code
         const int32_t n_short = min(T.valptr[t][kLutBits] + T.count[t][kLutBits], 256);
         for (int32_t i = tid; i < n_short; i += kT) {
@@ -283,7 +286,7 @@ __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const Im
     }
     __syncthreads();
     // second level: entry i of a block with nb extra bits covers prefix:i:anything
-    for (int t = 0; t < 4; t++) {
+    for (int t = t_lo; t < t_hi; t++) {
         const uint32_t used = min(T.sub_used[t], (uint32_t)kSubEntries);
         for (uint32_t i = tid; i < used; i += kT) {
             const uint32_t note = T.sub[t * kSubEntries + i];
@@ -645,14 +648,41 @@ __device__ inline void classify16(const uint4 v, uint32_t prev, uint32_t nextb, 
 // The workgroups also clear the coefficient workspace between them (the decoder stores only
 // the coefficients that symbols name): workgroup wg clears 16-byte units [wg, wg + 1) *
 // clear_per_wg of the clear_units that the batch uses.
+// Workgroups from n_windows on do something else: workgroup n_windows + 4 s + t expands
+// Huffman table t of image table_rep[s] into slot s of `tables`.
 __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
     const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
-    uint32_t *__restrict__ win_count, uint32_t *__restrict__ win_first,
+    uint32_t n_windows, uint32_t *__restrict__ win_count, uint32_t *__restrict__ win_first,
     int32_t *__restrict__ status, uint4 *__restrict__ clear, uint64_t clear_units,
-    uint64_t clear_per_wg)
+    uint64_t clear_per_wg, const uint32_t *__restrict__ table_rep, uint4 *__restrict__ tables)
 {
     __shared__ uint32_t s_cnt[kT / 64], s_first[kT / 64];
     const uint32_t wg = blockIdx.x;
+    if (wg >= n_windows) {
+        // four workgroups per slot, one table each, so that the expansion is not the longest
+        // thing this kernel does
+        __shared__ HuffTables tab;
+        const uint32_t slot = (wg - n_windows) >> 2;
+        const int t = (int)((wg - n_windows) & 3u);
+        const ImageRec &I = recs[table_rep[slot]];
+        build_tables(tab, bits + I.file_off, I, t, t + 1);
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(&tab);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(tables) + (size_t)slot * (sizeof(HuffTables) / 4);
+        // the members of table t, as 32-bit words of the struct
+        const uint32_t part[7][2] = {
+            {(uint32_t)offsetof(HuffTables, lut) + (uint32_t)t * (2u << kLutBits), 2u << kLutBits},
+            {(uint32_t)offsetof(HuffTables, sub) + (uint32_t)t * 2u * kSubEntries, 2u * kSubEntries},
+            {(uint32_t)offsetof(HuffTables, first) + (uint32_t)t * 68u, 68u},
+            {(uint32_t)offsetof(HuffTables, count) + (uint32_t)t * 68u, 68u},
+            {(uint32_t)offsetof(HuffTables, valptr) + (uint32_t)t * 68u, 68u},
+            {(uint32_t)offsetof(HuffTables, huffval) + (uint32_t)t * 256u, 256u},
+            {(uint32_t)offsetof(HuffTables, sub_used) + (uint32_t)t * 4u, 4u}};
+#pragma unroll
+        for (int m = 0; m < 7; m++)
+            for (uint32_t i = threadIdx.x; i < part[m][1] / 4; i += kT)
+                dst[part[m][0] / 4 + i] = src[part[m][0] / 4 + i];
+        return;
+    }
     {
         const uint64_t lo = (uint64_t)wg * clear_per_wg;
         const uint64_t hi = lo + clear_per_wg < clear_units ? lo + clear_per_wg : clear_units;
@@ -714,7 +744,7 @@ __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
 __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
     const uint32_t *__restrict__ win_count, const uint32_t *__restrict__ win_first,
-    int16_t *__restrict__ coef_all, int32_t *__restrict__ status)
+    int16_t *__restrict__ coef_all, int32_t *__restrict__ status, const uint4 *__restrict__ tables)
 {
     __shared__ DecodeShared S;
     const int tid = threadIdx.x;
@@ -783,7 +813,15 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     }
 
     const uint8_t *file = bits + R.file_off;
-    build_tables(S.tab, file, R);
+    if (R.table_slot != kNoTableSlot) {
+        // the tables were expanded once for the batch: copy them
+        constexpr uint32_t units = sizeof(HuffTables) / 16;
+        uint4 *dst = reinterpret_cast<uint4 *>(&S.tab);
+        for (uint32_t i = tid; i < units; i += kT) dst[i] = tables[(size_t)R.table_slot * units + i];
+        __syncthreads();
+    } else {
+        build_tables(S.tab, file, R);
+    }
 
     const uint8_t *seg = file + R.entropy_rel;
     int16_t *coef = coef_all + (size_t)R.coef_block0 * 64;
@@ -1039,25 +1077,32 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     }
 }
 
+size_t huff_tables_bytes() { return sizeof(HuffTables); }
+static_assert(sizeof(HuffTables) % 16 == 0, "table slots are copied in 16-byte units");
+
 void launch_scan_restart_markers(const uint8_t *bits, const ImageRec *recs, int n_images,
                                  uint32_t n_windows, uint32_t *win_count, uint32_t *win_first,
-                                 int32_t *status, int16_t *coef, uint64_t n_blocks, hipStream_t stream)
+                                 int32_t *status, int16_t *coef, uint64_t n_blocks,
+                                 const uint32_t *table_rep, uint32_t n_tables, uint8_t *tables,
+                                 hipStream_t stream)
 {
     if (n_windows == 0) return;
     const uint64_t clear_units = n_blocks * 8;  // 128 bytes per block, 16 per unit
     const uint64_t clear_per_wg = (clear_units + n_windows - 1) / n_windows;
-    hipLaunchKernelGGL(scan_restart_markers, dim3(n_windows), dim3(kDecodeThreads), 0, stream, bits,
-                       recs, n_images, win_count, win_first, status, reinterpret_cast<uint4 *>(coef),
-                       clear_units, clear_per_wg);
+    hipLaunchKernelGGL(scan_restart_markers, dim3(n_windows + 4 * n_tables), dim3(kDecodeThreads), 0, stream,
+                       bits, recs, n_images, n_windows, win_count, win_first, status,
+                       reinterpret_cast<uint4 *>(coef), clear_units, clear_per_wg, table_rep,
+                       reinterpret_cast<uint4 *>(tables));
 }
 
 void launch_decode_entropy(const uint8_t *bits, const ImageRec *recs, int n_images,
                            uint32_t n_windows, const uint32_t *win_count, const uint32_t *win_first,
-                           int16_t *coef, int32_t *status, hipStream_t stream)
+                           int16_t *coef, int32_t *status, const uint8_t *tables, hipStream_t stream)
 {
     if (n_windows == 0) return;
     hipLaunchKernelGGL(decode_entropy, dim3(n_windows), dim3(kDecodeThreads), 0, stream, bits, recs,
-                       n_images, win_count, win_first, coef, status);
+                       n_images, win_count, win_first, coef, status,
+                       reinterpret_cast<const uint4 *>(tables));
 }
 
 }  // namespace prep

@@ -1,6 +1,7 @@
 // Launchers of libprep's HIP kernels (one translation unit per stage).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include "prep_internal.h"
@@ -8,12 +9,17 @@
 namespace prep {
 
 // entropy.hip
+// bytes of one slot of expanded Huffman tables
+size_t huff_tables_bytes();
+// table_rep[s] = an image whose tables go into slot s of `tables` (n_tables slots)
 void launch_scan_restart_markers(const uint8_t *bits, const ImageRec *recs, int n_images,
                                  uint32_t n_windows, uint32_t *win_count, uint32_t *win_first,
-                                 int32_t *status, int16_t *coef, uint64_t n_blocks, hipStream_t stream);
+                                 int32_t *status, int16_t *coef, uint64_t n_blocks,
+                                 const uint32_t *table_rep, uint32_t n_tables, uint8_t *tables,
+                                 hipStream_t stream);
 void launch_decode_entropy(const uint8_t *bits, const ImageRec *recs, int n_images,
                            uint32_t n_windows, const uint32_t *win_count, const uint32_t *win_first,
-                           int16_t *coef, int32_t *status, hipStream_t stream);
+                           int16_t *coef, int32_t *status, const uint8_t *tables, hipStream_t stream);
 
 // reconstruct.hip
 void launch_reconstruct(const uint8_t *bits, const ImageRec *recs, const uint32_t *group0, int n_images,

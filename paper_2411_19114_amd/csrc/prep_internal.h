@@ -16,6 +16,11 @@ constexpr int kChunkRaw = kDecodeThreads * kSubseqBytes;    // raw bytes staged 
 constexpr int kChunkTail = 16;                              // bytes a non-final chunk keeps back
 constexpr int kWindowBytes = 12288;                         // raw bytes between workgroup starts
 constexpr int kLutBits = 10;                                // first-level Huffman lookup width
+// Images of a batch mostly share their Huffman tables (encoders write the tables of T.81
+// Annex K unless asked to optimise): each distinct set of four tables is expanded once per
+// batch into a slot of device memory and copied into LDS by the workgroups that need it.
+constexpr uint32_t kMaxTableSlots = 1024;
+constexpr uint32_t kNoTableSlot = 0xFFFFFFFFu;             // expand the tables in the workgroup
 
 // ---- reconstruction geometry ----------------------------------------------
 // One workgroup turns kReconBlocks 8x8 blocks (a run of MCUs of one MCU row)
@@ -48,6 +53,8 @@ struct ImageRec {
     uint8_t sampling;           // PREP_SAMPLING_*
     uint8_t blocks_per_mcu;
     int32_t status;             // host verdict; kernels skip images that are not PREP_OK
+    uint32_t table_slot;        // expanded Huffman tables of this image, or kNoTableSlot
+    uint32_t pad_;
 };
 static_assert(sizeof(ImageRec) % 8 == 0, "ImageRec must keep 8-byte alignment in arrays");
 
