@@ -47,6 +47,9 @@ enum {
 };
 
 enum { PREP_F32 = 0, PREP_F16 = 1 };
+/* prep_config.flags: expand the Huffman tables in every decoder workgroup instead of once
+ * per distinct table set of the batch (same results; kept for checking that path) */
+enum { PREP_FLAG_TABLES_PER_WORKGROUP = 1 };
 enum { PREP_SAMPLING_444 = 0, PREP_SAMPLING_420 = 1, PREP_SAMPLING_GRAY = 2 };
 
 typedef struct prep_handle prep_handle;
@@ -59,7 +62,7 @@ typedef struct {
     uint64_t max_bitstream_bytes; /* largest sum of file sizes of one call           */
     uint64_t max_total_pixels;    /* largest sum of width*height of one call;
                                      0 = max_batch * max_width * max_height         */
-    uint32_t flags;               /* reserved, must be 0                             */
+    uint32_t flags;               /* 0 or PREP_FLAG_*; other bits must be 0          */
 } prep_config;
 
 /* Resize / crop / normalize parameters, the same for every image of a call. */

@@ -11,6 +11,7 @@ _SOURCES = ["entropy.hip", "reconstruct.hip", "resize.hip", "api.cpp", "parser.c
 
 OK, E_INVALID_ARG, E_TOO_LARGE, E_HIP, E_UNSUPPORTED, E_CORRUPT, E_NOMEM = 0, -1, -2, -3, -4, -5, -6
 F32, F16 = 0, 1
+FLAG_TABLES_PER_WORKGROUP = 1
 
 
 def lib_path():
@@ -164,10 +165,10 @@ class Preprocessor:
     """Owns one prep_handle.  Device pointers are plain integers (tensor.data_ptr())."""
 
     def __init__(self, device=0, max_batch=256, max_width=640, max_height=640,
-                 max_bitstream_bytes=64 << 20, max_total_pixels=0):
+                 max_bitstream_bytes=64 << 20, max_total_pixels=0, flags=0):
         self._h = C.c_void_p()
         cfg = Config(device, max_batch, max_width, max_height, max_bitstream_bytes,
-                     max_total_pixels, 0)
+                     max_total_pixels, flags)
         _check(lib().prep_create(C.byref(self._h), C.byref(cfg)), "prep_create")
 
     def close(self):

@@ -8,8 +8,6 @@
 
 #include <algorithm>
 #include <new>
-#include <string>
-#include <unordered_map>
 #include <vector>
 
 #include "../../include/prep.h"
@@ -55,8 +53,8 @@ struct prep_handle {
     ImageRec *d_recs = nullptr;   // n records, then n first-group indices, then <= n table owners
     uint8_t *d_tables = nullptr;  // table_slots expanded Huffman table sets
     uint32_t table_slots = 0;
-    std::vector<uint32_t> table_rep;                      // image that owns each slot of this call
-    std::unordered_map<std::string, uint32_t> table_of;   // DHT bytes -> slot, per call
+    std::vector<uint32_t> table_rep;   // image that owns each slot of this call
+    std::vector<uint32_t> table_hash;  // open-addressed: slot + 1 of a table set by the hash of its DHT bytes, 0 = free
     ResizeRec *d_rr = nullptr;
     int32_t *d_status = nullptr;
     uint32_t *d_win_count = nullptr, *d_win_first = nullptr;
@@ -125,6 +123,37 @@ bool make_resize_rec(int w, int h, const prep_params *p, uint64_t src_off, uint3
     return true;
 }
 
+// Images with the same four Huffman tables share one expanded copy: the slot of image i's
+// tables, found by the bytes of its DHT segments (BITS and HUFFVAL of the four tables), or
+// kNoTableSlot when the handle's slots are used up.  h->parsed[i] must be filled.
+uint32_t table_slot_of(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int32_t i)
+{
+    const ParsedImage &pi = h->parsed[(size_t)i];
+    const uint8_t *file = bits + offsets[i];
+    auto len_of = [](const ParsedImage &p, int t) { return 16u + std::min<uint32_t>(p.dht_nval[t], 256u); };
+    uint64_t hash = 1469598103934665603ull;  // FNV-1a
+    for (int t = 0; t < 4; t++)
+        for (uint32_t k = 0; k < len_of(pi, t); k++) hash = (hash ^ file[pi.dht_off[t] + k]) * 1099511628211ull;
+    const size_t mask = h->table_hash.size() - 1;  // a power of two, twice the slots
+    for (size_t at = (size_t)hash & mask;; at = (at + 1) & mask) {
+        const uint32_t entry = h->table_hash[at];
+        if (entry == 0) {
+            if (h->table_rep.size() >= h->table_slots) return kNoTableSlot;
+            h->table_rep.push_back((uint32_t)i);
+            h->table_hash[at] = (uint32_t)h->table_rep.size();
+            return (uint32_t)h->table_rep.size() - 1;
+        }
+        const uint32_t j = h->table_rep[entry - 1];
+        const ParsedImage &pj = h->parsed[j];
+        const uint8_t *other = bits + offsets[j];
+        bool same = true;
+        for (int t = 0; t < 4 && same; t++)
+            same = len_of(pi, t) == len_of(pj, t) &&
+                   memcmp(file + pi.dht_off[t], other + pj.dht_off[t], len_of(pi, t)) == 0;
+        if (same) return entry - 1;
+    }
+}
+
 // Parse every file and lay the batch out in the workspace.
 int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int32_t n,
                const prep_params *params, Plan *plan)
@@ -133,7 +162,7 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
     h->recs.resize((size_t)n);
     h->rr.resize((size_t)n);
     h->table_rep.clear();
-    h->table_of.clear();
+    std::fill(h->table_hash.begin(), h->table_hash.end(), 0u);
     Plan P;
     for (int32_t i = 0; i < n; i++) {
         if (offsets[i + 1] < offsets[i]) return PREP_E_INVALID_ARG;
@@ -166,23 +195,7 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
             const int per = recon_mcus_per_group(I.sampling);
             R.groups_per_row = (uint32_t)((I.mcu_cols + per - 1) / per);
             for (int t = 0; t < 4; t++) { R.dht_off[t] = pi.dht_off[t]; R.dht_nval[t] = pi.dht_nval[t]; }
-            {
-                // images with the same four tables share one expanded copy
-                std::string key;
-                for (int t = 0; t < 4; t++)
-                    key.append(reinterpret_cast<const char *>(bits + offsets[i] + pi.dht_off[t]),
-                               16 + (size_t)std::min<uint32_t>(pi.dht_nval[t], 256u));
-                auto it = h->table_of.find(key);
-                if (it != h->table_of.end()) {
-                    R.table_slot = it->second;
-                } else if (h->table_rep.size() < h->table_slots) {
-                    R.table_slot = (uint32_t)h->table_rep.size();
-                    h->table_of.emplace(std::move(key), R.table_slot);
-                    h->table_rep.push_back((uint32_t)i);
-                } else {
-                    R.table_slot = kNoTableSlot;
-                }
-            }
+            R.table_slot = table_slot_of(h, bits, offsets, i);
             for (int c = 0; c < 3; c++) R.dqt_off[c] = pi.dqt_off[c];
             R.width = (uint16_t)I.width;
             R.height = (uint16_t)I.height;
@@ -309,7 +322,8 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     *out = nullptr;
     if (!cfg || cfg->max_batch < 1 || cfg->max_batch > 65535 || cfg->max_width < 1 ||
         cfg->max_height < 1 || cfg->max_width > 65535 || cfg->max_height > 65535 ||
-        cfg->max_bitstream_bytes < 1 || cfg->max_bitstream_bytes > 0x7FFF0000ull || cfg->flags != 0)
+        cfg->max_bitstream_bytes < 1 || cfg->max_bitstream_bytes > 0x7FFF0000ull ||
+        (cfg->flags & ~(uint32_t)PREP_FLAG_TABLES_PER_WORKGROUP) != 0)
         return PREP_E_INVALID_ARG;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) {
@@ -336,8 +350,10 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     ok = ok && hipMalloc((void **)&h->d_coef, h->cap_blocks * 128) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_rgb, h->cap_rgb) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_recs, (sizeof(ImageRec) + 2 * sizeof(uint32_t)) * n) == hipSuccess;
-    h->table_slots = std::min<uint32_t>((uint32_t)n, kMaxTableSlots);
-    ok = ok && hipMalloc((void **)&h->d_tables, (size_t)h->table_slots * huff_tables_bytes()) == hipSuccess;
+    h->table_slots = (cfg->flags & PREP_FLAG_TABLES_PER_WORKGROUP) ? 0u : std::min<uint32_t>((uint32_t)n, kMaxTableSlots);
+    h->table_rep.reserve(h->table_slots);
+    h->table_hash.assign(2 * (size_t)kMaxTableSlots, 0u);
+    ok = ok && hipMalloc((void **)&h->d_tables, (size_t)std::max<uint32_t>(h->table_slots, 1u) * huff_tables_bytes()) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_rr, sizeof(ResizeRec) * n) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_status, sizeof(int32_t) * n) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_win_count, sizeof(uint32_t) * h->cap_windows) == hipSuccess;

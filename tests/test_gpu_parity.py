@@ -286,3 +286,23 @@ def test_concurrent_handles_and_streams(prep):
         for j in range(per_batch):
             err = np.abs(results[i][j] - ref[i * per_batch + j][3]).max()
             assert err <= TENSOR_ABS_TOL, f"worker {i} image {j}: tensor off by {err}"
+
+
+def test_tables_expanded_per_workgroup_give_the_same_coefficients(prep):
+    # the decoder normally copies Huffman tables that were expanded once per distinct table
+    # set of the batch; the flag makes every workgroup expand its own (the path taken when a
+    # batch has more distinct table sets than the handle has slots)
+    h = prep.Preprocessor(device=0, max_batch=16, max_width=640, max_height=640,
+                          max_bitstream_bytes=8 << 20, flags=prep.FLAG_TABLES_PER_WORKGROUP)
+    try:
+        streams = synth.make_batch(2, 8) + synth.make_batch(5, 6)   # default and optimised tables
+        check_against_oracle(h, streams, 256, 224, 224, "f16")
+    finally:
+        h.close()
+
+
+def test_many_distinct_table_sets_in_one_batch(pp):
+    # every image brings its own optimised Huffman tables
+    streams = [oracle.encode(_img(600 + k, 96 + 8 * k, 80), 70 + 2 * k, (MODE_420, MODE_444, MODE_GRAY)[k % 3],
+                             (0, 2, 5)[k % 3], table_mode=1)[0] for k in range(12)]
+    check_against_oracle(pp, streams, 0, 64, 64, "f32")
