@@ -36,7 +36,9 @@ struct Slot {
 
 struct Plan {                         // what one call will run
     uint32_t n_windows = 0;
-    uint32_t n_groups = 0;
+    uint32_t n_groups = 0;      // reconstruction groups of all images
+    uint32_t recon_wgs = 0;     // reconstruction workgroups
+    uint32_t groups_per_wg = 1; // consecutive groups of one image that a workgroup takes
     uint32_t n_tables = 0;     // distinct sets of Huffman tables (<= the handle's table slots)
     uint64_t n_blocks = 0;
     uint64_t rgb_bytes = 0;
@@ -218,6 +220,15 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
         P.n_windows += R.n_windows;
     }
     P.n_tables = (uint32_t)h->table_rep.size();
+    // A reconstruction workgroup takes several groups of its image when there are plenty, so
+    // that it can fetch one while it works on another; group0 counts workgroups.
+    P.groups_per_wg = std::min<uint32_t>(std::max<uint32_t>(P.n_groups / kReconGroupsPerWgDivisor, 1u), kReconMaxGroupsPerWg);
+    for (int32_t i = 0; i < n; i++) {
+        ImageRec &R = h->recs[(size_t)i];
+        R.group0 = P.recon_wgs;
+        if (R.status == PREP_OK)
+            P.recon_wgs += (R.groups_per_row * R.mcu_rows + P.groups_per_wg - 1) / P.groups_per_wg;
+    }
     if (P.n_blocks > h->cap_blocks || P.rgb_bytes > h->cap_rgb || P.n_windows > h->cap_windows)
         return PREP_E_TOO_LARGE;
     *plan = P;
@@ -297,8 +308,8 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
                               h->d_coef, h->d_status, h->d_tables, stream);
         if (timing) HIP_TRY(hipEventRecord(ev[2], stream));
     }
-    launch_reconstruct(d_bits, h->d_recs, reinterpret_cast<const uint32_t *>(h->d_recs + n), n, P.n_groups,
-                       h->d_coef, h->d_rgb, stream);
+    launch_reconstruct(d_bits, h->d_recs, reinterpret_cast<const uint32_t *>(h->d_recs + n), n, P.recon_wgs,
+                       P.groups_per_wg, h->d_coef, h->d_rgb, stream);
     if (timing) HIP_TRY(hipEventRecord(ev[3], stream));
     launch_resize_normalize(h->d_rgb, h->d_rr, h->d_status, n, params->crop_h, params->crop_w,
                             params->out_dtype, params->mean, params->std, out, true, stream);

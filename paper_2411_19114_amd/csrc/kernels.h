@@ -23,7 +23,8 @@ void launch_decode_entropy(const uint8_t *bits, const ImageRec *recs, int n_imag
 
 // reconstruct.hip
 void launch_reconstruct(const uint8_t *bits, const ImageRec *recs, const uint32_t *group0, int n_images,
-                        uint32_t n_groups, const int16_t *coef, uint8_t *rgb, hipStream_t stream);
+                        uint32_t n_workgroups, uint32_t groups_per_wg, const int16_t *coef, uint8_t *rgb,
+                        hipStream_t stream);
 
 // resize.hip
 void launch_resize_normalize(const uint8_t *rgb, const ResizeRec *rr, const int32_t *status,

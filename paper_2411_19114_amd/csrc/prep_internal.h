@@ -28,6 +28,10 @@ constexpr uint32_t kNoTableSlot = 0xFFFFFFFFu;             // expand the tables 
 constexpr int kReconThreads = 256;
 constexpr int kReconBlocks = 32;
 inline constexpr int recon_mcus_per_group(int sampling) { return sampling == 1 ? 5 : sampling == 0 ? 10 : 32; }
+// A workgroup takes up to kReconMaxGroupsPerWg consecutive groups of one image: as many as
+// leave about kReconGroupsPerWgDivisor workgroups in the launch (two rounds of a full chip).
+constexpr uint32_t kReconMaxGroupsPerWg = 8;
+constexpr uint32_t kReconGroupsPerWgDivisor = 3072;
 
 // Per-image record, written by the host parser (T.81 Annex B) and read by
 // every kernel.  file_off is the byte offset of the file in the device copy of

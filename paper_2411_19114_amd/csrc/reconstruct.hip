@@ -45,6 +45,21 @@ struct ZigZag {
 };
 __device__ const ZigZag kZigZag{};
 
+// for column u, the zig-zag positions of its eight coefficients F(v, u), v = 0..7, packed a
+// byte each: lane u of a block fetches them in one 8-byte load
+struct ZigZagColumns {
+    unsigned long long pos[8];
+    constexpr ZigZagColumns() : pos()
+    {
+        ZigZag z;
+        for (int k = 0; k < 64; k++) {
+            const int v = z.nat[k] >> 3, u = z.nat[k] & 7;
+            pos[u] |= (unsigned long long)k << (8 * v);
+        }
+    }
+};
+__device__ const ZigZagColumns kZigZagColumns{};
+
 // 8-point inverse DCT with basis m(x,0) = 1, m(x,u) = sqrt(2) cos((2x+1) u pi/16):
 // the 2-D result still needs a factor 1/8.  Even and odd frequencies are summed
 // separately because the odd basis is antisymmetric about the centre.
@@ -124,13 +139,18 @@ struct ReconShared {
     uint32_t chroma[2][8 * kChromaPitch / 4];
 };
 
-// The work of one workgroup, with the sampling mode a compile-time constant so that every
-// block / pixel index is divided by constants.
+// The work of one workgroup: groups gi0 .. gi0 + n_groups - 1 of one image (a group is a run
+// of MCUs of one MCU row, numbered row by row), one after the other.  The sampling mode is
+// a compile-time constant so that every block / pixel index is divided by constants.
+//
+// A group's time is mostly the latency of its coefficient loads, and LDS limits a compute
+// unit to six workgroups, so the coefficients of the next group are fetched into registers
+// while the current one is transformed and converted.
 template <int sampling>
-__device__ __forceinline__ void reconstruct_group(ReconShared &S, const uint8_t *__restrict__ bits,
-                                                  const ImageRec &R, uint32_t mrow, uint32_t gcol,
-                                                  const int16_t *__restrict__ coef_all,
-                                                  uint8_t *__restrict__ rgb_all)
+__device__ __forceinline__ void reconstruct_groups(ReconShared &S, const uint8_t *__restrict__ bits,
+                                                   const ImageRec &R, uint32_t gi0, uint32_t n_groups,
+                                                   const int16_t *__restrict__ coef_all,
+                                                   uint8_t *__restrict__ rgb_all)
 {
     double *tile = S.tile;
     int32_t (*qi)[64] = S.qi;
@@ -141,122 +161,135 @@ __device__ __forceinline__ void reconstruct_group(ReconShared &S, const uint8_t 
     constexpr int hs = sampling == PREP_SAMPLING_420 ? 2 : 1;  // luma blocks per MCU per axis
     constexpr int n_luma = hs * hs;
     constexpr int per_group = recon_mcus_per_group(sampling);
-    const uint32_t mcu_x0 = gcol * per_group;
-    const int gcount = min(per_group, (int)R.mcu_cols - (int)mcu_x0);
-    const int n_blk = gcount * bpm;  // <= kReconBlocks
 
     const uint8_t *file = bits + R.file_off;
     if (tid < 192) qi[tid >> 6][tid & 63] = (int32_t)file[R.dqt_off[tid >> 6] + (tid & 63)];
-    __syncthreads();
 
     const int b = tid >> 3, l = tid & 7;
-    const bool have = b < n_blk;
-    const int mcu = have ? b / bpm : 0, blk = have ? b % bpm : 0;
+    const int mcu = b / bpm, blk = b % bpm;  // of the lane's block, if the group has that many
     const int comp = blk < n_luma ? 0 : blk - n_luma + 1;
     double *T = tile + b * kTileSize;
+    // the luma sample plane doubles as the landing place of a group's raw coefficients (128
+    // bytes per block, zig-zag order): it is free until the row pass
+    int16_t *zz16 = reinterpret_cast<int16_t *>(luma);
+    const unsigned long long pos = kZigZagColumns.pos[l];
 
-    // ---- dequantise, undo the zig-zag (A.3.4) ------------------------------------
-    if (have) {
-        const size_t gb = (size_t)R.coef_block0 +
-                          ((size_t)mrow * R.mcu_cols + mcu_x0 + mcu) * bpm + blk;
-        const uint4 raw = *reinterpret_cast<const uint4 *>(coef_all + gb * 64 + l * 8);
-        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+    uint32_t mrow = gi0 / R.groups_per_row, gcol = gi0 - mrow * R.groups_per_row;
+    // the lane's eight coefficients of group (mrow, gcol), or zeros past the group's blocks
+    auto fetch = [&](uint32_t row, uint32_t col) {
+        const uint32_t x0 = col * per_group;
+        const int count = min(per_group, (int)R.mcu_cols - (int)x0);
+        if (b >= count * bpm) return make_uint4(0, 0, 0, 0);
+        const size_t gb = (size_t)R.coef_block0 + ((size_t)row * R.mcu_cols + x0 + mcu) * bpm + blk;
+        return *reinterpret_cast<const uint4 *>(coef_all + gb * 64 + l * 8);
+    };
+    uint4 raw = fetch(mrow, gcol);
+    for (uint32_t g = 0; g < n_groups; g++) {
+        const uint32_t mcu_x0 = gcol * per_group;
+        const int gcount = min(per_group, (int)R.mcu_cols - (int)mcu_x0);
+        const bool have = b < gcount * bpm;  // <= kReconBlocks blocks
+        if (have) *reinterpret_cast<uint4 *>(zz16 + b * 64 + l * 8) = raw;
+        __syncthreads();  // also: the quantisation tables are in place
+        // next group of this workgroup, row by row
+        uint32_t next_row = mrow, next_col = gcol + 1;
+        if (next_col == R.groups_per_row) { next_col = 0; next_row++; }
+        // ---- columns: lane l gathers column u = l through the zig-zag (A.3.4), dequantises
+        // and transforms it ----------------------------------------------------------------
+        if (have) {
+            double F[8], o[8];
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
-            const int k = l * 8 + j;
-            const int c = (int)(int16_t)(w[j >> 1] >> (16 * (j & 1)));
-            const int nat = kZigZag.nat[k];
-            T[(nat >> 3) * kTileStride + (nat & 7)] = (double)__mul24(c, qi[comp][k]);  // 16 x 8 bits: exact
+            for (int v = 0; v < 8; v++) {
+                const int k = (int)((pos >> (8 * v)) & 63u);
+                F[v] = (double)__mul24((int)zz16[b * 64 + k], qi[comp][k]);  // 16 x 8 bits: exact
+            }
+            idct8(F, o);
+#pragma unroll
+            for (int y = 0; y < 8; y++) T[y * kTileStride + l] = o[y];
         }
-    }
-    __syncthreads();
-    // ---- columns: lane l transforms column u = l ------------------------------------
-    if (have) {
-        double F[8], o[8];
+        if (g + 1 < n_groups) raw = fetch(next_row, next_col);
+        __syncthreads();
+        // ---- rows: lane l transforms row y = l, level shift, round, clamp (A.3.1) ---------
+        if (have) {
+            double F[8], o[8];
 #pragma unroll
-        for (int v = 0; v < 8; v++) F[v] = T[v * kTileStride + l];
-        idct8(F, o);
+            for (int u = 0; u < 8; u++) F[u] = T[l * kTileStride + u];
+            idct8(F, o);
+            uint32_t pk[2] = {0, 0};
 #pragma unroll
-        for (int y = 0; y < 8; y++) T[y * kTileStride + l] = o[y];
-    }
-    __syncthreads();
-    // ---- rows: lane l transforms row y = l, level shift, round, clamp (A.3.1) ---------
-    if (have) {
-        double F[8], o[8];
-#pragma unroll
-        for (int u = 0; u < 8; u++) F[u] = T[l * kTileStride + u];
-        idct8(F, o);
-        uint32_t pk[2] = {0, 0};
-#pragma unroll
-        for (int x = 0; x < 8; x++) {
-            // level shift and round half up; truncation instead of floor differs only below
-            // zero, where both clamp to 0
-            const int sample = (int)fma(o[x], 0.125, 128.5 + kTieEps);
-            pk[x >> 2] |= (uint32_t)min(max(sample, 0), 255) << (8 * (x & 3));
+            for (int x = 0; x < 8; x++) {
+                // level shift and round half up; truncation instead of floor differs only below
+                // zero, where both clamp to 0
+                const int sample = (int)fma(o[x], 0.125, 128.5 + kTieEps);
+                pk[x >> 2] |= (uint32_t)min(max(sample, 0), 255) << (8 * (x & 3));
+            }
+            if (comp == 0) {
+                const int bx = blk & (hs - 1), by = hs == 2 ? blk >> 1 : 0;
+                const int row = by * 8 + l, col = (mcu * hs + bx) * 8;
+                luma[(row * kLumaPitch + col) / 4] = pk[0];
+                luma[(row * kLumaPitch + col) / 4 + 1] = pk[1];
+            } else {
+                chroma[comp - 1][(l * kChromaPitch + mcu * 8) / 4] = pk[0];
+                chroma[comp - 1][(l * kChromaPitch + mcu * 8) / 4 + 1] = pk[1];
+            }
         }
-        if (comp == 0) {
-            const int bx = blk & (hs - 1), by = hs == 2 ? blk >> 1 : 0;
-            const int row = by * 8 + l, col = (mcu * hs + bx) * 8;
-            luma[(row * kLumaPitch + col) / 4] = pk[0];
-            luma[(row * kLumaPitch + col) / 4 + 1] = pk[1];
+        __syncthreads();
+        // ---- colour ---------------------------------------------------------------------------
+        const int rows = 8 * hs, width = gcount * 8 * hs, quads = width >> 2;
+        uint8_t *dst0 = rgb_all + R.rgb_off + (size_t)mrow * rows * R.rgb_pitch +
+                        (size_t)mcu_x0 * 8 * hs * 3;
+        if (sampling == PREP_SAMPLING_420) {
+            // an item is 4 x 2 pixels: two chroma samples serve it, so their terms are formed once
+            const int items = (rows >> 1) * quads;
+            const uint16_t *cb16 = reinterpret_cast<const uint16_t *>(chroma[0]);
+            const uint16_t *cr16 = reinterpret_cast<const uint16_t *>(chroma[1]);
+            for (int it = tid; it < items; it += kReconThreads) {
+                const int rp = it / quads, q = it - rp * quads;
+                const uint32_t cbp = cb16[(rp * kChromaPitch) / 2 + q], crp = cr16[(rp * kChromaPitch) / 2 + q];
+                const ChromaTerms t0 = chroma_terms(cbp & 255u, crp & 255u);
+                const ChromaTerms t1 = chroma_terms(cbp >> 8, crp >> 8);
+#pragma unroll
+                for (int r = 0; r < 2; r++) {
+                    const int row = 2 * rp + r;
+                    const uint32_t y4 = luma[(row * kLumaPitch) / 4 + q];
+                    const uint32_t px[4] = {rgb_of(y4 & 255u, t0), rgb_of((y4 >> 8) & 255u, t0),
+                                            rgb_of((y4 >> 16) & 255u, t1), rgb_of(y4 >> 24, t1)};
+                    store_rgb4(dst0 + (size_t)row * R.rgb_pitch + q * 12, px);
+                }
+            }
         } else {
-            chroma[comp - 1][(l * kChromaPitch + mcu * 8) / 4] = pk[0];
-            chroma[comp - 1][(l * kChromaPitch + mcu * 8) / 4 + 1] = pk[1];
-        }
-    }
-    __syncthreads();
-    // ---- colour ---------------------------------------------------------------------------
-    const int rows = 8 * hs, width = gcount * 8 * hs, quads = width >> 2;
-    uint8_t *dst0 = rgb_all + R.rgb_off + (size_t)mrow * rows * R.rgb_pitch +
-                    (size_t)mcu_x0 * 8 * hs * 3;
-    if (sampling == PREP_SAMPLING_420) {
-        // an item is 4 x 2 pixels: two chroma samples serve it, so their terms are formed once
-        const int items = (rows >> 1) * quads;
-        const uint16_t *cb16 = reinterpret_cast<const uint16_t *>(chroma[0]);
-        const uint16_t *cr16 = reinterpret_cast<const uint16_t *>(chroma[1]);
-        for (int it = tid; it < items; it += kReconThreads) {
-            const int rp = it / quads, q = it - rp * quads;
-            const uint32_t cbp = cb16[(rp * kChromaPitch) / 2 + q], crp = cr16[(rp * kChromaPitch) / 2 + q];
-            const ChromaTerms t0 = chroma_terms(cbp & 255u, crp & 255u);
-            const ChromaTerms t1 = chroma_terms(cbp >> 8, crp >> 8);
-#pragma unroll
-            for (int r = 0; r < 2; r++) {
-                const int row = 2 * rp + r;
+            // an item is 4 pixels of one row
+            const int items = rows * quads;
+            for (int it = tid; it < items; it += kReconThreads) {
+                const int row = it / quads, q = it - row * quads;
                 const uint32_t y4 = luma[(row * kLumaPitch) / 4 + q];
-                const uint32_t px[4] = {rgb_of(y4 & 255u, t0), rgb_of((y4 >> 8) & 255u, t0),
-                                        rgb_of((y4 >> 16) & 255u, t1), rgb_of(y4 >> 24, t1)};
+                uint32_t px[4];
+                if (sampling == PREP_SAMPLING_GRAY) {
+#pragma unroll
+                    for (int j = 0; j < 4; j++) px[j] = ((y4 >> (8 * j)) & 255u) * 0x010101u;
+                } else {
+                    const uint32_t cb4 = chroma[0][(row * kChromaPitch) / 4 + q];
+                    const uint32_t cr4 = chroma[1][(row * kChromaPitch) / 4 + q];
+#pragma unroll
+                    for (int j = 0; j < 4; j++)
+                        px[j] = rgb_of((y4 >> (8 * j)) & 255u,
+                                       chroma_terms((cb4 >> (8 * j)) & 255u, (cr4 >> (8 * j)) & 255u));
+                }
                 store_rgb4(dst0 + (size_t)row * R.rgb_pitch + q * 12, px);
             }
         }
-    } else {
-        // an item is 4 pixels of one row
-        const int items = rows * quads;
-        for (int it = tid; it < items; it += kReconThreads) {
-            const int row = it / quads, q = it - row * quads;
-            const uint32_t y4 = luma[(row * kLumaPitch) / 4 + q];
-            uint32_t px[4];
-            if (sampling == PREP_SAMPLING_GRAY) {
-#pragma unroll
-                for (int j = 0; j < 4; j++) px[j] = ((y4 >> (8 * j)) & 255u) * 0x010101u;
-            } else {
-                const uint32_t cb4 = chroma[0][(row * kChromaPitch) / 4 + q];
-                const uint32_t cr4 = chroma[1][(row * kChromaPitch) / 4 + q];
-#pragma unroll
-                for (int j = 0; j < 4; j++)
-                    px[j] = rgb_of((y4 >> (8 * j)) & 255u,
-                                   chroma_terms((cb4 >> (8 * j)) & 255u, (cr4 >> (8 * j)) & 255u));
-            }
-            store_rgb4(dst0 + (size_t)row * R.rgb_pitch + q * 12, px);
-        }
+        mrow = next_row;
+        gcol = next_col;
+        __syncthreads();  // the sample planes are free again
     }
 }
 
-// group0[i] = first workgroup of image i (ascending).  The image of workgroup wg is the last
-// one whose entry does not exceed wg: every lane tests one entry and the hits are counted.
+// group0[i] = first workgroup of image i (ascending); a workgroup takes groups_per_wg
+// consecutive groups of its image.  The image of workgroup wg is the last one whose entry
+// does not exceed wg: every lane tests one entry and the hits are counted.
 __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
     const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs,
-    const uint32_t *__restrict__ group0, int n_images, const int16_t *__restrict__ coef_all,
-    uint8_t *__restrict__ rgb_all)
+    const uint32_t *__restrict__ group0, int n_images, uint32_t groups_per_wg,
+    const int16_t *__restrict__ coef_all, uint8_t *__restrict__ rgb_all)
 {
     __shared__ ReconShared S;
     __shared__ uint32_t s_hits[kReconThreads / 64];
@@ -273,23 +306,25 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
     if (hits == 0) return;
     const ImageRec &R = recs[hits - 1];
     if (R.status != PREP_OK) return;
-    const uint32_t gi = wg - R.group0;
-    const uint32_t mrow = gi / R.groups_per_row, gcol = gi - mrow * R.groups_per_row;
-    if (mrow >= R.mcu_rows) return;
+    const uint32_t total = R.groups_per_row * (uint32_t)R.mcu_rows;
+    const uint32_t gi0 = (wg - R.group0) * groups_per_wg;
+    if (gi0 >= total) return;
+    const uint32_t n = min(groups_per_wg, total - gi0);
     if (R.sampling == PREP_SAMPLING_420)
-        reconstruct_group<PREP_SAMPLING_420>(S, bits, R, mrow, gcol, coef_all, rgb_all);
+        reconstruct_groups<PREP_SAMPLING_420>(S, bits, R, gi0, n, coef_all, rgb_all);
     else if (R.sampling == PREP_SAMPLING_444)
-        reconstruct_group<PREP_SAMPLING_444>(S, bits, R, mrow, gcol, coef_all, rgb_all);
+        reconstruct_groups<PREP_SAMPLING_444>(S, bits, R, gi0, n, coef_all, rgb_all);
     else
-        reconstruct_group<PREP_SAMPLING_GRAY>(S, bits, R, mrow, gcol, coef_all, rgb_all);
+        reconstruct_groups<PREP_SAMPLING_GRAY>(S, bits, R, gi0, n, coef_all, rgb_all);
 }
 
 void launch_reconstruct(const uint8_t *bits, const ImageRec *recs, const uint32_t *group0, int n_images,
-                        uint32_t n_groups, const int16_t *coef, uint8_t *rgb, hipStream_t stream)
+                        uint32_t n_workgroups, uint32_t groups_per_wg, const int16_t *coef, uint8_t *rgb,
+                        hipStream_t stream)
 {
-    if (n_groups == 0) return;
-    hipLaunchKernelGGL(reconstruct_rgb, dim3(n_groups), dim3(kReconThreads), 0, stream, bits, recs, group0,
-                       n_images, coef, rgb);
+    if (n_workgroups == 0) return;
+    hipLaunchKernelGGL(reconstruct_rgb, dim3(n_workgroups), dim3(kReconThreads), 0, stream, bits, recs,
+                       group0, n_images, groups_per_wg, coef, rgb);
 }
 
 }  // namespace prep
