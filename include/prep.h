@@ -112,7 +112,8 @@ int prep_destroy(prep_handle *h);
  *              must stay valid until `stream` has run the enqueued work
  *   stream     a hipStream_t (NULL = the default stream)
  * The call copies what it needs from the host buffers before it returns and
- * returns as soon as the GPU work is enqueued on `stream`.  Whole-call errors
+ * returns as soon as the GPU work is enqueued on `stream` (uploads of large
+ * batches run on a stream of the handle that `stream` is made to wait for).  Whole-call errors
  * (INVALID_ARG, TOO_LARGE, HIP) enqueue nothing.  A file that cannot be decoded
  * does not fail the call: its status is reported by prep_get_status and its
  * slab of `out` is filled with zeros.

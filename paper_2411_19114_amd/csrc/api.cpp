@@ -24,13 +24,22 @@ constexpr size_t kBitsPad = 256;     // readable slack after the last file
 constexpr size_t kRgbAlign = 256;
 constexpr size_t kRgbSlack = 16;     // readable bytes kept after every image's RGB rows
 constexpr int kTimedCalls = 256;     // calls whose stage events are kept
+constexpr uint64_t kCopyStreamMinBytes = 64 << 10;  // bitstream uploads from this size on use the copy stream
+constexpr int32_t kCopyStreamMinImages = 128;       // and so do the records of batches from this size on
 
+// What one call uploads lives in one of kSlots sets of buffers, pinned host side and device
+// side, so that the upload of a call (on the handle's copy stream) overlaps the kernels of the
+// call before it (on the caller's stream).
 struct Slot {
     uint8_t *h_bits = nullptr;
-    ImageRec *h_recs = nullptr;
+    ImageRec *h_recs = nullptr;   // n records, then n first-workgroup indices, then <= n table owners
     ResizeRec *h_rr = nullptr;
     int32_t *h_status = nullptr;
-    hipEvent_t done = nullptr;
+    uint8_t *d_bits = nullptr;
+    ImageRec *d_recs = nullptr;
+    ResizeRec *d_rr = nullptr;
+    hipEvent_t copied = nullptr;  // uploads of the slot's call are done
+    hipEvent_t done = nullptr;    // kernels of the slot's call are done
     bool pending = false;
 };
 
@@ -49,15 +58,13 @@ struct Plan {                         // what one call will run
 struct prep_handle {
     prep_config cfg{};
     uint64_t cap_blocks = 0, cap_rgb = 0, cap_windows = 0, cap_bits = 0;
-    uint8_t *d_bits = nullptr;
+    hipStream_t copy_stream = nullptr;
     int16_t *d_coef = nullptr;
     uint8_t *d_rgb = nullptr;
-    ImageRec *d_recs = nullptr;   // n records, then n first-group indices, then <= n table owners
     uint8_t *d_tables = nullptr;  // table_slots expanded Huffman table sets
     uint32_t table_slots = 0;
     std::vector<uint32_t> table_rep;   // image that owns each slot of this call
     std::vector<uint32_t> table_hash;  // open-addressed: slot + 1 of a table set by the hash of its DHT bytes, 0 = free
-    ResizeRec *d_rr = nullptr;
     int32_t *d_status = nullptr;
     uint32_t *d_win_count = nullptr, *d_win_first = nullptr;
     Slot slot[kSlots];
@@ -280,14 +287,24 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
     for (int32_t i = 0; i < n; i++) h_group0[i] = h->recs[(size_t)i].group0;
     for (uint32_t t = 0; t < P.n_tables; t++) h_group0[n + (int32_t)t] = h->table_rep[t];
     memcpy(s->h_rr, h->rr.data(), sizeof(ResizeRec) * (size_t)n);
-    const uint8_t *d_bits = bits_dev ? bits_dev + offsets[0] : h->d_bits;
+    // Large uploads go on the handle's copy stream and the caller's stream waits for them, so
+    // that they overlap the kernels of the call before.  Small ones stay on the caller's
+    // stream: there the hop between streams costs more than it hides (with several handles
+    // at work it also couples their streams through the few hardware queues).
+    const bool aside = (!bits_dev && total >= kCopyStreamMinBytes) || n >= kCopyStreamMinImages;
+    hipStream_t up = aside ? h->copy_stream : stream;
+    const uint8_t *d_bits = bits_dev ? bits_dev + offsets[0] : s->d_bits;
     if (!bits_dev) {
         memcpy(s->h_bits, base_host, total);
-        HIP_TRY(hipMemcpyAsync(h->d_bits, s->h_bits, total, hipMemcpyHostToDevice, stream));
+        HIP_TRY(hipMemcpyAsync(s->d_bits, s->h_bits, total, hipMemcpyHostToDevice, up));
     }
-    HIP_TRY(hipMemcpyAsync(h->d_recs, s->h_recs, (sizeof(ImageRec) + 2 * sizeof(uint32_t)) * (size_t)n,
-                           hipMemcpyHostToDevice, stream));
-    HIP_TRY(hipMemcpyAsync(h->d_rr, s->h_rr, sizeof(ResizeRec) * (size_t)n, hipMemcpyHostToDevice, stream));
+    HIP_TRY(hipMemcpyAsync(s->d_recs, s->h_recs, (sizeof(ImageRec) + 2 * sizeof(uint32_t)) * (size_t)n,
+                           hipMemcpyHostToDevice, up));
+    HIP_TRY(hipMemcpyAsync(s->d_rr, s->h_rr, sizeof(ResizeRec) * (size_t)n, hipMemcpyHostToDevice, up));
+    if (aside) {
+        HIP_TRY(hipEventRecord(s->copied, h->copy_stream));
+        HIP_TRY(hipStreamWaitEvent(stream, s->copied, 0));
+    }
     const bool timing = h->timing;
     hipEvent_t *ev = timing ? &h->ev[(size_t)(h->timed_calls % kTimedCalls) * 5] : nullptr;
     if (timing) HIP_TRY(hipEventRecord(ev[0], stream));
@@ -299,19 +316,19 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
         if (timing) { HIP_TRY(hipEventRecord(ev[1], stream)); HIP_TRY(hipEventRecord(ev[2], stream)); }
     } else {
         // the scan also clears the coefficients of the batch (P.n_windows >= n > 0)
-        launch_scan_restart_markers(d_bits, h->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
+        launch_scan_restart_markers(d_bits, s->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
                                     h->d_status, h->d_coef, P.n_blocks,
-                                    reinterpret_cast<const uint32_t *>(h->d_recs + n) + n, P.n_tables,
+                                    reinterpret_cast<const uint32_t *>(s->d_recs + n) + n, P.n_tables,
                                     h->d_tables, stream);
         if (timing) HIP_TRY(hipEventRecord(ev[1], stream));
-        launch_decode_entropy(d_bits, h->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
+        launch_decode_entropy(d_bits, s->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
                               h->d_coef, h->d_status, h->d_tables, stream);
         if (timing) HIP_TRY(hipEventRecord(ev[2], stream));
     }
-    launch_reconstruct(d_bits, h->d_recs, reinterpret_cast<const uint32_t *>(h->d_recs + n), n, P.recon_wgs,
+    launch_reconstruct(d_bits, s->d_recs, reinterpret_cast<const uint32_t *>(s->d_recs + n), n, P.recon_wgs,
                        P.groups_per_wg, h->d_coef, h->d_rgb, stream);
     if (timing) HIP_TRY(hipEventRecord(ev[3], stream));
-    launch_resize_normalize(h->d_rgb, h->d_rr, h->d_status, n, params->crop_h, params->crop_w,
+    launch_resize_normalize(h->d_rgb, s->d_rr, h->d_status, n, params->crop_h, params->crop_w,
                             params->out_dtype, params->mean, params->std, out, true, stream);
     if (timing) HIP_TRY(hipEventRecord(ev[4], stream));
     HIP_TRY(hipGetLastError());
@@ -357,15 +374,13 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     if (h->cap_blocks > 0xFFFFFFFFull) { delete h; return PREP_E_TOO_LARGE; }
 
     bool ok = hipSetDevice(cfg->device) == hipSuccess;
-    ok = ok && hipMalloc((void **)&h->d_bits, h->cap_bits) == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&h->copy_stream, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_coef, h->cap_blocks * 128) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_rgb, h->cap_rgb) == hipSuccess;
-    ok = ok && hipMalloc((void **)&h->d_recs, (sizeof(ImageRec) + 2 * sizeof(uint32_t)) * n) == hipSuccess;
     h->table_slots = (cfg->flags & PREP_FLAG_TABLES_PER_WORKGROUP) ? 0u : std::min<uint32_t>((uint32_t)n, kMaxTableSlots);
     h->table_rep.reserve(h->table_slots);
     h->table_hash.assign(2 * (size_t)kMaxTableSlots, 0u);
     ok = ok && hipMalloc((void **)&h->d_tables, (size_t)std::max<uint32_t>(h->table_slots, 1u) * huff_tables_bytes()) == hipSuccess;
-    ok = ok && hipMalloc((void **)&h->d_rr, sizeof(ResizeRec) * n) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_status, sizeof(int32_t) * n) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_win_count, sizeof(uint32_t) * h->cap_windows) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_win_first, sizeof(uint32_t) * h->cap_windows) == hipSuccess;
@@ -375,6 +390,10 @@ int prep_create(prep_handle **out, const prep_config *cfg)
         ok = ok && hipHostMalloc((void **)&s.h_recs, (sizeof(ImageRec) + 2 * sizeof(uint32_t)) * n, hipHostMallocDefault) == hipSuccess;
         ok = ok && hipHostMalloc((void **)&s.h_rr, sizeof(ResizeRec) * n, hipHostMallocDefault) == hipSuccess;
         ok = ok && hipHostMalloc((void **)&s.h_status, sizeof(int32_t) * n, hipHostMallocDefault) == hipSuccess;
+        ok = ok && hipMalloc((void **)&s.d_bits, h->cap_bits) == hipSuccess;
+        ok = ok && hipMalloc((void **)&s.d_recs, (sizeof(ImageRec) + 2 * sizeof(uint32_t)) * n) == hipSuccess;
+        ok = ok && hipMalloc((void **)&s.d_rr, sizeof(ResizeRec) * n) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&s.copied, hipEventDisableTiming) == hipSuccess;
         ok = ok && hipEventCreateWithFlags(&s.done, hipEventDisableTiming) == hipSuccess;
     }
     h->ev.assign((size_t)kTimedCalls * 5, nullptr);
@@ -394,12 +413,9 @@ int prep_destroy(prep_handle *h)
     if (!h) return PREP_E_INVALID_ARG;
     (void)hipSetDevice(h->cfg.device);
     (void)hipDeviceSynchronize();
-    (void)hipFree(h->d_bits);
     (void)hipFree(h->d_coef);
     (void)hipFree(h->d_rgb);
-    (void)hipFree(h->d_recs);
     (void)hipFree(h->d_tables);
-    (void)hipFree(h->d_rr);
     (void)hipFree(h->d_status);
     (void)hipFree(h->d_win_count);
     (void)hipFree(h->d_win_first);
@@ -409,10 +425,15 @@ int prep_destroy(prep_handle *h)
         if (s.h_recs) (void)hipHostFree(s.h_recs);
         if (s.h_rr) (void)hipHostFree(s.h_rr);
         if (s.h_status) (void)hipHostFree(s.h_status);
+        (void)hipFree(s.d_bits);
+        (void)hipFree(s.d_recs);
+        (void)hipFree(s.d_rr);
+        if (s.copied) (void)hipEventDestroy(s.copied);
         if (s.done) (void)hipEventDestroy(s.done);
     }
     for (hipEvent_t e : h->ev)
         if (e) (void)hipEventDestroy(e);
+    if (h->copy_stream) (void)hipStreamDestroy(h->copy_stream);
     (void)hipGetLastError();
     delete h;
     return PREP_OK;
@@ -525,8 +546,8 @@ int prep_resize_normalize(prep_handle *h, const uint8_t *rgb, const uint64_t *rg
             return PREP_E_INVALID_ARG;
     }
     hipStream_t st = (hipStream_t)stream;
-    HIP_TRY(hipMemcpyAsync(h->d_rr, s->h_rr, sizeof(ResizeRec) * (size_t)n, hipMemcpyHostToDevice, st));
-    launch_resize_normalize(rgb, h->d_rr, nullptr, n, params->crop_h, params->crop_w,
+    HIP_TRY(hipMemcpyAsync(s->d_rr, s->h_rr, sizeof(ResizeRec) * (size_t)n, hipMemcpyHostToDevice, st));
+    launch_resize_normalize(rgb, s->d_rr, nullptr, n, params->crop_h, params->crop_w,
                             params->out_dtype, params->mean, params->std, out, false, st);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(s->done, st));
