@@ -306,3 +306,28 @@ def test_many_distinct_table_sets_in_one_batch(pp):
     streams = [oracle.encode(_img(600 + k, 96 + 8 * k, 80), 70 + 2 * k, (MODE_420, MODE_444, MODE_GRAY)[k % 3],
                              (0, 2, 5)[k % 3], table_mode=1)[0] for k in range(12)]
     check_against_oracle(pp, streams, 0, 64, 64, "f32")
+
+
+def test_more_images_than_lanes_in_a_workgroup(prep):
+    # 300 small images in one call: image lookups that span more than one pass of a workgroup,
+    # a few distinct table sets, every sampling mode
+    h = prep.Preprocessor(device=0, max_batch=300, max_width=64, max_height=64,
+                          max_bitstream_bytes=4 << 20)
+    try:
+        base = []
+        for k in range(10):
+            mode = (MODE_420, MODE_444, MODE_GRAY)[k % 3]
+            base.append(oracle.encode(_img(700 + k, 24 + 4 * k, 60 - 3 * k), 80 + k, mode, (0, 1, 2)[k % 3],
+                                      table_mode=k % 2)[0])
+        streams = [base[(7 * i) % 10] for i in range(300)]
+        status, got = run_gpu(h, streams, 0, 20, 20, "f32")
+        assert status == [0] * 300
+        ref = oracle_batch(base, 0, 20, 20)
+        for i in range(300):
+            err = np.abs(got[i] - ref[(7 * i) % 10][3]).max()
+            assert err <= TENSOR_ABS_TOL, f"image {i}: tensor off by {err}"
+        for i in (0, 255, 256, 299):
+            coef = ref[(7 * i) % 10][0]
+            assert np.array_equal(h.debug_last_coefficients(i, coef.shape[0]), coef)
+    finally:
+        h.close()
