@@ -46,12 +46,12 @@ N_STREAMS, STREAM_BATCH = 7, 8
 # scaled by what the same counters read for a plain 256 MiB copy (FETCH_SIZE x 2, WRITE_SIZE x 1).
 # They describe the kernels whose sources hash to MEASURED_SOURCES; for any other sources the
 # figure is reported as null.
-MEASURED_SOURCES = "710c253c839c347c261086ec8b040fe7c50e8f1e15a0f3c44a92c1aac9bfd871"
+MEASURED_SOURCES = "3d9bbd8a16170d18b7e56361292bbe8baf7db99b3b8cc25a5a28d04ce94c68f5"
 MEASURED_TRAFFIC = {
-    2: {"scan": (5351 * 2 + 67) * 1024, "decode": (108421 * 2 + 147208) * 1024,
-        "reconstruct": (69793 * 2 + 147962) * 1024, "resize": (49123 * 2 + 75264) * 1024},
-    4: {"scan": (23759 * 2 + 248) * 1024, "decode": (220512 * 2 + 415168) * 1024,
-        "reconstruct": (196022 * 2 + 417792) * 1024, "resize": (91169 * 2 + 55296) * 1024},
+    2: {"scan": (5424 * 2 + 139059) * 1024, "decode": (111700 * 2 + 147221) * 1024,
+        "reconstruct": (69819 * 2 + 144310) * 1024, "resize": (49117 * 2 + 75264) * 1024},
+    4: {"scan": (23831 * 2 + 392766) * 1024, "decode": (220633 * 2 + 420937) * 1024,
+        "reconstruct": (196019 * 2 + 410914) * 1024, "resize": (91349 * 2 + 55296) * 1024},
 }
 
 
