@@ -384,9 +384,10 @@ __device__ __forceinline__ uint32_t window32(const DecodeShared &S, const Geomet
 // (F.2.2.1 EXTEND); adv = code length + s
 __device__ __forceinline__ int32_t coefficient_value(uint32_t win, uint32_t adv, uint32_t s)
 {
-    const uint32_t after = win << (adv - s);
-    const uint32_t extra = (after >> 1) >> (31 - s);
-    return ((int32_t)after < 0 || s == 0) ? (int32_t)extra : (int32_t)extra - (int32_t)((1u << s) - 1u);
+    const uint32_t after = win << (adv - s);            // the appended bits, left-aligned
+    const uint32_t mag = (after >> 1) >> (s ^ 31u);     // RECEIVE(s); 31 - s without a borrow; 0 for s = 0
+    const uint32_t positive = (uint32_t)((int32_t)after >> 31);  // all ones if the first bit is 1
+    return (int32_t)(mag - (((1u << s) - 1u) & ~positive));      // EXTEND: negative values lie 2^s - 1 lower
 }
 
 // Decode from packed state `st` until the bit position reaches end_bit.
@@ -511,6 +512,77 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
         } while (p < end_bit);
     }
     if (kWrite) wc->bad |= broken | no_code | (late < 0 ? 1 : 0) | (int32_t)((over >> 6) & 1u);
+    *nblk = done;
+    return pack_state(p, blk, zz);
+}
+
+// The short-interval pass: one lane decodes one restart interval from its start state to
+// end_bit, which is the next restart boundary (or the end of the data), and writes its
+// coefficients.  Same symbol loop as decode_span, specialised for what that pass knows: the
+// span's end and the next boundary are the same position, so the loop ends where a symbol no
+// longer fits and never steps over a boundary; the stream is staged without pad words; and
+// the caller's count of the interval's blocks stands in for the running check against
+// restart intervals.  Returns the end state (at end_bit if the stream is sound).
+__device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const Geometry &g, uint32_t st,
+                                                    uint32_t end_bit, uint32_t *nblk, WriteCtx *wc)
+{
+    uint32_t p = st >> 9, blk = (st >> 6) & 7u, zz = st & 63u;
+    uint32_t done = 0;
+    uint32_t boff = wc->block * 64u;
+    const uint32_t last = g.n_blocks * 64u - 1u;
+    const uint16_t *lut = S.tab.lut;
+    const uint32_t chroma_tb = 2u << kLutBits, ac_bit = 1u << kLutBits;
+    uint32_t tb = (blk >= g.n_luma ? chroma_tb : 0u) | (zz ? ac_bit : 0u);
+    int32_t broken = 0;
+    uint32_t over = 0;
+    uint32_t w = p >> 5;
+    uint32_t hi = S.clean[w], lo = S.clean[w + 1], ahead = S.clean[w + 2];
+    // look a symbol up: its table entry, or the invalid entry for bits that are no code word
+    // (an error unless they are the padding before the boundary, which the invalid entry is too
+    // long to fit before)
+    auto lookup = [&](uint32_t win) {
+        uint32_t e = lut[tb + (win >> (32 - kLutBits))];
+        if (__builtin_expect((e >> 11) == 0, 0)) {
+            e = resolve_long_code(S.tab, e, tb >> kLutBits, win);
+            if ((e >> 11) == 0) {
+                e = kInvalidEntry;
+                if (p + (kInvalidEntry >> 11) <= end_bit) broken = 1;
+            }
+        }
+        return e;
+    };
+    uint32_t win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
+    uint32_t e = lookup(win);
+    // the loop runs while the symbol that was looked up fits before the end: what does not fit
+    // is padding, or nothing at all
+    while (p + (e >> 11) <= end_bit) {
+        const uint32_t adv = e >> 11;
+        const uint32_t k = zz + ((e >> 4) & 63u);  // index of the symbol's coefficient
+        // every symbol stores (see decode_span)
+        wc->coef[min(boff + min(k, 63u), last)] = (int16_t)coefficient_value(win, adv, e & 15u);
+        over |= (e >> 4) & k;
+        p += adv;
+        {
+            const bool moved = (p >> 5) != w;
+            hi = moved ? lo : hi;
+            lo = moved ? ahead : lo;
+            w += moved ? 1u : 0u;
+            ahead = S.clean[w + 2];
+        }
+        const bool endb = k >= 63u;  // zz = k + 1 reaches 64
+        const uint32_t blk1 = blk + 1u == g.bpm ? 0u : blk + 1u;
+        zz = endb ? 0u : k + 1u;
+        blk = endb ? blk1 : blk;
+        done += endb ? 1u : 0u;
+        tb = endb ? (blk1 >= g.n_luma ? chroma_tb : 0u) : tb | ac_bit;
+        boff += endb ? 64u : 0u;
+        win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
+        e = lookup(win);
+    }
+    // the lane must stand between MCUs, fewer than eight (padding) bits before the end
+    if (blk != 0 || zz != 0 || end_bit - p >= 8) broken = 1;
+    else p = end_bit;
+    wc->bad |= broken | (int32_t)((over >> 6) & 1u);
     *nblk = done;
     return pack_state(p, blk, zz);
 }
@@ -891,7 +963,21 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         if (tid == 0) S.keep_off[kT] = clean_len;
         // zeros behind the data: the last word is written byte by byte, and lookups near the
         // end read a few words past it
-        if (tid < 12) S.clean[clean_index((clean_len >> 2) + (uint32_t)tid)] = 0;
+        // Which of the two passes will decode the chunk is known now.  Intervals 0..n_iv-1 of
+        // the chunk end inside it: the first runs from the chunk's start state to the first
+        // listed start, interval k > 0 between listed starts k-1 and k, and in the last chunk
+        // one more runs to the end of the data.
+        const uint32_t n_iv = last ? nbnd + 1 : nbnd;
+        const bool short_intervals = g.ri_blocks != 0 && n_iv >= 1 && nbnd <= (uint32_t)kMaxBoundaries &&
+                                     clean_len <= kShortInterval * (nbnd + 1);
+        // the short-interval pass reads the stream without pad words (its lanes start anywhere)
+        const uint32_t pad_shift = short_intervals ? 31u : (uint32_t)kPadShift;
+        // zeros behind the data: the last word is written byte by byte, and lookups near the
+        // end read a few words past it
+        if (tid < 12) {
+            const uint32_t wd = (clean_len >> 2) + (uint32_t)tid;
+            S.clean[wd + (wd >> pad_shift)] = 0;
+        }
         __syncthreads();  // zero fill done before bytes are written
         {
             uint8_t *cb = reinterpret_cast<uint8_t *>(S.clean);
@@ -913,7 +999,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
                         rank++;
                     }
                     if ((kp >> i) & 1u) {
-                        cb[(clean_index(o >> 2) << 2) | ((o & 3u) ^ 3u)] = (uint8_t)((wv[i >> 2] >> (8 * (i & 3))) & 255u);
+                        cb[(((o >> 2) + ((o >> 2) >> pad_shift)) << 2) | ((o & 3u) ^ 3u)] =
+                            (uint8_t)((wv[i >> 2] >> (8 * (i & 3))) & 255u);
                         o++;
                     }
                 }
@@ -944,16 +1031,11 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         wc.bad = 0;
 
         // ---- short intervals: one lane per restart interval, one pass -----------------
-        // Intervals 0..n_iv-1 of the chunk end inside it: the first runs from the chunk's
-        // start state to the first listed start, interval k > 0 between listed starts k-1
-        // and k, and in the last chunk one more runs to the end of the data.  A decoding
-        // lane is bound by the latency of its own dependent instructions, and a wave takes
-        // as long as its slowest lane whatever the number of busy lanes: consecutive
-        // intervals go to consecutive lanes, so that they fill as few waves as possible and
-        // the other waves of the workgroup leave their SIMDs to other workgroups.
-        const uint32_t n_iv = last ? nbnd + 1 : nbnd;
-        if (g.ri_blocks != 0 && n_iv >= 1 && nbnd <= (uint32_t)kMaxBoundaries &&
-            clean_len <= kShortInterval * (nbnd + 1)) {
+        // A decoding lane is bound by the latency of its own dependent instructions, and a
+        // wave takes as long as its slowest lane whatever the number of busy lanes:
+        // consecutive intervals go to consecutive lanes, so that they fill as few waves as
+        // possible and the other waves of the workgroup leave their SIMDs to other workgroups.
+        if (short_intervals) {
             const uint32_t rem0 = g.ri_blocks - block_base % g.ri_blocks;  // blocks left in interval 0
             for (uint32_t k = (uint32_t)tid; k < n_iv; k += kT) {
                 const uint32_t start = k ? pack_state((uint32_t)S.bpos[k - 1] * 8u, 0, 0) : st0;
@@ -961,10 +1043,9 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
                 const uint32_t blk0 = k ? block_base + rem0 + (k - 1) * g.ri_blocks : block_base;
                 const uint32_t want = min(k ? g.ri_blocks : rem0, block_end > blk0 ? block_end - blk0 : 0u);
                 wc.block = blk0;
-                wc.iv_rem = (int32_t)(k ? g.ri_blocks : rem0);
                 uint32_t got;
-                const uint32_t fin = decode_span<true>(S, g, start, k != 0, end_bit, limit_bits, &got, &wc);
-                // the interval must end on its boundary, between MCUs, with all its blocks
+                const uint32_t fin = decode_interval(S, g, start, end_bit, &got, &wc);
+                // the interval must end on its boundary, between MCUs, with exactly its blocks
                 if (got != want || (fin & 511u) != 0 || (fin >> 9) != end_bit) wc.bad = 1;
             }
             bad |= wc.bad;
