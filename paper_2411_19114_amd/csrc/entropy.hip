@@ -429,10 +429,10 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
     const uint32_t chroma_tb = 2u << kLutBits, ac_bit = 1u << kLutBits;
     // tb: first entry of the current table (DC luma 0, AC luma 1024, DC chroma 2048, AC 3072)
     uint32_t tb = (blk >= g.n_luma ? chroma_tb : 0u) | (zz ? ac_bit : 0u);
-    // what a writing pass has to refuse is gathered without branches: no_code = bits that are
-    // no code word; bit 6 of over = a coefficient index past its block; sign of late = a
-    // symbol where a restart marker had to come
-    int32_t no_code = 0, late = 0, broken = 0;
+    // what a writing pass has to refuse is gathered without branches in the loop: bit 6 of
+    // over = a coefficient index past its block; sign of late = a symbol where a restart marker
+    // had to come; broken = what the rare branches find
+    int32_t late = 0, broken = 0;
     uint32_t over = 0;
     // the stream words that hold bit p, the one after, and the one after that, kept in
     // registers: a symbol is shorter than a word, so at most one new word is needed per
@@ -440,18 +440,24 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
     uint32_t w = p >> 5;
     uint32_t hi = S.clean[clean_index(w)], lo = S.clean[clean_index(w + 1)];
     uint32_t ahead = S.clean[clean_index(w + 2)];
-    if (p < end_bit) {
-        do {
-            const uint32_t win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
-            uint32_t e = lut[tb + (win >> (32 - kLutBits))];
-            int32_t unknown = 0;
-            if (__builtin_expect((e >> 11) == 0, 0)) {
-                e = resolve_long_code(S.tab, e, tb >> kLutBits, win);
-                if ((e >> 11) == 0) {
-                    unknown = 1;
-                    e = kInvalidEntry;
-                }
+    // look a symbol up: its table entry, or the invalid entry for bits that are no code word
+    // (an error unless they are the padding before a boundary, which the invalid entry is too
+    // long to fit before)
+    auto lookup = [&](uint32_t win) {
+        uint32_t e = lut[tb + (win >> (32 - kLutBits))];
+        if (__builtin_expect((e >> 11) == 0, 0)) {
+            e = resolve_long_code(S.tab, e, tb >> kLutBits, win);
+            if ((e >> 11) == 0) {
+                e = kInvalidEntry;
+                if (kWrite && p + (kInvalidEntry >> 11) <= nb) broken = 1;
             }
+        }
+        return e;
+    };
+    if (p < end_bit) {
+        uint32_t win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
+        uint32_t e = lookup(win);
+        do {
             const uint32_t adv = e >> 11;
             if (__builtin_expect(p + adv > nb, 0)) {
                 // the symbol does not fit before the next restart boundary / the end of the data
@@ -486,7 +492,6 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                     // past the image keeps overwriting the image's last coefficient; the block
                     // count then gives it away.
                     wc->coef[min(boff + min(k, 63u), last)] = (int16_t)coefficient_value(win, adv, e & 15u);
-                    no_code |= unknown;
                     over |= (e >> 4) & k;
                     late |= iv_rem - 1;
                 }
@@ -509,9 +514,12 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                     iv_rem -= endb ? 1 : 0;
                 }
             }
+            // the next symbol's lookup, issued before the loop test
+            win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
+            e = lookup(win);
         } while (p < end_bit);
     }
-    if (kWrite) wc->bad |= broken | no_code | (late < 0 ? 1 : 0) | (int32_t)((over >> 6) & 1u);
+    if (kWrite) wc->bad |= broken | (late < 0 ? 1 : 0) | (int32_t)((over >> 6) & 1u);
     *nblk = done;
     return pack_state(p, blk, zz);
 }
