@@ -30,7 +30,7 @@ INT_ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # essential integer operations of decoding one Huffman symbol by the serial definition
 # (peek, table lookup, split length/symbol, two buffer shifts, position update, receive
 #  bits, two for sign extension, run/zig-zag update, end-of-block test, address, store,
-#  refill share): see DESIGN.md, "entropy decode roofline"
+#  refill share)
 OPS_PER_SYMBOL = 16
 
 WORKLOAD_NAMES = {
@@ -46,7 +46,7 @@ N_STREAMS, STREAM_BATCH = 7, 8
 # scaled by what the same counters read for a plain 256 MiB copy (FETCH_SIZE x 2, WRITE_SIZE x 1).
 # They describe the kernels whose sources hash to MEASURED_SOURCES; for any other sources the
 # figure is reported as null.
-MEASURED_SOURCES = "b756b1fa055a058ec0dbbe8278b112285f08e4d639ce8b2170e12d2f337f691a"
+MEASURED_SOURCES = "70cf0fa328c340e7a1f32d456514af43099f61090a57df0f6b31332833de9c27"
 MEASURED_TRAFFIC = {
     2: {"scan": (5422 * 2 + 139101) * 1024, "decode": (114357 * 2 + 147385) * 1024,
         "reconstruct": (69818 * 2 + 144297) * 1024, "resize": (49118 * 2 + 75264) * 1024},
@@ -111,7 +111,8 @@ def symbols_in(streams, limit=64):
 
 
 def algorithmic_bytes(infos, pr):
-    """Bytes each HBM-bound stage has to move for these images (rooflines)."""
+    """Bytes each HBM-bound stage has to move for these images: what the stage reads and
+    writes by its definition, each byte once."""
     esz = 2 if pr["out_dtype"] == "f16" else 4
     n = len(infos)
     out_bytes = n * 3 * pr["crop_h"] * pr["crop_w"] * esz

@@ -51,7 +51,7 @@ static_assert(kSubseqBytes == 64 && (kSubseqBytes / 4) == (1 << kPadShift), "one
 // A first-level entry that is not a code entry is 0 (no such code), kUseLoop, or a
 // reference to a second-level block: bits 10..8 = extra index bits (1..6),
 // bits 7..0 = offset into the table's second-level pool.
-constexpr uint32_t kStore = 0x0400u, kUseLoop = 0x07FFu;
+constexpr uint32_t kUseLoop = 0x07FFu;
 constexpr uint32_t kInvalidEntry = (16u << 11) | (63u << 4);  // 16 bits, ends the block
 
 struct alignas(16) HuffTables {
@@ -369,15 +369,6 @@ __device__ __forceinline__ uint32_t resolve_long_code(const HuffTables &T, uint3
 __device__ __forceinline__ uint32_t clean_index(uint32_t w)
 {
     return w + (w >> kPadShift);
-}
-
-// The next 32 bits of the staged stream at bit position p (two LDS words and a shift).
-__device__ __forceinline__ uint32_t window32(const DecodeShared &S, const Geometry &g, uint32_t p)
-{
-    const uint32_t w = min(p >> 5, (uint32_t)(kChunkRaw / 4 + 8));
-    const unsigned long long pair = ((unsigned long long)S.clean[clean_index(w)] << 32) |
-                                    S.clean[clean_index(w + 1)];
-    return (uint32_t)(pair >> (32 - (p & 31u)));
 }
 
 // value of a stored coefficient: appended bits (T.81 F.2.2.4 RECEIVE) and sign extension

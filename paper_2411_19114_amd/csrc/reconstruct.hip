@@ -43,7 +43,6 @@ struct ZigZag {
         }
     }
 };
-__device__ const ZigZag kZigZag{};
 
 // for column u, the zig-zag positions of its eight coefficients F(v, u), v = 0..7, packed a
 // byte each: lane u of a block fetches them in one 8-byte load
