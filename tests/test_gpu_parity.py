@@ -331,3 +331,48 @@ def test_more_images_than_lanes_in_a_workgroup(prep):
             assert np.array_equal(h.debug_last_coefficients(i, coef.shape[0]), coef)
     finally:
         h.close()
+
+
+# ---- full batches in the configuration that bench.py times, checked on samples --------------
+
+def _full_batch_sampled(prep, config, sample):
+    import torch
+    from paper_2411_19114_amd.binding import make_params
+    streams = synth.make_batch(config)
+    n = len(streams)
+    blob, offsets = synth.pack(streams)
+    pr = synth.params_of(config)
+    params = make_params(pr["resize_short"], pr["crop_h"], pr["crop_w"], pr["out_dtype"], MEAN, STD)
+    infos = prep.parse_headers(blob, offsets)
+    h = prep.Preprocessor(device=0, max_batch=n, max_width=max(i.width for i in infos),
+                          max_height=max(i.height for i in infos), max_bitstream_bytes=int(offsets[-1]),
+                          max_total_pixels=sum(i.width * i.height for i in infos))
+    try:
+        dt = torch.float16 if pr["out_dtype"] == "f16" else torch.float32
+        out = torch.full((n, 3, pr["crop_h"], pr["crop_w"]), 777.0, dtype=dt, device="cuda:0")
+        dev_bits = torch.from_numpy(blob).to("cuda:0")
+        hs = torch.cuda.Stream(device="cuda:0")
+        hs.wait_stream(torch.cuda.current_stream())
+        for _ in range(3):  # back-to-back calls, as the timed loop makes them
+            h.decode_resize_batch_resident(blob, dev_bits.data_ptr(), offsets, params, out.data_ptr(),
+                                           hs.cuda_stream)
+        hs.synchronize()
+        assert h.get_status(n) == [0] * n
+        got = out.float().cpu().numpy().astype(np.float64)
+        # every output element was written and is a plausible normalized value
+        assert np.isfinite(got).all() and np.abs(got).max() < 3.0
+        picks = sorted(set(np.linspace(0, n - 1, sample).astype(int).tolist()))
+        ref = oracle_batch([streams[i] for i in picks], pr["resize_short"], pr["crop_h"], pr["crop_w"])
+        for i, (coef, rgb, info, ten) in zip(picks, ref):
+            assert np.array_equal(h.debug_last_coefficients(i, coef.shape[0]), coef), f"image {i}: coefficients"
+            d = np.abs(h.debug_last_rgb(i, info.height, info.width).astype(np.int32) - rgb.astype(np.int32))
+            assert d.max() <= 1 and (d == 0).mean() >= 0.999, f"image {i}: rgb"
+            err = np.abs(got[i] - ten).max()
+            assert err <= TENSOR_ABS_TOL, f"image {i}: tensor off by {err}"
+    finally:
+        h.close()
+
+
+@pytest.mark.parametrize("config,sample", [(1, 8), (2, 16), (5, 16)])
+def test_full_batch_as_benchmarked(prep, config, sample):
+    _full_batch_sampled(prep, config, sample)
