@@ -64,3 +64,62 @@ def check_against_oracle(pp, streams, resize_short, crop_h, crop_w, out_dtype, r
     if check_intermediates:
         assert n_exact >= RGB_EXACT_FRACTION * n_values, f"only {n_exact / n_values:.5f} of RGB exact"
     return got
+
+
+# ---- damaged streams ------------------------------------------------------------------
+DAMAGE_BASES = [(96, 64, oracle.MODE_420, 2, 85), (96, 64, oracle.MODE_420, 0, 90),
+                (80, 72, oracle.MODE_444, 0, 92), (120, 90, oracle.MODE_GRAY, 0, 80),
+                (200, 160, oracle.MODE_420, 13, 95), (64, 48, oracle.MODE_444, 1, 60),
+                (320, 240, oracle.MODE_420, 0, 96)]
+
+
+def damaged_streams(seed, per_base, n_bases=len(DAMAGE_BASES)):
+    """Sound oracle-encoded files whose entropy-coded segment is then damaged at random: bit
+    flips, inserted marker bytes, deleted runs, garbage runs, truncation, runs of FF.
+    Headers stay intact, so every file reaches the decoder kernels."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for k, (w, h, mode, dri, q) in enumerate(DAMAGE_BASES[:n_bases]):
+        rgb = synth.gradient_noise_image(np.random.default_rng(50 + k), w, h, 14.0)
+        b = oracle.encode(rgb, q, mode, dri, table_mode=k % 2)[0]
+        sos = b.index(b"\xff\xda")
+        start, end = sos + 2 + int.from_bytes(b[sos + 2:sos + 4], "big"), len(b) - 2
+        for _ in range(per_base):
+            a = bytearray(b)
+            kind = int(rng.integers(0, 6))
+            pos = int(rng.integers(start, end))
+            if kind == 0:
+                for _ in range(int(rng.integers(1, 4))):
+                    a[int(rng.integers(start, end))] ^= 1 << int(rng.integers(0, 8))
+            elif kind == 1:
+                a[pos:pos] = bytes([0xFF, int(rng.choice([0xD0, 0xD3, 0xD7, 0x00, 0xFF, 0xD9, 0xC4]))])
+            elif kind == 2:
+                del a[pos:pos + int(rng.integers(1, 40))]
+            elif kind == 3:
+                n = int(rng.integers(1, 64))
+                a[pos:pos + n] = rng.integers(0, 256, n, dtype=np.uint8).tobytes()
+            elif kind == 4:
+                a = a[:pos] + b"\xff\xd9"
+            else:
+                n = int(rng.integers(1, 30))
+                a[pos:pos + n] = b"\xff" * n
+            out.append(bytes(a))
+    return out
+
+
+def check_damaged(streams, status, coefficients_of, tensor):
+    """A damaged stream is either refused (zero slab) or decoded to the oracle's coefficients;
+    the kernels never accept what the oracle refuses."""
+    refused = 0
+    for i, s in enumerate(streams):
+        try:
+            c0 = oracle.decode(s, want_rgb=False)[0]
+        except oracle.OracleError:
+            c0 = None
+        if status[i] == 0:
+            assert c0 is not None, f"stream {i}: accepted, but the oracle refuses it"
+            assert np.array_equal(coefficients_of(i, c0.shape[0]), c0), f"stream {i}: coefficients differ"
+        else:
+            refused += 1
+            assert (tensor[i] == 0).all(), f"stream {i}: refused but its slab is not zero"
+    return refused

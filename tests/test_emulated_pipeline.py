@@ -2,10 +2,13 @@
 by g++ against a CPU stand-in for HIP (one OS thread per lane, AddressSanitizer and UBSan
 on) and run end to end through the C ABI.  The product never uses this build; the GPU
 parity tests are the ones marked `gpu`."""
+import os
+
 import numpy as np
 import pytest
 
 import emul
+import helpers
 import oracle
 import synth
 from oracle import MODE_420, MODE_444, MODE_GRAY
@@ -68,3 +71,16 @@ def test_broken_streams_are_reported_and_zero_filled():
                good[0][:i - 1] + good[0][i + 2:],
                good[0][:sos + 30] + bytes(60) + good[0][sos + 90:]]
     _check(streams, 32, 24, 24, "f32", expect_status=[0, -5, 0, -4, -5, -5])
+
+
+def test_damaged_entropy_data_stays_in_bounds():
+    """Random damage to the entropy-coded bytes: the sanitizers see no access out of bounds,
+    every kernel loop ends, and each stream is refused or decoded as the oracle decodes it.
+    PREP_DAMAGE_FULL=1 runs the larger set that the GPU test of the same name uses."""
+    if os.environ.get("PREP_DAMAGE_FULL"):
+        streams = helpers.damaged_streams(11, 12) + helpers.damaged_streams(12, 12)
+    else:
+        streams = helpers.damaged_streams(7, 4, n_bases=4)
+    per, ten = emul.run(streams, 32, 24, 24, "f32", MEAN, STD, timeout=3000)
+    refused = helpers.check_damaged(streams, [p[0] for p in per], lambda i, nb: per[i][1], ten)
+    assert refused >= len(streams) // 2

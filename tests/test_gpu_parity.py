@@ -376,3 +376,25 @@ def _full_batch_sampled(prep, config, sample):
 @pytest.mark.parametrize("config,sample", [(1, 8), (2, 16), (5, 16)])
 def test_full_batch_as_benchmarked(prep, config, sample):
     _full_batch_sampled(prep, config, sample)
+
+
+def test_damaged_entropy_data_is_refused_or_decoded_exactly(pp):
+    """Random damage to the entropy-coded bytes (the streams that the CPU build of the kernels
+    decodes under AddressSanitizer in test_emulated_pipeline): each stream is refused with a
+    zero slab or decoded to the oracle's coefficients, and sound images in the same batch
+    are untouched."""
+    from helpers import check_damaged, damaged_streams
+    good = synth.make_batch(1, 2)
+    ref = oracle_batch(good, 32, 24, 24)
+    damaged = damaged_streams(7, 4, n_bases=4) + damaged_streams(11, 12) + damaged_streams(12, 12)
+    refused = 0
+    for lo in range(0, len(damaged), 60):
+        part = damaged[lo:lo + 60]
+        streams = [good[0]] + part + [good[1]]
+        status, got = run_gpu(pp, streams, 32, 24, 24, "f32")
+        assert status[0] == 0 and status[-1] == 0
+        assert np.abs(got[0] - ref[0][3]).max() <= TENSOR_ABS_TOL
+        assert np.abs(got[-1] - ref[1][3]).max() <= TENSOR_ABS_TOL
+        refused += check_damaged(part, status[1:-1], lambda i, nb: pp.debug_last_coefficients(i + 1, nb),
+                                 got[1:-1])
+    assert refused >= len(damaged) // 2
