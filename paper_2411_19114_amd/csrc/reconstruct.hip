@@ -7,6 +7,7 @@
 // (128 B per block), everything else lives in LDS, and RGB leaves as aligned
 // 32-bit stores covering the whole MCU grid (the row pitch includes padding).
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include "../../include/prep.h"
@@ -91,52 +92,82 @@ __device__ inline void idct8(const double F[8], double out[8])
 // rational results of the IDCT definition carry ~1e-13 of evaluation noise.
 constexpr double kTieEps = 1.0 / 1048576.0;
 
-// JFIF colour values are sums of an integer and one or two products of small integers
-// with three-decimal constants; in float they stay well clear of the half-way points that
-// matter except for isolated saturated-blue cases, so single precision decides the rounding.
-// v_half = value + 0.5.  Rounding half up is floor(v_half); the conversion truncates
-// instead, which differs only below zero, where both results clamp to 0.
-__device__ inline uint32_t round_clamp_u8(float v_half)
+// One colour value -> byte `lane` of `word`: round to nearest, clamp to 0..255, in one
+// conversion instruction.  It rounds exact half-way values to even, where the rounding of
+// T.81 A.3.1 (used for the colour conversion too) goes up; see chroma_terms.
+__device__ inline uint32_t put_u8(float v, uint32_t lane, uint32_t word)
 {
-    return (uint32_t)min(max((int)v_half, 0), 255);
+    return __builtin_amdgcn_cvt_pk_u8_f32(v, lane, word);
 }
 
-// the three colour values of one pixel from its luma + 0.5 and the chroma terms of its
-// chroma sample, packed R | G << 8 | B << 16
+// JFIF colour values are sums of an integer and one or two products of small integers with
+// three- or six-decimal constants, so single precision decides the rounding wherever a value
+// is not within ~1e-5 of a half-way point.  Exactly half way lie: red never (1.402 Cr has no
+// fraction .5 for |Cr| <= 128); blue for Cb = +-125 only (1.772 * 125 = 221.5), and its
+// fractions are multiples of .004, so adding .001 to the blue term turns round-to-nearest
+// into round-half-up without moving any other value across a half-way point; green for
+// (Cb, Cr) = (+-50, -+50), with fractions too fine for such a shift, so green is rounded as
+// floor(value + 1/2) before the conversion, which then only clamps and packs.
 struct ChromaTerms {
-    float r, g, b;  // 1.402 Cr, -0.344136 Cb - 0.714136 Cr, 1.772 Cb (Cb, Cr less 128)
+    float r, g, b;  // 1.402 Cr, -0.344136 Cb - 0.714136 Cr + .5, 1.772 Cb + .001 (Cb, Cr less 128)
 };
 __device__ inline ChromaTerms chroma_terms(uint32_t cb_byte, uint32_t cr_byte)
 {
     const float cb = (float)((int)cb_byte - 128), cr = (float)((int)cr_byte - 128);
     ChromaTerms t;
     t.r = 1.402f * cr;
-    t.g = fmaf(-0.714136f, cr, -0.344136f * cb);
-    t.b = 1.772f * cb;
+    t.g = fmaf(-0.714136f, cr, fmaf(-0.344136f, cb, 0.5f));
+    t.b = fmaf(1.772f, cb, 0.001f);
     return t;
 }
-__device__ inline uint32_t rgb_of(uint32_t y_byte, const ChromaTerms &t)
+// Four pixels of one row -> twelve bytes R G B R G B ... as three words; pixel j has luma byte
+// j of y4 and the chroma terms t[j].  Every value is converted straight into its byte.
+__device__ inline void store_rgb4(uint8_t *dst, uint32_t y4, const ChromaTerms &t0, const ChromaTerms &t1,
+                                  const ChromaTerms &t2, const ChromaTerms &t3)
 {
-    const float yh = (float)y_byte + 0.5f;
-    return round_clamp_u8(yh + t.r) | (round_clamp_u8(yh + t.g) << 8) | (round_clamp_u8(yh + t.b) << 16);
-}
-// four packed pixels -> twelve bytes R G B R G B ...
-__device__ inline void store_rgb4(uint8_t *dst, const uint32_t px[4])
-{
+    const float y0 = (float)(y4 & 255u), y1 = (float)((y4 >> 8) & 255u);
+    const float y2 = (float)((y4 >> 16) & 255u), y3 = (float)(y4 >> 24);
+    uint32_t d0 = 0, d1 = 0, d2 = 0;
+    d0 = put_u8(y0 + t0.r, 0, d0); d0 = put_u8(floorf(y0 + t0.g), 1, d0); d0 = put_u8(y0 + t0.b, 2, d0);
+    d0 = put_u8(y1 + t1.r, 3, d0); d1 = put_u8(floorf(y1 + t1.g), 0, d1); d1 = put_u8(y1 + t1.b, 1, d1);
+    d1 = put_u8(y2 + t2.r, 2, d1); d1 = put_u8(floorf(y2 + t2.g), 3, d1); d2 = put_u8(y2 + t2.b, 0, d2);
+    d2 = put_u8(y3 + t3.r, 1, d2); d2 = put_u8(floorf(y3 + t3.g), 2, d2); d2 = put_u8(y3 + t3.b, 3, d2);
     uint32_t *d = reinterpret_cast<uint32_t *>(dst);
-    d[0] = px[0] | (px[1] << 24);
-    d[1] = (px[1] >> 8) | (px[2] << 16);
-    d[2] = (px[2] >> 16) | (px[3] << 8);
+    d[0] = d0;
+    d[1] = d1;
+    d[2] = d2;
+}
+// four gray pixels: every byte of y4 three times
+__device__ inline void store_gray4(uint8_t *dst, uint32_t y4)
+{
+    const uint32_t a = y4 & 255u, b = (y4 >> 8) & 255u, c = (y4 >> 16) & 255u, e = y4 >> 24;
+    uint32_t *d = reinterpret_cast<uint32_t *>(dst);
+    d[0] = a * 0x010101u | (b << 24);
+    d[1] = b * 0x0101u | (c * 0x0101u << 16);
+    d[2] = c | (e * 0x010101u << 8);
 }
 
 }  // namespace
 
+// A group's raw coefficients land in LDS block by block, 64 in zig-zag order, kRawPitch
+// int16 apart: 72 = 36 words keeps the 16-byte stores aligned and puts the blocks of a wave
+// four banks apart, so that lanes of different blocks reading the same zig-zag position do
+// not meet in one bank.
+constexpr int kRawPitch = 72;
+
 struct ReconShared {
     double tile[kReconBlocks * kTileSize];
     int32_t qi[3][64];
+    // the sample planes, luma first; free between a group's colour conversion and the next
+    // group's row pass, which is when the raw coefficients use the same bytes
     uint32_t luma[16 * kLumaPitch / 4];
     uint32_t chroma[2][8 * kChromaPitch / 4];
 };
+static_assert(offsetof(ReconShared, chroma) == offsetof(ReconShared, luma) + sizeof(uint32_t) * 16 * kLumaPitch / 4,
+              "the chroma planes follow the luma plane");
+static_assert(kReconBlocks * kRawPitch * sizeof(int16_t) <=
+                  sizeof(uint32_t) * (16 * kLumaPitch / 4 + 2 * 8 * kChromaPitch / 4),
+              "the raw coefficients fit in the sample planes");
 
 // The work of one workgroup: groups gi0 .. gi0 + n_groups - 1 of one image (a group is a run
 // of MCUs of one MCU row, numbered row by row), one after the other.  The sampling mode is
@@ -168,10 +199,15 @@ __device__ __forceinline__ void reconstruct_groups(ReconShared &S, const uint8_t
     const int mcu = b / bpm, blk = b % bpm;  // of the lane's block, if the group has that many
     const int comp = blk < n_luma ? 0 : blk - n_luma + 1;
     double *T = tile + b * kTileSize;
-    // the luma sample plane doubles as the landing place of a group's raw coefficients (128
-    // bytes per block, zig-zag order): it is free until the row pass
+    // the sample planes double as the landing place of a group's raw coefficients: they are
+    // free until the row pass
     int16_t *zz16 = reinterpret_cast<int16_t *>(luma);
     const unsigned long long pos = kZigZagColumns.pos[l];
+    // the lane's column of its component's quantisation table, kept for all groups
+    __syncthreads();
+    int32_t qcol[8];
+#pragma unroll
+    for (int v = 0; v < 8; v++) qcol[v] = qi[comp][(int)((pos >> (8 * v)) & 63u)];
 
     uint32_t mrow = gi0 / R.groups_per_row, gcol = gi0 - mrow * R.groups_per_row;
     // the lane's eight coefficients of group (mrow, gcol), or zeros past the group's blocks
@@ -187,8 +223,8 @@ __device__ __forceinline__ void reconstruct_groups(ReconShared &S, const uint8_t
         const uint32_t mcu_x0 = gcol * per_group;
         const int gcount = min(per_group, (int)R.mcu_cols - (int)mcu_x0);
         const bool have = b < gcount * bpm;  // <= kReconBlocks blocks
-        if (have) *reinterpret_cast<uint4 *>(zz16 + b * 64 + l * 8) = raw;
-        __syncthreads();  // also: the quantisation tables are in place
+        if (have) *reinterpret_cast<uint4 *>(zz16 + b * kRawPitch + l * 8) = raw;
+        __syncthreads();
         // next group of this workgroup, row by row
         uint32_t next_row = mrow, next_col = gcol + 1;
         if (next_col == R.groups_per_row) { next_col = 0; next_row++; }
@@ -199,7 +235,7 @@ __device__ __forceinline__ void reconstruct_groups(ReconShared &S, const uint8_t
 #pragma unroll
             for (int v = 0; v < 8; v++) {
                 const int k = (int)((pos >> (8 * v)) & 63u);
-                F[v] = (double)__mul24((int)zz16[b * 64 + k], qi[comp][k]);  // 16 x 8 bits: exact
+                F[v] = (double)__mul24((int)zz16[b * kRawPitch + k], qcol[v]);  // 16 x 8 bits: exact
             }
             idct8(F, o);
 #pragma unroll
@@ -249,10 +285,8 @@ __device__ __forceinline__ void reconstruct_groups(ReconShared &S, const uint8_t
 #pragma unroll
                 for (int r = 0; r < 2; r++) {
                     const int row = 2 * rp + r;
-                    const uint32_t y4 = luma[(row * kLumaPitch) / 4 + q];
-                    const uint32_t px[4] = {rgb_of(y4 & 255u, t0), rgb_of((y4 >> 8) & 255u, t0),
-                                            rgb_of((y4 >> 16) & 255u, t1), rgb_of(y4 >> 24, t1)};
-                    store_rgb4(dst0 + (size_t)row * R.rgb_pitch + q * 12, px);
+                    store_rgb4(dst0 + (size_t)row * R.rgb_pitch + q * 12, luma[(row * kLumaPitch) / 4 + q],
+                               t0, t0, t1, t1);
                 }
             }
         } else {
@@ -261,19 +295,17 @@ __device__ __forceinline__ void reconstruct_groups(ReconShared &S, const uint8_t
             for (int it = tid; it < items; it += kReconThreads) {
                 const int row = it / quads, q = it - row * quads;
                 const uint32_t y4 = luma[(row * kLumaPitch) / 4 + q];
-                uint32_t px[4];
+                uint8_t *dst = dst0 + (size_t)row * R.rgb_pitch + q * 12;
                 if (sampling == PREP_SAMPLING_GRAY) {
-#pragma unroll
-                    for (int j = 0; j < 4; j++) px[j] = ((y4 >> (8 * j)) & 255u) * 0x010101u;
+                    store_gray4(dst, y4);
                 } else {
                     const uint32_t cb4 = chroma[0][(row * kChromaPitch) / 4 + q];
                     const uint32_t cr4 = chroma[1][(row * kChromaPitch) / 4 + q];
-#pragma unroll
-                    for (int j = 0; j < 4; j++)
-                        px[j] = rgb_of((y4 >> (8 * j)) & 255u,
-                                       chroma_terms((cb4 >> (8 * j)) & 255u, (cr4 >> (8 * j)) & 255u));
+                    store_rgb4(dst, y4, chroma_terms(cb4 & 255u, cr4 & 255u),
+                               chroma_terms((cb4 >> 8) & 255u, (cr4 >> 8) & 255u),
+                               chroma_terms((cb4 >> 16) & 255u, (cr4 >> 16) & 255u),
+                               chroma_terms(cb4 >> 24, cr4 >> 24));
                 }
-                store_rgb4(dst0 + (size_t)row * R.rgb_pitch + q * 12, px);
             }
         }
         mrow = next_row;

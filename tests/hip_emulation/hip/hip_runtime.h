@@ -146,6 +146,15 @@ inline uint32_t __builtin_amdgcn_alignbit(uint32_t hi, uint32_t lo, uint32_t shi
 {
     return (uint32_t)(((((uint64_t)hi) << 32) | lo) >> (shift & 31u));
 }
+// V_CVT_PK_U8_F32: v rounded to the nearest integer (half-way to even), clamped to 0..255,
+// into byte `lane` of `word`
+inline uint32_t __builtin_amdgcn_cvt_pk_u8_f32(float v, uint32_t lane, uint32_t word)
+{
+    const float r = __builtin_nearbyintf(v);
+    const uint32_t b = !(r > 0.0f) ? 0u : r >= 255.0f ? 255u : (uint32_t)r;
+    const uint32_t sh = 8u * (lane & 3u);
+    return (word & ~(255u << sh)) | (b << sh);
+}
 inline int __mul24(int a, int b) { return a * b; }
 inline int __popcll(unsigned long long v) { return __builtin_popcountll(v); }
 
