@@ -121,8 +121,10 @@ def algorithmic_bytes(infos, pr):
     out_bytes = n * 3 * pr["crop_h"] * pr["crop_w"] * esz
     entropy_bytes = sum(i.entropy_bytes for i in infos)
     blocks = sum(i.mcu_cols * i.mcu_rows * i.blocks_per_mcu for i in infos)
-    # source footprint of the crop: the window of each image that the outputs map back to
+    # source footprint of the crop: the window of each image that the outputs map back to;
+    # reconstruction owes the MCUs that hold the pixels its bilinear taps read
     foot = 0
+    recon = 0
     for i in infos:
         s = pr["resize_short"]
         if s:
@@ -130,10 +132,21 @@ def algorithmic_bytes(infos, pr):
         else:
             ow, oh = i.width, i.height
         foot += int(round(pr["crop_w"] * i.width / ow)) * int(round(pr["crop_h"] * i.height / oh)) * 3
-    padded_rgb = sum(i.mcu_cols * i.mcu_rows * (256 if i.sampling == 1 else 64) * 3 for i in infos)
+        mcu_px = 16 if i.sampling == 1 else 8
+        mcus = 1
+        for size, out_size, count in ((i.width, ow, pr["crop_w"]), (i.height, oh, pr["crop_h"])):
+            first = (out_size - count) // 2
+            # taps floor(s), floor(s) + 1 of the first and last output; 2 s out_size is an integer
+            s2_first = (2 * first + 1) * size - out_size
+            s2_last = (2 * (first + count - 1) + 1) * size - out_size
+            lo = s2_first // (2 * out_size)
+            hi = s2_last // (2 * out_size) + (1 if s2_last % (2 * out_size) else 0)
+            lo, hi = min(max(lo, 0), size - 1), min(max(hi, 0), size - 1)
+            mcus *= hi // mcu_px - lo // mcu_px + 1
+        recon += mcus * (i.blocks_per_mcu * 128 + mcu_px * mcu_px * 3)
     return {
         "scan": entropy_bytes + blocks * 128,           # read stream once + clear coefficients
-        "reconstruct": blocks * 128 + padded_rgb,       # coefficients in, RGB out
+        "reconstruct": recon,                           # coefficients in, RGB out, MCUs under the crop
         "resize": foot + out_bytes,                     # crop footprint in, tensor out
     }, entropy_bytes
 
@@ -175,6 +188,8 @@ def run_streams(args, torch, prep, synth, make_params):
     batches of STREAM_BATCH images back to back; one step = one batch on every stream.
     Reports whole-job images/s and the distribution of per-batch latency (submit -> done)."""
     import threading
+    N_STREAMS = args.streams or globals()["N_STREAMS"]
+    STREAM_BATCH = args.stream_batch
     t0 = time.perf_counter()
     streams = synth.make_batch(3)
     gen_s = time.perf_counter() - t0
@@ -254,15 +269,16 @@ def run_streams(args, torch, prep, synth, make_params):
         "dtype": "int32 entropy decode, f64 IDCT, f32 resize -> " + pr["out_dtype"] + " output",
         "data": "synthetic",
         "config": {"workload": WORKLOAD_NAMES[3], "streams": N_STREAMS, "batch": STREAM_BATCH,
+                   "hw_queues": int(os.environ["GPU_MAX_HW_QUEUES"]),
                    "input": "resident in HBM", "pool_images": len(streams),
                    "sha256": synth.sha256_of(streams), "input_generation_s": round(gen_s, 2)},
         "latency_ms": {"p50": float(np.percentile(all_lat, 50)), "p95": float(np.percentile(all_lat, 95)),
                        "p99": float(np.percentile(all_lat, 99)), "max": float(all_lat[-1]),
-                       "what": "one batch of 8: call of the entry point until its stream is idle",
+                       "what": f"one batch of {STREAM_BATCH}: call of the entry point until its stream is idle",
                        "samples": int(all_lat.size)},
         "roofline": roofline,
         "stages": stages,
-        "stage_timing": "stream 0 only, one batch of 8 images per launch",
+        "stage_timing": f"stream 0 only, one batch of {STREAM_BATCH} images per launch",
         "gpu_ms_per_step": float(stage.sum()),
         "cpu_baseline": cpu,
     }
@@ -278,10 +294,15 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--streams", type=int, default=1,
+    ap.add_argument("--streams", type=int, default=None,
                     help="workloads 1, 2, 4, 5: deal the steps in turn to this many handles, each "
                          "with its own HIP stream, so that batches overlap on the GPU (default 1: "
-                         "one batch at a time)")
+                         "one batch at a time); workload 3: number of host threads (default 7)")
+    ap.add_argument("--hw-queues", type=int, default=8,
+                    help="workload 3: hardware queues the HIP runtime may use (GPU_MAX_HW_QUEUES; its "
+                         "default of 4 makes seven streams share queues and wait for each other)")
+    ap.add_argument("--stream-batch", type=int, default=STREAM_BATCH,
+                    help="workload 3: images per batch (default 8; 1 = the single-input latency case)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy (a reference for HBM counters)")
     ap.add_argument("--host-input", action="store_true",
@@ -293,6 +314,9 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
+    if args.workload == 3:
+        # read by the HIP runtime when it starts, so it is set before torch loads it
+        os.environ["GPU_MAX_HW_QUEUES"] = str(min(max(args.hw_queues, 1), 32))
     import torch
     import paper_2411_19114_amd as prep
     import synth
@@ -324,7 +348,7 @@ def main():
     blocks = sum(i.mcu_cols * i.mcu_rows * i.blocks_per_mcu for i in infos)
 
     dev = torch.device("cuda:0")
-    n_handles = max(1, args.streams)
+    n_handles = max(1, args.streams or 1)
     pps = [prep.Preprocessor(device=0, max_batch=n, max_width=max_w, max_height=max_h,
                              max_bitstream_bytes=int(offsets[-1]), max_total_pixels=pixels)
            for _ in range(n_handles)]

@@ -47,9 +47,16 @@ enum {
 };
 
 enum { PREP_F32 = 0, PREP_F16 = 1 };
-/* prep_config.flags: expand the Huffman tables in every decoder workgroup instead of once
- * per distinct table set of the batch (same results; kept for checking that path) */
-enum { PREP_FLAG_TABLES_PER_WORKGROUP = 1 };
+/* prep_config.flags.
+ * PREP_FLAG_TABLES_PER_WORKGROUP: expand the Huffman tables in every decoder workgroup
+ *   instead of once per distinct table set of the batch (same results; kept for checking
+ *   that path).
+ * PREP_FLAG_FULL_RGB: convert every MCU of every image to RGB.  Without it only the MCUs
+ *   whose pixels the crop window's bilinear taps read are converted (the output tensor is the
+ *   same; the paper's image unit streams decode into resize and crop without keeping a
+ *   decoded image either, section 4.2), and prep_debug_last_rgb returns what the workspace
+ *   holds outside those MCUs. */
+enum { PREP_FLAG_TABLES_PER_WORKGROUP = 1, PREP_FLAG_FULL_RGB = 2 };
 enum { PREP_SAMPLING_444 = 0, PREP_SAMPLING_420 = 1, PREP_SAMPLING_GRAY = 2 };
 
 typedef struct prep_handle prep_handle;
@@ -190,8 +197,17 @@ int64_t prep_debug_last_coefficients(prep_handle *h, int32_t image, int16_t *hos
                                      uint64_t cap);
 
 /* Decoded RGB of image `image`: height*width*3 bytes, interleaved, tightly
- * packed.  Returns the number of bytes written or a negative code.            */
+ * packed.  Returns the number of bytes written or a negative code.  Only the
+ * pixels inside the rectangle of prep_debug_last_region are the image's.      */
 int64_t prep_debug_last_rgb(prep_handle *h, int32_t image, uint8_t *host_out_hwc, uint64_t cap);
+
+/* The pixels of image `image` that the last call converted to RGB:
+ * rect = {x0, y0, x1, y1}, columns x0 <= x < x1 and rows y0 <= y < y1 (HOST,
+ * 4 entries).  It is the whole image for a handle created with
+ * PREP_FLAG_FULL_RGB, else the MCUs that the crop window's bilinear taps
+ * read, clipped to the image.  Returns PREP_OK, the image's own status if
+ * it was refused, or PREP_E_INVALID_ARG.                                      */
+int prep_debug_last_region(prep_handle *h, int32_t image, int32_t rect[4]);
 
 /* Stage timing.  While enabled, every batch call brackets its GPU stages with
  * events on the call's stream (calls that enqueue no decode are not counted).

@@ -12,6 +12,7 @@ _SOURCES = ["entropy.hip", "reconstruct.hip", "resize.hip", "api.cpp", "parser.c
 OK, E_INVALID_ARG, E_TOO_LARGE, E_HIP, E_UNSUPPORTED, E_CORRUPT, E_NOMEM = 0, -1, -2, -3, -4, -5, -6
 F32, F16 = 0, 1
 FLAG_TABLES_PER_WORKGROUP = 1
+FLAG_FULL_RGB = 2
 
 
 def lib_path():
@@ -64,7 +65,7 @@ EXPORTS = [
     "prep_create", "prep_destroy", "prep_decode_resize_batch", "prep_decode_resize_batch_resident",
     "prep_get_status", "prep_strerror", "prep_parse_headers", "prep_interval_descriptors",
     "prep_resize_normalize", "prep_reconstruct_from_coefficients", "prep_debug_last_coefficients",
-    "prep_debug_last_rgb", "prep_stage_ms", "prep_set_timing",
+    "prep_debug_last_rgb", "prep_debug_last_region", "prep_stage_ms", "prep_set_timing",
 ]
 
 _lib = None
@@ -105,6 +106,7 @@ def lib():
         L.prep_debug_last_coefficients.restype = C.c_int64
         L.prep_debug_last_rgb.argtypes = [vp, C.c_int32, vp, C.c_uint64]
         L.prep_debug_last_rgb.restype = C.c_int64
+        L.prep_debug_last_region.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32)]
         L.prep_stage_ms.argtypes = [vp, C.c_int32, C.POINTER(C.c_float)]
         L.prep_set_timing.argtypes = [vp, C.c_int32]
         _lib = L
@@ -238,6 +240,12 @@ class Preprocessor:
             raise PrepError(int(n), "prep_debug_last_rgb")
         assert n == out.size
         return out
+
+    def debug_last_region(self, image):
+        """(x0, y0, x1, y1): the pixels of the image that the last call converted to RGB."""
+        rect = (C.c_int32 * 4)()
+        _check(lib().prep_debug_last_region(self._h, image, rect), "prep_debug_last_region")
+        return tuple(rect)
 
     def set_timing(self, enabled):
         _check(lib().prep_set_timing(self._h, int(bool(enabled))), "prep_set_timing")

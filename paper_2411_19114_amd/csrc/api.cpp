@@ -79,6 +79,7 @@ struct prep_handle {
     std::vector<ParsedImage> parsed;
     std::vector<ImageRec> recs;
     std::vector<ResizeRec> rr;
+    std::vector<uint64_t> rel;         // file offsets relative to the batch's first byte
 };
 
 namespace {
@@ -130,6 +131,19 @@ bool make_resize_rec(int w, int h, const prep_params *p, uint64_t src_off, uint3
     r->pad_ = 0;
     r->src_off = src_off;
     return true;
+}
+
+// First and last source row (or column) whose pixels count in n_out outputs: the same
+// fixed-point mapping as the resize kernel's, taps i and i + 1 clamped to the image; the
+// second tap of the last output does not count where its weight is exactly zero.
+void tap_span(uint64_t off, uint64_t scale, int n_out, int size, int *lo, int *hi)
+{
+    const uint64_t t_last = off + (uint64_t)(n_out - 1) * scale;
+    const bool weighted = (t_last & ((1ull << kCoordFrac) - 1)) != 0;
+    const int64_t first = (int64_t)(off >> kCoordFrac) - kCoordBias;
+    const int64_t last = (int64_t)(t_last >> kCoordFrac) - kCoordBias + (weighted ? 1 : 0);
+    *lo = (int)std::min<int64_t>(std::max<int64_t>(first, 0), size - 1);
+    *hi = (int)std::min<int64_t>(std::max<int64_t>(last, 0), size - 1);
 }
 
 // Images with the same four Huffman tables share one expanded copy: the slot of image i's
@@ -192,7 +206,6 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
         R.rgb_off = P.rgb_bytes;
         R.status = I.status;
         R.n_windows = 1;
-        R.groups_per_row = 1;
         if (I.status == PREP_OK) {
             const int hs = I.sampling == PREP_SAMPLING_420 ? 2 : 1;
             R.entropy_rel = (uint32_t)I.entropy_offset;
@@ -201,8 +214,6 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
             R.n_windows = (uint32_t)((I.entropy_bytes + kWindowBytes - 1) / kWindowBytes);
             if (R.n_windows == 0) R.n_windows = 1;
             R.rgb_pitch = (uint32_t)I.mcu_cols * 8u * hs * 3u;
-            const int per = recon_mcus_per_group(I.sampling);
-            R.groups_per_row = (uint32_t)((I.mcu_cols + per - 1) / per);
             for (int t = 0; t < 4; t++) { R.dht_off[t] = pi.dht_off[t]; R.dht_nval[t] = pi.dht_nval[t]; }
             R.table_slot = table_slot_of(h, bits, offsets, i);
             for (int c = 0; c < 3; c++) R.dqt_off[c] = pi.dqt_off[c];
@@ -219,10 +230,25 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
             }
         }
         if (R.status == PREP_OK) {
+            // Region of interest of the reconstruction, in groups of MCUs: the whole MCU grid,
+            // or the MCUs whose pixels the crop window's bilinear taps read.
+            const int per = recon_mcus_per_group(I.sampling);
+            const int mcu_px = I.sampling == PREP_SAMPLING_420 ? 16 : 8;
+            int x_lo = 0, x_hi = I.width - 1, y_lo = 0, y_hi = I.height - 1;
+            if (!(h->cfg.flags & PREP_FLAG_FULL_RGB)) {
+                tap_span(Z.off_x, Z.scale_x, params->crop_w, I.width, &x_lo, &x_hi);
+                tap_span(Z.off_y, Z.scale_y, params->crop_h, I.height, &y_lo, &y_hi);
+            }
+            R.roi_row0 = (uint16_t)(y_lo / mcu_px);
+            R.roi_rows = (uint16_t)(y_hi / mcu_px - y_lo / mcu_px + 1);
+            R.roi_gcol0 = (uint16_t)(x_lo / mcu_px / per);
+            R.roi_gcols = (uint16_t)(x_hi / mcu_px / per - x_lo / mcu_px / per + 1);
+        }
+        if (R.status == PREP_OK) {
             const uint64_t rows = (uint64_t)R.mcu_rows * 8u * (R.sampling == PREP_SAMPLING_420 ? 2 : 1);
             P.n_blocks += R.n_blocks;
             P.rgb_bytes += ((uint64_t)R.rgb_pitch * rows + kRgbSlack + kRgbAlign - 1) / kRgbAlign * kRgbAlign;
-            P.n_groups += R.groups_per_row * R.mcu_rows;
+            P.n_groups += (uint32_t)R.roi_gcols * R.roi_rows;
         }
         P.n_windows += R.n_windows;
     }
@@ -234,7 +260,7 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
         ImageRec &R = h->recs[(size_t)i];
         R.group0 = P.recon_wgs;
         if (R.status == PREP_OK)
-            P.recon_wgs += (R.groups_per_row * R.mcu_rows + P.groups_per_wg - 1) / P.groups_per_wg;
+            P.recon_wgs += ((uint32_t)R.roi_gcols * R.roi_rows + P.groups_per_wg - 1) / P.groups_per_wg;
     }
     if (P.n_blocks > h->cap_blocks || P.rgb_bytes > h->cap_rgb || P.n_windows > h->cap_windows)
         return PREP_E_TOO_LARGE;
@@ -268,7 +294,8 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
     Plan P;
     // offsets are taken relative to the first file so that a batch may start anywhere
     const uint8_t *base_host = bits_host + offsets[0];
-    std::vector<uint64_t> rel((size_t)n + 1);
+    std::vector<uint64_t> &rel = h->rel;
+    rel.resize((size_t)n + 1);
     for (int32_t i = 0; i <= n; i++) {
         if (offsets[i] < offsets[0]) return PREP_E_INVALID_ARG;
         rel[(size_t)i] = offsets[i] - offsets[0];
@@ -351,7 +378,7 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     if (!cfg || cfg->max_batch < 1 || cfg->max_batch > 65535 || cfg->max_width < 1 ||
         cfg->max_height < 1 || cfg->max_width > 65535 || cfg->max_height > 65535 ||
         cfg->max_bitstream_bytes < 1 || cfg->max_bitstream_bytes > 0x7FFF0000ull ||
-        (cfg->flags & ~(uint32_t)PREP_FLAG_TABLES_PER_WORKGROUP) != 0)
+        (cfg->flags & ~(uint32_t)(PREP_FLAG_TABLES_PER_WORKGROUP | PREP_FLAG_FULL_RGB)) != 0)
         return PREP_E_INVALID_ARG;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) {
@@ -580,6 +607,20 @@ int64_t prep_debug_last_rgb(prep_handle *h, int32_t image, uint8_t *host_out_hwc
     HIP_TRY(hipMemcpy2D(host_out_hwc, row, h->d_rgb + R.rgb_off, R.rgb_pitch, row, R.height,
                         hipMemcpyDeviceToHost));
     return (int64_t)count;
+}
+
+int prep_debug_last_region(prep_handle *h, int32_t image, int32_t rect[4])
+{
+    if (!h || !rect || image < 0 || image >= h->last_n) return PREP_E_INVALID_ARG;
+    const ImageRec &R = h->recs[(size_t)image];
+    if (R.status != PREP_OK) return R.status;
+    const int mcu_px = R.sampling == PREP_SAMPLING_420 ? 16 : 8;
+    const int group_px = mcu_px * recon_mcus_per_group(R.sampling);
+    rect[0] = std::min<int>(R.roi_gcol0 * group_px, R.width);
+    rect[1] = std::min<int>(R.roi_row0 * mcu_px, R.height);
+    rect[2] = std::min<int>((R.roi_gcol0 + R.roi_gcols) * group_px, R.width);
+    rect[3] = std::min<int>((R.roi_row0 + R.roi_rows) * mcu_px, R.height);
+    return PREP_OK;
 }
 
 int prep_set_timing(prep_handle *h, int32_t enabled)

@@ -47,7 +47,11 @@ struct ImageRec {
     uint32_t n_windows;
     uint32_t rgb_pitch;     // bytes between RGB rows (covers the whole MCU grid)
     uint32_t group0;        // first reconstruction workgroup of this image
-    uint32_t groups_per_row;  // reconstruction workgroups per MCU row
+    // The groups (runs of MCUs of one MCU row) that reconstruction produces: MCU rows
+    // roi_row0 .. + roi_rows - 1, groups roi_gcol0 .. + roi_gcols - 1 of each.  It is what the
+    // bilinear taps of the crop window touch, or the whole MCU grid.
+    uint16_t roi_row0, roi_rows;
+    uint16_t roi_gcol0, roi_gcols;
     uint32_t dht_off[4];    // offset of BITS[16] of: DC luma, AC luma, DC chroma, AC chroma
     uint32_t dht_nval[4];   // number of HUFFVAL bytes that follow the 16 BITS bytes
     uint32_t dqt_off[3];    // offset of the 64 zig-zag ordered table bytes per component
@@ -58,7 +62,6 @@ struct ImageRec {
     uint8_t blocks_per_mcu;
     int32_t status;             // host verdict; kernels skip images that are not PREP_OK
     uint32_t table_slot;        // expanded Huffman tables of this image, or kNoTableSlot
-    uint32_t pad_;
 };
 static_assert(sizeof(ImageRec) % 8 == 0, "ImageRec must keep 8-byte alignment in arrays");
 

@@ -209,7 +209,11 @@ __device__ __forceinline__ void reconstruct_groups(ReconShared &S, const uint8_t
 #pragma unroll
     for (int v = 0; v < 8; v++) qcol[v] = qi[comp][(int)((pos >> (8 * v)) & 63u)];
 
-    uint32_t mrow = gi0 / R.groups_per_row, gcol = gi0 - mrow * R.groups_per_row;
+    // groups are numbered row by row inside the image's region of interest
+    const uint32_t gcol_end = (uint32_t)R.roi_gcol0 + R.roi_gcols;
+    uint32_t mrow = gi0 / R.roi_gcols, gcol = gi0 - mrow * R.roi_gcols;
+    mrow += R.roi_row0;
+    gcol += R.roi_gcol0;
     // the lane's eight coefficients of group (mrow, gcol), or zeros past the group's blocks
     auto fetch = [&](uint32_t row, uint32_t col) {
         const uint32_t x0 = col * per_group;
@@ -227,7 +231,7 @@ __device__ __forceinline__ void reconstruct_groups(ReconShared &S, const uint8_t
         __syncthreads();
         // next group of this workgroup, row by row
         uint32_t next_row = mrow, next_col = gcol + 1;
-        if (next_col == R.groups_per_row) { next_col = 0; next_row++; }
+        if (next_col == gcol_end) { next_col = R.roi_gcol0; next_row++; }
         // ---- columns: lane l gathers column u = l through the zig-zag (A.3.4), dequantises
         // and transforms it ----------------------------------------------------------------
         if (have) {
@@ -337,7 +341,7 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
     if (hits == 0) return;
     const ImageRec &R = recs[hits - 1];
     if (R.status != PREP_OK) return;
-    const uint32_t total = R.groups_per_row * (uint32_t)R.mcu_rows;
+    const uint32_t total = (uint32_t)R.roi_gcols * (uint32_t)R.roi_rows;
     const uint32_t gi0 = (wg - R.group0) * groups_per_wg;
     if (gi0 >= total) return;
     const uint32_t n = min(groups_per_wg, total - gi0);

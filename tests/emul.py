@@ -29,8 +29,9 @@ def build(force=False):
     return BINARY
 
 
-def run(streams, resize_short, crop_h, crop_w, out_dtype, mean, std, timeout=600):
-    """-> list of (status, coef [nb,64] or None, rgb flat or None), tensor [n,3,ch,cw]."""
+def run(streams, resize_short, crop_h, crop_w, out_dtype, mean, std, timeout=600, flags=0):
+    """-> list of (status, coef [nb,64] or None, rgb flat or None, rect), tensor [n,3,ch,cw];
+    rect = (x0, y0, x1, y1), the pixels of the image that were converted to RGB."""
     build()
     n = len(streams)
     offsets = np.zeros(n + 1, dtype=np.uint64)
@@ -43,7 +44,7 @@ def run(streams, resize_short, crop_h, crop_w, out_dtype, mean, std, timeout=600
             f.write(struct.pack("<6f", *mean, *std))
             f.write(offsets.tobytes())
             f.write(b"".join(streams))
-        env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0")
+        env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", PREP_EMUL_FLAGS=str(int(flags)))
         r = subprocess.run([BINARY, fin, fout], capture_output=True, text=True, timeout=timeout,
                            env=env)
         if os.environ.get("PREP_EMUL_VERBOSE") and r.stderr:
@@ -58,10 +59,11 @@ def run(streams, resize_short, crop_h, crop_w, out_dtype, mean, std, timeout=600
         nc, = struct.unpack_from("<q", blob, pos); pos += 8
         coef = np.frombuffer(blob, dtype=np.int16, count=nc, offset=pos).reshape(-1, 64) if nc else None
         pos += 2 * nc
+        rect = struct.unpack_from("<4i", blob, pos); pos += 16
         nr, = struct.unpack_from("<q", blob, pos); pos += 8
         rgb = np.frombuffer(blob, dtype=np.uint8, count=nr, offset=pos) if nr else None
         pos += nr
-        per_image.append((status, coef, rgb))
+        per_image.append((status, coef, rgb, rect))
     dt = np.float16 if f16 else np.float32
     tensor = np.frombuffer(blob, dtype=dt, offset=pos).reshape(n, 3, crop_h, crop_w)
     return per_image, tensor

@@ -15,6 +15,36 @@ RGB_EXACT_FRACTION = 0.999   # ... and at least 99.9 % of all values exact
 TENSOR_ABS_TOL = 0.02    # normalized tensor, absolute
 
 
+def tap_footprint(width, height, resize_short, crop_h, crop_w):
+    """(x_lo, y_lo, x_hi, y_hi), inclusive: the source pixels that count in the crop window's
+    outputs, from the mapping in exact rational arithmetic (pixel centres at half-integers,
+    per-axis scale in/out, taps floor(s) and floor(s) + 1 clamped to the image; the second tap
+    has weight zero where s is an integer)."""
+    from fractions import Fraction
+    ow, oh = oracle.resized_size(width, height, resize_short)
+    top, left = (oh - crop_h) // 2, (ow - crop_w) // 2
+
+    def span(size, out_size, first, count):
+        s_first = Fraction(2 * first + 1, 2) * Fraction(size, out_size) - Fraction(1, 2)
+        s_last = Fraction(2 * (first + count - 1) + 1, 2) * Fraction(size, out_size) - Fraction(1, 2)
+        lo = s_first.numerator // s_first.denominator
+        hi = s_last.numerator // s_last.denominator + (0 if s_last.denominator == 1 else 1)
+        return min(max(lo, 0), size - 1), min(max(hi, 0), size - 1)
+
+    x_lo, x_hi = span(width, ow, left, crop_w)
+    y_lo, y_hi = span(height, oh, top, crop_h)
+    return x_lo, y_lo, x_hi, y_hi
+
+
+def rgb_in_region(rect, got_rgb, ref_rgb, footprint):
+    """|got - ref| over the pixels that the library converted (rect = x0, y0, x1, y1), after
+    checking that they cover the crop window's taps."""
+    x0, y0, x1, y1 = rect
+    x_lo, y_lo, x_hi, y_hi = footprint
+    assert x0 <= x_lo and x_hi < x1 and y0 <= y_lo and y_hi < y1, (rect, footprint)
+    return np.abs(got_rgb[y0:y1, x0:x1].astype(np.int32) - ref_rgb[y0:y1, x0:x1].astype(np.int32))
+
+
 def oracle_batch(streams, resize_short, crop_h, crop_w, workers=8):
     """[(coef, rgb, info, tensor float64)] for every stream, computed by the oracle."""
     def one(s):
@@ -55,7 +85,8 @@ def check_against_oracle(pp, streams, resize_short, crop_h, crop_w, out_dtype, r
         if check_intermediates:
             mine = pp.debug_last_coefficients(i, coef.shape[0])
             assert np.array_equal(mine, coef), f"image {i}: entropy-decoded coefficients differ"
-            d = np.abs(pp.debug_last_rgb(i, info.height, info.width).astype(np.int32) - rgb.astype(np.int32))
+            d = rgb_in_region(pp.debug_last_region(i), pp.debug_last_rgb(i, info.height, info.width), rgb,
+                              tap_footprint(info.width, info.height, resize_short, crop_h, crop_w))
             assert d.max() <= RGB_MAX_LSB, f"image {i}: RGB off by {d.max()} LSB"
             n_values += d.size
             n_exact += int((d == 0).sum())

@@ -49,6 +49,7 @@ int main(int argc, char **argv)
         }
     cfg.max_total_pixels = px ? px : 1;
     cfg.max_bitstream_bytes = off[n] ? off[n] : 1;
+    if (const char *f = getenv("PREP_EMUL_FLAGS")) cfg.flags = (uint32_t)atoi(f);
     prep_handle *h = nullptr;
     rc = prep_create(&h, &cfg);
     if (rc) die("prep_create", rc);
@@ -65,6 +66,7 @@ int main(int argc, char **argv)
     for (int32_t i = 0; i < n; i++) {
         fwrite(&status[i], 4, 1, o);
         int64_t nc = 0, nr = 0;
+        int32_t rect[4] = {0, 0, 0, 0};
         std::vector<int16_t> coef;
         std::vector<uint8_t> rgb;
         if (status[i] == PREP_OK || status[i] == PREP_E_CORRUPT) {
@@ -75,10 +77,12 @@ int main(int argc, char **argv)
                 nr = prep_debug_last_rgb(h, i, rgb.data(), rgb.size());
                 if (nc < 0) nc = 0;
                 if (nr < 0) nr = 0;
+                if (nr && prep_debug_last_region(h, i, rect) != PREP_OK) nr = 0;
             }
         }
         fwrite(&nc, 8, 1, o);
         if (nc) fwrite(coef.data(), 2, (size_t)nc, o);
+        fwrite(rect, 4, 4, o);
         fwrite(&nr, 8, 1, o);
         if (nr) fwrite(rgb.data(), 1, (size_t)nr, o);
     }

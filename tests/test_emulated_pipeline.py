@@ -20,10 +20,10 @@ def _img(seed, w, h, sigma=12.0):
     return synth.gradient_noise_image(np.random.default_rng(seed), w, h, sigma)
 
 
-def _check(streams, rs, ch, cw, dt, expect_status=None):
-    per, ten = emul.run(streams, rs, ch, cw, dt, MEAN, STD)
+def _check(streams, rs, ch, cw, dt, expect_status=None, flags=0):
+    per, ten = emul.run(streams, rs, ch, cw, dt, MEAN, STD, flags=flags)
     for i, s in enumerate(streams):
-        status, coef, rgb = per[i]
+        status, coef, rgb, rect = per[i]
         if expect_status and expect_status[i] != 0:
             assert status == expect_status[i]
             assert (ten[i] == 0).all()
@@ -31,7 +31,10 @@ def _check(streams, rs, ch, cw, dt, expect_status=None):
         assert status == 0, f"image {i}: status {status}"
         c0, r0, info = oracle.decode(s)
         assert np.array_equal(coef, c0), f"image {i}: coefficients differ"
-        d = np.abs(rgb.reshape(r0.shape).astype(int) - r0.astype(int))
+        if flags & 2:
+            assert rect == (0, 0, info.width, info.height)
+        d = helpers.rgb_in_region(rect, rgb.reshape(r0.shape), r0,
+                                  helpers.tap_footprint(info.width, info.height, rs, ch, cw))
         assert d.max() <= 1 and (d == 0).mean() >= 0.999, f"image {i}: rgb"
         ref = oracle.preprocess(r0, rs, ch, cw, MEAN, STD)
         assert np.abs(ten[i].astype(np.float64) - ref).max() <= 0.02, f"image {i}: tensor"
@@ -44,7 +47,7 @@ def test_modes_restart_intervals_and_odd_sizes():
             cols = -(-w // (16 if mode == MODE_420 else 8))
             for dri in (0, 1, cols):
                 streams.append(oracle.encode(_img(10 + k, w, h), 88, mode, dri, table_mode=k % 2)[0])
-    _check(streams, 0, 1, 1, "f32")
+    _check(streams, 0, 1, 1, "f32", flags=2)  # whole images are converted to RGB and compared
 
 
 def test_pillow_streams_of_workloads_1_and_5():

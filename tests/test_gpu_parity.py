@@ -5,7 +5,8 @@ import pytest
 
 import oracle
 import synth
-from helpers import MEAN, STD, TENSOR_ABS_TOL, check_against_oracle, oracle_batch, run_gpu
+from helpers import (MEAN, STD, TENSOR_ABS_TOL, check_against_oracle, oracle_batch, rgb_in_region, run_gpu,
+                     tap_footprint)
 from oracle import MODE_420, MODE_444, MODE_GRAY
 
 pytestmark = pytest.mark.gpu
@@ -17,10 +18,13 @@ def prep():
     return p
 
 
-@pytest.fixture(scope="module")
-def pp(prep):
+# every test that takes `pp` runs twice: with the default handle, which converts to RGB only
+# the MCUs that the crop window reads, and with one that converts whole images
+@pytest.fixture(scope="module", params=[0, 2], ids=["crop-region", "full-rgb"])
+def pp(prep, request):
+    assert prep.FLAG_FULL_RGB == 2
     h = prep.Preprocessor(device=0, max_batch=64, max_width=2048, max_height=1200,
-                          max_bitstream_bytes=48 << 20, max_total_pixels=24 << 20)
+                          max_bitstream_bytes=48 << 20, max_total_pixels=24 << 20, flags=request.param)
     yield h
     h.close()
 
@@ -224,7 +228,8 @@ def test_reconstruct_stage_alone_on_oracle_coefficients(pp):
     assert pp.get_status(len(streams)) == [0] * len(streams)
     got = out.cpu().numpy().astype(np.float64)
     for i, (_, rgb, info, ten) in enumerate(ref):
-        d = np.abs(pp.debug_last_rgb(i, info.height, info.width).astype(int) - rgb.astype(int))
+        d = rgb_in_region(pp.debug_last_region(i), pp.debug_last_rgb(i, info.height, info.width), rgb,
+                          tap_footprint(info.width, info.height, 256, 224, 224))
         assert d.max() <= 1 and (d == 0).mean() >= 0.999
         assert np.abs(got[i] - ten).max() <= 0.02
 
@@ -365,7 +370,8 @@ def _full_batch_sampled(prep, config, sample):
         ref = oracle_batch([streams[i] for i in picks], pr["resize_short"], pr["crop_h"], pr["crop_w"])
         for i, (coef, rgb, info, ten) in zip(picks, ref):
             assert np.array_equal(h.debug_last_coefficients(i, coef.shape[0]), coef), f"image {i}: coefficients"
-            d = np.abs(h.debug_last_rgb(i, info.height, info.width).astype(np.int32) - rgb.astype(np.int32))
+            d = rgb_in_region(h.debug_last_region(i), h.debug_last_rgb(i, info.height, info.width), rgb,
+                              tap_footprint(info.width, info.height, pr["resize_short"], pr["crop_h"], pr["crop_w"]))
             assert d.max() <= 1 and (d == 0).mean() >= 0.999, f"image {i}: rgb"
             err = np.abs(got[i] - ten).max()
             assert err <= TENSOR_ABS_TOL, f"image {i}: tensor off by {err}"
