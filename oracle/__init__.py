@@ -15,7 +15,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SOURCES = ["transforms.c", "huffman.c", "jpeg_encode.c", "jpeg_decode.c"]
 LIB_PATH = os.path.join(_HERE, "liboracle.so")
 
-MODE_444, MODE_420, MODE_GRAY = 0, 1, 2
+MODE_444, MODE_420, MODE_GRAY, MODE_422, MODE_440 = 0, 1, 2, 3, 4
+# luma sampling factors (horizontal, vertical) and blocks per MCU of each mode
+MODE_GEOMETRY = {MODE_444: (1, 1, 3), MODE_420: (2, 2, 6), MODE_GRAY: (1, 1, 1), MODE_422: (2, 1, 4),
+                 MODE_440: (1, 2, 4)}
 OK, E_ARG, E_CORRUPT, E_UNSUPPORTED = 0, -1, -2, -3
 
 
@@ -169,9 +172,8 @@ def forward_blocks(rgb, mode, qluma, qchroma):
     h, w, _ = rgb.shape
     qluma = np.ascontiguousarray(qluma, dtype=np.uint16)
     qchroma = np.ascontiguousarray(qchroma, dtype=np.uint16)
-    hmax = 2 if mode == MODE_420 else 1
-    bpm = {MODE_444: 3, MODE_420: 6, MODE_GRAY: 1}[mode]
-    nb = -(-w // (8 * hmax)) * -(-h // (8 * hmax)) * bpm
+    hmax, vmax, bpm = MODE_GEOMETRY[mode]
+    nb = -(-w // (8 * hmax)) * -(-h // (8 * vmax)) * bpm
     coef = np.zeros((nb, 64), dtype=np.int16)
     info = Info()
     rc = lib().oracle_forward_blocks(_p(rgb, C.c_uint8), w, h, mode, _p(qluma, C.c_uint16),

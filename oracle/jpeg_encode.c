@@ -16,7 +16,10 @@ static void geometry(int w, int h, int mode, oracle_info *g)
     g->height = h;
     g->ncomp = mode == ORACLE_GRAY ? 1 : 3;
     for (int c = 0; c < 3; c++) g->hs[c] = g->vs[c] = 1;
+    /* luma sampling factors (T.81 A.1.1); the chroma components are 1 x 1 */
     if (mode == ORACLE_420) g->hs[0] = g->vs[0] = 2;
+    if (mode == ORACLE_422) g->hs[0] = 2;
+    if (mode == ORACLE_440) g->vs[0] = 2;
     g->hmax = g->hs[0];
     g->vmax = g->vs[0];
     g->mcu_cols = (w + 8 * g->hmax - 1) / (8 * g->hmax);
@@ -37,7 +40,7 @@ int oracle_forward_blocks(const uint8_t *rgb, int w, int h, int mode,
                           const uint16_t qluma[64], const uint16_t qchroma[64],
                           int16_t *coef, size_t coef_cap, oracle_info *info)
 {
-    if (!rgb || !coef || w < 1 || h < 1 || mode < 0 || mode > 2) return ORACLE_E_ARG;
+    if (!rgb || !coef || w < 1 || h < 1 || mode < 0 || mode > ORACLE_440) return ORACLE_E_ARG;
     oracle_info g;
     geometry(w, h, mode, &g);
     if (coef_cap < (size_t)g.nblocks * 64) return ORACLE_E_ARG;
@@ -257,7 +260,7 @@ int64_t oracle_write_jpeg(const int16_t *coef, int w, int h, int mode,
                           const uint16_t qluma[64], const uint16_t qchroma[64],
                           int dri, int table_mode, uint8_t *out, size_t cap)
 {
-    if (!coef || !out || w < 1 || h < 1 || w > 65535 || h > 65535 || mode < 0 || mode > 2 ||
+    if (!coef || !out || w < 1 || h < 1 || w > 65535 || h > 65535 || mode < 0 || mode > ORACLE_440 ||
         dri < 0 || dri > 65535)
         return ORACLE_E_ARG;
     oracle_info g;

@@ -28,7 +28,7 @@ enum {
     ORACLE_E_UNSUPPORTED = -3 /* valid JPEG outside the baseline subset   */
 };
 
-enum { ORACLE_444 = 0, ORACLE_420 = 1, ORACLE_GRAY = 2 };
+enum { ORACLE_444 = 0, ORACLE_420 = 1, ORACLE_GRAY = 2, ORACLE_422 = 3, ORACLE_440 = 4 };
 
 typedef struct {
     int32_t width, height;        /* SOF0 X, Y                             */
@@ -89,7 +89,8 @@ void oracle_quant_table(int quality, int chroma, uint16_t q[64]);
 /* RGB8 HWC -> quantised coefficients in scan order (MCU by MCU; inside an
  * MCU the components in order, each V_i rows x H_i columns of blocks), 64
  * int16 per block in zig-zag order, DC stored as the absolute value.
- * mode: ORACLE_444 / ORACLE_420 / ORACLE_GRAY (gray = luma of the RGB).
+ * mode: ORACLE_444 / ORACLE_420 / ORACLE_GRAY (gray = luma of the RGB) / ORACLE_422 (luma
+ * 2 x 1: chroma halved horizontally) / ORACLE_440 (luma 1 x 2: chroma halved vertically).
  * qluma/qchroma natural order.  coef must hold info->nblocks*64 entries.   */
 int oracle_forward_blocks(const uint8_t *rgb, int w, int h, int mode,
                           const uint16_t qluma[64], const uint16_t qchroma[64],

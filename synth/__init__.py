@@ -16,7 +16,7 @@ import io
 
 import numpy as np
 
-MODE_444, MODE_420, MODE_GRAY = 0, 1, 2
+MODE_444, MODE_420, MODE_GRAY, MODE_422 = 0, 1, 2, 3
 
 IMAGENET_MEAN = (0.485, 0.456, 0.406)
 IMAGENET_STD = (0.229, 0.224, 0.225)
@@ -75,7 +75,7 @@ def encode_jpeg(rgb, quality, mode, restart_blocks=0, restart_rows=0, optimize=F
     if mode == MODE_GRAY:
         im = im.convert("L")
     else:
-        kw["subsampling"] = 0 if mode == MODE_444 else 2
+        kw["subsampling"] = {MODE_444: 0, MODE_422: 1, MODE_420: 2}[mode]
     buf = io.BytesIO()
     im.save(buf, "JPEG", **kw)
     return buf.getvalue()

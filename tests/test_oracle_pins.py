@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import MODE_420, MODE_444, MODE_GRAY
+from oracle import MODE_420, MODE_422, MODE_440, MODE_444, MODE_GRAY
 
 MEAN = (0.485, 0.456, 0.406)
 STD = (0.229, 0.224, 0.225)
@@ -224,12 +224,12 @@ def test_colour_known_values_and_roundtrip():
 SIZES = [(1, 1), (7, 9), (17, 33), (64, 48), (300, 251)]
 
 
-@pytest.mark.parametrize("mode", [MODE_444, MODE_420, MODE_GRAY])
+@pytest.mark.parametrize("mode", [MODE_444, MODE_420, MODE_GRAY, MODE_422, MODE_440])
 @pytest.mark.parametrize("size", SIZES)
 def test_roundtrip_recovers_quantised_coefficients(mode, size):
     w, h = size
     rgb = _noise_image(100 + w + h + mode, w, h)
-    hmax = 2 if mode == MODE_420 else 1
+    hmax = oracle.MODE_GEOMETRY[mode][0]
     mcu_cols = -(-w // (8 * hmax))
     for dri in (0, 1, mcu_cols, 8):
         for table_mode in (0, 1):
@@ -349,6 +349,43 @@ def test_pillow_decodes_oracle_files_to_nearly_the_same_pixels(mode):
         assert diff.max() <= (1 if mode == MODE_GRAY else 3) and diff.mean() < 0.3
 
 
+@pytest.mark.parametrize("mode", [MODE_422, MODE_440])
+def test_pillow_decodes_oracle_422_and_440_files(mode):
+    rgb = _noise_image(15, 90, 70, sigma=3.0)
+    data, _ = oracle.encode(rgb, quality=92, mode=mode, dri=4)
+    _, mine, info = oracle.decode(data, want_coef=False)
+    assert (info.hs[0], info.vs[0], info.blocks_per_mcu) == oracle.MODE_GEOMETRY[mode]
+    theirs = _pil_decode(data)  # libjpeg interpolates chroma where this decoder replicates it
+    assert np.abs(mine.astype(int) - theirs.astype(int)).mean() < 1.5
+    assert np.abs(mine.astype(int) - rgb.astype(int)).mean() < 6.0
+
+
+@pytest.mark.parametrize("mode", [MODE_422, MODE_440])
+def test_chroma_pairs_start_at_even_positions(mode):
+    # Colour stripes two pixels wide across the halved axis lose nothing when they start at even
+    # positions (each chroma sample covers one stripe) and are smeared when they start at odd
+    # ones.  The axis itself is pinned by Pillow, which reads the sampling factors from the
+    # frame header (the tests above and below).
+    rng = np.random.default_rng(16)
+    colours = rng.integers(40, 216, size=(24, 3)).astype(np.uint8)
+    stripes = np.repeat(colours, 2, axis=0)                      # 48 lines, 2 alike in a row
+    if mode == MODE_422:
+        good = np.broadcast_to(stripes[None, :, :], (32, 48, 3)).copy()   # varies along x
+        bad = np.roll(good, 1, axis=1)
+    else:
+        good = np.broadcast_to(stripes[:, None, :], (48, 32, 3)).copy()   # varies along y
+        bad = np.roll(good, 1, axis=0)
+    one = np.ones(64, dtype=np.uint16)  # no quantisation loss beyond rounding
+
+    def error(rgb):
+        coef, info = oracle.forward_blocks(rgb, mode, one, one)
+        data = oracle.write_jpeg(coef, info.width, info.height, mode, one, one)
+        return np.abs(oracle.decode(data, want_coef=False)[1].astype(int) - rgb.astype(int))
+
+    assert error(good).max() <= 3
+    assert error(bad).mean() > 5
+
+
 def test_pillow_decodes_oracle_420_file():
     rgb = _noise_image(12, 80, 64, sigma=3.0)
     data, _ = oracle.encode(rgb, quality=92, mode=MODE_420, dri=5)
@@ -358,7 +395,7 @@ def test_pillow_decodes_oracle_420_file():
     assert np.abs(mine.astype(int) - rgb.astype(int)).mean() < 6.0
 
 
-@pytest.mark.parametrize("mode", [MODE_444, MODE_420, MODE_GRAY])
+@pytest.mark.parametrize("mode", [MODE_444, MODE_420, MODE_GRAY, MODE_422])
 def test_oracle_decodes_pillow_files(mode):
     import synth
     rgb = _noise_image(13, 101, 77, sigma=6.0)
@@ -367,7 +404,7 @@ def test_oracle_decodes_pillow_files(mode):
         _, mine, info = oracle.decode(data, want_coef=False)
         theirs = _pil_decode(data)
         diff = np.abs(mine.astype(int) - theirs.astype(int))
-        if mode == MODE_420:
+        if mode in (MODE_420, MODE_422):
             assert diff.mean() < 1.5
         else:
             assert diff.max() <= (1 if mode == MODE_GRAY else 3) and diff.mean() < 0.3
