@@ -57,7 +57,10 @@ enum { PREP_F32 = 0, PREP_F16 = 1 };
  *   decoded image either, section 4.2), and prep_debug_last_rgb returns what the workspace
  *   holds outside those MCUs. */
 enum { PREP_FLAG_TABLES_PER_WORKGROUP = 1, PREP_FLAG_FULL_RGB = 2 };
-enum { PREP_SAMPLING_444 = 0, PREP_SAMPLING_420 = 1, PREP_SAMPLING_GRAY = 2 };
+/* luma sampling factors H x V (chroma is 1 x 1): 4:4:4 = 1 x 1, 4:2:0 = 2 x 2, 4:2:2 = 2 x 1,
+ * 4:4:0 = 1 x 2; GRAY = one component */
+enum { PREP_SAMPLING_444 = 0, PREP_SAMPLING_420 = 1, PREP_SAMPLING_GRAY = 2, PREP_SAMPLING_422 = 3,
+       PREP_SAMPLING_440 = 4 };
 
 typedef struct prep_handle prep_handle;
 

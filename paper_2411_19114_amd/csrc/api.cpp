@@ -207,7 +207,7 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
         R.status = I.status;
         R.n_windows = 1;
         if (I.status == PREP_OK) {
-            const int hs = I.sampling == PREP_SAMPLING_420 ? 2 : 1;
+            const int hs = luma_h(I.sampling);
             R.entropy_rel = (uint32_t)I.entropy_offset;
             R.entropy_len = (uint32_t)I.entropy_bytes;
             R.n_blocks = (uint32_t)((uint64_t)I.mcu_cols * I.mcu_rows * I.blocks_per_mcu);
@@ -233,19 +233,19 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
             // Region of interest of the reconstruction, in groups of MCUs: the whole MCU grid,
             // or the MCUs whose pixels the crop window's bilinear taps read.
             const int per = recon_mcus_per_group(I.sampling);
-            const int mcu_px = I.sampling == PREP_SAMPLING_420 ? 16 : 8;
+            const int mcu_w = 8 * luma_h(I.sampling), mcu_h = 8 * luma_v(I.sampling);
             int x_lo = 0, x_hi = I.width - 1, y_lo = 0, y_hi = I.height - 1;
             if (!(h->cfg.flags & PREP_FLAG_FULL_RGB)) {
                 tap_span(Z.off_x, Z.scale_x, params->crop_w, I.width, &x_lo, &x_hi);
                 tap_span(Z.off_y, Z.scale_y, params->crop_h, I.height, &y_lo, &y_hi);
             }
-            R.roi_row0 = (uint16_t)(y_lo / mcu_px);
-            R.roi_rows = (uint16_t)(y_hi / mcu_px - y_lo / mcu_px + 1);
-            R.roi_gcol0 = (uint16_t)(x_lo / mcu_px / per);
-            R.roi_gcols = (uint16_t)(x_hi / mcu_px / per - x_lo / mcu_px / per + 1);
+            R.roi_row0 = (uint16_t)(y_lo / mcu_h);
+            R.roi_rows = (uint16_t)(y_hi / mcu_h - y_lo / mcu_h + 1);
+            R.roi_gcol0 = (uint16_t)(x_lo / mcu_w / per);
+            R.roi_gcols = (uint16_t)(x_hi / mcu_w / per - x_lo / mcu_w / per + 1);
         }
         if (R.status == PREP_OK) {
-            const uint64_t rows = (uint64_t)R.mcu_rows * 8u * (R.sampling == PREP_SAMPLING_420 ? 2 : 1);
+            const uint64_t rows = (uint64_t)R.mcu_rows * 8u * (uint32_t)luma_v(R.sampling);
             P.n_blocks += R.n_blocks;
             P.rgb_bytes += ((uint64_t)R.rgb_pitch * rows + kRgbSlack + kRgbAlign - 1) / kRgbAlign * kRgbAlign;
             P.n_groups += (uint32_t)R.roi_gcols * R.roi_rows;
@@ -614,12 +614,12 @@ int prep_debug_last_region(prep_handle *h, int32_t image, int32_t rect[4])
     if (!h || !rect || image < 0 || image >= h->last_n) return PREP_E_INVALID_ARG;
     const ImageRec &R = h->recs[(size_t)image];
     if (R.status != PREP_OK) return R.status;
-    const int mcu_px = R.sampling == PREP_SAMPLING_420 ? 16 : 8;
-    const int group_px = mcu_px * recon_mcus_per_group(R.sampling);
+    const int mcu_h = 8 * luma_v(R.sampling);
+    const int group_px = 8 * luma_h(R.sampling) * recon_mcus_per_group(R.sampling);
     rect[0] = std::min<int>(R.roi_gcol0 * group_px, R.width);
-    rect[1] = std::min<int>(R.roi_row0 * mcu_px, R.height);
+    rect[1] = std::min<int>(R.roi_row0 * mcu_h, R.height);
     rect[2] = std::min<int>((R.roi_gcol0 + R.roi_gcols) * group_px, R.width);
-    rect[3] = std::min<int>((R.roi_row0 + R.roi_rows) * mcu_px, R.height);
+    rect[3] = std::min<int>((R.roi_row0 + R.roi_rows) * mcu_h, R.height);
     return PREP_OK;
 }
 

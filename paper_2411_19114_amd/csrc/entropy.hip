@@ -827,7 +827,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
 
     Geometry g;
     g.bpm = R.blocks_per_mcu;
-    g.n_luma = R.sampling == PREP_SAMPLING_420 ? 4u : 1u;
+    g.n_luma = (uint32_t)(luma_h(R.sampling) * luma_v(R.sampling));
     g.ri_blocks = (uint32_t)R.restart_interval * g.bpm;
     g.n_blocks = R.n_blocks;
 

@@ -6,6 +6,8 @@
 
 #include <string.h>
 
+#include "prep_internal.h"
+
 namespace prep {
 
 namespace {
@@ -105,17 +107,17 @@ int parse_image(const uint8_t *d, uint64_t len, ParsedImage *out)
             if (ncomp == 1) {
                 I.sampling = PREP_SAMPLING_GRAY;  // A.2.2: one component is never interleaved
             } else if (comp_h[1] == 1 && comp_v[1] == 1 && comp_h[2] == 1 && comp_v[2] == 1 &&
-                       comp_h[0] == comp_v[0] && (comp_h[0] == 1 || comp_h[0] == 2)) {
-                I.sampling = comp_h[0] == 1 ? PREP_SAMPLING_444 : PREP_SAMPLING_420;
+                       comp_h[0] <= 2 && comp_v[0] <= 2) {
+                I.sampling = comp_h[0] == 1 ? (comp_v[0] == 1 ? PREP_SAMPLING_444 : PREP_SAMPLING_440)
+                                            : (comp_v[0] == 1 ? PREP_SAMPLING_422 : PREP_SAMPLING_420);
             } else {
                 I.status = PREP_E_UNSUPPORTED;
                 return I.status;
             }
-            const int mcu = I.sampling == PREP_SAMPLING_420 ? 16 : 8;
-            I.mcu_cols = (I.width + mcu - 1) / mcu;
-            I.mcu_rows = (I.height + mcu - 1) / mcu;
-            I.blocks_per_mcu = I.sampling == PREP_SAMPLING_GRAY ? 1
-                               : I.sampling == PREP_SAMPLING_444 ? 3 : 6;
+            const int mcu_w = 8 * luma_h(I.sampling), mcu_h = 8 * luma_v(I.sampling);
+            I.mcu_cols = (I.width + mcu_w - 1) / mcu_w;
+            I.mcu_rows = (I.height + mcu_h - 1) / mcu_h;
+            I.blocks_per_mcu = blocks_per_mcu_of(I.sampling);
             have_frame = true;
         } else if (m >= 0xC1 && m <= 0xCF && m != 0xC8) {
             I.status = PREP_E_UNSUPPORTED;  // extended, progressive, lossless, arithmetic

@@ -23,11 +23,19 @@ constexpr uint32_t kMaxTableSlots = 1024;
 constexpr uint32_t kNoTableSlot = 0xFFFFFFFFu;             // expand the tables in the workgroup
 
 // ---- reconstruction geometry ----------------------------------------------
+// Sampling modes (the PREP_SAMPLING_* values): luma blocks per MCU along x and y (T.81
+// A.1.1, chroma is 1 x 1) and blocks per MCU (A.2.3).
+inline constexpr int luma_h(int sampling) { return sampling == 1 || sampling == 3 ? 2 : 1; }
+inline constexpr int luma_v(int sampling) { return sampling == 1 || sampling == 4 ? 2 : 1; }
+inline constexpr int blocks_per_mcu_of(int sampling)
+{
+    return sampling == 2 ? 1 : luma_h(sampling) * luma_v(sampling) + 2;
+}
 // One workgroup turns kReconBlocks 8x8 blocks (a run of MCUs of one MCU row)
-// into RGB pixels: 5 MCUs of 4:2:0, 10 of 4:4:4, 32 of grayscale.
+// into RGB pixels: 5 MCUs of 4:2:0, 10 of 4:4:4, 8 of 4:2:2 or 4:4:0, 32 of grayscale.
 constexpr int kReconThreads = 256;
 constexpr int kReconBlocks = 32;
-inline constexpr int recon_mcus_per_group(int sampling) { return sampling == 1 ? 5 : sampling == 0 ? 10 : 32; }
+inline constexpr int recon_mcus_per_group(int sampling) { return kReconBlocks / blocks_per_mcu_of(sampling); }
 // A workgroup takes up to kReconMaxGroupsPerWg consecutive groups of one image: as many as
 // leave about kReconGroupsPerWgDivisor workgroups in the launch (two rounds of a full chip).
 constexpr uint32_t kReconMaxGroupsPerWg = 8;

@@ -187,10 +187,12 @@ __device__ __forceinline__ void reconstruct_groups(ReconShared &S, const uint8_t
     uint32_t *luma = S.luma;
     uint32_t (*chroma)[8 * kChromaPitch / 4] = S.chroma;
     const int tid = threadIdx.x;
-    constexpr int bpm = sampling == PREP_SAMPLING_420 ? 6 : sampling == PREP_SAMPLING_444 ? 3 : 1;
-    constexpr int hs = sampling == PREP_SAMPLING_420 ? 2 : 1;  // luma blocks per MCU per axis
-    constexpr int n_luma = hs * hs;
+    constexpr int bpm = blocks_per_mcu_of(sampling);
+    constexpr int hs = luma_h(sampling), vs = luma_v(sampling);  // luma blocks per MCU along x, y
+    constexpr int n_luma = hs * vs;
     constexpr int per_group = recon_mcus_per_group(sampling);
+    static_assert(per_group * 8 * hs <= kLumaPitch && 8 * vs <= 16, "a group's luma fits its plane");
+    static_assert(bpm == 1 || per_group * 8 <= kChromaPitch, "a group's chroma fits its plane");
 
     const uint8_t *file = bits + R.file_off;
     if (tid < 192) qi[tid >> 6][tid & 63] = (int32_t)file[R.dqt_off[tid >> 6] + (tid & 63)];
@@ -262,7 +264,7 @@ __device__ __forceinline__ void reconstruct_groups(ReconShared &S, const uint8_t
                 pk[x >> 2] |= (uint32_t)min(max(sample, 0), 255) << (8 * (x & 3));
             }
             if (comp == 0) {
-                const int bx = blk & (hs - 1), by = hs == 2 ? blk >> 1 : 0;
+                const int bx = blk % hs, by = blk / hs;  // luma blocks of an MCU run row by row (A.2.3)
                 const int row = by * 8 + l, col = (mcu * hs + bx) * 8;
                 luma[(row * kLumaPitch + col) / 4] = pk[0];
                 luma[(row * kLumaPitch + col) / 4 + 1] = pk[1];
@@ -273,42 +275,40 @@ __device__ __forceinline__ void reconstruct_groups(ReconShared &S, const uint8_t
         }
         __syncthreads();
         // ---- colour ---------------------------------------------------------------------------
-        const int rows = 8 * hs, width = gcount * 8 * hs, quads = width >> 2;
+        const int rows = 8 * vs, width = gcount * 8 * hs, quads = width >> 2;
         uint8_t *dst0 = rgb_all + R.rgb_off + (size_t)mrow * rows * R.rgb_pitch +
                         (size_t)mcu_x0 * 8 * hs * 3;
-        if (sampling == PREP_SAMPLING_420) {
-            // an item is 4 x 2 pixels: two chroma samples serve it, so their terms are formed once
-            const int items = (rows >> 1) * quads;
-            const uint16_t *cb16 = reinterpret_cast<const uint16_t *>(chroma[0]);
-            const uint16_t *cr16 = reinterpret_cast<const uint16_t *>(chroma[1]);
-            for (int it = tid; it < items; it += kReconThreads) {
-                const int rp = it / quads, q = it - rp * quads;
-                const uint32_t cbp = cb16[(rp * kChromaPitch) / 2 + q], crp = cr16[(rp * kChromaPitch) / 2 + q];
-                const ChromaTerms t0 = chroma_terms(cbp & 255u, crp & 255u);
-                const ChromaTerms t1 = chroma_terms(cbp >> 8, crp >> 8);
-#pragma unroll
-                for (int r = 0; r < 2; r++) {
-                    const int row = 2 * rp + r;
-                    store_rgb4(dst0 + (size_t)row * R.rgb_pitch + q * 12, luma[(row * kLumaPitch) / 4 + q],
-                               t0, t0, t1, t1);
-                }
-            }
-        } else {
+        if (sampling == PREP_SAMPLING_GRAY) {
             // an item is 4 pixels of one row
             const int items = rows * quads;
             for (int it = tid; it < items; it += kReconThreads) {
                 const int row = it / quads, q = it - row * quads;
-                const uint32_t y4 = luma[(row * kLumaPitch) / 4 + q];
-                uint8_t *dst = dst0 + (size_t)row * R.rgb_pitch + q * 12;
-                if (sampling == PREP_SAMPLING_GRAY) {
-                    store_gray4(dst, y4);
+                store_gray4(dst0 + (size_t)row * R.rgb_pitch + q * 12, luma[(row * kLumaPitch) / 4 + q]);
+            }
+        } else {
+            // an item is 4 pixels of vs rows: the pixels that 4 / hs chroma samples of one chroma
+            // row serve, so the terms of a chroma sample are formed once for all of them
+            const int items = (rows / vs) * quads;
+            for (int it = tid; it < items; it += kReconThreads) {
+                const int rp = it / quads, q = it - rp * quads;
+                ChromaTerms t[4];
+                if (hs == 2) {
+                    const uint16_t *cb16 = reinterpret_cast<const uint16_t *>(chroma[0]);
+                    const uint16_t *cr16 = reinterpret_cast<const uint16_t *>(chroma[1]);
+                    const uint32_t cbp = cb16[(rp * kChromaPitch) / 2 + q], crp = cr16[(rp * kChromaPitch) / 2 + q];
+                    t[0] = t[1] = chroma_terms(cbp & 255u, crp & 255u);
+                    t[2] = t[3] = chroma_terms(cbp >> 8, crp >> 8);
                 } else {
-                    const uint32_t cb4 = chroma[0][(row * kChromaPitch) / 4 + q];
-                    const uint32_t cr4 = chroma[1][(row * kChromaPitch) / 4 + q];
-                    store_rgb4(dst, y4, chroma_terms(cb4 & 255u, cr4 & 255u),
-                               chroma_terms((cb4 >> 8) & 255u, (cr4 >> 8) & 255u),
-                               chroma_terms((cb4 >> 16) & 255u, (cr4 >> 16) & 255u),
-                               chroma_terms(cb4 >> 24, cr4 >> 24));
+                    const uint32_t cb4 = chroma[0][(rp * kChromaPitch) / 4 + q];
+                    const uint32_t cr4 = chroma[1][(rp * kChromaPitch) / 4 + q];
+#pragma unroll
+                    for (int j = 0; j < 4; j++) t[j] = chroma_terms((cb4 >> (8 * j)) & 255u, (cr4 >> (8 * j)) & 255u);
+                }
+#pragma unroll
+                for (int r = 0; r < vs; r++) {
+                    const int row = vs * rp + r;
+                    store_rgb4(dst0 + (size_t)row * R.rgb_pitch + q * 12, luma[(row * kLumaPitch) / 4 + q],
+                               t[0], t[1], t[2], t[3]);
                 }
             }
         }
@@ -349,6 +349,10 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
         reconstruct_groups<PREP_SAMPLING_420>(S, bits, R, gi0, n, coef_all, rgb_all);
     else if (R.sampling == PREP_SAMPLING_444)
         reconstruct_groups<PREP_SAMPLING_444>(S, bits, R, gi0, n, coef_all, rgb_all);
+    else if (R.sampling == PREP_SAMPLING_422)
+        reconstruct_groups<PREP_SAMPLING_422>(S, bits, R, gi0, n, coef_all, rgb_all);
+    else if (R.sampling == PREP_SAMPLING_440)
+        reconstruct_groups<PREP_SAMPLING_440>(S, bits, R, gi0, n, coef_all, rgb_all);
     else
         reconstruct_groups<PREP_SAMPLING_GRAY>(S, bits, R, gi0, n, coef_all, rgb_all);
 }

@@ -11,7 +11,7 @@ import emul
 import helpers
 import oracle
 import synth
-from oracle import MODE_420, MODE_444, MODE_GRAY
+from oracle import MODE_420, MODE_422, MODE_440, MODE_444, MODE_GRAY
 
 MEAN, STD = synth.IMAGENET_MEAN, synth.IMAGENET_STD
 
@@ -43,8 +43,8 @@ def _check(streams, rs, ch, cw, dt, expect_status=None, flags=0):
 def test_modes_restart_intervals_and_odd_sizes():
     streams = []
     for k, (w, h) in enumerate([(1, 1), (17, 33), (70, 45)]):
-        for mode in (MODE_444, MODE_420, MODE_GRAY):
-            cols = -(-w // (16 if mode == MODE_420 else 8))
+        for mode in (MODE_444, MODE_420, MODE_GRAY, MODE_422, MODE_440):
+            cols = -(-w // (8 * oracle.MODE_GEOMETRY[mode][0]))
             for dri in (0, 1, cols):
                 streams.append(oracle.encode(_img(10 + k, w, h), 88, mode, dri, table_mode=k % 2)[0])
     _check(streams, 0, 1, 1, "f32", flags=2)  # whole images are converted to RGB and compared

@@ -7,7 +7,7 @@ import oracle
 import synth
 from helpers import (MEAN, STD, TENSOR_ABS_TOL, check_against_oracle, oracle_batch, rgb_in_region, run_gpu,
                      tap_footprint)
-from oracle import MODE_420, MODE_444, MODE_GRAY
+from oracle import MODE_420, MODE_422, MODE_440, MODE_444, MODE_GRAY
 
 pytestmark = pytest.mark.gpu
 
@@ -46,16 +46,27 @@ def test_workload_4_full_hd(pp):
     check_against_oracle(pp, synth.make_batch(4, 2), r["resize_short"], r["crop"], r["crop"], "f16")
 
 
-@pytest.mark.parametrize("mode", [MODE_444, MODE_420, MODE_GRAY])
+@pytest.mark.parametrize("mode", [MODE_444, MODE_420, MODE_GRAY, MODE_422, MODE_440])
 def test_odd_sizes_and_restart_intervals(pp, mode):
     streams = []
     for k, (w, h) in enumerate([(1, 1), (7, 9), (17, 33), (64, 48), (300, 251)]):
         rgb = _img(200 + k + mode, w, h)
-        cols = -(-w // (16 if mode == MODE_420 else 8))
+        cols = -(-w // (8 * oracle.MODE_GEOMETRY[mode][0]))
         for dri in (0, 1, cols, 8):
             streams.append(oracle.encode(rgb, 88, mode, dri, table_mode=k % 2)[0])
     # no resize, 1x1 crop fits every image; intermediates carry the check
     check_against_oracle(pp, streams, 0, 1, 1, "f32")
+
+
+def test_422_and_440_files_resized_and_cropped(pp):
+    # Pillow's 4:2:2 files (standard and optimised tables, restart markers) and the oracle's
+    # 4:2:2 / 4:4:0 files, long enough for the subsequence pass, through resize and crop
+    streams = []
+    for k, (w, h) in enumerate([(333, 250), (640, 427), (500, 375)]):
+        rgb = _img(700 + k, w, h, sigma=10.0)
+        streams.append(synth.encode_jpeg(rgb, 90, synth.MODE_422, restart_blocks=8 if k else 0, optimize=k == 2))
+        streams.append(oracle.encode(rgb, 85 + 5 * k, MODE_422 if k % 2 else MODE_440, dri=0 if k else 7)[0])
+    check_against_oracle(pp, streams, 256, 224, 224, "f16")
 
 
 def test_upscaling_small_images(pp):

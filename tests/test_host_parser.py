@@ -84,7 +84,8 @@ def test_parser_rejects_what_it_does_not_support():
     assert status(good.replace(b"\xff\xc0", b"\xff\xc9", 1)) == prep.E_UNSUPPORTED   # arithmetic
     sof = good.index(b"\xff\xc0")
     assert status(good[:sof + 4] + b"\x0c" + good[sof + 5:]) == prep.E_UNSUPPORTED   # 12 bit
-    assert status(good[:sof + 11] + b"\x21" + good[sof + 12:]) == prep.E_UNSUPPORTED  # 4:2:2
+    assert status(good[:sof + 11] + b"\x41" + good[sof + 12:]) == prep.E_UNSUPPORTED  # luma 4 x 1
+    assert status(good[:sof + 14] + b"\x21" + good[sof + 15:]) == prep.E_UNSUPPORTED  # chroma 2 x 1
     assert status(good[:-2]) == prep.E_CORRUPT                                       # no EOI
     assert status(b"\x00" + good[1:]) == prep.E_CORRUPT                              # no SOI
     dht = good.index(b"\xff\xc4")
