@@ -215,12 +215,24 @@ def run_streams(args, torch, prep, synth, make_params):
     span = [None] * N_STREAMS
     gate = threading.Barrier(N_STREAMS)
     errors = []
+    # Open-loop mode: requests (one batch each) arrive as a Poisson process of the given rate,
+    # as in the paper's methodology (section 5, input query modeling), and wait in one queue
+    # for the next free stream; latency then counts from the arrival, queueing included.
+    rate = args.poisson_rate
+    n_requests = N_STREAMS * args.steps
+    if rate:
+        sys.setswitchinterval(1e-4)
+        gaps = np.random.default_rng(3000).exponential(1.0 / rate, size=n_requests)
+        arrivals = np.cumsum(gaps)
+        taken = [0]
+        take_lock = threading.Lock()
+        epoch = [None]
 
     def worker(i):
         try:
             pp, out, hs = pps[i], outs[i], hip_streams[i]
             b = i
-            for k in range(args.warmup + args.steps):
+            for k in range(args.warmup + (0 if rate else args.steps)):
                 if k == args.warmup:
                     if i == 0:
                         pp.set_timing(True)
@@ -233,6 +245,31 @@ def run_streams(args, torch, prep, synth, make_params):
                 if k >= args.warmup:
                     lat[i].append(time.perf_counter() - t)
                 b = (b + N_STREAMS) % n_batches
+            if rate:
+                if i == 0:
+                    pp.set_timing(True)
+                gate.wait()
+                if i == 0:
+                    epoch[0] = time.perf_counter() + 0.001
+                gate.wait()
+                span[i] = [epoch[0], None]
+                while True:
+                    with take_lock:
+                        r = taken[0]
+                        taken[0] += 1
+                    if r >= n_requests:
+                        break
+                    due = epoch[0] + arrivals[r]
+                    wait = due - time.perf_counter()
+                    if wait > 3e-4:
+                        time.sleep(wait - 2e-4)  # gives the interpreter to the other threads
+                    while time.perf_counter() < due:
+                        pass
+                    b = r % n_batches
+                    o = offsets[b * STREAM_BATCH:(b + 1) * STREAM_BATCH + 1]
+                    pp.decode_resize_batch_resident(blob, dev_bits.data_ptr(), o, params, out.data_ptr(), hs.cuda_stream)
+                    hs.synchronize()
+                    lat[i].append(time.perf_counter() - due)
             span[i][1] = time.perf_counter()
             assert pp.get_status(STREAM_BATCH) == [0] * STREAM_BATCH
         except Exception as e:  # surfaced by the main thread
@@ -253,7 +290,7 @@ def run_streams(args, torch, prep, synth, make_params):
     wall = max(s[1] for s in span) - min(s[0] for s in span)
     images = N_STREAMS * args.steps * STREAM_BATCH
     all_lat = np.sort(np.concatenate([np.array(l) for l in lat])) * 1e3
-    k = min(args.steps, 256)
+    k = max(1, min(len(lat[0]), 256))
     stage = np.array([pps[0].stage_ms(i) for i in range(k)]).mean(axis=0)
     pps[0].set_timing(False)
     work, entropy_bytes = algorithmic_bytes(infos[:STREAM_BATCH], pr)
@@ -269,12 +306,14 @@ def run_streams(args, torch, prep, synth, make_params):
         "dtype": "int32 entropy decode, f64 IDCT, f32 resize -> " + pr["out_dtype"] + " output",
         "data": "synthetic",
         "config": {"workload": WORKLOAD_NAMES[3], "streams": N_STREAMS, "batch": STREAM_BATCH,
-                   "hw_queues": int(os.environ["GPU_MAX_HW_QUEUES"]),
+                   "hw_queues": int(os.environ["GPU_MAX_HW_QUEUES"]), "poisson_rate": rate or None,
                    "input": "resident in HBM", "pool_images": len(streams),
                    "sha256": synth.sha256_of(streams), "input_generation_s": round(gen_s, 2)},
         "latency_ms": {"p50": float(np.percentile(all_lat, 50)), "p95": float(np.percentile(all_lat, 95)),
                        "p99": float(np.percentile(all_lat, 99)), "max": float(all_lat[-1]),
-                       "what": f"one batch of {STREAM_BATCH}: call of the entry point until its stream is idle",
+                       "what": (f"one batch of {STREAM_BATCH}: arrival (Poisson, {rate:g} batches/s, one queue) "
+                                "until its stream is idle" if rate else
+                                f"one batch of {STREAM_BATCH}: call of the entry point until its stream is idle"),
                        "samples": int(all_lat.size)},
         "roofline": roofline,
         "stages": stages,
@@ -301,6 +340,9 @@ def main():
     ap.add_argument("--hw-queues", type=int, default=8,
                     help="workload 3: hardware queues the HIP runtime may use (GPU_MAX_HW_QUEUES; its "
                          "default of 4 makes seven streams share queues and wait for each other)")
+    ap.add_argument("--poisson-rate", type=float, default=0.0,
+                    help="workload 3: requests (batches) per second arriving as a Poisson process and "
+                         "served by the next free stream; 0 = every stream runs back to back")
     ap.add_argument("--stream-batch", type=int, default=STREAM_BATCH,
                     help="workload 3: images per batch (default 8; 1 = the single-input latency case)")
     ap.add_argument("--copy-probe", action="store_true",
