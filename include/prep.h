@@ -222,6 +222,71 @@ int prep_debug_last_region(prep_handle *h, int32_t image, int32_t rect[4]);
 int prep_set_timing(prep_handle *h, int32_t enabled);
 int prep_stage_ms(prep_handle *h, int32_t calls_back, float ms[4]);
 
+/* ---- dynamic batching (PREBA section 4.3, "Dynamic Batching System") --------
+ *
+ * Single-input requests wait in one queue.  A batch is released as soon as
+ * batch_max requests wait (Batch_max) or the oldest has waited time_queue
+ * (Time_queue, which the paper sets to the consumer's tail latency at the knee
+ * divided by the number of consumers); a free consumer then takes the oldest
+ * requests waiting at that moment, at most batch_max.
+ *
+ * prep_policy_* is that rule alone, driven by the caller's clock: host only,
+ * no GPU, not thread safe.  Times are integer nanoseconds on any one clock.   */
+typedef struct prep_policy prep_policy;
+
+int prep_policy_create(prep_policy **out, int32_t batch_max, int64_t time_queue_ns);
+void prep_policy_destroy(prep_policy *p);
+/* Request `id` arrives at t_ns (no earlier than the arrival before it). */
+int prep_policy_arrive(prep_policy *p, uint64_t id, int64_t t_ns);
+/* Earliest time at which a batch is released given no further arrival:
+ * INT64_MAX when nothing waits.                                               */
+int64_t prep_policy_deadline(const prep_policy *p);
+/* A consumer is free at now_ns: if a batch is released by then, writes its
+ * ids (HOST, cap >= batch_max entries), oldest first, removes them from the
+ * queue and returns their number; else returns 0.  Negative on bad arguments. */
+int32_t prep_policy_take(prep_policy *p, int64_t now_ns, uint64_t *ids, int32_t cap);
+int32_t prep_policy_pending(const prep_policy *p);
+
+/* prep_server_*: that rule in front of n_consumers handles, each with its own
+ * HIP stream and host thread (the paper's vGPUs consuming batches).  Requests
+ * are copied on submission; every request's tensor slab [3, crop_h, crop_w]
+ * lands in device memory owned by the server.  All calls are thread safe.     */
+typedef struct prep_server prep_server;
+
+typedef struct {
+    prep_config handle;        /* capacity of each consumer's handle; max_batch is taken from batch_max */
+    prep_params params;
+    int32_t n_consumers;       /* 1..64                                          */
+    int32_t batch_max;         /* 1..65535                                       */
+    int64_t time_queue_us;     /* >= 0                                           */
+    int32_t max_request_bytes; /* largest file accepted                          */
+    int32_t queue_capacity;    /* requests that may wait; more are refused       */
+} prep_server_config;
+
+typedef struct {
+    uint64_t tag;              /* the caller's tag                               */
+    int32_t status;            /* PREP_OK or the image's error                   */
+    int32_t batch_size;        /* size of the batch it was served in             */
+    int32_t consumer;          /* which consumer served it                       */
+    int32_t reserved;
+    int64_t arrival_ns, start_ns, done_ns; /* steady clock: submitted, batch taken, tensor ready */
+    const void *tensor;        /* DEVICE: this request's slab; valid until the same
+                                * consumer has finished two more batches          */
+} prep_server_result;
+
+int prep_server_create(prep_server **out, const prep_server_config *cfg);
+/* Stops the consumers (requests still waiting are dropped) and frees everything. */
+int prep_server_destroy(prep_server *s);
+/* Queues one JPEG file (HOST, copied before the call returns).
+ * PREP_E_TOO_LARGE: the file is larger than max_request_bytes or the queue is full. */
+int prep_server_submit(prep_server *s, const uint8_t *jpeg, uint64_t len, uint64_t tag);
+/* Next finished request, in order of completion: 1 and *out filled, 0 after
+ * timeout_us without one, negative on bad arguments.                          */
+int prep_server_next(prep_server *s, prep_server_result *out, int64_t timeout_us);
+/* Copies a finished request's tensor slab (3*crop_h*crop_w elements of the
+ * configured dtype) to host_out (HOST); for checks, while the slab is valid.  */
+int prep_server_copy_tensor(prep_server *s, const prep_server_result *r, void *host_out);
+
 #ifdef __cplusplus
 }
 #endif

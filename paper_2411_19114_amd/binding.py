@@ -7,7 +7,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
-_SOURCES = ["entropy.hip", "reconstruct.hip", "resize.hip", "api.cpp", "parser.cpp"]
+_SOURCES = ["entropy.hip", "reconstruct.hip", "resize.hip", "api.cpp", "parser.cpp", "batcher.cpp"]
 
 OK, E_INVALID_ARG, E_TOO_LARGE, E_HIP, E_UNSUPPORTED, E_CORRUPT, E_NOMEM = 0, -1, -2, -3, -4, -5, -6
 F32, F16 = 0, 1
@@ -22,7 +22,7 @@ def lib_path():
 def build(verbose=False):
     """Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
+    cmd = [hipcc, "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared", "-pthread",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-o", lib_path()] + [os.path.join(_CSRC, s) for s in _SOURCES]
     r = subprocess.run(cmd, capture_output=not verbose, text=True)
@@ -48,6 +48,17 @@ class Params(C.Structure):
                 ("out_dtype", C.c_int32), ("mean", C.c_float * 3), ("std", C.c_float * 3)]
 
 
+class ServerConfig(C.Structure):
+    _fields_ = [("handle", Config), ("params", Params), ("n_consumers", C.c_int32), ("batch_max", C.c_int32),
+                ("time_queue_us", C.c_int64), ("max_request_bytes", C.c_int32), ("queue_capacity", C.c_int32)]
+
+
+class ServerResult(C.Structure):
+    _fields_ = [("tag", C.c_uint64), ("status", C.c_int32), ("batch_size", C.c_int32), ("consumer", C.c_int32),
+                ("reserved", C.c_int32), ("arrival_ns", C.c_int64), ("start_ns", C.c_int64),
+                ("done_ns", C.c_int64), ("tensor", C.c_void_p)]
+
+
 class ImageInfo(C.Structure):
     _fields_ = [("status", C.c_int32), ("width", C.c_int32), ("height", C.c_int32),
                 ("sampling", C.c_int32), ("mcu_cols", C.c_int32), ("mcu_rows", C.c_int32),
@@ -66,6 +77,9 @@ EXPORTS = [
     "prep_get_status", "prep_strerror", "prep_parse_headers", "prep_interval_descriptors",
     "prep_resize_normalize", "prep_reconstruct_from_coefficients", "prep_debug_last_coefficients",
     "prep_debug_last_rgb", "prep_debug_last_region", "prep_stage_ms", "prep_set_timing",
+    "prep_policy_create", "prep_policy_destroy", "prep_policy_arrive", "prep_policy_deadline",
+    "prep_policy_take", "prep_policy_pending", "prep_server_create", "prep_server_destroy",
+    "prep_server_submit", "prep_server_next", "prep_server_copy_tensor",
 ]
 
 _lib = None
@@ -109,6 +123,19 @@ def lib():
         L.prep_debug_last_region.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32)]
         L.prep_stage_ms.argtypes = [vp, C.c_int32, C.POINTER(C.c_float)]
         L.prep_set_timing.argtypes = [vp, C.c_int32]
+        L.prep_policy_create.argtypes = [C.POINTER(vp), C.c_int32, C.c_int64]
+        L.prep_policy_destroy.argtypes = [vp]
+        L.prep_policy_destroy.restype = None
+        L.prep_policy_arrive.argtypes = [vp, C.c_uint64, C.c_int64]
+        L.prep_policy_deadline.argtypes = [vp]
+        L.prep_policy_deadline.restype = C.c_int64
+        L.prep_policy_take.argtypes = [vp, C.c_int64, C.POINTER(C.c_uint64), C.c_int32]
+        L.prep_policy_pending.argtypes = [vp]
+        L.prep_server_create.argtypes = [C.POINTER(vp), C.POINTER(ServerConfig)]
+        L.prep_server_destroy.argtypes = [vp]
+        L.prep_server_submit.argtypes = [vp, vp, C.c_uint64, C.c_uint64]
+        L.prep_server_next.argtypes = [vp, C.POINTER(ServerResult), C.c_int64]
+        L.prep_server_copy_tensor.argtypes = [vp, C.POINTER(ServerResult), vp]
         _lib = L
     return _lib
 
@@ -254,3 +281,70 @@ class Preprocessor:
         ms = (C.c_float * 4)()
         _check(lib().prep_stage_ms(self._h, calls_back, ms), "prep_stage_ms")
         return list(ms)
+
+
+class BatchPolicy:
+    """The batching rule alone (prep_policy_*), driven by the caller's clock."""
+
+    def __init__(self, batch_max, time_queue_ns):
+        self._p = C.c_void_p()
+        _check(lib().prep_policy_create(C.byref(self._p), int(batch_max), int(time_queue_ns)), "prep_policy_create")
+        self._ids = (C.c_uint64 * int(batch_max))()
+
+    def arrive(self, request_id, t_ns):
+        _check(lib().prep_policy_arrive(self._p, int(request_id), int(t_ns)), "prep_policy_arrive")
+
+    def deadline(self):
+        return int(lib().prep_policy_deadline(self._p))
+
+    def take(self, now_ns):
+        n = lib().prep_policy_take(self._p, int(now_ns), self._ids, len(self._ids))
+        if n < 0:
+            raise PrepError(int(n), "prep_policy_take")
+        return [int(self._ids[i]) for i in range(n)]
+
+    def pending(self):
+        return int(lib().prep_policy_pending(self._p))
+
+    def close(self):
+        if self._p:
+            lib().prep_policy_destroy(self._p)
+            self._p = C.c_void_p()
+
+
+class Server:
+    """prep_server_*: the batching rule in front of n_consumers handles and streams."""
+
+    def __init__(self, n_consumers, batch_max, time_queue_us, params, max_width, max_height,
+                 max_request_bytes, queue_capacity=4096, device=0, flags=0):
+        cfg = ServerConfig()
+        cfg.handle = Config(device, batch_max, max_width, max_height, batch_max * max_request_bytes,
+                            0, flags)
+        cfg.params = params
+        cfg.n_consumers, cfg.batch_max, cfg.time_queue_us = int(n_consumers), int(batch_max), int(time_queue_us)
+        cfg.max_request_bytes, cfg.queue_capacity = int(max_request_bytes), int(queue_capacity)
+        self._shape = (3, params.crop_h, params.crop_w)
+        self._dtype = np.float16 if params.out_dtype == F16 else np.float32
+        self._s = C.c_void_p()
+        _check(lib().prep_server_create(C.byref(self._s), C.byref(cfg)), "prep_server_create")
+
+    def submit(self, jpeg, tag):
+        a, p = _u8(np.frombuffer(jpeg, dtype=np.uint8) if isinstance(jpeg, (bytes, bytearray)) else jpeg)
+        return int(lib().prep_server_submit(self._s, p, a.size, int(tag)))
+
+    def next(self, timeout_us=1000000):
+        r = ServerResult()
+        got = lib().prep_server_next(self._s, C.byref(r), int(timeout_us))
+        if got < 0:
+            raise PrepError(int(got), "prep_server_next")
+        return r if got else None
+
+    def copy_tensor(self, result):
+        out = np.empty(self._shape, dtype=self._dtype)
+        _check(lib().prep_server_copy_tensor(self._s, C.byref(result), out.ctypes.data), "prep_server_copy_tensor")
+        return out
+
+    def close(self):
+        if self._s:
+            lib().prep_server_destroy(self._s)
+            self._s = C.c_void_p()
