@@ -326,6 +326,88 @@ def run_streams(args, torch, prep, synth, make_params):
         pp.close()
 
 
+def run_server(args, torch, prep, synth, make_params):
+    """Workload 3 through the batching server: single-image requests arrive as a Poisson
+    process (the paper's query model, section 5), wait for Batch_max / Time_queue (section 4.3)
+    and are served by --streams consumers.  Latency = arrival until the tensor is ready, on
+    the library's clock."""
+    import threading
+    n_consumers = args.streams or N_STREAMS
+    streams = synth.make_batch(3)
+    pr = synth.params_of(3)
+    params = make_params(pr["resize_short"], pr["crop_h"], pr["crop_w"], pr["out_dtype"], pr["mean"], pr["std"])
+    blob, offsets = synth.pack(streams)
+    infos = prep.parse_headers(blob, offsets)
+    max_w, max_h = max(i.width for i in infos), max(i.height for i in infos)
+    server = prep.Server(n_consumers=n_consumers, batch_max=args.batch_max, time_queue_us=args.time_queue_us,
+                         params=params, max_width=max_w, max_height=max_h,
+                         max_request_bytes=max(len(x) for x in streams), queue_capacity=8192)
+    rate = args.poisson_rate or 10000.0
+    n_req = n_consumers * args.steps * args.batch_max
+    # warm-up: every consumer serves a few full batches (the first calls on a stream load code
+    # and take milliseconds), all results are read, then the timed arrivals start
+    n_warm = max(args.warmup, 4) * n_consumers * args.batch_max
+    for k in range(n_warm):
+        assert server.submit(streams[k % len(streams)], k) == 0
+        if (k + 1) % (n_consumers * args.batch_max) == 0:
+            time.sleep(0.03)
+    for _ in range(n_warm):
+        assert server.next(5000000) is not None, "warm-up request lost"
+    arrivals = np.cumsum(np.random.default_rng(3000).exponential(1.0 / rate, size=n_warm + n_req))
+    arrivals[n_warm:] -= arrivals[n_warm]
+    results = []
+    refused = [0]
+
+    def collect():
+        while len(results) + refused[0] < n_req:
+            r = server.next(2000000)
+            if r is None:
+                break
+            results.append((r.tag, r.status, r.batch_size, r.arrival_ns, r.start_ns, r.done_ns))
+
+    col = threading.Thread(target=collect)
+    col.start()
+    sys.setswitchinterval(1e-4)
+    t0 = time.perf_counter()
+    for k in range(n_warm, n_warm + n_req):
+        due = t0 + arrivals[k]
+        wait = due - time.perf_counter()
+        if wait > 3e-4:
+            time.sleep(wait - 2e-4)
+        while time.perf_counter() < due:
+            pass
+        if server.submit(streams[k % len(streams)], k) != 0:
+            refused[0] += 1
+    col.join()
+    server.close()
+    timed = [r for r in results if r[0] >= n_warm]
+    assert timed and all(r[1] == 0 for r in timed), "a request failed"
+    lat = np.sort(np.array([(r[5] - r[3]) * 1e-6 for r in timed]))
+    wait_q = np.array([(r[4] - r[3]) * 1e-6 for r in timed])
+    span = (max(r[5] for r in timed) - min(r[3] for r in timed)) * 1e-9
+    batches = {}
+    for r in timed:
+        batches[(r[4], r[2])] = r[2]
+    result = {
+        "metric": METRIC, "value": len(timed) / span, "unit": "images/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": span / max(len(batches), 1) * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32 entropy decode, f64 IDCT, f32 resize -> " + pr["out_dtype"] + " output",
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[3] + ", one image per request through the batching server",
+                   "consumers": n_consumers, "batch_max": args.batch_max, "time_queue_us": args.time_queue_us,
+                   "poisson_rate": rate, "hw_queues": int(os.environ["GPU_MAX_HW_QUEUES"]),
+                   "input": "host memory", "refused": refused[0]},
+        "latency_ms": {"p50": float(np.percentile(lat, 50)), "p95": float(np.percentile(lat, 95)),
+                       "p99": float(np.percentile(lat, 99)), "max": float(lat[-1]),
+                       "what": "one request: submission until its tensor is ready", "samples": int(lat.size)},
+        "batching": {"batches": len(batches), "mean_batch": float(np.mean(list(batches.values()))),
+                     "mean_wait_ms": float(wait_q.mean()), "max_wait_ms": float(wait_q.max())},
+        "roofline": None, "cpu_baseline": None,
+    }
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -343,6 +425,11 @@ def main():
     ap.add_argument("--poisson-rate", type=float, default=0.0,
                     help="workload 3: requests (batches) per second arriving as a Poisson process and "
                          "served by the next free stream; 0 = every stream runs back to back")
+    ap.add_argument("--server", action="store_true",
+                    help="workload 3: single-image requests through the batching server (Batch_max, "
+                         "Time_queue) with --streams consumers; needs --poisson-rate")
+    ap.add_argument("--batch-max", type=int, default=8, help="--server: Batch_max")
+    ap.add_argument("--time-queue-us", type=int, default=200, help="--server: Time_queue in microseconds")
     ap.add_argument("--stream-batch", type=int, default=STREAM_BATCH,
                     help="workload 3: images per batch (default 8; 1 = the single-input latency case)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -373,7 +460,10 @@ def main():
 
     cfg = args.workload
     if cfg == 3:
-        run_streams(args, torch, prep, synth, make_params)
+        if args.server:
+            run_server(args, torch, prep, synth, make_params)
+        else:
+            run_streams(args, torch, prep, synth, make_params)
         return
     t0 = time.perf_counter()
     streams = synth.make_batch(cfg)
