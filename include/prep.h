@@ -287,6 +287,47 @@ int prep_server_next(prep_server *s, prep_server_result *out, int64_t timeout_us
  * configured dtype) to host_out (HOST); for checks, while the slab is valid.  */
 int prep_server_copy_tensor(prep_server *s, const prep_server_result *r, void *host_out);
 
+/* ---- audio path (PREBA section 2.3 item b; section 4.2, Fig. 11(b), Table 2) ----
+ *
+ * Resample -> log-Mel spectrogram -> per-feature normalize, the three units of
+ * the paper's audio compute units.  Definitions: band-limited interpolation
+ * with a Hann-windowed sinc (six zero crossings, cut-off at 0.99 of the lower
+ * Nyquist rate); frames of n_fft samples every hop samples, frame t centred on
+ * sample t*hop of the signal extended by reflection; periodic Hann window of
+ * win_length samples centred in the frame; squared magnitude of the DFT;
+ * n_mels unit-peak triangles with corners equally spaced on
+ * m(f) = 2595 log10(1 + f/700) between 0 and rate/2; ln(x + 2^-24); per Mel
+ * channel of an utterance mean, variance (mean squared deviation) and
+ * (x - mean) / (sqrt(variance) + 1e-5).                                        */
+typedef struct prep_audio prep_audio;
+
+typedef struct {
+    int32_t device;
+    int32_t max_batch;          /* utterances per call                             */
+    int32_t rate;               /* sampling rate the features are computed at      */
+    int32_t n_fft;              /* 512                                             */
+    int32_t win_length;         /* 1 .. n_fft                                      */
+    int32_t hop;                /* >= 1                                            */
+    int32_t n_mels;             /* 1 .. 128                                        */
+    int32_t reserved;
+    uint64_t max_total_samples; /* samples per call, before and after resampling   */
+} prep_audio_config;
+
+int prep_audio_create(prep_audio **out, const prep_audio_config *cfg);
+int prep_audio_destroy(prep_audio *h);
+/* Frames of an utterance of samples_in samples at rate_in: 1 + ceil(samples_in *
+ * rate / rate_in) / hop (integer division), or a negative code.                 */
+int64_t prep_audio_frames(const prep_audio_config *cfg, uint64_t samples_in, int32_t rate_in);
+/* waveforms: DEVICE, float32 mono, n utterances back to back; offsets: HOST,
+ * n+1 entries in samples; rate_in: their sampling rate.  out: DEVICE float32;
+ * utterance i lands at out_offsets[i] (HOST, n+1 entries, written by the call,
+ * in elements) as [n_mels][frames_i], frames innermost.  Every utterance must
+ * be longer than n_fft/2 samples after resampling.  Enqueues on `stream` (a
+ * hipStream_t, NULL = the default stream) and
+ * returns; allocates nothing except when the rate pair changes.                 */
+int prep_audio_features(prep_audio *h, const float *waveforms, const uint64_t *offsets, int32_t n,
+                        int32_t rate_in, float *out, uint64_t *out_offsets, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

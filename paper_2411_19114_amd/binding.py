@@ -7,7 +7,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
-_SOURCES = ["entropy.hip", "reconstruct.hip", "resize.hip", "api.cpp", "parser.cpp", "batcher.cpp"]
+_SOURCES = ["entropy.hip", "reconstruct.hip", "resize.hip", "api.cpp", "parser.cpp", "batcher.cpp", "audio.hip"]
 
 OK, E_INVALID_ARG, E_TOO_LARGE, E_HIP, E_UNSUPPORTED, E_CORRUPT, E_NOMEM = 0, -1, -2, -3, -4, -5, -6
 F32, F16 = 0, 1
@@ -48,6 +48,12 @@ class Params(C.Structure):
                 ("out_dtype", C.c_int32), ("mean", C.c_float * 3), ("std", C.c_float * 3)]
 
 
+class AudioConfig(C.Structure):
+    _fields_ = [("device", C.c_int32), ("max_batch", C.c_int32), ("rate", C.c_int32), ("n_fft", C.c_int32),
+                ("win_length", C.c_int32), ("hop", C.c_int32), ("n_mels", C.c_int32), ("reserved", C.c_int32),
+                ("max_total_samples", C.c_uint64)]
+
+
 class ServerConfig(C.Structure):
     _fields_ = [("handle", Config), ("params", Params), ("n_consumers", C.c_int32), ("batch_max", C.c_int32),
                 ("time_queue_us", C.c_int64), ("max_request_bytes", C.c_int32), ("queue_capacity", C.c_int32)]
@@ -80,6 +86,7 @@ EXPORTS = [
     "prep_policy_create", "prep_policy_destroy", "prep_policy_arrive", "prep_policy_deadline",
     "prep_policy_take", "prep_policy_pending", "prep_server_create", "prep_server_destroy",
     "prep_server_submit", "prep_server_next", "prep_server_copy_tensor",
+    "prep_audio_create", "prep_audio_destroy", "prep_audio_frames", "prep_audio_features",
 ]
 
 _lib = None
@@ -136,6 +143,11 @@ def lib():
         L.prep_server_submit.argtypes = [vp, vp, C.c_uint64, C.c_uint64]
         L.prep_server_next.argtypes = [vp, C.POINTER(ServerResult), C.c_int64]
         L.prep_server_copy_tensor.argtypes = [vp, C.POINTER(ServerResult), vp]
+        L.prep_audio_create.argtypes = [C.POINTER(vp), C.POINTER(AudioConfig)]
+        L.prep_audio_destroy.argtypes = [vp]
+        L.prep_audio_frames.argtypes = [C.POINTER(AudioConfig), C.c_uint64, C.c_int32]
+        L.prep_audio_frames.restype = C.c_int64
+        L.prep_audio_features.argtypes = [vp, vp, u64p, C.c_int32, C.c_int32, vp, u64p, vp]
         _lib = L
     return _lib
 
@@ -348,3 +360,30 @@ class Server:
         if self._s:
             lib().prep_server_destroy(self._s)
             self._s = C.c_void_p()
+
+
+class AudioPreprocessor:
+    """prep_audio_*: resample -> log-Mel spectrogram -> per-feature normalize on the GPU."""
+
+    def __init__(self, max_batch, max_total_samples, rate=16000, n_fft=512, win_length=400, hop=160, n_mels=80,
+                 device=0):
+        self.cfg = AudioConfig(device, max_batch, rate, n_fft, win_length, hop, n_mels, 0, max_total_samples)
+        self._h = C.c_void_p()
+        _check(lib().prep_audio_create(C.byref(self._h), C.byref(self.cfg)), "prep_audio_create")
+
+    def frames(self, samples_in, rate_in):
+        return int(lib().prep_audio_frames(C.byref(self.cfg), int(samples_in), int(rate_in)))
+
+    def features(self, waveforms_ptr, offsets, rate_in, out_ptr, stream=0):
+        """Enqueues the batch; returns the output offsets (elements) of the utterances."""
+        o, op = _u64(offsets)
+        out_offsets = np.zeros(len(o), dtype=np.uint64)
+        _check(lib().prep_audio_features(self._h, C.c_void_p(waveforms_ptr), op, len(o) - 1, int(rate_in),
+                                         C.c_void_p(out_ptr), out_offsets.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                         C.c_void_p(stream)), "prep_audio_features")
+        return out_offsets
+
+    def close(self):
+        if self._h:
+            lib().prep_audio_destroy(self._h)
+            self._h = C.c_void_p()

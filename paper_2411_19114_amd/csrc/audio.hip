@@ -1,0 +1,470 @@
+// Audio preprocessing for gfx950: resample -> log-Mel spectrogram -> per-feature normalize.
+//
+// The audio compute units of PREBA's DPU (section 2.3 item b; section 4.2, Fig. 11(b), Table 2:
+// Resample, Mel spectrogram, Normalize).  The paper names the operations only; the definitions
+// are: band-limited interpolation with a Hann-windowed sinc (six zero crossings, cut-off at
+// 0.99 of the lower Nyquist rate); frames of n_fft samples every hop samples, centred by
+// reflecting the signal at both ends, a periodic Hann window of win_length samples centred in
+// the frame, squared magnitude of the DFT; n_mels unit-peak triangles with corners equally
+// spaced on m(f) = 2595 log10(1 + f/700) from 0 to half the rate; ln(x + 2^-24); per Mel
+// channel and utterance mean, variance (mean squared deviation) and
+// (x - mean) / (sqrt(variance) + 1e-5).
+//
+// Tables (interpolation taps per phase, window, twiddle factors, Mel weights) are computed on
+// the host in double precision.  From the input samples to the logarithm everything is double:
+// fp64 runs at the rate of unpacked fp32 on this chip, and in float the transform's rounding
+// noise (a few 1e-7 of the strongest bin) would be a visible fraction of the weak high bands
+// whose logarithm is taken.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <numeric>
+#include <vector>
+
+#include "../../include/prep.h"
+
+namespace {
+
+constexpr int kZeroCrossings = 6;
+constexpr double kRolloff = 0.99;
+constexpr float kLogGuard = 5.9604644775390625e-08f;  // 2^-24
+constexpr float kStdGuard = 1e-5f;
+constexpr int kFft = 512;                             // the transform the kernel is built for
+constexpr int kFrameThreads = 256;                    // four frames per workgroup, one wave each
+constexpr int kMaxMels = 128;
+
+struct Utterance {
+    uint64_t in_off;    // first input sample
+    uint64_t mid_off;   // first resampled sample in the workspace
+    uint64_t out_off;   // first output element
+    uint32_t in_len, mid_len, frames, pad_;
+};
+
+// ---- resample -----------------------------------------------------------------------------
+// Output m = a q + r of an utterance (r < q) is sum_j x[a p + first[r] + j] taps[r][j]: the
+// taps depend on the phase r only.
+__global__ __launch_bounds__(256) void resample_kernel(const float *__restrict__ in, const Utterance *__restrict__ utt,
+                                                       const uint64_t *__restrict__ mid_start, int n_utt,
+                                                       const double *__restrict__ taps, const int32_t *__restrict__ first,
+                                                       int p, int q, int n_taps, double *__restrict__ mid,
+                                                       uint64_t total)
+{
+    const uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= total) return;
+    // the utterance that holds output g: the last one whose first output does not exceed g
+    int lo = 0, hi = n_utt - 1;
+    while (lo < hi) {
+        const int m = (lo + hi + 1) >> 1;
+        if (mid_start[m] <= g) lo = m; else hi = m - 1;
+    }
+    const Utterance u = utt[lo];
+    const uint32_t m = (uint32_t)(g - u.mid_off);
+    const uint32_t a = m / (uint32_t)q, r = m - a * (uint32_t)q;
+    const int64_t n0 = (int64_t)a * p + first[r];
+    const float *x = in + u.in_off;
+    const double *t = taps + (size_t)r * n_taps;
+    double acc = 0.0;
+    for (int j = 0; j < n_taps; j++) {
+        const int64_t n = n0 + j;
+        if (n >= 0 && n < (int64_t)u.in_len) acc = fma((double)x[n], t[j], acc);
+    }
+    mid[g] = acc;
+}
+
+// ---- frames -> log-Mel --------------------------------------------------------------------
+__device__ __forceinline__ uint32_t reverse9(uint32_t v) { return __brev(v) >> 23; }
+
+struct MelTable {          // filter m covers bins start[m] .. start[m] + count[m] - 1
+    int32_t start[kMaxMels], count[kMaxMels], first_weight[kMaxMels];
+};
+
+// One wave per frame.  frame_start[u] = first frame of utterance u among all frames.  Sample is
+// double for a resampled signal, float where the input is framed as it is.
+template <typename Sample>
+__global__ __launch_bounds__(kFrameThreads) void log_mel_kernel(
+    const Sample *__restrict__ mid, const Utterance *__restrict__ utt, const uint64_t *__restrict__ frame_start,
+    int n_utt, uint64_t n_frames, int hop, const double *__restrict__ window, const double2 *__restrict__ twiddle,
+    MelTable mel, const double *__restrict__ mel_weights, int n_mels, float *__restrict__ out)
+{
+    __shared__ double2 s_x[kFrameThreads / 64][kFft];
+    __shared__ double s_power[kFrameThreads / 64][kFft / 2 + 1];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint64_t f = (uint64_t)blockIdx.x * (kFrameThreads / 64) + wave;
+    const bool live = f < n_frames;   // every wave keeps to the barriers
+    Utterance u;
+    uint32_t t = 0;
+    if (live) {
+        int lo = 0, hi = n_utt - 1;
+        while (lo < hi) {
+            const int m = (lo + hi + 1) >> 1;
+            if (frame_start[m] <= f) lo = m; else hi = m - 1;
+        }
+        u = utt[lo];
+        t = (uint32_t)(f - frame_start[lo]);
+    }
+    double2 *x = s_x[wave];
+    if (live) {
+        const Sample *sig = mid + u.mid_off;
+        const int64_t len = (int64_t)u.mid_len;
+        for (int j = lane; j < kFft; j += 64) {
+            int64_t s = (int64_t)t * hop + j - kFft / 2;
+            if (s < 0) s = -s;                       // reflection about the first sample
+            if (s >= len) s = 2 * (len - 1) - s;     // and about the last (len > n_fft / 2)
+            x[reverse9((uint32_t)j)] = make_double2((double)sig[s] * window[j], 0.0);
+        }
+    }
+    __syncthreads();
+    // radix-2, decimation in time: stage with butterflies `half` apart, 256 per stage
+    for (int half = 1; half < kFft; half <<= 1) {
+        if (live) {
+            const int step = (kFft / 2) / half;      // twiddle stride: W^(pos * 512 / (2 half))
+            for (int b = lane; b < kFft / 2; b += 64) {
+                const int pos = b & (half - 1);
+                const int i0 = ((b - pos) << 1) + pos, i1 = i0 + half;
+                const double2 w = twiddle[pos * step];
+                const double2 a = x[i0], c = x[i1];
+                const double2 wc = make_double2(w.x * c.x - w.y * c.y, w.x * c.y + w.y * c.x);
+                x[i0] = make_double2(a.x + wc.x, a.y + wc.y);
+                x[i1] = make_double2(a.x - wc.x, a.y - wc.y);
+            }
+        }
+        __syncthreads();
+    }
+    if (live) {
+        for (int k = lane; k <= kFft / 2; k += 64) s_power[wave][k] = x[k].x * x[k].x + x[k].y * x[k].y;  // double
+    }
+    __syncthreads();
+    if (live) {
+        for (int m = lane; m < n_mels; m += 64) {
+            const double *w = mel_weights + mel.first_weight[m];
+            const double *pw = s_power[wave] + mel.start[m];
+            double acc = 0.0;
+            for (int k = 0; k < mel.count[m]; k++) acc = fma(w[k], pw[k], acc);
+            out[u.out_off + (uint64_t)m * u.frames + t] = (float)log(acc + (double)kLogGuard);
+        }
+    }
+}
+
+// ---- normalize ----------------------------------------------------------------------------
+// One workgroup per (utterance, Mel channel) row: mean, then the mean squared deviation, then
+// the normalised values, the row held in registers (up to kRowPerThread * 256 frames) or
+// re-read from memory when longer.
+constexpr int kRowPerThread = 16;
+
+__device__ __forceinline__ double block_sum_256(double v, double *s)
+{
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) s[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return s[0] + s[1] + s[2] + s[3];
+}
+
+__global__ __launch_bounds__(256) void normalize_kernel(const Utterance *__restrict__ utt, int n_mels, float *__restrict__ out)
+{
+    __shared__ double s[4];
+    const Utterance u = utt[blockIdx.x / n_mels];
+    float *row = out + u.out_off + (uint64_t)(blockIdx.x % n_mels) * u.frames;
+    const uint32_t n = u.frames;
+    const bool cached = n <= (uint32_t)kRowPerThread * 256u;
+    float v[kRowPerThread];
+    double sum = 0.0;
+    if (cached) {
+#pragma unroll
+        for (int i = 0; i < kRowPerThread; i++) {
+            const uint32_t k = threadIdx.x + 256u * i;
+            v[i] = k < n ? row[k] : 0.0f;
+            sum += v[i];
+        }
+    } else {
+        for (uint32_t k = threadIdx.x; k < n; k += 256) sum += row[k];
+    }
+    const double mean = block_sum_256(sum, s) / (double)n;
+    double dev = 0.0;
+    if (cached) {
+#pragma unroll
+        for (int i = 0; i < kRowPerThread; i++) {
+            const uint32_t k = threadIdx.x + 256u * i;
+            const double d = (double)v[i] - mean;
+            dev += k < n ? d * d : 0.0;
+        }
+    } else {
+        for (uint32_t k = threadIdx.x; k < n; k += 256) { const double d = (double)row[k] - mean; dev += d * d; }
+    }
+    const double var = block_sum_256(dev, s) / (double)n;
+    const double scale = 1.0 / (sqrt(var) + (double)kStdGuard);
+    if (cached) {
+#pragma unroll
+        for (int i = 0; i < kRowPerThread; i++) {
+            const uint32_t k = threadIdx.x + 256u * i;
+            if (k < n) row[k] = (float)(((double)v[i] - mean) * scale);
+        }
+    } else {
+        for (uint32_t k = threadIdx.x; k < n; k += 256) row[k] = (float)(((double)row[k] - mean) * scale);
+    }
+}
+
+double sinc(double u) { return u == 0.0 ? 1.0 : sin(M_PI * u) / (M_PI * u); }
+
+}  // namespace
+
+struct prep_audio {
+    prep_audio_config cfg;
+    // tables on the device
+    double *d_window = nullptr;
+    double2 *d_twiddle = nullptr;
+    double *d_mel_weights = nullptr;
+    MelTable mel;
+    // interpolation taps of the rate pair seen last
+    int taps_p = 0, taps_q = 0, n_taps = 0;
+    double *d_taps = nullptr;
+    int32_t *d_first = nullptr;
+    size_t taps_cap = 0;
+    // per call
+    Utterance *h_utt = nullptr, *d_utt = nullptr;
+    uint64_t *h_starts = nullptr, *d_starts = nullptr;  // [mid_start n][frame_start n]
+    double *d_mid = nullptr;
+    hipEvent_t done = nullptr;
+    bool pending = false;
+    std::vector<double> h_taps;
+    std::vector<int32_t> h_first;
+};
+
+namespace {
+
+#define AUDIO_TRY(expr)                                   \
+    do {                                                  \
+        if ((expr) != hipSuccess) {                       \
+            (void)hipGetLastError();                      \
+            return PREP_E_HIP;                            \
+        }                                                 \
+    } while (0)
+
+uint64_t resampled_length(uint64_t len, int p, int q) { return (len * (uint64_t)q + (uint64_t)p - 1) / (uint64_t)p; }
+
+// taps[r][j] = h((first[r] + j) / p - r / q) for phase r of p : q (input : output rate, reduced)
+void make_taps(int p, int q, std::vector<double> *taps, std::vector<int32_t> *first, int *n_taps)
+{
+    const double base = kRolloff * std::min(p, q);
+    const double reach = kZeroCrossings / base * p;  // in input samples
+    int width = 0;
+    first->resize((size_t)q);
+    std::vector<int> last((size_t)q);
+    for (int r = 0; r < q; r++) {
+        const double centre = (double)r * p / q;
+        (*first)[(size_t)r] = (int32_t)ceil(centre - reach);
+        last[(size_t)r] = (int)floor(centre + reach);
+        width = std::max(width, last[(size_t)r] - (*first)[(size_t)r] + 1);
+    }
+    *n_taps = width;
+    taps->assign((size_t)q * width, 0.0);
+    for (int r = 0; r < q; r++)
+        for (int j = 0; j < width; j++) {
+            const int n = (*first)[(size_t)r] + j;
+            const double uarg = base * ((double)n / p - (double)r / q);
+            if (fabs(uarg) < kZeroCrossings && n <= last[(size_t)r]) {
+                const double c = cos(M_PI * uarg / (2.0 * kZeroCrossings));
+                (*taps)[(size_t)r * width + j] = (base / p) * sinc(uarg) * c * c;
+            }
+        }
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t prep_audio_frames(const prep_audio_config *cfg, uint64_t samples_in, int32_t rate_in)
+{
+    if (!cfg || rate_in < 1 || cfg->rate < 1 || cfg->hop < 1) return PREP_E_INVALID_ARG;
+    const int g = std::gcd(rate_in, cfg->rate);
+    const uint64_t len = resampled_length(samples_in, rate_in / g, cfg->rate / g);
+    return (int64_t)(1 + len / (uint64_t)cfg->hop);
+}
+
+int prep_audio_create(prep_audio **out, const prep_audio_config *cfg)
+{
+    if (!out) return PREP_E_INVALID_ARG;
+    *out = nullptr;
+    if (!cfg || cfg->max_batch < 1 || cfg->rate < 1 || cfg->n_fft != kFft || cfg->win_length < 1 ||
+        cfg->win_length > cfg->n_fft || cfg->hop < 1 || cfg->n_mels < 1 || cfg->n_mels > kMaxMels ||
+        cfg->max_total_samples < 1)
+        return PREP_E_INVALID_ARG;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) {
+        (void)hipGetLastError();
+        return PREP_E_HIP;
+    }
+    prep_audio *h = new (std::nothrow) prep_audio;
+    if (!h) return PREP_E_NOMEM;
+    h->cfg = *cfg;
+    // window, twiddle factors, Mel triangles: double precision, rounded once
+    std::vector<double> window((size_t)kFft, 0.0);
+    const int left = (kFft - cfg->win_length) / 2;
+    for (int i = 0; i < cfg->win_length; i++)
+        window[(size_t)(left + i)] = 0.5 - 0.5 * cos(2.0 * M_PI * i / cfg->win_length);
+    std::vector<double2> tw((size_t)kFft / 2);
+    for (int k = 0; k < kFft / 2; k++)
+        tw[(size_t)k] = make_double2(cos(2.0 * M_PI * k / kFft), -sin(2.0 * M_PI * k / kFft));
+    std::vector<double> weights;
+    {
+        auto mel_of = [](double f) { return 2595.0 * log10(1.0 + f / 700.0); };
+        auto hz_of = [](double m) { return 700.0 * (pow(10.0, m / 2595.0) - 1.0); };
+        const double top = mel_of(cfg->rate / 2.0);
+        std::vector<double> corner((size_t)cfg->n_mels + 2);
+        for (int i = 0; i < cfg->n_mels + 2; i++) corner[(size_t)i] = hz_of(top * i / (cfg->n_mels + 1));
+        for (int m = 0; m < cfg->n_mels; m++) {
+            const double lo = corner[(size_t)m], mid = corner[(size_t)m + 1], hi = corner[(size_t)m + 2];
+            h->mel.start[m] = 0;
+            h->mel.count[m] = 0;
+            h->mel.first_weight[m] = (int32_t)weights.size();
+            for (int k = 0; k <= kFft / 2; k++) {
+                const double f = (double)k * cfg->rate / kFft;
+                const double w = std::max(0.0, std::min((f - lo) / (mid - lo), (hi - f) / (hi - mid)));
+                if (w > 0.0) {
+                    if (h->mel.count[m] == 0) h->mel.start[m] = k;
+                    // zeros between positive weights cannot occur in a triangle
+                    h->mel.count[m] = k - h->mel.start[m] + 1;
+                    weights.push_back(w);
+                }
+            }
+        }
+        if (weights.empty()) weights.push_back(0.0);
+    }
+    const size_t n = (size_t)cfg->max_batch;
+    bool ok = hipSetDevice(cfg->device) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_window, sizeof(double) * kFft) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_twiddle, sizeof(double2) * kFft / 2) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_mel_weights, sizeof(double) * weights.size()) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_utt, sizeof(Utterance) * n) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_starts, sizeof(uint64_t) * 2 * n) == hipSuccess;
+    ok = ok && hipHostMalloc((void **)&h->h_utt, sizeof(Utterance) * n, hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipHostMalloc((void **)&h->h_starts, sizeof(uint64_t) * 2 * n, hipHostMallocDefault) == hipSuccess;
+    // the resampled signal is never longer than max_total_samples scaled by the largest ratio accepted
+    ok = ok && hipMalloc((void **)&h->d_mid, sizeof(double) * (cfg->max_total_samples + n)) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&h->done, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipMemcpy(h->d_window, window.data(), sizeof(double) * kFft, hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(h->d_twiddle, tw.data(), sizeof(double2) * kFft / 2, hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(h->d_mel_weights, weights.data(), sizeof(double) * weights.size(), hipMemcpyHostToDevice) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        prep_audio_destroy(h);
+        return PREP_E_NOMEM;
+    }
+    *out = h;
+    return PREP_OK;
+}
+
+int prep_audio_destroy(prep_audio *h)
+{
+    if (!h) return PREP_E_INVALID_ARG;
+    (void)hipSetDevice(h->cfg.device);
+    if (h->pending) (void)hipEventSynchronize(h->done);
+    (void)hipFree(h->d_window);
+    (void)hipFree(h->d_twiddle);
+    (void)hipFree(h->d_mel_weights);
+    (void)hipFree(h->d_utt);
+    (void)hipFree(h->d_starts);
+    (void)hipFree(h->d_mid);
+    (void)hipFree(h->d_taps);
+    (void)hipFree(h->d_first);
+    if (h->h_utt) (void)hipHostFree(h->h_utt);
+    if (h->h_starts) (void)hipHostFree(h->h_starts);
+    if (h->done) (void)hipEventDestroy(h->done);
+    delete h;
+    return PREP_OK;
+}
+
+int prep_audio_features(prep_audio *h, const float *waveforms, const uint64_t *offsets, int32_t n, int32_t rate_in,
+                        float *out, uint64_t *out_offsets, void *stream_ptr)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_ptr);
+    if (!h || !waveforms || !offsets || !out || !out_offsets || n < 0 || rate_in < 1) return PREP_E_INVALID_ARG;
+    if (n > h->cfg.max_batch) return PREP_E_TOO_LARGE;
+    out_offsets[0] = 0;
+    if (n == 0) return PREP_OK;
+    const int g = std::gcd(rate_in, h->cfg.rate);
+    const int p = rate_in / g, q = h->cfg.rate / g;
+    if (p > 4096 || q > 4096) return PREP_E_INVALID_ARG;  // the tap table has q rows
+    AUDIO_TRY(hipSetDevice(h->cfg.device));
+    if (h->pending) {  // the pinned records of the call before are still being read
+        AUDIO_TRY(hipEventSynchronize(h->done));
+        h->pending = false;
+    }
+    uint64_t mid_total = 0, frames_total = 0, out_total = 0;
+    for (int32_t i = 0; i < n; i++) {
+        if (offsets[i + 1] < offsets[i] || offsets[i + 1] - offsets[i] > 0xFFFFFFFFull) return PREP_E_INVALID_ARG;
+        Utterance &u = h->h_utt[i];
+        u.in_off = offsets[i];
+        u.in_len = (uint32_t)(offsets[i + 1] - offsets[i]);
+        const uint64_t len = resampled_length(u.in_len, p, q);
+        // centring reflects n_fft / 2 samples at both ends
+        if (len <= (uint64_t)kFft / 2 || len > 0x7FFFFFFFull) return PREP_E_INVALID_ARG;
+        u.mid_len = (uint32_t)len;
+        u.frames = (uint32_t)(1 + len / (uint64_t)h->cfg.hop);
+        u.mid_off = mid_total;
+        u.out_off = out_total;
+        u.pad_ = 0;
+        h->h_starts[i] = mid_total;
+        h->h_starts[(size_t)n + i] = frames_total;
+        mid_total += len;
+        frames_total += u.frames;
+        out_total += (uint64_t)u.frames * (uint64_t)h->cfg.n_mels;
+        out_offsets[i + 1] = out_total;
+    }
+    if (offsets[n] - offsets[0] > h->cfg.max_total_samples || mid_total > h->cfg.max_total_samples + (uint64_t)n)
+        return PREP_E_TOO_LARGE;
+    if (p != q && (p != h->taps_p || q != h->taps_q)) {
+        // a new rate pair: build its taps (the stream is drained so that the old ones are free)
+        AUDIO_TRY(hipStreamSynchronize(stream));
+        make_taps(p, q, &h->h_taps, &h->h_first, &h->n_taps);
+        const size_t need = h->h_taps.size();
+        if (need > h->taps_cap) {
+            (void)hipFree(h->d_taps);
+            (void)hipFree(h->d_first);
+            h->d_taps = nullptr;
+            h->d_first = nullptr;
+            h->taps_cap = 0;
+            if (hipMalloc((void **)&h->d_taps, sizeof(double) * need) != hipSuccess ||
+                hipMalloc((void **)&h->d_first, sizeof(int32_t) * 4096) != hipSuccess) {
+                (void)hipGetLastError();
+                return PREP_E_NOMEM;
+            }
+            h->taps_cap = need;
+        }
+        AUDIO_TRY(hipMemcpy(h->d_taps, h->h_taps.data(), sizeof(double) * need, hipMemcpyHostToDevice));
+        AUDIO_TRY(hipMemcpy(h->d_first, h->h_first.data(), sizeof(int32_t) * (size_t)q, hipMemcpyHostToDevice));
+        h->taps_p = p;
+        h->taps_q = q;
+    }
+    if (p == q) {
+        // same rate: the frames read the input itself; utterance offsets are the input's
+        for (int32_t i = 0; i < n; i++) h->h_utt[i].mid_off = h->h_utt[i].in_off;
+    }
+    AUDIO_TRY(hipMemcpyAsync(h->d_utt, h->h_utt, sizeof(Utterance) * (size_t)n, hipMemcpyHostToDevice, stream));
+    AUDIO_TRY(hipMemcpyAsync(h->d_starts, h->h_starts, sizeof(uint64_t) * 2 * (size_t)n, hipMemcpyHostToDevice, stream));
+    if (p != q) {
+        hipLaunchKernelGGL(resample_kernel, dim3((unsigned)((mid_total + 255) / 256)), dim3(256), 0, stream, waveforms,
+                           h->d_utt, h->d_starts, n, h->d_taps, h->d_first, p, q, h->n_taps, h->d_mid, mid_total);
+    }
+    const dim3 frame_grid((unsigned)((frames_total + 3) / 4));
+    if (p == q)
+        hipLaunchKernelGGL(log_mel_kernel<float>, frame_grid, dim3(kFrameThreads), 0, stream, waveforms, h->d_utt,
+                           h->d_starts + n, n, frames_total, h->cfg.hop, h->d_window, h->d_twiddle, h->mel,
+                           h->d_mel_weights, h->cfg.n_mels, out);
+    else
+        hipLaunchKernelGGL(log_mel_kernel<double>, frame_grid, dim3(kFrameThreads), 0, stream, (const double *)h->d_mid,
+                           h->d_utt, h->d_starts + n, n, frames_total, h->cfg.hop, h->d_window, h->d_twiddle, h->mel,
+                           h->d_mel_weights, h->cfg.n_mels, out);
+    hipLaunchKernelGGL(normalize_kernel, dim3((unsigned)n * (unsigned)h->cfg.n_mels), dim3(256), 0, stream, h->d_utt,
+                       h->cfg.n_mels, out);
+    AUDIO_TRY(hipGetLastError());
+    AUDIO_TRY(hipEventRecord(h->done, stream));
+    h->pending = true;
+    return PREP_OK;
+}
+
+}  // extern "C"
