@@ -408,6 +408,92 @@ def run_server(args, torch, prep, synth, make_params):
     print(json.dumps(result))
 
 
+def audio_batch(n=64, rate=44100, seed=6000):
+    """Seeded stand-in for a batch of speech utterances (the paper evaluates on LibriSpeech,
+    section 5; its Fig. 13 shows lengths of a few to 35 s with most between 10 and 17 s):
+    lengths from a clipped normal (12.3 s, 4 s), each a few drifting harmonics under a slow
+    envelope plus low-pass noise, float32, peak 0.5."""
+    rng = np.random.default_rng(seed)
+    waves = []
+    for k in range(n):
+        sec = float(np.clip(rng.normal(12.3, 4.0), 1.5, 35.0))
+        m = int(rate * sec)
+        t = np.arange(m) / rate
+        f0 = 110.0 + 60.0 * rng.random() + 20.0 * np.sin(2 * np.pi * (0.7 + rng.random()) * t)
+        phase = 2 * np.pi * np.cumsum(f0) / rate
+        x = np.zeros(m)
+        for h in range(1, 16):
+            x += rng.random() / (h ** 0.8) * np.sin(h * phase + rng.random() * 6.28)
+        x *= 0.55 + 0.45 * np.sin(2 * np.pi * 3.1 * t + rng.random() * 6.28)
+        x += 0.6 * np.convolve(rng.standard_normal(m + 15), np.hanning(16) / 8.0, mode="valid")
+        waves.append((0.5 * x / np.abs(x).max()).astype(np.float32))
+    return waves
+
+
+def run_audio(args, torch, prep):
+    """The audio path (resample 44.1 kHz -> 16 kHz, log-Mel spectrogram, normalize) on a batch
+    of 64 synthetic utterances resident in HBM; one step = the whole batch."""
+    rate_in = 44100
+    t0 = time.perf_counter()
+    waves = audio_batch(64, rate_in)
+    gen_s = time.perf_counter() - t0
+    offsets = np.zeros(len(waves) + 1, dtype=np.uint64)
+    np.cumsum([len(w) for w in waves], out=offsets[1:])
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(np.concatenate(waves)).to(dev)
+    ap = prep.AudioPreprocessor(max_batch=len(waves), max_total_samples=int(offsets[-1]))
+    frames = [ap.frames(len(w), rate_in) for w in waves]
+    out = torch.empty(80 * sum(frames), dtype=torch.float32, device=dev)
+    stream = torch.cuda.Stream(device=dev)
+    for _ in range(args.warmup):
+        ap.features(x.data_ptr(), offsets, rate_in, out.data_ptr(), stream.cuda_stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ap.features(x.data_ptr(), offsets, rate_in, out.data_ptr(), stream.cuda_stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    seconds_of_audio = float(offsets[-1]) / rate_in
+    # algorithmic work per step: double-precision operations of the definitions' fast forms
+    n_frames = sum(frames)
+    mid = sum(-(-len(w) * 160 // 441) for w in waves)
+    flops = mid * 2 * 34 + n_frames * (9 * 256 * 10 + 512 + 257 * 3 + 2 * 514)
+    traffic = int(offsets[-1]) * 4 + mid * 8 * 2 + n_frames * 80 * 4 * 3
+    cpu = None
+    if not args.no_cpu_baseline:
+        from concurrent.futures import ThreadPoolExecutor
+        from oracle import audio as oracle_audio
+        cores = min(16, len(os.sched_getaffinity(0)))
+        sample = sorted(waves, key=len)[:cores]  # the shortest: the oracle's resampler is a Python loop
+        t1 = time.perf_counter()
+        with ThreadPoolExecutor(cores) as ex:
+            list(ex.map(lambda w: oracle_audio.preprocess(w.astype(np.float64), rate_in), sample))
+        dt = time.perf_counter() - t1
+        cpu = {"value": len(sample) / dt, "unit": "utterances/s", "cores": cores, "kind": "oracle",
+               "sample": f"the {len(sample)} shortest utterances of the batch "
+                         f"({sum(len(w) for w in sample) / rate_in:.0f} s of audio), one per task, {cores} threads, "
+                         f"{dt:.1f} s wall", "audio_seconds_per_s": sum(len(w) for w in sample) / rate_in / dt}
+    ms = wall / args.steps * 1e3
+    result = {
+        "metric": "utterances/sec audio -> normalized log-Mel features on 1 MI355X", "value": len(waves) * args.steps / wall,
+        "unit": "utterances/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64 arithmetic, f32 in and out",
+        "data": "synthetic",
+        "config": {"workload": "audio: 64 utterances of 1.5-35 s (mean 12.3 s) at 44.1 kHz -> 16 kHz, 512-point "
+                               "frames of 400 samples every 160, 80 Mel channels, per-feature normalisation",
+                   "batch": len(waves), "audio_seconds": seconds_of_audio, "frames": n_frames,
+                   "realtime_factor": seconds_of_audio * args.steps / wall, "input": "resident in HBM",
+                   "input_generation_s": round(gen_s, 2)},
+        "roofline": {"bound": "alu", "achieved": flops / (ms * 1e-3) / 1e12, "peak": 78.6, "unit": "TFLOP/s",
+                     "frac": flops / (ms * 1e-3) / 1e12 / 78.6, "traffic": None,
+                     "kernel": "whole step (resample_kernel, log_mel_kernel, normalize_kernel)",
+                     "algorithmic_bytes": traffic, "hbm_frac_by_algorithmic_bytes": traffic / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result))
+    ap.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -425,6 +511,8 @@ def main():
     ap.add_argument("--poisson-rate", type=float, default=0.0,
                     help="workload 3: requests (batches) per second arriving as a Poisson process and "
                          "served by the next free stream; 0 = every stream runs back to back")
+    ap.add_argument("--audio", action="store_true",
+                    help="the audio path (resample, log-Mel spectrogram, normalize) instead of a JPEG workload")
     ap.add_argument("--server", action="store_true",
                     help="workload 3: single-image requests through the batching server (Batch_max, "
                          "Time_queue) with --streams consumers; needs --poisson-rate")
@@ -458,6 +546,9 @@ def main():
         import __graft_entry__
         __graft_entry__.build()
 
+    if args.audio:
+        run_audio(args, torch, prep)
+        return
     cfg = args.workload
     if cfg == 3:
         if args.server:

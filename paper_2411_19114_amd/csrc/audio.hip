@@ -45,8 +45,9 @@ struct Utterance {
 };
 
 // ---- resample -----------------------------------------------------------------------------
-// Output m = a q + r of an utterance (r < q) is sum_j x[a p + first[r] + j] taps[r][j]: the
-// taps depend on the phase r only.
+// Output m = a q + r of an utterance (r < q) is sum_j x[a p + first[r] + j] taps[j][r]: the
+// taps depend on the phase r only.  Neighbouring lanes have neighbouring phases, so tap j of
+// all phases is contiguous.
 __global__ __launch_bounds__(256) void resample_kernel(const float *__restrict__ in, const Utterance *__restrict__ utt,
                                                        const uint64_t *__restrict__ mid_start, int n_utt,
                                                        const double *__restrict__ taps, const int32_t *__restrict__ first,
@@ -66,86 +67,141 @@ __global__ __launch_bounds__(256) void resample_kernel(const float *__restrict__
     const uint32_t a = m / (uint32_t)q, r = m - a * (uint32_t)q;
     const int64_t n0 = (int64_t)a * p + first[r];
     const float *x = in + u.in_off;
-    const double *t = taps + (size_t)r * n_taps;
+    const double *t = taps + r;
     double acc = 0.0;
-    for (int j = 0; j < n_taps; j++) {
-        const int64_t n = n0 + j;
-        if (n >= 0 && n < (int64_t)u.in_len) acc = fma((double)x[n], t[j], acc);
+    if (n0 >= 0 && n0 + n_taps <= (int64_t)u.in_len) {
+        // every tap lies inside the utterance
+        const float *xs = x + n0;
+#pragma unroll 4
+        for (int j = 0; j < n_taps; j++) acc = fma((double)xs[j], t[(size_t)j * q], acc);
+    } else {
+        for (int j = 0; j < n_taps; j++) {
+            const int64_t n = n0 + j;
+            if (n >= 0 && n < (int64_t)u.in_len) acc = fma((double)x[n], t[(size_t)j * q], acc);
+        }
     }
     mid[g] = acc;
 }
 
 // ---- frames -> log-Mel --------------------------------------------------------------------
-__device__ __forceinline__ uint32_t reverse9(uint32_t v) { return __brev(v) >> 23; }
-
 struct MelTable {          // filter m covers bins start[m] .. start[m] + count[m] - 1
     int32_t start[kMaxMels], count[kMaxMels], first_weight[kMaxMels];
 };
 
-// One wave per frame.  frame_start[u] = first frame of utterance u among all frames.  Sample is
-// double for a resampled signal, float where the input is framed as it is.
+__device__ __forceinline__ double2 cadd(double2 a, double2 b) { return make_double2(a.x + b.x, a.y + b.y); }
+__device__ __forceinline__ double2 csub(double2 a, double2 b) { return make_double2(a.x - b.x, a.y - b.y); }
+__device__ __forceinline__ double2 cmul(double2 a, double2 b)
+{
+    return make_double2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
+}
+__device__ __forceinline__ double2 times_minus_i(double2 a) { return make_double2(a.y, -a.x); }
+
+// Forward DFT of four values: Y[k] = sum_n y[n] (-i)^(n k)
+__device__ __forceinline__ void dft4(const double2 y[4], double2 *Y0, double2 *Y1, double2 *Y2, double2 *Y3)
+{
+    const double2 s02 = cadd(y[0], y[2]), d02 = csub(y[0], y[2]);
+    const double2 s13 = cadd(y[1], y[3]), d13 = times_minus_i(csub(y[1], y[3]));
+    *Y0 = cadd(s02, s13);
+    *Y2 = csub(s02, s13);
+    *Y1 = cadd(d02, d13);
+    *Y3 = csub(d02, d13);
+}
+
+// Forward DFT of eight values in place, natural order: even outputs from x[n] + x[n+4], odd
+// ones from (x[n] - x[n+4]) W^n, W = exp(-2 pi i / 8).
+__device__ __forceinline__ void dft8(double2 v[8])
+{
+    constexpr double h = 0.70710678118654752440;
+    double2 e[4], o[4];
+#pragma unroll
+    for (int n = 0; n < 4; n++) {
+        e[n] = cadd(v[n], v[n + 4]);
+        o[n] = csub(v[n], v[n + 4]);
+    }
+    o[1] = make_double2(h * (o[1].x + o[1].y), h * (o[1].y - o[1].x));     // * (1 - i) / sqrt 2
+    o[2] = times_minus_i(o[2]);
+    o[3] = make_double2(h * (o[3].y - o[3].x), -h * (o[3].x + o[3].y));    // * (-1 - i) / sqrt 2
+    dft4(e, &v[0], &v[2], &v[4], &v[6]);
+    dft4(o, &v[1], &v[3], &v[5], &v[7]);
+}
+
+// LDS index of element i of a frame: one spare element after every eight keeps the eight lanes
+// that a 16-byte access serves per cycle on different banks in every pass.
+__device__ __forceinline__ int padded(int i) { return i + (i >> 3); }
+constexpr int kFramePadded = kFft + kFft / 8;
+
+// One wave per frame; a 512-point transform in three radix-8 passes (self-sorting: pass s reads
+// element j + 64 r, multiplies by W512^(r k 512 / (8 Ns)), k = j mod Ns, Ns = 8^s, transforms
+// the eight values and writes them Ns apart from (j / Ns) 8 Ns + k), each lane holding eight
+// values in registers; the first pass reads the signal itself.  frame_start[u] = first frame of
+// utterance u among all frames.  Sample is double for a resampled signal, float where the
+// input is framed as it is.
 template <typename Sample>
 __global__ __launch_bounds__(kFrameThreads) void log_mel_kernel(
     const Sample *__restrict__ mid, const Utterance *__restrict__ utt, const uint64_t *__restrict__ frame_start,
     int n_utt, uint64_t n_frames, int hop, const double *__restrict__ window, const double2 *__restrict__ twiddle,
     MelTable mel, const double *__restrict__ mel_weights, int n_mels, float *__restrict__ out)
 {
-    __shared__ double2 s_x[kFrameThreads / 64][kFft];
+    __shared__ double2 s_x[kFrameThreads / 64][kFramePadded];
     __shared__ double s_power[kFrameThreads / 64][kFft / 2 + 1];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const uint64_t f = (uint64_t)blockIdx.x * (kFrameThreads / 64) + wave;
-    const bool live = f < n_frames;   // every wave keeps to the barriers
-    Utterance u;
-    uint32_t t = 0;
-    if (live) {
-        int lo = 0, hi = n_utt - 1;
-        while (lo < hi) {
-            const int m = (lo + hi + 1) >> 1;
-            if (frame_start[m] <= f) lo = m; else hi = m - 1;
-        }
-        u = utt[lo];
-        t = (uint32_t)(f - frame_start[lo]);
+    if (f >= n_frames) return;   // no workgroup-wide barrier below: a wave works on its own frame
+    int lo = 0, hi = n_utt - 1;
+    while (lo < hi) {
+        const int m = (lo + hi + 1) >> 1;
+        if (frame_start[m] <= f) lo = m; else hi = m - 1;
     }
+    const Utterance u = utt[lo];
+    const uint32_t t = (uint32_t)(f - frame_start[lo]);
     double2 *x = s_x[wave];
-    if (live) {
+    double2 v[8];
+    {
         const Sample *sig = mid + u.mid_off;
         const int64_t len = (int64_t)u.mid_len;
-        for (int j = lane; j < kFft; j += 64) {
+#pragma unroll
+        for (int r = 0; r < 8; r++) {
+            const int j = lane + 64 * r;
             int64_t s = (int64_t)t * hop + j - kFft / 2;
             if (s < 0) s = -s;                       // reflection about the first sample
             if (s >= len) s = 2 * (len - 1) - s;     // and about the last (len > n_fft / 2)
-            x[reverse9((uint32_t)j)] = make_double2((double)sig[s] * window[j], 0.0);
+            v[r] = make_double2((double)sig[s] * window[j], 0.0);
         }
     }
-    __syncthreads();
-    // radix-2, decimation in time: stage with butterflies `half` apart, 256 per stage
-    for (int half = 1; half < kFft; half <<= 1) {
-        if (live) {
-            const int step = (kFft / 2) / half;      // twiddle stride: W^(pos * 512 / (2 half))
-            for (int b = lane; b < kFft / 2; b += 64) {
-                const int pos = b & (half - 1);
-                const int i0 = ((b - pos) << 1) + pos, i1 = i0 + half;
-                const double2 w = twiddle[pos * step];
-                const double2 a = x[i0], c = x[i1];
-                const double2 wc = make_double2(w.x * c.x - w.y * c.y, w.x * c.y + w.y * c.x);
-                x[i0] = make_double2(a.x + wc.x, a.y + wc.y);
-                x[i1] = make_double2(a.x - wc.x, a.y - wc.y);
-            }
+    dft8(v);
+#pragma unroll
+    for (int r = 0; r < 8; r++) x[padded(lane * 8 + r)] = v[r];
+    // the accesses of one wave to LDS complete in order; the fence keeps the compiler from
+    // moving loads over the stores
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+    for (int pass = 1; pass < 3; pass++) {
+        const int ns = pass == 1 ? 8 : 64;
+        const int k = lane & (ns - 1);
+#pragma unroll
+        for (int r = 0; r < 8; r++) v[r] = x[padded(lane + 64 * r)];
+#pragma unroll
+        for (int r = 1; r < 8; r++) v[r] = cmul(v[r], twiddle[r * k * (kFft / (8 * ns))]);
+        dft8(v);
+        if (pass == 1) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            const int j0 = (lane >> 3) * 64 + k;
+#pragma unroll
+            for (int r = 0; r < 8; r++) x[padded(j0 + 8 * r)] = v[r];
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         }
-        __syncthreads();
     }
-    if (live) {
-        for (int k = lane; k <= kFft / 2; k += 64) s_power[wave][k] = x[k].x * x[k].x + x[k].y * x[k].y;  // double
-    }
-    __syncthreads();
-    if (live) {
-        for (int m = lane; m < n_mels; m += 64) {
-            const double *w = mel_weights + mel.first_weight[m];
-            const double *pw = s_power[wave] + mel.start[m];
-            double acc = 0.0;
-            for (int k = 0; k < mel.count[m]; k++) acc = fma(w[k], pw[k], acc);
-            out[u.out_off + (uint64_t)m * u.frames + t] = (float)log(acc + (double)kLogGuard);
-        }
+    // after the last pass value r of lane j is bin j + 64 r: bins 0 .. 255, and 256 in lane 0
+#pragma unroll
+    for (int r = 0; r < 4; r++) s_power[wave][lane + 64 * r] = v[r].x * v[r].x + v[r].y * v[r].y;
+    if (lane == 0) s_power[wave][kFft / 2] = v[4].x * v[4].x + v[4].y * v[4].y;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    for (int m = lane; m < n_mels; m += 64) {
+        const double *w = mel_weights + mel.first_weight[m];
+        const double *pw = s_power[wave] + mel.start[m];
+        double acc = 0.0;
+        for (int k = 0; k < mel.count[m]; k++) acc = fma(w[k], pw[k], acc);
+        out[u.out_off + (uint64_t)m * u.frames + t] = (float)log(acc + (double)kLogGuard);
     }
 }
 
@@ -246,7 +302,7 @@ namespace {
 
 uint64_t resampled_length(uint64_t len, int p, int q) { return (len * (uint64_t)q + (uint64_t)p - 1) / (uint64_t)p; }
 
-// taps[r][j] = h((first[r] + j) / p - r / q) for phase r of p : q (input : output rate, reduced)
+// taps[j][r] = h((first[r] + j) / p - r / q) for phase r of p : q (input : output rate, reduced)
 void make_taps(int p, int q, std::vector<double> *taps, std::vector<int32_t> *first, int *n_taps)
 {
     const double base = kRolloff * std::min(p, q);
@@ -268,7 +324,7 @@ void make_taps(int p, int q, std::vector<double> *taps, std::vector<int32_t> *fi
             const double uarg = base * ((double)n / p - (double)r / q);
             if (fabs(uarg) < kZeroCrossings && n <= last[(size_t)r]) {
                 const double c = cos(M_PI * uarg / (2.0 * kZeroCrossings));
-                (*taps)[(size_t)r * width + j] = (base / p) * sinc(uarg) * c * c;
+                (*taps)[(size_t)j * q + r] = (base / p) * sinc(uarg) * c * c;
             }
         }
 }
@@ -306,8 +362,8 @@ int prep_audio_create(prep_audio **out, const prep_audio_config *cfg)
     const int left = (kFft - cfg->win_length) / 2;
     for (int i = 0; i < cfg->win_length; i++)
         window[(size_t)(left + i)] = 0.5 - 0.5 * cos(2.0 * M_PI * i / cfg->win_length);
-    std::vector<double2> tw((size_t)kFft / 2);
-    for (int k = 0; k < kFft / 2; k++)
+    std::vector<double2> tw((size_t)kFft);  // W^k = exp(-2 pi i k / 512), k = 0 .. 511 (r k reaches 7 * 63)
+    for (int k = 0; k < kFft; k++)
         tw[(size_t)k] = make_double2(cos(2.0 * M_PI * k / kFft), -sin(2.0 * M_PI * k / kFft));
     std::vector<double> weights;
     {
@@ -337,7 +393,7 @@ int prep_audio_create(prep_audio **out, const prep_audio_config *cfg)
     const size_t n = (size_t)cfg->max_batch;
     bool ok = hipSetDevice(cfg->device) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_window, sizeof(double) * kFft) == hipSuccess;
-    ok = ok && hipMalloc((void **)&h->d_twiddle, sizeof(double2) * kFft / 2) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_twiddle, sizeof(double2) * kFft) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_mel_weights, sizeof(double) * weights.size()) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_utt, sizeof(Utterance) * n) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_starts, sizeof(uint64_t) * 2 * n) == hipSuccess;
@@ -347,7 +403,7 @@ int prep_audio_create(prep_audio **out, const prep_audio_config *cfg)
     ok = ok && hipMalloc((void **)&h->d_mid, sizeof(double) * (cfg->max_total_samples + n)) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&h->done, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipMemcpy(h->d_window, window.data(), sizeof(double) * kFft, hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && hipMemcpy(h->d_twiddle, tw.data(), sizeof(double2) * kFft / 2, hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(h->d_twiddle, tw.data(), sizeof(double2) * kFft, hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(h->d_mel_weights, weights.data(), sizeof(double) * weights.size(), hipMemcpyHostToDevice) == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
