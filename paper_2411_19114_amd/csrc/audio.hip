@@ -83,6 +83,54 @@ __global__ __launch_bounds__(256) void resample_kernel(const float *__restrict__
     mid[g] = acc;
 }
 
+// The same sum with the taps in registers: a thread keeps one phase r for all its outputs (the
+// workgroup has a multiple of q threads and steps over whole multiples of q outputs), so its
+// taps are loaded once and only the signal is read in the loop.  tile_start[u] = first
+// workgroup of utterance u; a workgroup makes kTilesPerWg * blockDim.x consecutive outputs.
+constexpr int kMaxTaps = 40;
+constexpr int kTilesPerWg = 8;
+
+__global__ __launch_bounds__(512) void resample_phase_kernel(
+    const float *__restrict__ in, const Utterance *__restrict__ utt, const uint64_t *__restrict__ tile_start,
+    int n_utt, const double *__restrict__ taps, const int32_t *__restrict__ first, int p, int q, int n_taps,
+    double *__restrict__ mid)
+{
+    int lo = 0, hi = n_utt - 1;
+    while (lo < hi) {
+        const int m = (lo + hi + 1) >> 1;
+        if (tile_start[m] <= blockIdx.x) lo = m; else hi = m - 1;
+    }
+    const Utterance u = utt[lo];
+    const uint32_t r = threadIdx.x % (uint32_t)q, sub = threadIdx.x / (uint32_t)q;
+    const uint32_t per_tile = blockDim.x / (uint32_t)q;            // blocks of q outputs per tile
+    double tap[kMaxTaps];
+#pragma unroll
+    for (int j = 0; j < kMaxTaps; j++) tap[j] = j < n_taps ? taps[(size_t)j * q + r] : 0.0;
+    const float *x = in + u.in_off;
+    double *y = mid + u.mid_off;
+    // a = index of the block of q outputs
+    uint32_t a = ((uint32_t)(blockIdx.x - tile_start[lo]) * kTilesPerWg) * per_tile + sub;
+    const int32_t f = first[r];
+    for (int it = 0; it < kTilesPerWg; it++, a += per_tile) {
+        const uint64_t m = (uint64_t)a * (uint32_t)q + r;
+        if (m >= u.mid_len) break;
+        const int64_t n0 = (int64_t)a * p + f;
+        double acc = 0.0;
+        if (n0 >= 0 && n0 + kMaxTaps <= (int64_t)u.in_len) {
+            const float *xs = x + n0;
+#pragma unroll
+            for (int j = 0; j < kMaxTaps; j++) acc = fma((double)xs[j], tap[j], acc);
+        } else {
+#pragma unroll
+            for (int j = 0; j < kMaxTaps; j++) {
+                const int64_t n = n0 + j;
+                if (n >= 0 && n < (int64_t)u.in_len) acc = fma((double)x[n], tap[j], acc);
+            }
+        }
+        y[m] = acc;
+    }
+}
+
 // ---- frames -> log-Mel --------------------------------------------------------------------
 struct MelTable {          // filter m covers bins start[m] .. start[m] + count[m] - 1
     int32_t start[kMaxMels], count[kMaxMels], first_weight[kMaxMels];
@@ -196,12 +244,19 @@ __global__ __launch_bounds__(kFrameThreads) void log_mel_kernel(
     for (int r = 0; r < 4; r++) s_power[wave][lane + 64 * r] = v[r].x * v[r].x + v[r].y * v[r].y;
     if (lane == 0) s_power[wave][kFft / 2] = v[4].x * v[4].x + v[4].y * v[4].y;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    for (int m = lane; m < n_mels; m += 64) {
-        const double *w = mel_weights + mel.first_weight[m];
-        const double *pw = s_power[wave] + mel.start[m];
-        double acc = 0.0;
-        for (int k = 0; k < mel.count[m]; k++) acc = fma(w[k], pw[k], acc);
-        out[u.out_off + (uint64_t)m * u.frames + t] = (float)log(acc + (double)kLogGuard);
+    // The triangles widen with their number, so a lane takes a narrow one and then the wide one
+    // that mirrors it (m and n_mels - 1 - m): every busy lane sums about the same number of bins.
+    for (int i = lane; i < (n_mels + 1) / 2; i += 64) {
+#pragma unroll
+        for (int side = 0; side < 2; side++) {
+            const int m = side == 0 ? i : n_mels - 1 - i;
+            if (side == 1 && m == i) break;  // the middle one of an odd number
+            const double *w = mel_weights + mel.first_weight[m];
+            const double *pw = s_power[wave] + mel.start[m];
+            double acc = 0.0;
+            for (int k = 0; k < mel.count[m]; k++) acc = fma(w[k], pw[k], acc);
+            out[u.out_off + (uint64_t)m * u.frames + t] = (float)log(acc + (double)kLogGuard);
+        }
     }
 }
 
@@ -282,7 +337,7 @@ struct prep_audio {
     size_t taps_cap = 0;
     // per call
     Utterance *h_utt = nullptr, *d_utt = nullptr;
-    uint64_t *h_starts = nullptr, *d_starts = nullptr;  // [mid_start n][frame_start n]
+    uint64_t *h_starts = nullptr, *d_starts = nullptr;  // [mid_start n][frame_start n][tile_start n]
     double *d_mid = nullptr;
     hipEvent_t done = nullptr;
     bool pending = false;
@@ -396,9 +451,9 @@ int prep_audio_create(prep_audio **out, const prep_audio_config *cfg)
     ok = ok && hipMalloc((void **)&h->d_twiddle, sizeof(double2) * kFft) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_mel_weights, sizeof(double) * weights.size()) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_utt, sizeof(Utterance) * n) == hipSuccess;
-    ok = ok && hipMalloc((void **)&h->d_starts, sizeof(uint64_t) * 2 * n) == hipSuccess;
+    ok = ok && hipMalloc((void **)&h->d_starts, sizeof(uint64_t) * 3 * n) == hipSuccess;
     ok = ok && hipHostMalloc((void **)&h->h_utt, sizeof(Utterance) * n, hipHostMallocDefault) == hipSuccess;
-    ok = ok && hipHostMalloc((void **)&h->h_starts, sizeof(uint64_t) * 2 * n, hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipHostMalloc((void **)&h->h_starts, sizeof(uint64_t) * 3 * n, hipHostMallocDefault) == hipSuccess;
     // the resampled signal is never longer than max_total_samples scaled by the largest ratio accepted
     ok = ok && hipMalloc((void **)&h->d_mid, sizeof(double) * (cfg->max_total_samples + n)) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&h->done, hipEventDisableTiming) == hipSuccess;
@@ -450,7 +505,10 @@ int prep_audio_features(prep_audio *h, const float *waveforms, const uint64_t *o
         AUDIO_TRY(hipEventSynchronize(h->done));
         h->pending = false;
     }
-    uint64_t mid_total = 0, frames_total = 0, out_total = 0;
+    uint64_t mid_total = 0, frames_total = 0, out_total = 0, tiles_total = 0;
+    // threads per workgroup of the resampler that keeps its taps in registers: a multiple of q
+    const uint32_t phase_threads = q <= 320 ? (uint32_t)q * (uint32_t)std::max(1, 320 / q) : 0u;
+    const uint64_t per_wg = (uint64_t)phase_threads * kTilesPerWg;
     for (int32_t i = 0; i < n; i++) {
         if (offsets[i + 1] < offsets[i] || offsets[i + 1] - offsets[i] > 0xFFFFFFFFull) return PREP_E_INVALID_ARG;
         Utterance &u = h->h_utt[i];
@@ -466,6 +524,8 @@ int prep_audio_features(prep_audio *h, const float *waveforms, const uint64_t *o
         u.pad_ = 0;
         h->h_starts[i] = mid_total;
         h->h_starts[(size_t)n + i] = frames_total;
+        h->h_starts[2 * (size_t)n + i] = tiles_total;
+        if (per_wg) tiles_total += (len + per_wg - 1) / per_wg;
         mid_total += len;
         frames_total += u.frames;
         out_total += (uint64_t)u.frames * (uint64_t)h->cfg.n_mels;
@@ -501,8 +561,11 @@ int prep_audio_features(prep_audio *h, const float *waveforms, const uint64_t *o
         for (int32_t i = 0; i < n; i++) h->h_utt[i].mid_off = h->h_utt[i].in_off;
     }
     AUDIO_TRY(hipMemcpyAsync(h->d_utt, h->h_utt, sizeof(Utterance) * (size_t)n, hipMemcpyHostToDevice, stream));
-    AUDIO_TRY(hipMemcpyAsync(h->d_starts, h->h_starts, sizeof(uint64_t) * 2 * (size_t)n, hipMemcpyHostToDevice, stream));
-    if (p != q) {
+    AUDIO_TRY(hipMemcpyAsync(h->d_starts, h->h_starts, sizeof(uint64_t) * 3 * (size_t)n, hipMemcpyHostToDevice, stream));
+    if (p != q && phase_threads && h->n_taps <= kMaxTaps && tiles_total <= 0x7FFFFFFFull) {
+        hipLaunchKernelGGL(resample_phase_kernel, dim3((unsigned)tiles_total), dim3(phase_threads), 0, stream, waveforms,
+                           h->d_utt, h->d_starts + 2 * n, n, h->d_taps, h->d_first, p, q, h->n_taps, h->d_mid);
+    } else if (p != q) {
         hipLaunchKernelGGL(resample_kernel, dim3((unsigned)((mid_total + 255) / 256)), dim3(256), 0, stream, waveforms,
                            h->d_utt, h->d_starts, n, h->d_taps, h->d_first, p, q, h->n_taps, h->d_mid, mid_total);
     }
