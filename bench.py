@@ -352,18 +352,24 @@ def run_server(args, torch, prep, synth, make_params):
         if (k + 1) % (n_consumers * args.batch_max) == 0:
             time.sleep(0.03)
     for _ in range(n_warm):
-        assert server.next(5000000) is not None, "warm-up request lost"
+        r = server.next(5000000)
+        assert r is not None, "warm-up request lost"
+        server.release(r)
     arrivals = np.cumsum(np.random.default_rng(3000).exponential(1.0 / rate, size=n_warm + n_req))
     arrivals[n_warm:] -= arrivals[n_warm]
     results = []
     refused = [0]
 
     def collect():
+        from paper_2411_19114_amd.binding import ServerResult
+        buf = (ServerResult * 256)()
         while len(results) + refused[0] < n_req:
-            r = server.next(2000000)
-            if r is None:
+            k = server.next_many(buf, 2000000)
+            if k == 0:
                 break
-            results.append((r.tag, r.status, r.batch_size, r.arrival_ns, r.start_ns, r.done_ns))
+            for r in buf[:k]:
+                results.append((r.tag, r.status, r.batch_size, r.arrival_ns, r.start_ns, r.done_ns))
+            server.release_many(buf, k)
 
     col = threading.Thread(target=collect)
     col.start()

@@ -268,10 +268,10 @@ typedef struct {
     int32_t status;            /* PREP_OK or the image's error                   */
     int32_t batch_size;        /* size of the batch it was served in             */
     int32_t consumer;          /* which consumer served it                       */
-    int32_t reserved;
+    int32_t slot;              /* which of the consumer's output buffers holds it */
     int64_t arrival_ns, start_ns, done_ns; /* steady clock: submitted, batch taken, tensor ready */
-    const void *tensor;        /* DEVICE: this request's slab; valid until the same
-                                * consumer has finished two more batches          */
+    const void *tensor;        /* DEVICE: this request's slab, valid until
+                                * prep_server_release                             */
 } prep_server_result;
 
 int prep_server_create(prep_server **out, const prep_server_config *cfg);
@@ -281,8 +281,16 @@ int prep_server_destroy(prep_server *s);
  * PREP_E_TOO_LARGE: the file is larger than max_request_bytes or the queue is full. */
 int prep_server_submit(prep_server *s, const uint8_t *jpeg, uint64_t len, uint64_t tag);
 /* Next finished request, in order of completion: 1 and *out filled, 0 after
- * timeout_us without one, negative on bad arguments.                          */
+ * timeout_us without one, negative on bad arguments.  Every result must be
+ * given back with prep_server_release: a consumer has three output buffers
+ * and reuses one only when all results of the batch it held are released.     */
 int prep_server_next(prep_server *s, prep_server_result *out, int64_t timeout_us);
+/* The caller is done with the result's tensor.                                */
+int prep_server_release(prep_server *s, const prep_server_result *r);
+/* The same for several results at once: up to cap finished requests into out
+ * (HOST), waiting at most timeout_us for the first; returns their number.     */
+int32_t prep_server_next_many(prep_server *s, prep_server_result *out, int32_t cap, int64_t timeout_us);
+int prep_server_release_many(prep_server *s, const prep_server_result *r, int32_t n);
 /* Copies a finished request's tensor slab (3*crop_h*crop_w elements of the
  * configured dtype) to host_out (HOST); for checks, while the slab is valid.  */
 int prep_server_copy_tensor(prep_server *s, const prep_server_result *r, void *host_out);

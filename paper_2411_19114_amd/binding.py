@@ -61,7 +61,7 @@ class ServerConfig(C.Structure):
 
 class ServerResult(C.Structure):
     _fields_ = [("tag", C.c_uint64), ("status", C.c_int32), ("batch_size", C.c_int32), ("consumer", C.c_int32),
-                ("reserved", C.c_int32), ("arrival_ns", C.c_int64), ("start_ns", C.c_int64),
+                ("slot", C.c_int32), ("arrival_ns", C.c_int64), ("start_ns", C.c_int64),
                 ("done_ns", C.c_int64), ("tensor", C.c_void_p)]
 
 
@@ -85,7 +85,8 @@ EXPORTS = [
     "prep_debug_last_rgb", "prep_debug_last_region", "prep_stage_ms", "prep_set_timing",
     "prep_policy_create", "prep_policy_destroy", "prep_policy_arrive", "prep_policy_deadline",
     "prep_policy_take", "prep_policy_pending", "prep_server_create", "prep_server_destroy",
-    "prep_server_submit", "prep_server_next", "prep_server_copy_tensor",
+    "prep_server_submit", "prep_server_next", "prep_server_release", "prep_server_next_many",
+    "prep_server_release_many", "prep_server_copy_tensor",
     "prep_audio_create", "prep_audio_destroy", "prep_audio_frames", "prep_audio_features",
 ]
 
@@ -143,6 +144,9 @@ def lib():
         L.prep_server_submit.argtypes = [vp, vp, C.c_uint64, C.c_uint64]
         L.prep_server_next.argtypes = [vp, C.POINTER(ServerResult), C.c_int64]
         L.prep_server_copy_tensor.argtypes = [vp, C.POINTER(ServerResult), vp]
+        L.prep_server_release.argtypes = [vp, C.POINTER(ServerResult)]
+        L.prep_server_next_many.argtypes = [vp, C.POINTER(ServerResult), C.c_int32, C.c_int64]
+        L.prep_server_release_many.argtypes = [vp, C.POINTER(ServerResult), C.c_int32]
         L.prep_audio_create.argtypes = [C.POINTER(vp), C.POINTER(AudioConfig)]
         L.prep_audio_destroy.argtypes = [vp]
         L.prep_audio_frames.argtypes = [C.POINTER(AudioConfig), C.c_uint64, C.c_int32]
@@ -350,6 +354,20 @@ class Server:
         if got < 0:
             raise PrepError(int(got), "prep_server_next")
         return r if got else None
+
+    def next_many(self, results, timeout_us=1000000):
+        """Fills `results` (a ctypes array of ServerResult) with finished requests; returns how many."""
+        n = lib().prep_server_next_many(self._s, results, len(results), int(timeout_us))
+        if n < 0:
+            raise PrepError(int(n), "prep_server_next_many")
+        return int(n)
+
+    def release_many(self, results, n):
+        _check(lib().prep_server_release_many(self._s, results, int(n)), "prep_server_release_many")
+
+    def release(self, result):
+        """The caller is done with the result's tensor (every result must be released)."""
+        _check(lib().prep_server_release(self._s, C.byref(result)), "prep_server_release")
 
     def copy_tensor(self, result):
         out = np.empty(self._shape, dtype=self._dtype)

@@ -33,6 +33,19 @@ int64_t deadline_of(const prep_policy &p)
     return due;
 }
 
+// Timed wait on a condition variable.  The steady clock is the right one; a build for a
+// sanitizer whose runtime does not know the steady-clock wait of the C library defines
+// PREP_WAIT_ON_SYSTEM_CLOCK and waits on the system clock instead.
+template <typename Lock>
+void wait_ns(std::condition_variable &cv, Lock &lock, int64_t ns)
+{
+#ifdef PREP_WAIT_ON_SYSTEM_CLOCK
+    cv.wait_until(lock, std::chrono::system_clock::now() + std::chrono::nanoseconds(ns));
+#else
+    cv.wait_for(lock, std::chrono::nanoseconds(ns));
+#endif
+}
+
 int64_t now_ns()
 {
     return std::chrono::duration_cast<std::chrono::nanoseconds>(
@@ -89,7 +102,7 @@ int32_t prep_policy_pending(const prep_policy *p) { return p ? (int32_t)p->queue
 // ---- the server -------------------------------------------------------------------------------
 namespace {
 
-constexpr int kOutputSlots = 3;  // a tensor stays valid while its consumer finishes two more batches
+constexpr int kOutputSlots = 3;  // output buffers per consumer; one is reused when its results are released
 
 struct Request {
     uint64_t tag = 0;
@@ -102,6 +115,7 @@ struct Consumer {
     prep_handle *handle = nullptr;
     hipStream_t stream = nullptr;
     void *d_out[kOutputSlots] = {nullptr, nullptr, nullptr};
+    int32_t unreleased[kOutputSlots] = {0, 0, 0};  // results of the slot's batch still with the caller
     int slot = 0;
     std::vector<uint8_t> bits;       // the batch's files back to back
     std::vector<uint64_t> offsets;
@@ -120,7 +134,9 @@ struct prep_server {
     prep_policy *policy = nullptr;
     std::vector<Request> requests;   // pool; a request's id in the policy is its index here
     std::vector<uint32_t> free_requests;
-    std::deque<prep_server_result> results;
+    struct Finished { prep_server_result result; uint32_t request; };
+    std::deque<Finished> results;
+    std::condition_variable slot_free;
     std::vector<Consumer> consumers;
     bool stopping = false;
     int failed = PREP_OK;            // first batch-level failure of a consumer
@@ -143,7 +159,7 @@ void consume(prep_server *s, int ci)
             if (due == std::numeric_limits<int64_t>::max())
                 s->work.wait(lock);
             else
-                s->work.wait_for(lock, std::chrono::nanoseconds(std::max<int64_t>(due - now_ns(), 0)));
+                wait_ns(s->work, lock, std::max<int64_t>(due - now_ns(), 0));
         }
         if (s->stopping || n < 0) return;
         const int64_t start = now_ns();
@@ -155,13 +171,18 @@ void consume(prep_server *s, int ci)
             at += r.len;
         }
         c.offsets[(size_t)n] = at;
+        // the output buffer whose turn it is; the caller may still hold tensors of the batch
+        // that used it last
+        const int slot = c.slot;
+        c.slot = (c.slot + 1) % kOutputSlots;
+        while (c.unreleased[slot] != 0 && !s->stopping) s->slot_free.wait(lock);
+        if (s->stopping) return;
         lock.unlock();
         for (int32_t i = 0; i < n; i++) {
             const Request &r = s->requests[(size_t)c.ids[(size_t)i]];
             memcpy(c.bits.data() + c.offsets[(size_t)i], r.bytes.data(), r.len);
         }
-        void *out = c.d_out[c.slot];
-        c.slot = (c.slot + 1) % kOutputSlots;
+        void *out = c.d_out[slot];
         int rc = prep_decode_resize_batch(c.handle, c.bits.data(), c.offsets.data(), n, &s->cfg.params, out,
                                           c.stream);
         if (rc == PREP_OK) rc = prep_get_status(c.handle, c.status.data(), n);  // waits for the stream
@@ -177,12 +198,13 @@ void consume(prep_server *s, int ci)
             res.status = rc != PREP_OK ? rc : c.status[(size_t)i];
             res.batch_size = n;
             res.consumer = ci;
-            res.reserved = (int32_t)id;  // the request's place is given back when the result is read
+            res.slot = slot;
             res.arrival_ns = r.arrival;
             res.start_ns = start;
             res.done_ns = done;
             res.tensor = static_cast<const uint8_t *>(out) + (size_t)i * s->slab_bytes;
-            s->results.push_back(res);
+            s->results.push_back({res, id});  // the request's place is given back when the result is read
+            c.unreleased[slot]++;
         }
         s->results_ready.notify_all();
     }
@@ -254,6 +276,7 @@ int prep_server_destroy(prep_server *s)
     }
     s->work.notify_all();
     s->results_ready.notify_all();
+    s->slot_free.notify_all();
     for (Consumer &c : s->consumers) {
         if (c.thread.joinable()) c.thread.join();
         if (c.handle) prep_destroy(c.handle);
@@ -308,15 +331,60 @@ int prep_server_next(prep_server *s, prep_server_result *out, int64_t timeout_us
 {
     if (!s || !out || timeout_us < 0) return PREP_E_INVALID_ARG;
     std::unique_lock<std::mutex> lock(s->m);
-    if (!s->results_ready.wait_for(lock, std::chrono::microseconds(timeout_us),
-                                   [&] { return !s->results.empty() || s->stopping; }))
-        return 0;
+    const int64_t until = now_ns() + timeout_us * 1000;
+    while (s->results.empty() && !s->stopping) {
+        const int64_t left = until - now_ns();
+        if (left <= 0) return 0;
+        wait_ns(s->results_ready, lock, left);
+    }
     if (s->results.empty()) return 0;
-    *out = s->results.front();
+    *out = s->results.front().result;
+    s->free_requests.push_back(s->results.front().request);
     s->results.pop_front();
-    s->free_requests.push_back((uint32_t)out->reserved);
-    out->reserved = 0;
     return 1;
+}
+
+int32_t prep_server_next_many(prep_server *s, prep_server_result *out, int32_t cap, int64_t timeout_us)
+{
+    if (!s || !out || cap < 1 || timeout_us < 0) return PREP_E_INVALID_ARG;
+    std::unique_lock<std::mutex> lock(s->m);
+    const int64_t until = now_ns() + timeout_us * 1000;
+    while (s->results.empty() && !s->stopping) {
+        const int64_t left = until - now_ns();
+        if (left <= 0) return 0;
+        wait_ns(s->results_ready, lock, left);
+    }
+    int32_t n = 0;
+    while (n < cap && !s->results.empty()) {
+        out[n++] = s->results.front().result;
+        s->free_requests.push_back(s->results.front().request);
+        s->results.pop_front();
+    }
+    return n;
+}
+
+int prep_server_release_many(prep_server *s, const prep_server_result *r, int32_t n)
+{
+    if (!s || !r || n < 0) return PREP_E_INVALID_ARG;
+    int rc = PREP_OK;
+    {
+        std::lock_guard<std::mutex> lock(s->m);
+        for (int32_t i = 0; i < n; i++) {
+            if (r[i].consumer < 0 || r[i].consumer >= (int32_t)s->consumers.size() || r[i].slot < 0 ||
+                r[i].slot >= kOutputSlots || s->consumers[(size_t)r[i].consumer].unreleased[r[i].slot] <= 0) {
+                rc = PREP_E_INVALID_ARG;
+                continue;
+            }
+            s->consumers[(size_t)r[i].consumer].unreleased[r[i].slot]--;
+        }
+    }
+    s->slot_free.notify_all();
+    return rc;
+}
+
+int prep_server_release(prep_server *s, const prep_server_result *r)
+{
+    return prep_server_release_many(s, r, r ? 1 : -1);
 }
 
 }  // extern "C"

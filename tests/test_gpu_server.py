@@ -29,6 +29,7 @@ def _collect(server, n, timeout_s=60.0):
         r = server.next(200000)
         if r is not None:
             got.append((r, server.copy_tensor(r) if r.status == 0 else None))
+            server.release(r)
     return got
 
 
