@@ -375,10 +375,10 @@ __device__ __forceinline__ uint32_t clean_index(uint32_t w)
 // (F.2.2.1 EXTEND); adv = code length + s
 __device__ __forceinline__ int32_t coefficient_value(uint32_t win, uint32_t adv, uint32_t s)
 {
-    const uint32_t after = win << (adv - s);            // the appended bits, left-aligned
-    const uint32_t mag = (after >> 1) >> (s ^ 31u);     // RECEIVE(s); 31 - s without a borrow; 0 for s = 0
-    const uint32_t positive = (uint32_t)((int32_t)after >> 31);  // all ones if the first bit is 1
-    return (int32_t)(mag - (((1u << s) - 1u) & ~positive));      // EXTEND: negative values lie 2^s - 1 lower
+    const uint32_t mag = __builtin_amdgcn_ubfe(win, 32u - adv, s);  // RECEIVE(s): the s bits after the code; 0 for s = 0
+    const int32_t lower = (int32_t)((0xFFFFFFFFu << s) + 1u);       // -(2^s - 1)
+    // EXTEND: a value whose first appended bit is 0 (2 mag < 2^s) lies 2^s - 1 lower
+    return (int32_t)mag + ((int32_t)(mag << 1) + lower > 0 ? 0 : lower);
 }
 
 // Decode from packed state `st` until the bit position reaches end_bit.
@@ -525,13 +525,17 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
 __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const Geometry &g, uint32_t st,
                                                     uint32_t end_bit, uint32_t *nblk, WriteCtx *wc)
 {
-    uint32_t p = st >> 9, blk = (st >> 6) & 7u, zz = st & 63u;
-    uint32_t done = 0;
-    uint32_t boff = wc->block * 64u;
+    uint32_t p = st >> 9, blk = (st >> 6) & 7u;
+    // Where the next symbol starts counting, as one number: 64 * (block of the image) + zig-zag
+    // index.  A symbol's coefficient index is clamped to 63, so one past the coefficient of a
+    // symbol that ends its block is the first coefficient of the next block by itself.  The
+    // count of completed blocks is how far the block has moved at the end.
+    const uint32_t first_block = wc->block;
+    uint32_t at = (first_block << 6) | (st & 63u);
     const uint32_t last = g.n_blocks * 64u - 1u;
     const uint16_t *lut = S.tab.lut;
     const uint32_t chroma_tb = 2u << kLutBits, ac_bit = 1u << kLutBits;
-    uint32_t tb = (blk >= g.n_luma ? chroma_tb : 0u) | (zz ? ac_bit : 0u);
+    uint32_t tb = (blk >= g.n_luma ? chroma_tb : 0u) | ((st & 63u) ? ac_bit : 0u);
     int32_t broken = 0;
     uint32_t over = 0;
     uint32_t w = p >> 5;
@@ -556,9 +560,11 @@ __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const
     // is padding, or nothing at all
     while (p + (e >> 11) <= end_bit) {
         const uint32_t adv = e >> 11;
-        const uint32_t k = zz + ((e >> 4) & 63u);  // index of the symbol's coefficient
+        const uint32_t k = (at & 63u) + ((e >> 4) & 63u);  // index of the symbol's coefficient
         // every symbol stores (see decode_span)
-        wc->coef[min(boff + min(k, 63u), last)] = (int16_t)coefficient_value(win, adv, e & 15u);
+        const uint32_t here = (at & ~63u) | min(k, 63u);
+        wc->coef[min(here, last)] = (int16_t)coefficient_value(win, adv, e & 15u);
+        at = here + 1u;
         over |= (e >> 4) & k;
         p += adv;
         {
@@ -568,21 +574,19 @@ __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const
             w += moved ? 1u : 0u;
             ahead = S.clean[w + 2];
         }
-        const bool endb = k >= 63u;  // zz = k + 1 reaches 64
+        const bool endb = k >= 63u;  // the zig-zag index reaches 64
         const uint32_t blk1 = blk + 1u == g.bpm ? 0u : blk + 1u;
-        zz = endb ? 0u : k + 1u;
         blk = endb ? blk1 : blk;
-        done += endb ? 1u : 0u;
         tb = endb ? (blk1 >= g.n_luma ? chroma_tb : 0u) : tb | ac_bit;
-        boff += endb ? 64u : 0u;
         win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
         e = lookup(win);
     }
     // the lane must stand between MCUs, fewer than eight (padding) bits before the end
+    const uint32_t zz = at & 63u;
     if (blk != 0 || zz != 0 || end_bit - p >= 8) broken = 1;
     else p = end_bit;
     wc->bad |= broken | (int32_t)((over >> 6) & 1u);
-    *nblk = done;
+    *nblk = (at >> 6) - first_block;
     return pack_state(p, blk, zz);
 }
 

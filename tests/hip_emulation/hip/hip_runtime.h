@@ -155,6 +155,13 @@ inline uint32_t __builtin_amdgcn_cvt_pk_u8_f32(float v, uint32_t lane, uint32_t 
     const uint32_t sh = 8u * (lane & 3u);
     return (word & ~(255u << sh)) | (b << sh);
 }
+// V_BFE_U32: `width` bits of v from bit `offset` up; 0 for width 0
+inline uint32_t __builtin_amdgcn_ubfe(uint32_t v, uint32_t offset, uint32_t width)
+{
+    offset &= 31u;
+    width &= 31u;
+    return width == 0 ? 0u : (v >> offset) & ((1u << width) - 1u);
+}
 inline int __mul24(int a, int b) { return a * b; }
 inline int __popcll(unsigned long long v) { return __builtin_popcountll(v); }
 
