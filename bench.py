@@ -46,12 +46,12 @@ N_STREAMS, STREAM_BATCH = 7, 8
 # scaled by what the same counters read for a plain 256 MiB copy (FETCH_SIZE x 2, WRITE_SIZE x 1).
 # They describe the kernels whose sources hash to MEASURED_SOURCES; for any other sources the
 # figure is reported as null.
-MEASURED_SOURCES = "e296fb85f52c1cbe44c645a80059624999b48035cd55c002d7b95fe62f6033b0"
+MEASURED_SOURCES = "c2012bc02b981dc0a9b2533abeec72ece0db40a53246ee2cdc3987c6d9099123"
 MEASURED_TRAFFIC = {
-    2: {"scan": (5423 * 2 + 139024) * 1024, "decode": (114809 * 2 + 147364) * 1024,
-        "reconstruct": (50648 * 2 + 104367) * 1024, "resize": (49116 * 2 + 75264) * 1024},
-    4: {"scan": (23827 * 2 + 392765) * 1024, "decode": (220653 * 2 + 422851) * 1024,
-        "reconstruct": (114444 * 2 + 240729) * 1024, "resize": (91322 * 2 + 55296) * 1024},
+    2: {"scan": (5422 * 2 + 139036) * 1024, "decode": (115700 * 2 + 147318) * 1024,
+        "reconstruct": (50645 * 2 + 104393) * 1024, "resize": (49114 * 2 + 75264) * 1024},
+    4: {"scan": (23827 * 2 + 392759) * 1024, "decode": (220658 * 2 + 419561) * 1024,
+        "reconstruct": (114447 * 2 + 241110) * 1024, "resize": (91462 * 2 + 55296) * 1024},
 }
 
 
