@@ -256,6 +256,23 @@ static void model_counts(int64_t freq[4][256])
     }
 }
 
+/* An AC table that is a valid prefix code (Annex C) and a poor one on purpose: one
+ * code of each length 2..15 for the symbols that occur least (long runs of large
+ * values), sixteen-bit codes for all the others, EOB and the short runs of small
+ * values last.  The Kraft sum is just above one half, so no code is all ones.       */
+static void lopsided_ac_table(enctable *t)
+{
+    int n = 0;
+    for (int r = 15; r >= 0; r--)
+        for (int s = 10; s >= 1; s--) t->huffval[n++] = (uint8_t)((r << 4) | s);
+    t->huffval[n++] = 0xF0;
+    t->huffval[n++] = 0x00;
+    t->nval = n;
+    memset(t->bits, 0, sizeof t->bits);
+    for (int l = 2; l <= 15; l++) t->bits[l] = 1;
+    t->bits[16] = (uint8_t)(n - 14);
+}
+
 int64_t oracle_write_jpeg(const int16_t *coef, int w, int h, int mode,
                           const uint16_t qluma[64], const uint16_t qchroma[64],
                           int dri, int table_mode, uint8_t *out, size_t cap)
@@ -278,8 +295,12 @@ int64_t oracle_write_jpeg(const int16_t *coef, int w, int h, int mode,
         int64_t any = 0;
         for (int i = 0; i < 256; i++) any += freq[t][i];
         if (!any) freq[t][0] = 1; /* a table must hold at least one code */
-        tab[t].nval = oracle_huff_from_freq(freq[t], tab[t].bits, tab[t].huffval);
-        if (tab[t].nval < 0) return tab[t].nval;
+        if (table_mode == 2 && (t & 1)) {
+            lopsided_ac_table(&tab[t]);
+        } else {
+            tab[t].nval = oracle_huff_from_freq(freq[t], tab[t].bits, tab[t].huffval);
+            if (tab[t].nval < 0) return tab[t].nval;
+        }
         int rc = finish_table(&tab[t]);
         if (rc) return rc;
     }

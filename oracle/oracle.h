@@ -100,7 +100,10 @@ int oracle_forward_blocks(const uint8_t *rgb, int w, int h, int mode,
  * (SOI DQT SOF0 DHT [DRI] SOS data EOI).
  * table_mode 0: Huffman tables built (K.2 procedure) from this image's own
  * symbol counts; 1: built from a fixed smooth count model that gives every
- * baseline symbol a code.  dri = restart interval in MCUs (0 = none).
+ * baseline symbol a code; 2: as 1 for DC, and for AC a fixed valid prefix code
+ * whose codes are sixteen bits long for all but fourteen rare symbols (decoders
+ * with short lookup tables meet their long-code path on every block).
+ * dri = restart interval in MCUs (0 = none).
  * Returns bytes written or a negative error.                              */
 int64_t oracle_write_jpeg(const int16_t *coef, int w, int h, int mode,
                           const uint16_t qluma[64], const uint16_t qchroma[64],

@@ -232,7 +232,7 @@ def test_roundtrip_recovers_quantised_coefficients(mode, size):
     hmax = oracle.MODE_GEOMETRY[mode][0]
     mcu_cols = -(-w // (8 * hmax))
     for dri in (0, 1, mcu_cols, 8):
-        for table_mode in (0, 1):
+        for table_mode in (0, 1, 2):
             data, coef = oracle.encode(rgb, quality=90, mode=mode, dri=dri, table_mode=table_mode)
             got, _, info = oracle.decode(data, want_rgb=False)
             assert (info.width, info.height) == (w, h)
@@ -262,7 +262,7 @@ def test_roundtrip_extreme_coefficients_and_byte_stuffing():
     coef[5:, 1:] = rng.integers(-3, 4, size=(nb - 5, 63))
     q = np.ones(64, dtype=np.uint16)
     for dri in (0, 1, 2):
-        for table_mode in (0, 1):
+        for table_mode in (0, 1, 2):
             data = oracle.write_jpeg(coef, w, h, mode, q, q, dri=dri, table_mode=table_mode)
             sos = data.index(b"\xff\xda")
             assert b"\xff\x00" in data[sos:], "no stuffed byte: test lost its point"
@@ -339,7 +339,7 @@ def _pil_decode(data):
 @pytest.mark.parametrize("mode", [MODE_444, MODE_GRAY])
 def test_pillow_decodes_oracle_files_to_nearly_the_same_pixels(mode):
     rgb = _noise_image(11, 83, 61)
-    for dri, table_mode in ((0, 0), (3, 1)):
+    for dri, table_mode in ((0, 0), (3, 1), (0, 2)):
         data, _ = oracle.encode(rgb, quality=92, mode=mode, dri=dri, table_mode=table_mode)
         _, mine, _ = oracle.decode(data, want_coef=False)
         theirs = _pil_decode(data)
@@ -347,6 +347,31 @@ def test_pillow_decodes_oracle_files_to_nearly_the_same_pixels(mode):
         # libjpeg's integer IDCT may be 1 LSB off per component; colour conversion amplifies
         # a chroma LSB by up to 1.772
         assert diff.max() <= (1 if mode == MODE_GRAY else 3) and diff.mean() < 0.3
+
+
+def test_lopsided_ac_table_is_the_prefix_code_it_is_meant_to_be():
+    # table_mode 2: one AC code of each length 2..15, sixteen bits for the other 148 symbols,
+    # EOB among them; Pillow (libjpeg) reads the file to the same pixels as the file with
+    # ordinary tables, so the table in the file and the codes in the scan agree
+    rgb = _noise_image(12, 64, 48)
+    plain, coef = oracle.encode(rgb, quality=90, mode=MODE_420, table_mode=1)
+    data, coef2 = oracle.encode(rgb, quality=90, mode=MODE_420, table_mode=2)
+    assert np.array_equal(coef, coef2) and len(data) > 2 * len(plain)
+    at, seen = 0, 0
+    while True:
+        at = data.find(b"\xff\xc4", at)
+        if at < 0 or at > data.index(b"\xff\xda"):
+            break
+        tc_th, bits = data[at + 4], list(data[at + 5:at + 21])
+        if tc_th >> 4 == 1:
+            vals = data[at + 21:at + 21 + sum(bits)]
+            assert bits == [0] + [1] * 14 + [148] and len(set(vals)) == 162
+            assert vals[-1] == 0x00 and vals[-2] == 0xF0 and vals[0] == 0xFA
+            assert sum(b / (1 << (l + 1)) for l, b in enumerate(bits)) < 1.0   # Kraft
+            seen += 1
+        at += 2
+    assert seen == 2
+    assert np.array_equal(_pil_decode(data), _pil_decode(plain))
 
 
 @pytest.mark.parametrize("mode", [MODE_422, MODE_440])
