@@ -22,8 +22,10 @@ def lib_path():
 def build(verbose=False):
     """Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    # -falign-loops: the entropy decoder's symbol loops run as lone waves that pay for every
+    # instruction fetch; where their headers fall in a fetch line moved its time by 3 %
     cmd = [hipcc, "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared", "-pthread",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-falign-loops=32",
            "-o", lib_path()] + [os.path.join(_CSRC, s) for s in _SOURCES]
     r = subprocess.run(cmd, capture_output=not verbose, text=True)
     if r.returncode != 0:

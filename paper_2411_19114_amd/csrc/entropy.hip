@@ -48,10 +48,13 @@ static_assert(kSubseqBytes == 64 && (kSubseqBytes / 4) == (1 << kPadShift), "one
 //   bit 10      the symbol's coefficient index must lie inside the block (all but EOB)
 //   bits 9..4   zig-zag advance - 1 (DC 1, AC run+1, ZRL 16, EOB 64)
 //   bits 3..0   number of appended bits
-// A first-level entry that is not a code entry is 0 (no such code), kUseLoop, or a
-// reference to a second-level block: bits 10..8 = extra index bits (1..6),
-// bits 7..0 = offset into the table's second-level pool.
+// A first-level entry that is not a code entry refers to the table's second-level pool:
+// bits 10..8 = extra index bits (0..6), bits 7..0 = offset of its block.  Two pool entries are
+// set aside so that every first-level miss is resolved by the same read: entry 0 holds 0 (no
+// such code; the first-level entry is 0 too), entry 1 holds kUseLoop (the table's blocks did
+// not fit the pool: search the canonical code lists instead).
 constexpr uint32_t kUseLoop = 0x07FFu;
+constexpr uint32_t kPoolReserved = 2, kPoolSearchRef = 1;
 constexpr uint32_t kInvalidEntry = (16u << 11) | (63u << 4);  // 16 bits, ends the block
 
 struct alignas(16) HuffTables {
@@ -229,7 +232,7 @@ __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const Im
             code = (code + c) << 1;
             k += c;
         }
-        T.sub_used[tid] = 0;
+        T.sub_used[tid] = kPoolReserved;
     }
     for (int t = t_lo; t < t_hi; t++) {
         const uint32_t nval = min(R.dht_nval[t], 256u);
@@ -278,7 +281,7 @@ __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const Im
                     for (uint32_t i = 0; i < size; i++)
                         T.sub[t * kSubEntries + off + i] = (uint16_t)((nb << 11) | x);
                 } else {
-                    e = kUseLoop;
+                    e = kPoolSearchRef;
                 }
             }
             T.lut[(t << kLutBits) + x] = (uint16_t)e;
@@ -290,7 +293,7 @@ __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const Im
         const uint32_t used = min(T.sub_used[t], (uint32_t)kSubEntries);
         for (uint32_t i = tid; i < used; i += kT) {
             const uint32_t note = T.sub[t * kSubEntries + i];
-            uint32_t e = 0;
+            uint32_t e = i == kPoolSearchRef ? kUseLoop : 0u;
             if (note) {
                 const uint32_t nb = note >> 11, x = note & ((1u << kLutBits) - 1u);
                 const uint32_t off = T.lut[(t << kLutBits) + x] & 0xFFu;
@@ -352,17 +355,15 @@ __device__ __attribute__((noinline)) uint32_t lookup_by_search(const HuffTables 
 }
 
 // Codes longer than the first level covers: e is the first-level entry (not a code entry),
-// win = the next 32 bits of the stream.  Returns a code entry or 0.
-__device__ __forceinline__ uint32_t resolve_long_code(const HuffTables &T, uint32_t e, uint32_t tsel,
-                                                      uint32_t win)
+// win = the next 32 bits of the stream, tb = first entry of the table in the first level.
+// Returns the second-level entry: a code entry, 0, or kUseLoop.
+__device__ __forceinline__ uint32_t second_level(const HuffTables &T, uint32_t e, uint32_t tb, uint32_t win)
 {
-    if (__builtin_expect(e == kUseLoop, 0)) return lookup_by_search(T, tsel, win);
-    // e = 0 (no such code) reads entry 0 of the pool with a zero index: harmless, and the
-    // result is discarded
+    static_assert((1 << kLutBits) == 4 * kSubEntries, "tb / 4 is the table's first pool entry");
     const uint32_t nbits = e >> 8;
-    const uint32_t idx = nbits ? (win << kLutBits) >> (32 - nbits) : 0u;
-    const uint32_t r = T.sub[tsel * kSubEntries + (e & 0xFFu) + idx];
-    return e ? r : 0u;
+    // the nbits bits after the first kLutBits; none for nbits = 0
+    const uint32_t idx = __builtin_amdgcn_ubfe(win, 32u - kLutBits - nbits, nbits);
+    return T.sub[(tb >> 2) + (e & 0xFFu) + idx];
 }
 
 // word w of the destuffed stream lives at this index of DecodeShared::clean
@@ -437,10 +438,13 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
     auto lookup = [&](uint32_t win) {
         uint32_t e = lut[tb + (win >> (32 - kLutBits))];
         if (__builtin_expect((e >> 11) == 0, 0)) {
-            e = resolve_long_code(S.tab, e, tb >> kLutBits, win);
-            if ((e >> 11) == 0) {
-                e = kInvalidEntry;
-                if (kWrite && p + (kInvalidEntry >> 11) <= nb) broken = 1;
+            e = second_level(S.tab, e, tb, win);
+            if (__builtin_expect((e >> 11) == 0, 0)) {
+                if (e == kUseLoop) e = lookup_by_search(S.tab, tb >> kLutBits, win);
+                if ((e >> 11) == 0) {
+                    e = kInvalidEntry;
+                    if (kWrite && p + (kInvalidEntry >> 11) <= nb) broken = 1;
+                }
             }
         }
         return e;
@@ -546,10 +550,13 @@ __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const
     auto lookup = [&](uint32_t win) {
         uint32_t e = lut[tb + (win >> (32 - kLutBits))];
         if (__builtin_expect((e >> 11) == 0, 0)) {
-            e = resolve_long_code(S.tab, e, tb >> kLutBits, win);
-            if ((e >> 11) == 0) {
-                e = kInvalidEntry;
-                if (p + (kInvalidEntry >> 11) <= end_bit) broken = 1;
+            e = second_level(S.tab, e, tb, win);
+            if (__builtin_expect((e >> 11) == 0, 0)) {
+                if (e == kUseLoop) e = lookup_by_search(S.tab, tb >> kLutBits, win);
+                if ((e >> 11) == 0) {
+                    e = kInvalidEntry;
+                    if (p + (kInvalidEntry >> 11) <= end_bit) broken = 1;
+                }
             }
         }
         return e;

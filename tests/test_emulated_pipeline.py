@@ -50,6 +50,14 @@ def test_modes_restart_intervals_and_odd_sizes():
     _check(streams, 0, 1, 1, "f32", flags=2)  # whole images are converted to RGB and compared
 
 
+def test_tables_whose_codes_are_mostly_sixteen_bits_long():
+    # nearly every AC symbol takes the decoder's second-level lookup, and the table's
+    # second-level blocks do not all fit their pool, so some take the canonical search
+    streams = [oracle.encode(_img(40 + k, 70, 45), 88, mode, dri, table_mode=2)[0]
+               for k, (mode, dri) in enumerate([(MODE_420, 0), (MODE_420, 2), (MODE_444, 0), (MODE_GRAY, 3)])]
+    _check(streams, 0, 1, 1, "f32", flags=2)
+
+
 def test_pillow_streams_of_workloads_1_and_5():
     streams = [synth.make_image(1, 5)[0], synth.make_image(5, 0)[0], synth.make_image(5, 1)[0],
                synth.make_image(5, 2)[0]]

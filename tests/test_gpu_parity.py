@@ -97,6 +97,19 @@ def test_extreme_coefficients_and_byte_stuffing(pp):
         assert np.array_equal(pp.debug_last_coefficients(i, nb), coef)
 
 
+def test_tables_whose_codes_are_mostly_sixteen_bits_long(pp):
+    # oracle table mode 2: 148 of the 162 AC codes are sixteen bits long, so nearly every AC
+    # symbol takes the second-level lookup, and the second-level blocks do not all fit their
+    # pool, so some take the canonical search; short intervals, long ones and none
+    streams = []
+    for k, (mode, dri, size) in enumerate([(MODE_420, 0, (200, 120)), (MODE_420, 2, (200, 120)),
+                                           (MODE_444, 0, (90, 70)), (MODE_GRAY, 3, (90, 70)),
+                                           (MODE_420, 40, (640, 200))]):
+        rgb = synth.gradient_noise_image(np.random.default_rng(60 + k), *size)
+        streams.append(oracle.encode(rgb, 90, mode, dri, table_mode=2)[0])
+    check_against_oracle(pp, streams, 96, 80, 80, "f32")
+
+
 def test_all_eob_and_dc_only_blocks(pp):
     # shortest possible blocks: hundreds of blocks per decoder subsequence
     w, h = 512, 256
