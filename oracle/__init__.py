@@ -87,6 +87,8 @@ def lib():
         L.oracle_preprocess.argtypes = [u8p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                         dp, dp, dp]
         L.oracle_preprocess.restype = C.c_int
+        L.oracle_preprocess_antialias.argtypes = L.oracle_preprocess.argtypes
+        L.oracle_preprocess_antialias.restype = C.c_int
         _lib = L
     return _lib
 
@@ -239,21 +241,25 @@ def resized_size(w, h, s):
     return ow.value, oh.value
 
 
-def preprocess(rgb, resize_short, crop_h, crop_w, mean, std):
-    """RGB8 HWC -> float64 [3, crop_h, crop_w] (resize, centre crop, normalize)."""
+def preprocess(rgb, resize_short, crop_h, crop_w, mean, std, antialias=False):
+    """RGB8 HWC -> float64 [3, crop_h, crop_w] (resize, centre crop, normalize).
+
+    antialias: the resize averages under a triangle as wide as an output sample where the
+    image shrinks (oracle_preprocess_antialias) instead of reading two samples per axis."""
     rgb = np.ascontiguousarray(rgb, dtype=np.uint8)
     h, w, _ = rgb.shape
     mean = np.ascontiguousarray(mean, dtype=np.float64)
     std = np.ascontiguousarray(std, dtype=np.float64)
     out = np.empty((3, crop_h, crop_w), dtype=np.float64)
-    rc = lib().oracle_preprocess(_p(rgb, C.c_uint8), w, h, int(resize_short), crop_h, crop_w,
-                                 _p(mean, C.c_double), _p(std, C.c_double), _p(out, C.c_double))
+    fn = lib().oracle_preprocess_antialias if antialias else lib().oracle_preprocess
+    rc = fn(_p(rgb, C.c_uint8), w, h, int(resize_short), crop_h, crop_w,
+            _p(mean, C.c_double), _p(std, C.c_double), _p(out, C.c_double))
     if rc:
         raise OracleError(rc, "preprocess")
     return out
 
 
-def decode_preprocess(data, resize_short, crop_h, crop_w, mean, std):
+def decode_preprocess(data, resize_short, crop_h, crop_w, mean, std, antialias=False):
     """Whole path for one image: JPEG bytes -> float64 tensor [3, crop_h, crop_w]."""
     _, rgb, _ = decode(data, want_coef=False, want_rgb=True)
-    return preprocess(rgb, resize_short, crop_h, crop_w, mean, std)
+    return preprocess(rgb, resize_short, crop_h, crop_w, mean, std, antialias)

@@ -141,6 +141,19 @@ int oracle_preprocess(const uint8_t *rgb, int w, int h, int resize_short,
                       int crop_h, int crop_w, const double mean[3], const double std[3],
                       double *out);
 
+/* The same with the antialiased bilinear resize that image libraries apply when they
+ * shrink (Pillow's BILINEAR resize, torch's interpolate(mode="bilinear", antialias=True)):
+ * along each axis an output sample is the triangle-weighted mean of the source samples
+ * within max(scale, 1) source samples of its centre (scale = in / out), the window cut at
+ * the image's edge and the weights scaled to sum 1; where the image grows this is the plain
+ * bilinear resize above.  PREBA names a Resize unit (section 4.2, Table 1) and no filter.
+ * pinned by: torch's CPU interpolate, Pillow's resize within its 8-bit rounding, the
+ * 1/8 3/8 3/8 1/8 weights of an exact 2:1 reduction, equality with oracle_preprocess
+ * when enlarging, constant images.                                                     */
+int oracle_preprocess_antialias(const uint8_t *rgb, int w, int h, int resize_short,
+                                int crop_h, int crop_w, const double mean[3], const double std[3],
+                                double *out);
+
 #ifdef __cplusplus
 }
 #endif

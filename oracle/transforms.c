@@ -184,3 +184,65 @@ int oracle_preprocess(const uint8_t *rgb, int w, int h, int resize_short,
             }
     return ORACLE_OK;
 }
+
+/* Weights of the source samples that one output sample of the antialiased resize reads along
+ * one axis: a triangle centred on the output sample's centre (in source units), as wide as
+ * the larger of one source sample and one output sample, cut at the image's edge and scaled
+ * to sum 1.  Returns the first source index; *count = number of weights written to wt.     */
+static int triangle_window(int out_index, double scale, int in_size, double *wt, int *count)
+{
+    double support = scale > 1.0 ? scale : 1.0;
+    double centre = (out_index + 0.5) * scale;
+    int first = (int)floor(centre - support + 0.5);
+    int end = (int)floor(centre + support + 0.5);
+    if (first < 0) first = 0;
+    if (end > in_size) end = in_size;
+    double total = 0.0;
+    for (int j = first; j < end; j++) {
+        double d = fabs(j + 0.5 - centre) / support;
+        wt[j - first] = d < 1.0 ? 1.0 - d : 0.0;
+        total += wt[j - first];
+    }
+    for (int j = first; j < end; j++) wt[j - first] /= total;
+    *count = end - first;
+    return first;
+}
+
+int oracle_preprocess_antialias(const uint8_t *rgb, int w, int h, int resize_short,
+                                int crop_h, int crop_w, const double mean[3], const double std[3],
+                                double *out)
+{
+    if (!rgb || !out || w < 1 || h < 1 || crop_h < 1 || crop_w < 1) return ORACLE_E_ARG;
+    int ow, oh;
+    oracle_resized_size(w, h, resize_short, &ow, &oh);
+    if (crop_w > ow || crop_h > oh) return ORACLE_E_ARG;
+    for (int c = 0; c < 3; c++)
+        if (!(std[c] > 0.0)) return ORACLE_E_ARG;
+    int top = (oh - crop_h) / 2, left = (ow - crop_w) / 2;
+    double scale_x = (double)w / (double)ow, scale_y = (double)h / (double)oh;
+    /* at most 2 * support + 2 samples fall under a triangle */
+    size_t cap_x = (size_t)(2.0 * (scale_x > 1.0 ? scale_x : 1.0)) + 3;
+    size_t cap_y = (size_t)(2.0 * (scale_y > 1.0 ? scale_y : 1.0)) + 3;
+    double *wx = malloc(cap_x * sizeof *wx), *wy = malloc(cap_y * sizeof *wy);
+    if (!wx || !wy) { free(wx); free(wy); return ORACLE_E_ARG; }
+    for (int y = 0; y < crop_h; y++) {
+        int ny, y0 = triangle_window(y + top, scale_y, h, wy, &ny);
+        for (int x = 0; x < crop_w; x++) {
+            int nx, x0 = triangle_window(x + left, scale_x, w, wx, &nx);
+            for (int c = 0; c < 3; c++) {
+                double v = 0.0;
+                for (int r = 0; r < ny; r++) {
+                    double row = 0.0;
+                    for (int k = 0; k < nx; k++)
+                        row += wx[k] * rgb[((size_t)(y0 + r) * w + (x0 + k)) * 3 + c];
+                    v += wy[r] * row;
+                }
+                out[((size_t)c * crop_h + y) * crop_w + x] = (v / 255.0 - mean[c]) / std[c];
+            }
+        }
+    }
+    free(wx);
+    free(wy);
+    return ORACLE_OK;
+}
+

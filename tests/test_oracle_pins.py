@@ -534,6 +534,72 @@ def test_downscale_by_two_averages_pixel_pairs():
     np.testing.assert_allclose(out, expect.transpose(2, 0, 1), atol=1e-9)
 
 
+# ---------------------------------------------------------------- antialiased resize
+
+def _torch_antialias(rgb, resize_short, crop_h, crop_w):
+    import torch
+    import torch.nn.functional as F
+    h, w, _ = rgb.shape
+    ow, oh = oracle.resized_size(w, h, resize_short)
+    t = torch.from_numpy(rgb.astype(np.float64)).permute(2, 0, 1)[None]
+    r = F.interpolate(t, size=(oh, ow), mode="bilinear", antialias=True, align_corners=False)[0].numpy()
+    top, left = (oh - crop_h) // 2, (ow - crop_w) // 2
+    r = r[:, top:top + crop_h, left:left + crop_w]
+    return (r / 255.0 - np.array(MEAN)[:, None, None]) / np.array(STD)[:, None, None]
+
+
+@pytest.mark.parametrize("size,resize,crop", [((97, 61), 40, (32, 40)), ((300, 451), 128, (112, 100)),
+                                               ((64, 48), 96, (80, 80)), ((201, 77), 64, (64, 150)),
+                                               ((37, 500), 31, (300, 31))])
+def test_antialiased_resize_against_torch_interpolate(size, resize, crop):
+    # a library routine with the same definition (torch's CPU antialiased bilinear), in double
+    w, h = size
+    rgb = np.random.default_rng(w + h).integers(0, 256, size=(h, w, 3), dtype=np.uint8)
+    got = oracle.preprocess(rgb, resize, crop[0], crop[1], MEAN, STD, antialias=True)
+    np.testing.assert_allclose(got, _torch_antialias(rgb, resize, *crop), atol=1e-9)
+
+
+def test_antialiased_resize_against_pillow_within_its_rounding():
+    from PIL import Image
+    rgb = _noise_image(31, 333, 222, sigma=20.0)
+    ow, oh = oracle.resized_size(333, 222, 100)
+    theirs = np.asarray(Image.fromarray(rgb).resize((ow, oh), Image.BILINEAR)).astype(np.float64)
+    mine = oracle.preprocess(rgb, 100, oh, ow, (0, 0, 0), (1, 1, 1), antialias=True) * 255.0
+    # Pillow rounds to 8 bits after each of its two passes
+    assert np.abs(mine.transpose(1, 2, 0) - theirs).max() <= 1.0 + 1e-9
+    # the plain two-tap resize is a different function on this image
+    plain = oracle.preprocess(rgb, 100, oh, ow, (0, 0, 0), (1, 1, 1)) * 255.0
+    assert np.abs(plain.transpose(1, 2, 0) - theirs).max() > 8.0
+
+
+def test_antialiased_reduction_by_two_has_weights_1_3_3_1_over_8():
+    rng = np.random.default_rng(32)
+    rgb = rng.integers(0, 256, size=(24, 40, 3), dtype=np.uint8)
+    out = oracle.preprocess(rgb, 12, 12, 20, (0, 0, 0), (1, 1, 1), antialias=True) * 255.0
+    f = rgb.astype(np.float64)
+    k = np.array([1.0, 3.0, 3.0, 1.0]) / 8.0
+    for y in range(1, 11):
+        for x in range(1, 19):
+            patch = f[2 * y - 1:2 * y + 3, 2 * x - 1:2 * x + 3]
+            np.testing.assert_allclose(out[:, y, x], np.einsum("r,c,rck->k", k, k, patch), atol=1e-9)
+    # at the edge the window loses a sample and the other three are scaled up: 3 3 1 over 7
+    e = np.array([3.0, 3.0, 1.0]) / 7.0
+    np.testing.assert_allclose(out[:, 0, 0], np.einsum("r,c,rck->k", e, e, f[0:3, 0:3]), atol=1e-9)
+
+
+def test_antialiased_resize_equals_the_plain_one_when_enlarging_and_keeps_constants():
+    rgb = _noise_image(33, 50, 40)
+    a = oracle.preprocess(rgb, 90, 80, 100, MEAN, STD, antialias=True)
+    b = oracle.preprocess(rgb, 90, 80, 100, MEAN, STD)
+    np.testing.assert_allclose(a, b, atol=1e-12)
+    same = oracle.preprocess(rgb, 0, 30, 30, MEAN, STD, antialias=True)
+    np.testing.assert_allclose(same, oracle.preprocess(rgb, 0, 30, 30, MEAN, STD), atol=1e-12)
+    flat = np.full((45, 70, 3), 77, dtype=np.uint8)
+    out = oracle.preprocess(flat, 20, 20, 20, MEAN, STD, antialias=True)
+    for c in range(3):
+        np.testing.assert_allclose(out[c], (77 / 255.0 - MEAN[c]) / STD[c], atol=1e-12)
+
+
 def test_preprocess_rejects_bad_arguments():
     rgb = np.zeros((10, 10, 3), dtype=np.uint8)
     with pytest.raises(oracle.OracleError):
