@@ -80,7 +80,8 @@ def cpu_baseline(streams, pr, max_seconds=60.0):
     cores = min(16, len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count())
 
     def one(s):
-        oracle.decode_preprocess(s, pr["resize_short"], pr["crop_h"], pr["crop_w"], pr["mean"], pr["std"])
+        oracle.decode_preprocess(s, pr["resize_short"], pr["crop_h"], pr["crop_w"], pr["mean"], pr["std"],
+                                 bool(pr.get("antialias")))
         return oracle.jpeg_info(s)
 
     # probe one image to bound the sample to roughly 20 s of CPU work
@@ -140,8 +141,14 @@ def algorithmic_bytes(infos, pr):
             # taps floor(s), floor(s) + 1 of the first and last output; 2 s out_size is an integer
             s2_first = (2 * first + 1) * size - out_size
             s2_last = (2 * (first + count - 1) + 1) * size - out_size
-            lo = s2_first // (2 * out_size)
-            hi = s2_last // (2 * out_size) + (1 if s2_last % (2 * out_size) else 0)
+            if pr.get("antialias") and size > out_size:
+                # the samples strictly inside the first and last output's triangle, half-width
+                # size / out_size around the centre s + 1/2: j > s - size/out_size, j < s + size/out_size
+                lo = (s2_first - 2 * size) // (2 * out_size) + 1
+                hi = -((-(s2_last + 2 * size)) // (2 * out_size)) - 1
+            else:
+                lo = s2_first // (2 * out_size)
+                hi = s2_last // (2 * out_size) + (1 if s2_last % (2 * out_size) else 0)
             lo, hi = min(max(lo, 0), size - 1), min(max(hi, 0), size - 1)
             mcus *= hi // mcu_px - lo // mcu_px + 1
         recon += mcus * (i.blocks_per_mcu * 128 + mcu_px * mcu_px * 3)
@@ -527,6 +534,9 @@ def main():
     ap.add_argument("--time-queue-us", type=int, default=200, help="--server: Time_queue in microseconds")
     ap.add_argument("--stream-batch", type=int, default=STREAM_BATCH,
                     help="workload 3: images per batch (default 8; 1 = the single-input latency case)")
+    ap.add_argument("--antialias", action="store_true",
+                    help="resize with the antialiased filter (a variant; the default is the plain "
+                         "two-tap bilinear filter of the workloads)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy (a reference for HBM counters)")
     ap.add_argument("--host-input", action="store_true",
@@ -568,8 +578,9 @@ def main():
     gen_s = time.perf_counter() - t0
     n = len(streams)
     blob, offsets = synth.pack(streams)
-    pr = synth.params_of(cfg)
-    params = make_params(pr["resize_short"], pr["crop_h"], pr["crop_w"], pr["out_dtype"], pr["mean"], pr["std"])
+    pr = dict(synth.params_of(cfg), antialias=bool(args.antialias))
+    params = make_params(pr["resize_short"], pr["crop_h"], pr["crop_w"], pr["out_dtype"], pr["mean"], pr["std"],
+                         prep.FILTER_ANTIALIAS if args.antialias else prep.FILTER_BILINEAR)
     infos = prep.parse_headers(blob, offsets)
     assert all(i.status == 0 for i in infos)
     max_w, max_h = max(i.width for i in infos), max(i.height for i in infos)
@@ -631,7 +642,10 @@ def main():
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(streams, pr)
         sym_per_byte = symbols_in(streams)
-    stages, roofline = stage_report(stage, work, entropy_bytes, sym_per_byte, cfg)
+    # counters were taken with the plain filter only
+    stages, roofline = stage_report(stage, work, entropy_bytes, sym_per_byte, None if args.antialias else cfg)
+    if args.antialias:
+        stages[3]["kernel"] = "resize_antialias_crop_normalize"
 
     result = {
         "metric": METRIC, "value": value, "unit": "images/s", "n_gpus": 1,
@@ -641,6 +655,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": WORKLOAD_NAMES[cfg], "batch": n, "streams": n_handles,
                    "input": "host memory" if args.host_input else "resident in HBM",
+                   "resize_filter": "antialiased bilinear" if args.antialias else "bilinear",
                    "compressed_bytes": int(offsets[-1]), "pixels": int(pixels),
                    "sha256": synth.sha256_of(streams), "input_generation_s": round(gen_s, 2)},
         "roofline": roofline,

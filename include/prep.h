@@ -47,6 +47,16 @@ enum {
 };
 
 enum { PREP_F32 = 0, PREP_F16 = 1 };
+
+/* The Resize unit's filter (PREBA section 4.2, Table 1 names the unit, not the filter).
+ * PREP_FILTER_BILINEAR: two samples per axis around the output sample's centre (half-pixel
+ *   centres, clamped at the border), whatever the scale.
+ * PREP_FILTER_ANTIALIAS: where an axis shrinks, the mean of the source samples under a
+ *   triangle centred on the output sample and as wide as an output sample (support
+ *   in/out source samples each way), the window cut at the image's edge and the weights
+ *   scaled to sum 1, which is what image libraries do when they reduce an image; where an
+ *   axis grows it is PREP_FILTER_BILINEAR. */
+enum { PREP_FILTER_BILINEAR = 0, PREP_FILTER_ANTIALIAS = 1 };
 /* prep_config.flags.
  * PREP_FLAG_TABLES_PER_WORKGROUP: expand the Huffman tables in every decoder workgroup
  *   instead of once per distinct table set of the batch (same results; kept for checking
@@ -81,6 +91,7 @@ typedef struct {
     int32_t crop_h, crop_w;
     int32_t out_dtype;     /* PREP_F32 or PREP_F16                                  */
     float mean[3], std[3]; /* on the 0..1 pixel scale, R, G, B                      */
+    int32_t filter;        /* PREP_FILTER_BILINEAR or PREP_FILTER_ANTIALIAS         */
 } prep_params;
 
 /* What the host marker parser learns about one file (T.81 Annex B). */

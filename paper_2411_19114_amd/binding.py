@@ -13,6 +13,7 @@ OK, E_INVALID_ARG, E_TOO_LARGE, E_HIP, E_UNSUPPORTED, E_CORRUPT, E_NOMEM = 0, -1
 F32, F16 = 0, 1
 FLAG_TABLES_PER_WORKGROUP = 1
 FLAG_FULL_RGB = 2
+FILTER_BILINEAR, FILTER_ANTIALIAS = 0, 1
 
 
 def lib_path():
@@ -47,7 +48,8 @@ class Config(C.Structure):
 
 class Params(C.Structure):
     _fields_ = [("resize_short", C.c_int32), ("crop_h", C.c_int32), ("crop_w", C.c_int32),
-                ("out_dtype", C.c_int32), ("mean", C.c_float * 3), ("std", C.c_float * 3)]
+                ("out_dtype", C.c_int32), ("mean", C.c_float * 3), ("std", C.c_float * 3),
+                ("filter", C.c_int32)]
 
 
 class AudioConfig(C.Structure):
@@ -177,10 +179,11 @@ def _u64(a):
     return a, a.ctypes.data_as(C.POINTER(C.c_uint64))
 
 
-def make_params(resize_short, crop_h, crop_w, out_dtype, mean, std):
+def make_params(resize_short, crop_h, crop_w, out_dtype, mean, std, filter=FILTER_BILINEAR):
     p = Params()
     p.resize_short, p.crop_h, p.crop_w = int(resize_short), int(crop_h), int(crop_w)
     p.out_dtype = {"f32": F32, "f16": F16}.get(out_dtype, out_dtype)
+    p.filter = int(filter)
     p.mean[:] = [float(m) for m in mean]
     p.std[:] = [float(s) for s in std]
     return p

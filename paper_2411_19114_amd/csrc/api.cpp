@@ -98,6 +98,7 @@ bool params_ok(const prep_params *p)
     if (p->resize_short < 0 || p->resize_short > 65535) return false;
     if (p->crop_h < 1 || p->crop_w < 1 || p->crop_h > 65535 || p->crop_w > 65535) return false;
     if (p->out_dtype != PREP_F32 && p->out_dtype != PREP_F16) return false;
+    if (p->filter != PREP_FILTER_BILINEAR && p->filter != PREP_FILTER_ANTIALIAS) return false;
     for (int c = 0; c < 3; c++)
         if (!(p->std[c] > 0.0f) || !isfinite(p->std[c]) || !isfinite(p->mean[c])) return false;
     return true;
@@ -142,6 +143,20 @@ void tap_span(uint64_t off, uint64_t scale, int n_out, int size, int *lo, int *h
     const bool weighted = (t_last & ((1ull << kCoordFrac) - 1)) != 0;
     const int64_t first = (int64_t)(off >> kCoordFrac) - kCoordBias;
     const int64_t last = (int64_t)(t_last >> kCoordFrac) - kCoordBias + (weighted ? 1 : 0);
+    *lo = (int)std::min<int64_t>(std::max<int64_t>(first, 0), size - 1);
+    *hi = (int)std::min<int64_t>(std::max<int64_t>(last, 0), size - 1);
+}
+
+// The same for the antialiased filter: the first sample under the first output's triangle and
+// the last under the last output's, by the kernel's own window arithmetic (a sample at the very
+// edge of a triangle, weight zero, may be counted).
+void window_span(uint64_t off, uint64_t scale, int n_out, int size, int *lo, int *hi)
+{
+    const uint64_t one = 1ull << kCoordFrac;
+    const uint64_t support = std::max(scale, one);
+    const uint64_t t_last = off + (uint64_t)(n_out - 1) * scale;
+    const int64_t first = ((int64_t)(off + one - support) >> kCoordFrac) - kCoordBias;
+    const int64_t last = (int64_t)((t_last + one + support) >> kCoordFrac) - kCoordBias - 1;
     *lo = (int)std::min<int64_t>(std::max<int64_t>(first, 0), size - 1);
     *hi = (int)std::min<int64_t>(std::max<int64_t>(last, 0), size - 1);
 }
@@ -236,8 +251,9 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
             const int mcu_w = 8 * luma_h(I.sampling), mcu_h = 8 * luma_v(I.sampling);
             int x_lo = 0, x_hi = I.width - 1, y_lo = 0, y_hi = I.height - 1;
             if (!(h->cfg.flags & PREP_FLAG_FULL_RGB)) {
-                tap_span(Z.off_x, Z.scale_x, params->crop_w, I.width, &x_lo, &x_hi);
-                tap_span(Z.off_y, Z.scale_y, params->crop_h, I.height, &y_lo, &y_hi);
+                const auto span = params->filter == PREP_FILTER_ANTIALIAS ? window_span : tap_span;
+                span(Z.off_x, Z.scale_x, params->crop_w, I.width, &x_lo, &x_hi);
+                span(Z.off_y, Z.scale_y, params->crop_h, I.height, &y_lo, &y_hi);
             }
             R.roi_row0 = (uint16_t)(y_lo / mcu_h);
             R.roi_rows = (uint16_t)(y_hi / mcu_h - y_lo / mcu_h + 1);
@@ -356,7 +372,8 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
                        P.groups_per_wg, h->d_coef, h->d_rgb, stream);
     if (timing) HIP_TRY(hipEventRecord(ev[3], stream));
     launch_resize_normalize(h->d_rgb, s->d_rr, h->d_status, n, params->crop_h, params->crop_w,
-                            params->out_dtype, params->mean, params->std, out, true, stream);
+                            params->out_dtype, params->filter, s->h_rr, params->mean,
+                            params->std, out, true, stream);
     if (timing) HIP_TRY(hipEventRecord(ev[4], stream));
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(s->done, stream));
@@ -575,7 +592,8 @@ int prep_resize_normalize(prep_handle *h, const uint8_t *rgb, const uint64_t *rg
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(hipMemcpyAsync(s->d_rr, s->h_rr, sizeof(ResizeRec) * (size_t)n, hipMemcpyHostToDevice, st));
     launch_resize_normalize(rgb, s->d_rr, nullptr, n, params->crop_h, params->crop_w,
-                            params->out_dtype, params->mean, params->std, out, false, st);
+                            params->out_dtype, params->filter, s->h_rr, params->mean,
+                            params->std, out, false, st);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(s->done, st));
     s->pending = true;

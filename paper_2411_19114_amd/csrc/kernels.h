@@ -27,9 +27,11 @@ void launch_reconstruct(const uint8_t *bits, const ImageRec *recs, const uint32_
                         hipStream_t stream);
 
 // resize.hip
+// host_rr: the host's copy of rr (the records of all n_images must be initialised); read for
+// PREP_FILTER_ANTIALIAS only, where the images are dealt to two launches by their scales.
 void launch_resize_normalize(const uint8_t *rgb, const ResizeRec *rr, const int32_t *status,
-                             int n_images, int crop_h, int crop_w, int out_dtype,
-                             const float mean[3], const float std[3], void *out, bool wide_reads,
-                             hipStream_t stream);
+                             int n_images, int crop_h, int crop_w, int out_dtype, int filter,
+                             const ResizeRec *host_rr, const float mean[3], const float std[3], void *out,
+                             bool wide_reads, hipStream_t stream);
 
 }  // namespace prep

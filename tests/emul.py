@@ -29,7 +29,7 @@ def build(force=False):
     return BINARY
 
 
-def run(streams, resize_short, crop_h, crop_w, out_dtype, mean, std, timeout=600, flags=0):
+def run(streams, resize_short, crop_h, crop_w, out_dtype, mean, std, timeout=600, flags=0, antialias=False):
     """-> list of (status, coef [nb,64] or None, rgb flat or None, rect), tensor [n,3,ch,cw];
     rect = (x0, y0, x1, y1), the pixels of the image that were converted to RGB."""
     build()
@@ -44,7 +44,8 @@ def run(streams, resize_short, crop_h, crop_w, out_dtype, mean, std, timeout=600
             f.write(struct.pack("<6f", *mean, *std))
             f.write(offsets.tobytes())
             f.write(b"".join(streams))
-        env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", PREP_EMUL_FLAGS=str(int(flags)))
+        env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", PREP_EMUL_FLAGS=str(int(flags)),
+                   PREP_EMUL_FILTER="1" if antialias else "0")
         r = subprocess.run([BINARY, fin, fout], capture_output=True, text=True, timeout=timeout,
                            env=env)
         if os.environ.get("PREP_EMUL_VERBOSE") and r.stderr:

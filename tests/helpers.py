@@ -36,6 +36,29 @@ def tap_footprint(width, height, resize_short, crop_h, crop_w):
     return x_lo, y_lo, x_hi, y_hi
 
 
+def window_footprint(width, height, resize_short, crop_h, crop_w):
+    """The same for the antialiased filter: the source pixels strictly inside the triangles of
+    the crop window's outputs (centre (i + 1/2) * in/out, half-width max(in/out, 1)), in exact
+    rational arithmetic."""
+    from fractions import Fraction
+    import math
+    ow, oh = oracle.resized_size(width, height, resize_short)
+    top, left = (oh - crop_h) // 2, (ow - crop_w) // 2
+
+    def span(size, out_size, first, count):
+        scale = Fraction(size, out_size)
+        support = max(scale, Fraction(1))
+        c_first = Fraction(2 * first + 1, 2) * scale
+        c_last = Fraction(2 * (first + count - 1) + 1, 2) * scale
+        lo = math.floor(c_first - support - Fraction(1, 2)) + 1   # j + 1/2 > centre - support
+        hi = math.ceil(c_last + support - Fraction(1, 2)) - 1     # j + 1/2 < centre + support
+        return min(max(lo, 0), size - 1), min(max(hi, 0), size - 1)
+
+    x_lo, x_hi = span(width, ow, left, crop_w)
+    y_lo, y_hi = span(height, oh, top, crop_h)
+    return x_lo, y_lo, x_hi, y_hi
+
+
 def rgb_in_region(rect, got_rgb, ref_rgb, footprint):
     """|got - ref| over the pixels that the library converted (rect = x0, y0, x1, y1), after
     checking that they cover the crop window's taps."""
@@ -45,21 +68,22 @@ def rgb_in_region(rect, got_rgb, ref_rgb, footprint):
     return np.abs(got_rgb[y0:y1, x0:x1].astype(np.int32) - ref_rgb[y0:y1, x0:x1].astype(np.int32))
 
 
-def oracle_batch(streams, resize_short, crop_h, crop_w, workers=8):
+def oracle_batch(streams, resize_short, crop_h, crop_w, workers=8, antialias=False):
     """[(coef, rgb, info, tensor float64)] for every stream, computed by the oracle."""
     def one(s):
         coef, rgb, info = oracle.decode(s)
-        ten = oracle.preprocess(rgb, resize_short, crop_h, crop_w, MEAN, STD)
+        ten = oracle.preprocess(rgb, resize_short, crop_h, crop_w, MEAN, STD, antialias)
         return coef, rgb, info, ten
     with ThreadPoolExecutor(workers) as ex:
         return list(ex.map(one, streams))
 
 
-def run_gpu(pp, streams, resize_short, crop_h, crop_w, out_dtype, resident=False):
+def run_gpu(pp, streams, resize_short, crop_h, crop_w, out_dtype, resident=False, antialias=False):
     import torch
-    from paper_2411_19114_amd.binding import make_params
+    from paper_2411_19114_amd.binding import FILTER_ANTIALIAS, FILTER_BILINEAR, make_params
     blob, offsets = synth.pack(streams)
-    params = make_params(resize_short, crop_h, crop_w, out_dtype, MEAN, STD)
+    params = make_params(resize_short, crop_h, crop_w, out_dtype, MEAN, STD,
+                         FILTER_ANTIALIAS if antialias else FILTER_BILINEAR)
     dt = torch.float16 if out_dtype == "f16" else torch.float32
     # poison the output so that unwritten elements show
     out = torch.full((len(streams), 3, crop_h, crop_w), 777.0, dtype=dt, device="cuda:0")
@@ -76,17 +100,18 @@ def run_gpu(pp, streams, resize_short, crop_h, crop_w, out_dtype, resident=False
 
 
 def check_against_oracle(pp, streams, resize_short, crop_h, crop_w, out_dtype, resident=False,
-                         check_intermediates=True):
-    status, got = run_gpu(pp, streams, resize_short, crop_h, crop_w, out_dtype, resident)
+                         check_intermediates=True, antialias=False):
+    status, got = run_gpu(pp, streams, resize_short, crop_h, crop_w, out_dtype, resident, antialias)
     assert status == [0] * len(streams), status
-    ref = oracle_batch(streams, resize_short, crop_h, crop_w)
+    ref = oracle_batch(streams, resize_short, crop_h, crop_w, antialias=antialias)
+    footprint = window_footprint if antialias else tap_footprint
     n_values = n_exact = 0
     for i, (coef, rgb, info, ten) in enumerate(ref):
         if check_intermediates:
             mine = pp.debug_last_coefficients(i, coef.shape[0])
             assert np.array_equal(mine, coef), f"image {i}: entropy-decoded coefficients differ"
             d = rgb_in_region(pp.debug_last_region(i), pp.debug_last_rgb(i, info.height, info.width), rgb,
-                              tap_footprint(info.width, info.height, resize_short, crop_h, crop_w))
+                              footprint(info.width, info.height, resize_short, crop_h, crop_w))
             assert d.max() <= RGB_MAX_LSB, f"image {i}: RGB off by {d.max()} LSB"
             n_values += d.size
             n_exact += int((d == 0).sum())

@@ -27,6 +27,8 @@ int main(int argc, char **argv)
     const int32_t n = hdr[0];
     P.resize_short = hdr[1]; P.crop_h = hdr[2]; P.crop_w = hdr[3]; P.out_dtype = hdr[4];
     if (fread(P.mean, 4, 3, f) != 3 || fread(P.std, 4, 3, f) != 3) return 1;
+    P.filter = PREP_FILTER_BILINEAR;
+    if (const char *v = getenv("PREP_EMUL_FILTER")) P.filter = atoi(v);
     std::vector<uint64_t> off((size_t)n + 1);
     if (fread(off.data(), 8, off.size(), f) != off.size()) return 1;
     std::vector<uint8_t> bits(off[n] ? off[n] : 1);

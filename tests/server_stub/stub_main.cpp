@@ -74,6 +74,7 @@ int main(int argc, char **argv)
     cfg.handle.max_bitstream_bytes = 1;
     cfg.params.crop_h = cfg.params.crop_w = 2;
     cfg.params.out_dtype = PREP_F32;
+    cfg.params.filter = PREP_FILTER_BILINEAR;
     cfg.n_consumers = 3;
     cfg.batch_max = 8;
     cfg.time_queue_us = 300;

@@ -20,8 +20,9 @@ def _img(seed, w, h, sigma=12.0):
     return synth.gradient_noise_image(np.random.default_rng(seed), w, h, sigma)
 
 
-def _check(streams, rs, ch, cw, dt, expect_status=None, flags=0):
-    per, ten = emul.run(streams, rs, ch, cw, dt, MEAN, STD, flags=flags)
+def _check(streams, rs, ch, cw, dt, expect_status=None, flags=0, antialias=False):
+    per, ten = emul.run(streams, rs, ch, cw, dt, MEAN, STD, flags=flags, antialias=antialias)
+    footprint = helpers.window_footprint if antialias else helpers.tap_footprint
     for i, s in enumerate(streams):
         status, coef, rgb, rect = per[i]
         if expect_status and expect_status[i] != 0:
@@ -34,9 +35,9 @@ def _check(streams, rs, ch, cw, dt, expect_status=None, flags=0):
         if flags & 2:
             assert rect == (0, 0, info.width, info.height)
         d = helpers.rgb_in_region(rect, rgb.reshape(r0.shape), r0,
-                                  helpers.tap_footprint(info.width, info.height, rs, ch, cw))
+                                  footprint(info.width, info.height, rs, ch, cw))
         assert d.max() <= 1 and (d == 0).mean() >= 0.999, f"image {i}: rgb"
-        ref = oracle.preprocess(r0, rs, ch, cw, MEAN, STD)
+        ref = oracle.preprocess(r0, rs, ch, cw, MEAN, STD, antialias)
         assert np.abs(ten[i].astype(np.float64) - ref).max() <= 0.02, f"image {i}: tensor"
 
 
@@ -56,6 +57,18 @@ def test_tables_whose_codes_are_mostly_sixteen_bits_long():
     streams = [oracle.encode(_img(40 + k, 70, 45), 88, mode, dri, table_mode=2)[0]
                for k, (mode, dri) in enumerate([(MODE_420, 0), (MODE_420, 2), (MODE_444, 0), (MODE_GRAY, 3)])]
     _check(streams, 0, 1, 1, "f32", flags=2)
+
+
+def test_antialiased_resize_reducing_enlarging_and_at_the_edges():
+    # reduce by 2.5 and by a non-integer factor, enlarge, keep the size; crop windows that
+    # touch the image's edge and ones well inside it (region of interest of the reconstruction)
+    streams = [oracle.encode(_img(50, 160, 100), 90, MODE_420, 4)[0],
+               oracle.encode(_img(51, 75, 131), 90, MODE_444, 0)[0],
+               oracle.encode(_img(52, 97, 64), 90, MODE_GRAY, 0)[0]]
+    _check(streams, 40, 40, 40, "f32", antialias=True)
+    _check(streams, 40, 24, 30, "f16", antialias=True)
+    _check(streams[:2], 150, 120, 150, "f32", antialias=True)
+    _check(streams[2:], 0, 64, 97, "f32", antialias=True)
 
 
 def test_pillow_streams_of_workloads_1_and_5():

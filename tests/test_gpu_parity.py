@@ -110,6 +110,21 @@ def test_tables_whose_codes_are_mostly_sixteen_bits_long(pp):
     check_against_oracle(pp, streams, 96, 80, 80, "f32")
 
 
+def test_antialiased_resize_over_the_whole_path(pp):
+    # the filter of image libraries when they reduce: workload-2 photos to 224 x 224, a full-HD
+    # frame to 384 x 384, odd sizes cropped at the image's edge, an enlargement, the size kept;
+    # the region of interest of the reconstruction must cover the wider windows
+    check_against_oracle(pp, synth.make_batch(2, 6), 256, 224, 224, "f16", antialias=True)
+    check_against_oracle(pp, synth.make_batch(4, 1), 384, 384, 384, "f16", antialias=True)
+    odd = [oracle.encode(synth.gradient_noise_image(np.random.default_rng(70 + k), w, h), 90, mode, dri)[0]
+           for k, (w, h, mode, dri) in enumerate([(333, 222, MODE_420, 5), (75, 131, MODE_444, 0),
+                                                  (97, 64, MODE_GRAY, 0), (640, 97, MODE_422, 3)])]
+    check_against_oracle(pp, odd, 40, 40, 40, "f32", antialias=True)
+    check_against_oracle(pp, odd, 64, 50, 64, "f32", antialias=True)
+    check_against_oracle(pp, odd[1:3], 150, 120, 150, "f32", antialias=True)
+    check_against_oracle(pp, odd[2:3], 0, 64, 97, "f32", antialias=True)
+
+
 def test_all_eob_and_dc_only_blocks(pp):
     # shortest possible blocks: hundreds of blocks per decoder subsequence
     w, h = 512, 256
@@ -222,21 +237,22 @@ def test_resize_stage_alone_on_oracle_rgb(pp):
     rng = np.random.default_rng(9)
     shapes = [(640, 480), (300, 500), (33, 77), (256, 256), (1920, 1080)]
     imgs = [rng.integers(0, 256, size=(h, w, 3), dtype=np.uint8) for w, h in shapes]
-    for rs, ch, cw, dt in ((256, 224, 224, "f32"), (32, 32, 30, "f16"), (384, 384, 384, "f16")):
+    for rs, ch, cw, dt, aa in ((256, 224, 224, "f32", 0), (32, 32, 30, "f16", 0), (384, 384, 384, "f16", 0),
+                               (256, 224, 224, "f32", 1), (32, 32, 30, "f16", 1), (700, 650, 690, "f32", 1)):
         flat = np.concatenate([im.reshape(-1) for im in imgs])
         offs = np.cumsum([0] + [im.size for im in imgs[:-1]]).astype(np.uint64)
         dev = torch.from_numpy(flat).to("cuda:0")
         tdt = torch.float16 if dt == "f16" else torch.float32
         out = torch.full((len(imgs), 3, ch, cw), 777.0, dtype=tdt, device="cuda:0")
         pp.resize_normalize(dev.data_ptr(), offs, [s[0] for s in shapes], [s[1] for s in shapes],
-                            [s[0] * 3 for s in shapes], make_params(rs, ch, cw, dt, MEAN, STD),
+                            [s[0] * 3 for s in shapes], make_params(rs, ch, cw, dt, MEAN, STD, aa),
                             out.data_ptr(), torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
         got = out.float().cpu().numpy().astype(np.float64)
         tol = 0.02 if dt == "f16" else 1e-4   # fp32 path: only interpolation rounding remains
         for i, im in enumerate(imgs):
-            ref = oracle.preprocess(im, rs, ch, cw, MEAN, STD)
-            assert np.abs(got[i] - ref).max() <= tol
+            ref = oracle.preprocess(im, rs, ch, cw, MEAN, STD, bool(aa))
+            assert np.abs(got[i] - ref).max() <= tol, (rs, ch, cw, dt, aa, i)
 
 
 def test_reconstruct_stage_alone_on_oracle_coefficients(pp):
