@@ -89,6 +89,8 @@ def lib():
         L.oracle_preprocess.restype = C.c_int
         L.oracle_preprocess_antialias.argtypes = L.oracle_preprocess.argtypes
         L.oracle_preprocess_antialias.restype = C.c_int
+        L.oracle_resize_crop_u8.argtypes = [u8p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, u8p]
+        L.oracle_resize_crop_u8.restype = C.c_int
         _lib = L
     return _lib
 
@@ -256,6 +258,18 @@ def preprocess(rgb, resize_short, crop_h, crop_w, mean, std, antialias=False):
             _p(mean, C.c_double), _p(std, C.c_double), _p(out, C.c_double))
     if rc:
         raise OracleError(rc, "preprocess")
+    return out
+
+
+def resize_crop_u8(rgb, resize_short, crop_h, crop_w, antialias=False):
+    """RGB8 HWC -> RGB8 [crop_h, crop_w, 3]: resize and centre crop, rounded to 8 bits."""
+    rgb = np.ascontiguousarray(rgb, dtype=np.uint8)
+    h, w, _ = rgb.shape
+    out = np.empty((crop_h, crop_w, 3), dtype=np.uint8)
+    rc = lib().oracle_resize_crop_u8(_p(rgb, C.c_uint8), w, h, int(resize_short), crop_h, crop_w,
+                                     int(bool(antialias)), _p(out, C.c_uint8))
+    if rc:
+        raise OracleError(rc, "resize_crop_u8")
     return out
 
 

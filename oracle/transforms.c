@@ -246,3 +246,24 @@ int oracle_preprocess_antialias(const uint8_t *rgb, int w, int h, int resize_sho
     return ORACLE_OK;
 }
 
+int oracle_resize_crop_u8(const uint8_t *rgb, int w, int h, int resize_short, int crop_h, int crop_w,
+                          int antialias, uint8_t *out)
+{
+    if (!rgb || !out || crop_h < 1 || crop_w < 1) return ORACLE_E_ARG;
+    const double zero[3] = {0.0, 0.0, 0.0}, unit[3] = {1.0, 1.0, 1.0};
+    double *planes = malloc((size_t)3 * crop_h * crop_w * sizeof *planes);
+    if (!planes) return ORACLE_E_ARG;
+    int rc = antialias ? oracle_preprocess_antialias(rgb, w, h, resize_short, crop_h, crop_w, zero, unit, planes)
+                       : oracle_preprocess(rgb, w, h, resize_short, crop_h, crop_w, zero, unit, planes);
+    if (rc == ORACLE_OK)
+        for (int y = 0; y < crop_h; y++)
+            for (int x = 0; x < crop_w; x++)
+                for (int c = 0; c < 3; c++) {
+                    /* planes hold sample / 255; nearest integer, halves upwards */
+                    double v = floor(planes[((size_t)c * crop_h + y) * crop_w + x] * 255.0 + 0.5);
+                    out[((size_t)y * crop_w + x) * 3 + c] = (uint8_t)(v < 0.0 ? 0.0 : (v > 255.0 ? 255.0 : v));
+                }
+    free(planes);
+    return rc;
+}
+

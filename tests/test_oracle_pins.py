@@ -600,6 +600,23 @@ def test_antialiased_resize_equals_the_plain_one_when_enlarging_and_keeps_consta
         np.testing.assert_allclose(out[c], (77 / 255.0 - MEAN[c]) / STD[c], atol=1e-12)
 
 
+def test_eight_bit_output_is_the_rounded_resized_sample():
+    rng = np.random.default_rng(34)
+    rgb = rng.integers(0, 256, size=(40, 60, 3), dtype=np.uint8)
+    # scale 1: the source pixels themselves, interleaved
+    assert np.array_equal(oracle.resize_crop_u8(rgb, 0, 30, 50), rgb[5:35, 5:55])
+    # 2:1 with the plain filter: means of four integers, halves upwards
+    f = rgb.astype(np.int64)
+    s4 = f[0::2, 0::2] + f[0::2, 1::2] + f[1::2, 0::2] + f[1::2, 1::2]
+    assert (s4 % 4 == 2).any(), "no half-way mean: the pin lost its point"
+    assert np.array_equal(oracle.resize_crop_u8(rgb, 20, 20, 30), (s4 + 2) // 4)
+    # antialiased: Pillow's own 8-bit result within a level (it rounds after each pass)
+    from PIL import Image
+    theirs = np.asarray(Image.fromarray(rgb).resize((30, 20), Image.BILINEAR)).astype(int)
+    mine = oracle.resize_crop_u8(rgb, 20, 20, 30, antialias=True).astype(int)
+    assert np.abs(mine - theirs).max() <= 1 and (mine == theirs).mean() > 0.75
+
+
 def test_preprocess_rejects_bad_arguments():
     rgb = np.zeros((10, 10, 3), dtype=np.uint8)
     with pytest.raises(oracle.OracleError):
