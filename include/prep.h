@@ -46,7 +46,11 @@ enum {
     PREP_E_NOMEM = -6        /* host or device allocation failed in prep_create     */
 };
 
-enum { PREP_F32 = 0, PREP_F16 = 1 };
+/* Output element type and layout.  PREP_F32, PREP_F16: the normalized tensor, planar
+ * [n][3][crop_h][crop_w].  PREP_U8_NHWC: Resize and Crop without Normalize (mean and std are
+ * not looked at), the resized samples rounded to the nearest integer, halves upwards, as
+ * interleaved RGB bytes [n][crop_h][crop_w][3]. */
+enum { PREP_F32 = 0, PREP_F16 = 1, PREP_U8_NHWC = 2 };
 
 /* The Resize unit's filter (PREBA section 4.2, Table 1 names the unit, not the filter).
  * PREP_FILTER_BILINEAR: two samples per axis around the output sample's centre (half-pixel
@@ -89,7 +93,7 @@ typedef struct {
 typedef struct {
     int32_t resize_short;  /* target length of the short side; 0 = keep the size    */
     int32_t crop_h, crop_w;
-    int32_t out_dtype;     /* PREP_F32 or PREP_F16                                  */
+    int32_t out_dtype;     /* PREP_F32, PREP_F16 or PREP_U8_NHWC                    */
     float mean[3], std[3]; /* on the 0..1 pixel scale, R, G, B                      */
     int32_t filter;        /* PREP_FILTER_BILINEAR or PREP_FILTER_ANTIALIAS         */
 } prep_params;
@@ -129,7 +133,8 @@ int prep_destroy(prep_handle *h);
  * to the GPU, entropy-decode, reconstruct RGB, resize + crop + normalize.
  *   bitstreams HOST   n files back to back
  *   offsets    HOST   n+1 entries; file i is bytes [offsets[i], offsets[i+1])
- *   out        DEVICE n*3*crop_h*crop_w elements of params->out_dtype, NCHW;
+ *   out        DEVICE n*3*crop_h*crop_w elements of params->out_dtype, NCHW (NHWC for
+ *              PREP_U8_NHWC);
  *              must stay valid until `stream` has run the enqueued work
  *   stream     a hipStream_t (NULL = the default stream)
  * The call copies what it needs from the host buffers before it returns and

@@ -152,16 +152,14 @@ void oracle_resized_size(int w, int h, int s, int *ow, int *oh)
 
 static int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-int oracle_preprocess(const uint8_t *rgb, int w, int h, int resize_short,
-                      int crop_h, int crop_w, const double mean[3], const double std[3],
-                      double *out)
+/* The resized and cropped samples on the 0..255 scale, planar out[c][y][x], not yet normalized. */
+static int resample_plain(const uint8_t *rgb, int w, int h, int resize_short, int crop_h, int crop_w,
+                          double *out)
 {
     if (!rgb || !out || w < 1 || h < 1 || crop_h < 1 || crop_w < 1) return ORACLE_E_ARG;
     int ow, oh;
     oracle_resized_size(w, h, resize_short, &ow, &oh);
     if (crop_w > ow || crop_h > oh) return ORACLE_E_ARG;
-    for (int c = 0; c < 3; c++)
-        if (!(std[c] > 0.0)) return ORACLE_E_ARG;
     int top = (oh - crop_h) / 2, left = (ow - crop_w) / 2;
     double scale_x = (double)w / (double)ow, scale_y = (double)h / (double)oh;
     for (int c = 0; c < 3; c++)
@@ -178,11 +176,33 @@ int oracle_preprocess(const uint8_t *rgb, int w, int h, int resize_short,
                 double p01 = rgb[((size_t)ya * w + xb) * 3 + c];
                 double p10 = rgb[((size_t)yb * w + xa) * 3 + c];
                 double p11 = rgb[((size_t)yb * w + xb) * 3 + c];
-                double v = (1.0 - fy) * ((1.0 - fx) * p00 + fx * p01) +
-                           fy * ((1.0 - fx) * p10 + fx * p11);
-                out[((size_t)c * crop_h + y) * crop_w + x] = (v / 255.0 - mean[c]) / std[c];
+                out[((size_t)c * crop_h + y) * crop_w + x] =
+                    (1.0 - fy) * ((1.0 - fx) * p00 + fx * p01) + fy * ((1.0 - fx) * p10 + fx * p11);
             }
     return ORACLE_OK;
+}
+
+/* Normalize (PREBA Table 1) in place: (v / 255 - mean[c]) / std[c]. */
+static int normalize_planes(double *v, int crop_h, int crop_w, const double mean[3], const double std[3])
+{
+    for (int c = 0; c < 3; c++)
+        if (!(std[c] > 0.0)) return ORACLE_E_ARG;
+    for (int c = 0; c < 3; c++)
+        for (size_t i = 0; i < (size_t)crop_h * crop_w; i++) {
+            double *p = &v[(size_t)c * crop_h * crop_w + i];
+            *p = (*p / 255.0 - mean[c]) / std[c];
+        }
+    return ORACLE_OK;
+}
+
+int oracle_preprocess(const uint8_t *rgb, int w, int h, int resize_short,
+                      int crop_h, int crop_w, const double mean[3], const double std[3],
+                      double *out)
+{
+    for (int c = 0; c < 3; c++)
+        if (!(std[c] > 0.0)) return ORACLE_E_ARG;
+    int rc = resample_plain(rgb, w, h, resize_short, crop_h, crop_w, out);
+    return rc ? rc : normalize_planes(out, crop_h, crop_w, mean, std);
 }
 
 /* Weights of the source samples that one output sample of the antialiased resize reads along
@@ -208,16 +228,13 @@ static int triangle_window(int out_index, double scale, int in_size, double *wt,
     return first;
 }
 
-int oracle_preprocess_antialias(const uint8_t *rgb, int w, int h, int resize_short,
-                                int crop_h, int crop_w, const double mean[3], const double std[3],
-                                double *out)
+static int resample_antialias(const uint8_t *rgb, int w, int h, int resize_short, int crop_h, int crop_w,
+                              double *out)
 {
     if (!rgb || !out || w < 1 || h < 1 || crop_h < 1 || crop_w < 1) return ORACLE_E_ARG;
     int ow, oh;
     oracle_resized_size(w, h, resize_short, &ow, &oh);
     if (crop_w > ow || crop_h > oh) return ORACLE_E_ARG;
-    for (int c = 0; c < 3; c++)
-        if (!(std[c] > 0.0)) return ORACLE_E_ARG;
     int top = (oh - crop_h) / 2, left = (ow - crop_w) / 2;
     double scale_x = (double)w / (double)ow, scale_y = (double)h / (double)oh;
     /* at most 2 * support + 2 samples fall under a triangle */
@@ -237,7 +254,7 @@ int oracle_preprocess_antialias(const uint8_t *rgb, int w, int h, int resize_sho
                         row += wx[k] * rgb[((size_t)(y0 + r) * w + (x0 + k)) * 3 + c];
                     v += wy[r] * row;
                 }
-                out[((size_t)c * crop_h + y) * crop_w + x] = (v / 255.0 - mean[c]) / std[c];
+                out[((size_t)c * crop_h + y) * crop_w + x] = v;
             }
         }
     }
@@ -246,24 +263,32 @@ int oracle_preprocess_antialias(const uint8_t *rgb, int w, int h, int resize_sho
     return ORACLE_OK;
 }
 
+int oracle_preprocess_antialias(const uint8_t *rgb, int w, int h, int resize_short,
+                                int crop_h, int crop_w, const double mean[3], const double std[3],
+                                double *out)
+{
+    for (int c = 0; c < 3; c++)
+        if (!(std[c] > 0.0)) return ORACLE_E_ARG;
+    int rc = resample_antialias(rgb, w, h, resize_short, crop_h, crop_w, out);
+    return rc ? rc : normalize_planes(out, crop_h, crop_w, mean, std);
+}
+
 int oracle_resize_crop_u8(const uint8_t *rgb, int w, int h, int resize_short, int crop_h, int crop_w,
                           int antialias, uint8_t *out)
 {
     if (!rgb || !out || crop_h < 1 || crop_w < 1) return ORACLE_E_ARG;
-    const double zero[3] = {0.0, 0.0, 0.0}, unit[3] = {1.0, 1.0, 1.0};
     double *planes = malloc((size_t)3 * crop_h * crop_w * sizeof *planes);
     if (!planes) return ORACLE_E_ARG;
-    int rc = antialias ? oracle_preprocess_antialias(rgb, w, h, resize_short, crop_h, crop_w, zero, unit, planes)
-                       : oracle_preprocess(rgb, w, h, resize_short, crop_h, crop_w, zero, unit, planes);
+    int rc = antialias ? resample_antialias(rgb, w, h, resize_short, crop_h, crop_w, planes)
+                       : resample_plain(rgb, w, h, resize_short, crop_h, crop_w, planes);
     if (rc == ORACLE_OK)
         for (int y = 0; y < crop_h; y++)
             for (int x = 0; x < crop_w; x++)
                 for (int c = 0; c < 3; c++) {
-                    /* planes hold sample / 255; nearest integer, halves upwards */
-                    double v = floor(planes[((size_t)c * crop_h + y) * crop_w + x] * 255.0 + 0.5);
+                    /* the resized sample itself: nearest integer, halves upwards */
+                    double v = floor(planes[((size_t)c * crop_h + y) * crop_w + x] + 0.5);
                     out[((size_t)y * crop_w + x) * 3 + c] = (uint8_t)(v < 0.0 ? 0.0 : (v > 255.0 ? 255.0 : v));
                 }
     free(planes);
     return rc;
 }
-

@@ -10,7 +10,7 @@ _CSRC = os.path.join(_HERE, "csrc")
 _SOURCES = ["entropy.hip", "reconstruct.hip", "resize.hip", "api.cpp", "parser.cpp", "batcher.cpp", "audio.hip"]
 
 OK, E_INVALID_ARG, E_TOO_LARGE, E_HIP, E_UNSUPPORTED, E_CORRUPT, E_NOMEM = 0, -1, -2, -3, -4, -5, -6
-F32, F16 = 0, 1
+F32, F16, U8_NHWC = 0, 1, 2
 FLAG_TABLES_PER_WORKGROUP = 1
 FLAG_FULL_RGB = 2
 FILTER_BILINEAR, FILTER_ANTIALIAS = 0, 1
@@ -182,7 +182,7 @@ def _u64(a):
 def make_params(resize_short, crop_h, crop_w, out_dtype, mean, std, filter=FILTER_BILINEAR):
     p = Params()
     p.resize_short, p.crop_h, p.crop_w = int(resize_short), int(crop_h), int(crop_w)
-    p.out_dtype = {"f32": F32, "f16": F16}.get(out_dtype, out_dtype)
+    p.out_dtype = {"f32": F32, "f16": F16, "u8": U8_NHWC}.get(out_dtype, out_dtype)
     p.filter = int(filter)
     p.mean[:] = [float(m) for m in mean]
     p.std[:] = [float(s) for s in std]
@@ -344,8 +344,11 @@ class Server:
         cfg.params = params
         cfg.n_consumers, cfg.batch_max, cfg.time_queue_us = int(n_consumers), int(batch_max), int(time_queue_us)
         cfg.max_request_bytes, cfg.queue_capacity = int(max_request_bytes), int(queue_capacity)
-        self._shape = (3, params.crop_h, params.crop_w)
-        self._dtype = np.float16 if params.out_dtype == F16 else np.float32
+        if params.out_dtype == U8_NHWC:
+            self._shape, self._dtype = (params.crop_h, params.crop_w, 3), np.uint8
+        else:
+            self._shape = (3, params.crop_h, params.crop_w)
+            self._dtype = np.float16 if params.out_dtype == F16 else np.float32
         self._s = C.c_void_p()
         _check(lib().prep_server_create(C.byref(self._s), C.byref(cfg)), "prep_server_create")
 

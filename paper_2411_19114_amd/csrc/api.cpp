@@ -97,8 +97,9 @@ bool params_ok(const prep_params *p)
     if (!p) return false;
     if (p->resize_short < 0 || p->resize_short > 65535) return false;
     if (p->crop_h < 1 || p->crop_w < 1 || p->crop_h > 65535 || p->crop_w > 65535) return false;
-    if (p->out_dtype != PREP_F32 && p->out_dtype != PREP_F16) return false;
+    if (p->out_dtype != PREP_F32 && p->out_dtype != PREP_F16 && p->out_dtype != PREP_U8_NHWC) return false;
     if (p->filter != PREP_FILTER_BILINEAR && p->filter != PREP_FILTER_ANTIALIAS) return false;
+    if (p->out_dtype == PREP_U8_NHWC) return true;  // no Normalize: mean and std are not looked at
     for (int c = 0; c < 3; c++)
         if (!(p->std[c] > 0.0f) || !isfinite(p->std[c]) || !isfinite(p->mean[c])) return false;
     return true;

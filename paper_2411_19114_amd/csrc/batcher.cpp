@@ -221,7 +221,8 @@ int prep_server_create(prep_server **out, const prep_server_config *cfg)
     if (!cfg || cfg->n_consumers < 1 || cfg->n_consumers > 64 || cfg->batch_max < 1 || cfg->batch_max > 65535 ||
         cfg->time_queue_us < 0 || cfg->max_request_bytes < 1 || cfg->queue_capacity < cfg->batch_max ||
         cfg->params.crop_h < 1 || cfg->params.crop_w < 1 ||
-        (cfg->params.out_dtype != PREP_F32 && cfg->params.out_dtype != PREP_F16))
+        (cfg->params.out_dtype != PREP_F32 && cfg->params.out_dtype != PREP_F16 &&
+         cfg->params.out_dtype != PREP_U8_NHWC))
         return PREP_E_INVALID_ARG;
     prep_server *s = new (std::nothrow) prep_server;
     if (!s) return PREP_E_NOMEM;
@@ -229,7 +230,8 @@ int prep_server_create(prep_server **out, const prep_server_config *cfg)
     s->cfg.handle.max_batch = cfg->batch_max;
     const uint64_t batch_bytes = (uint64_t)cfg->batch_max * (uint64_t)cfg->max_request_bytes;
     if (s->cfg.handle.max_bitstream_bytes < batch_bytes) s->cfg.handle.max_bitstream_bytes = batch_bytes;
-    s->slab_bytes = (size_t)3 * cfg->params.crop_h * cfg->params.crop_w * (cfg->params.out_dtype == PREP_F16 ? 2 : 4);
+    s->slab_bytes = (size_t)3 * cfg->params.crop_h * cfg->params.crop_w *
+                    (cfg->params.out_dtype == PREP_F32 ? 4 : cfg->params.out_dtype == PREP_F16 ? 2 : 1);
     int rc = prep_policy_create(&s->policy, cfg->batch_max, cfg->time_queue_us * 1000);
     // requests in flight: those waiting, those being served and those whose result nobody has
     // read yet (when these fill the pool, submissions are refused until results are read)

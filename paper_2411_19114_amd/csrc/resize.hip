@@ -44,6 +44,25 @@ __device__ inline void store_row(__half *p, const float v[kPx])
 static_assert(kPx == 4, "store_row writes four values");
 __device__ inline void store1(float *p, float v) { *p = v; }
 __device__ inline void store1(__half *p, float v) { *p = __float2half_rn(v); }
+__device__ inline void store1(uint8_t *p, float v);
+
+// 8-bit output: a resized sample (0 .. 255, no Normalize) to the nearest integer, halves upwards
+__device__ inline uint32_t to_byte(float v) { return min((uint32_t)(v + 0.5f), 255u); }
+__device__ inline void store1(uint8_t *p, float v) { *p = (uint8_t)to_byte(v); }
+
+// Where output (img, y, x) of plane c goes: planar [n][3][h][w], or interleaved [n][h][w][3]
+// for the 8-bit output.
+template <typename OutT>
+__device__ inline OutT *output_at(OutT *out, int img, int y, int x, int crop_h, int crop_w, size_t *plane)
+{
+    const size_t in_image = (size_t)y * crop_w + x, image = (size_t)crop_h * crop_w;
+    if (sizeof(OutT) == 1) {
+        *plane = 1;
+        return out + ((size_t)img * image + in_image) * 3;
+    }
+    *plane = image;
+    return out + (size_t)img * 3 * image + in_image;
+}
 
 }  // namespace
 
@@ -87,8 +106,8 @@ __global__ __launch_bounds__(kResizeThreads) void resize_crop_normalize(
     if (item >= groups * crop_h) return;
     const int y = item / groups, x0 = (item - y * groups) * kPx;
     const int nx = min(kPx, crop_w - x0);
-    const size_t plane = (size_t)crop_h * crop_w;
-    OutT *o = out + (size_t)img * 3 * plane + (size_t)y * crop_w + x0;
+    size_t plane;
+    OutT *o = output_at(out, img, y, x0, crop_h, crop_w, &plane);
     const bool vec = nx == kPx && vec_ok;
     float res[3][kPx];
     const bool ok = status == nullptr || status[img] == PREP_OK;
@@ -135,12 +154,29 @@ __global__ __launch_bounds__(kResizeThreads) void resize_crop_normalize(
             }
         }
     }
+    if constexpr (sizeof(OutT) == 1) {
+        // kPx pixels = 12 adjacent bytes
+        uint32_t b[3 * kPx];
 #pragma unroll
-    for (int c = 0; c < 3; c++) {
+        for (int j = 0; j < kPx; j++)
+#pragma unroll
+            for (int c = 0; c < 3; c++) b[3 * j + c] = to_byte(res[c][j]);
         if (vec) {
-            store_row(o + c * plane, res[c]);
+            uint32_t *w = reinterpret_cast<uint32_t *>(o);
+#pragma unroll
+            for (int k = 0; k < 3; k++)
+                w[k] = b[4 * k] | (b[4 * k + 1] << 8) | (b[4 * k + 2] << 16) | (b[4 * k + 3] << 24);
         } else {
-            for (int j = 0; j < nx; j++) store1(o + c * plane + j, res[c][j]);
+            for (int j = 0; j < 3 * nx; j++) o[j] = (uint8_t)b[j];
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < 3; c++) {
+            if (vec) {
+                store_row(o + c * plane, res[c]);
+            } else {
+                for (int j = 0; j < nx; j++) store1(o + c * plane + j, res[c][j]);
+            }
         }
     }
 }
@@ -329,8 +365,8 @@ __global__ __launch_bounds__(kResizeThreads) void resize_antialias_crop_normaliz
         }
     }
     if (inside) {
-        const size_t plane = (size_t)crop_h * crop_w;
-        OutT *o = out + (size_t)img * 3 * plane + (size_t)y * crop_w + x;
+        size_t plane;
+        OutT *o = output_at(out, img, y, x, crop_h, crop_w, &plane);
 #pragma unroll
         for (int ch = 0; ch < 3; ch++) store1(o + ch * plane, res[ch]);
     }
@@ -342,6 +378,48 @@ void resize_antialias_classes(const ResizeRec *rr, int n, bool *any_direct, bool
     for (int i = 0; i < n; i++) *(sums_columns_first(rr[i]) ? any_columns_first : any_direct) = true;
 }
 
+namespace {
+
+// The launches of one output type.
+template <typename OutT>
+void launch_for(const uint8_t *rgb, const ResizeRec *rr, const int32_t *status, int n_images, int crop_h,
+                int crop_w, int filter, const ResizeRec *host_rr, const NormConst &nc, OutT *out,
+                bool wide_reads, hipStream_t stream)
+{
+    dim3 block(kResizeThreads);
+    if (filter == PREP_FILTER_ANTIALIAS) {
+        dim3 grid((crop_w + kTileW - 1) / kTileW, (crop_h + kTileH - 1) / kTileH, n_images);
+        auto launch = [&](auto kernel) {
+            hipLaunchKernelGGL(kernel, grid, block, 0, stream, rgb, rr, status, crop_h, crop_w, nc, out);
+        };
+        // every image is done by exactly one of the two launches
+        bool direct, columns;
+        resize_antialias_classes(host_rr, n_images, &direct, &columns);
+        if (wide_reads) {
+            if (direct) launch(resize_antialias_crop_normalize<OutT, true, false>);
+            if (columns) launch(resize_antialias_crop_normalize<OutT, true, true>);
+        } else {
+            if (direct) launch(resize_antialias_crop_normalize<OutT, false, false>);
+            if (columns) launch(resize_antialias_crop_normalize<OutT, false, true>);
+        }
+        return;
+    }
+    const int groups = (crop_w + kPx - 1) / kPx;
+    const int items = groups * crop_h;
+    // vector stores need every group of kPx outputs to start 16-byte aligned (4-byte aligned
+    // for the 8-bit output, which the same test covers)
+    const int vec_ok = crop_w % kPx == 0 && ((uintptr_t)out & 15u) == 0;
+    dim3 grid((items + kResizeThreads - 1) / kResizeThreads, n_images);
+    if (wide_reads)
+        hipLaunchKernelGGL((resize_crop_normalize<OutT, true>), grid, block, 0, stream, rgb, rr, status,
+                           crop_h, crop_w, vec_ok, nc, out);
+    else
+        hipLaunchKernelGGL((resize_crop_normalize<OutT, false>), grid, block, 0, stream, rgb, rr, status,
+                           crop_h, crop_w, vec_ok, nc, out);
+}
+
+}  // namespace
+
 void launch_resize_normalize(const uint8_t *rgb, const ResizeRec *rr, const int32_t *status,
                              int n_images, int crop_h, int crop_w, int out_dtype, int filter,
                              const ResizeRec *host_rr, const float mean[3], const float std[3], void *out,
@@ -350,58 +428,16 @@ void launch_resize_normalize(const uint8_t *rgb, const ResizeRec *rr, const int3
     if (n_images <= 0) return;
     NormConst nc;
     for (int c = 0; c < 3; c++) {
-        nc.scale[c] = (float)(1.0 / (255.0 * (double)std[c]));
-        nc.bias[c] = (float)(-(double)mean[c] / (double)std[c]);
+        // the 8-bit output is the resized sample itself
+        nc.scale[c] = out_dtype == PREP_U8_NHWC ? 1.0f : (float)(1.0 / (255.0 * (double)std[c]));
+        nc.bias[c] = out_dtype == PREP_U8_NHWC ? 0.0f : (float)(-(double)mean[c] / (double)std[c]);
     }
-    if (filter == PREP_FILTER_ANTIALIAS) {
-        dim3 grid((crop_w + kTileW - 1) / kTileW, (crop_h + kTileH - 1) / kTileH, n_images);
-        dim3 block(kResizeThreads);
-        auto launch = [&](auto kernel, auto *o) {
-            hipLaunchKernelGGL(kernel, grid, block, 0, stream, rgb, rr, status, crop_h, crop_w, nc, o);
-        };
-        // every image is done by exactly one of the two launches
-        bool direct, columns;
-        resize_antialias_classes(host_rr, n_images, &direct, &columns);
-        if (out_dtype == PREP_F16) {
-            if (wide_reads) {
-                if (direct) launch(resize_antialias_crop_normalize<__half, true, false>, (__half *)out);
-                if (columns) launch(resize_antialias_crop_normalize<__half, true, true>, (__half *)out);
-            } else {
-                if (direct) launch(resize_antialias_crop_normalize<__half, false, false>, (__half *)out);
-                if (columns) launch(resize_antialias_crop_normalize<__half, false, true>, (__half *)out);
-            }
-        } else {
-            if (wide_reads) {
-                if (direct) launch(resize_antialias_crop_normalize<float, true, false>, (float *)out);
-                if (columns) launch(resize_antialias_crop_normalize<float, true, true>, (float *)out);
-            } else {
-                if (direct) launch(resize_antialias_crop_normalize<float, false, false>, (float *)out);
-                if (columns) launch(resize_antialias_crop_normalize<float, false, true>, (float *)out);
-            }
-        }
-        return;
-    }
-    const int groups = (crop_w + kPx - 1) / kPx;
-    const int items = groups * crop_h;
-    // vector stores need every group of kPx outputs to start 16-byte aligned
-    const int vec_ok = crop_w % kPx == 0 && ((uintptr_t)out & 15u) == 0;
-    dim3 grid((items + kResizeThreads - 1) / kResizeThreads, n_images);
-    dim3 block(kResizeThreads);
-    if (out_dtype == PREP_F16) {
-        if (wide_reads)
-            hipLaunchKernelGGL((resize_crop_normalize<__half, true>), grid, block, 0, stream, rgb, rr,
-                               status, crop_h, crop_w, vec_ok, nc, (__half *)out);
-        else
-            hipLaunchKernelGGL((resize_crop_normalize<__half, false>), grid, block, 0, stream, rgb, rr,
-                               status, crop_h, crop_w, vec_ok, nc, (__half *)out);
-    } else {
-        if (wide_reads)
-            hipLaunchKernelGGL((resize_crop_normalize<float, true>), grid, block, 0, stream, rgb, rr,
-                               status, crop_h, crop_w, vec_ok, nc, (float *)out);
-        else
-            hipLaunchKernelGGL((resize_crop_normalize<float, false>), grid, block, 0, stream, rgb, rr,
-                               status, crop_h, crop_w, vec_ok, nc, (float *)out);
-    }
+    if (out_dtype == PREP_F16)
+        launch_for(rgb, rr, status, n_images, crop_h, crop_w, filter, host_rr, nc, (__half *)out, wide_reads, stream);
+    else if (out_dtype == PREP_U8_NHWC)
+        launch_for(rgb, rr, status, n_images, crop_h, crop_w, filter, host_rr, nc, (uint8_t *)out, wide_reads, stream);
+    else
+        launch_for(rgb, rr, status, n_images, crop_h, crop_w, filter, host_rr, nc, (float *)out, wide_reads, stream);
 }
 
 }  // namespace prep

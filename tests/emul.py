@@ -37,10 +37,11 @@ def run(streams, resize_short, crop_h, crop_w, out_dtype, mean, std, timeout=600
     offsets = np.zeros(n + 1, dtype=np.uint64)
     np.cumsum([len(s) for s in streams], out=offsets[1:])
     f16 = out_dtype == "f16"
+    code = {"f32": 0, "f16": 1, "u8": 2}[out_dtype]
     with tempfile.TemporaryDirectory() as d:
         fin, fout = os.path.join(d, "in.bin"), os.path.join(d, "out.bin")
         with open(fin, "wb") as f:
-            f.write(struct.pack("<5i", n, resize_short, crop_h, crop_w, 1 if f16 else 0))
+            f.write(struct.pack("<5i", n, resize_short, crop_h, crop_w, code))
             f.write(struct.pack("<6f", *mean, *std))
             f.write(offsets.tobytes())
             f.write(b"".join(streams))
@@ -65,6 +66,8 @@ def run(streams, resize_short, crop_h, crop_w, out_dtype, mean, std, timeout=600
         rgb = np.frombuffer(blob, dtype=np.uint8, count=nr, offset=pos) if nr else None
         pos += nr
         per_image.append((status, coef, rgb, rect))
+    if out_dtype == "u8":
+        return per_image, np.frombuffer(blob, dtype=np.uint8, offset=pos).reshape(n, crop_h, crop_w, 3)
     dt = np.float16 if f16 else np.float32
     tensor = np.frombuffer(blob, dtype=dt, offset=pos).reshape(n, 3, crop_h, crop_w)
     return per_image, tensor

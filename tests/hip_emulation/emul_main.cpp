@@ -55,7 +55,7 @@ int main(int argc, char **argv)
     prep_handle *h = nullptr;
     rc = prep_create(&h, &cfg);
     if (rc) die("prep_create", rc);
-    const size_t esz = P.out_dtype == PREP_F16 ? 2 : 4;
+    const size_t esz = P.out_dtype == PREP_F32 ? 4 : P.out_dtype == PREP_F16 ? 2 : 1;
     std::vector<uint8_t> out((size_t)n * 3 * P.crop_h * P.crop_w * esz + 16, 0xAB);
     rc = prep_decode_resize_batch(h, bits.data(), off.data(), n, &P, out.data(), nullptr);
     if (rc) die("prep_decode_resize_batch", rc);

@@ -71,6 +71,26 @@ def test_antialiased_resize_reducing_enlarging_and_at_the_edges():
     _check(streams[2:], 0, 64, 97, "f32", antialias=True)
 
 
+def test_eight_bit_interleaved_output_of_both_filters():
+    streams = [oracle.encode(_img(60, 160, 100), 90, MODE_420, 4)[0],
+               oracle.encode(_img(61, 75, 131), 90, MODE_444, 0)[0],
+               b"not a jpeg"]
+    for rs, ch, cw, aa in ((40, 40, 40, False), (40, 33, 38, True), (0, 64, 75, False), (150, 120, 150, True)):
+        per, got = emul.run(streams, rs, ch, cw, "u8", MEAN, STD, antialias=aa)
+        assert [p[0] for p in per][:2] == [0, 0] and per[2][0] != 0
+        assert (got[2] == 0).all()    # a failed image's slab is zero-filled
+        exact = total = 0
+        for i in range(2):
+            _, rgb, _ = oracle.decode(streams[i], want_coef=False)
+            ref = oracle.resize_crop_u8(rgb, rs, ch, cw, aa).astype(int)
+            d = np.abs(got[i].astype(int) - ref)
+            # the decoded pixels may be a level off and the rounding may fall the other way
+            assert d.max() <= 2, (rs, ch, cw, aa, i, d.max())
+            exact += int((d == 0).sum())
+            total += d.size
+        assert exact >= 0.97 * total, (rs, ch, cw, aa, exact / total)
+
+
 def test_pillow_streams_of_workloads_1_and_5():
     streams = [synth.make_image(1, 5)[0], synth.make_image(5, 0)[0], synth.make_image(5, 1)[0],
                synth.make_image(5, 2)[0]]

@@ -125,6 +125,44 @@ def test_antialiased_resize_over_the_whole_path(pp):
     check_against_oracle(pp, odd[2:3], 0, 64, 97, "f32", antialias=True)
 
 
+def test_eight_bit_interleaved_output(pp):
+    # Resize and Crop without Normalize, rounded to bytes, [n][h][w][3]: the resize stage alone on
+    # given pixels (only the rounding of near-ties can differ), then the whole path (a decoded
+    # pixel may be a level off, and the output with it)
+    import torch
+    from paper_2411_19114_amd.binding import make_params
+    rng = np.random.default_rng(11)
+    shapes = [(640, 480), (300, 500), (33, 77), (256, 256)]
+    imgs = [rng.integers(0, 256, size=(h, w, 3), dtype=np.uint8) for w, h in shapes]
+    flat = np.concatenate([im.reshape(-1) for im in imgs])
+    offs = np.cumsum([0] + [im.size for im in imgs[:-1]]).astype(np.uint64)
+    dev = torch.from_numpy(flat).to("cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    for rs, ch, cw, aa in ((256, 224, 224, 0), (32, 31, 30, 0), (128, 128, 128, 1), (32, 31, 30, 1), (600, 600, 598, 1)):
+        out = torch.full((len(imgs), ch, cw, 3), 77, dtype=torch.uint8, device="cuda:0")
+        pp.resize_normalize(dev.data_ptr(), offs, [s[0] for s in shapes], [s[1] for s in shapes],
+                            [s[0] * 3 for s in shapes], make_params(rs, ch, cw, "u8", MEAN, STD, aa),
+                            out.data_ptr(), stream)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(int)
+        d = np.stack([np.abs(got[i] - oracle.resize_crop_u8(im, rs, ch, cw, bool(aa)).astype(int))
+                      for i, im in enumerate(imgs)])
+        assert d.max() <= 1 and (d == 0).mean() >= 0.999, (rs, ch, cw, aa, d.max(), (d == 0).mean())
+    streams = synth.make_batch(2, 6) + [b"no image"]
+    blob, offsets = synth.pack(streams)
+    for aa in (0, 1):
+        out = torch.full((len(streams), 224, 224, 3), 77, dtype=torch.uint8, device="cuda:0")
+        pp.decode_resize_batch(blob, offsets, make_params(256, 224, 224, "u8", MEAN, STD, aa), out.data_ptr(), stream)
+        status = pp.get_status(len(streams))
+        assert status[:-1] == [0] * 6 and status[-1] != 0
+        got = out.cpu().numpy().astype(int)
+        assert (got[-1] == 0).all()
+        d = np.stack([np.abs(got[i] - oracle.resize_crop_u8(oracle.decode(s, want_coef=False)[1], 256, 224, 224,
+                                                            bool(aa)).astype(int))
+                      for i, s in enumerate(streams[:-1])])
+        assert d.max() <= 2 and (d == 0).mean() >= 0.995, (aa, d.max(), (d == 0).mean())
+
+
 def test_all_eob_and_dc_only_blocks(pp):
     # shortest possible blocks: hundreds of blocks per decoder subsequence
     w, h = 512, 256

@@ -610,6 +610,11 @@ def test_eight_bit_output_is_the_rounded_resized_sample():
     s4 = f[0::2, 0::2] + f[0::2, 1::2] + f[1::2, 0::2] + f[1::2, 1::2]
     assert (s4 % 4 == 2).any(), "no half-way mean: the pin lost its point"
     assert np.array_equal(oracle.resize_crop_u8(rgb, 20, 20, 30), (s4 + 2) // 4)
+    # 8:1 with the plain filter: the mean of the four pixels around 8 i + 4, halves upwards
+    big = rng.integers(0, 256, size=(64, 64, 3), dtype=np.int64)
+    m4 = big[3::8, 3::8] + big[3::8, 4::8] + big[4::8, 3::8] + big[4::8, 4::8]
+    assert (m4 % 4 == 2).any()
+    assert np.array_equal(oracle.resize_crop_u8(big.astype(np.uint8), 8, 8, 8), (m4 + 2) // 4)
     # antialiased: Pillow's own 8-bit result within a level (it rounds after each pass)
     from PIL import Image
     theirs = np.asarray(Image.fromarray(rgb).resize((30, 20), Image.BILINEAR)).astype(int)
