@@ -48,7 +48,9 @@ enum {
 
 /* Output element type and layout.  PREP_F32, PREP_F16: the normalized tensor, planar
  * [n][3][crop_h][crop_w].  PREP_U8_NHWC: Resize and Crop without Normalize (mean and std are
- * not looked at), the resized samples rounded to the nearest integer, halves upwards, as
+ * not looked at), the resized samples rounded to the nearest integer, halves upwards (a
+ * sample within 1/1024 below a half counts as a half: rational scales produce exact halves
+ * all the time, and they must not depend on the last bit of the interpolation), as
  * interleaved RGB bytes [n][crop_h][crop_w][3]. */
 enum { PREP_F32 = 0, PREP_F16 = 1, PREP_U8_NHWC = 2 };
 

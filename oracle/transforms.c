@@ -285,8 +285,11 @@ int oracle_resize_crop_u8(const uint8_t *rgb, int w, int h, int resize_short, in
         for (int y = 0; y < crop_h; y++)
             for (int x = 0; x < crop_w; x++)
                 for (int c = 0; c < 3; c++) {
-                    /* the resized sample itself: nearest integer, halves upwards */
-                    double v = floor(planes[((size_t)c * crop_h + y) * crop_w + x] + 0.5);
+                    /* the resized sample itself to the nearest integer, halves upwards; a sample
+                     * within 1/1024 below a half counts as a half, so that the halves that rational
+                     * scales produce all the time (weights k/42 and the like) do not depend on the
+                     * last bit of the arithmetic that formed them */
+                    double v = floor(planes[((size_t)c * crop_h + y) * crop_w + x] + 0.5 + 1.0 / 1024.0);
                     out[((size_t)y * crop_w + x) * 3 + c] = (uint8_t)(v < 0.0 ? 0.0 : (v > 255.0 ? 255.0 : v));
                 }
     free(planes);

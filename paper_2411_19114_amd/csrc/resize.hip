@@ -46,8 +46,10 @@ __device__ inline void store1(float *p, float v) { *p = v; }
 __device__ inline void store1(__half *p, float v) { *p = __float2half_rn(v); }
 __device__ inline void store1(uint8_t *p, float v);
 
-// 8-bit output: a resized sample (0 .. 255, no Normalize) to the nearest integer, halves upwards
-__device__ inline uint32_t to_byte(float v) { return min((uint32_t)(v + 0.5f), 255u); }
+// 8-bit output: a resized sample (0 .. 255, no Normalize) to the nearest integer, halves
+// upwards, where a sample within 1/1024 below a half counts as a half (far more than the
+// interpolation's rounding error, far less than matters)
+__device__ inline uint32_t to_byte(float v) { return min((uint32_t)(v + (0.5f + 1.0f / 1024.0f)), 255u); }
 __device__ inline void store1(uint8_t *p, float v) { *p = (uint8_t)to_byte(v); }
 
 // Where output (img, y, x) of plane c goes: planar [n][3][h][w], or interleaved [n][h][w][3]
