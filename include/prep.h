@@ -10,16 +10,18 @@
  * The paper fixes nothing below that level; this library reads it as
  *   decode    : ITU-T T.81 baseline sequential DCT, Huffman coded, 8 bit,
  *               1 or 3 components in one interleaved scan, sampling gray /
- *               4:4:4 / 4:2:0, optional restart intervals; chroma upsampled by
+ *               4:4:4 / 4:2:0 / 4:2:2 / 4:4:0, optional restart intervals; chroma upsampled by
  *               sample replication; JFIF YCbCr -> RGB; samples and RGB values
  *               rounded half up and clamped to 0..255;
  *   resize    : short side -> resize_short, long side floor(resize_short *
  *               long / short); bilinear, pixel centres at half-integers,
  *               per-axis scale in/out, taps clamped at the border, no
- *               prefilter, no intermediate rounding;
+ *               prefilter, no intermediate rounding (PREP_FILTER_BILINEAR), or the
+ *               antialiased form of it (PREP_FILTER_ANTIALIAS, see there);
  *   crop      : centre window crop_h x crop_w, origin floor(margin / 2);
  *   normalize : (v / 255 - mean[c]) / std[c];
- *   output    : planar NCHW, RGB channel order, fp32 or fp16.
+ *   output    : planar NCHW, RGB channel order, fp32 or fp16; or, without normalize,
+ *               the resized crop as interleaved 8-bit RGB (PREP_U8_NHWC).
  *
  * All entry points are plain C.  "HOST" pointers are ordinary process memory,
  * "DEVICE" pointers are HIP device memory of the handle's GPU.  A handle may be
@@ -68,7 +70,8 @@ enum { PREP_FILTER_BILINEAR = 0, PREP_FILTER_ANTIALIAS = 1 };
  *   instead of once per distinct table set of the batch (same results; kept for checking
  *   that path).
  * PREP_FLAG_FULL_RGB: convert every MCU of every image to RGB.  Without it only the MCUs
- *   whose pixels the crop window's bilinear taps read are converted (the output tensor is the
+ *   whose pixels the crop window's outputs read (the two taps per axis of the bilinear filter,
+ *   the samples under the triangles of the antialiased one) are converted (the output tensor is the
  *   same; the paper's image unit streams decode into resize and crop without keeping a
  *   decoded image either, section 4.2), and prep_debug_last_rgb returns what the workspace
  *   holds outside those MCUs. */
@@ -225,8 +228,8 @@ int64_t prep_debug_last_rgb(prep_handle *h, int32_t image, uint8_t *host_out_hwc
 /* The pixels of image `image` that the last call converted to RGB:
  * rect = {x0, y0, x1, y1}, columns x0 <= x < x1 and rows y0 <= y < y1 (HOST,
  * 4 entries).  It is the whole image for a handle created with
- * PREP_FLAG_FULL_RGB, else the MCUs that the crop window's bilinear taps
- * read, clipped to the image.  Returns PREP_OK, the image's own status if
+ * PREP_FLAG_FULL_RGB, else the MCUs that the crop window's outputs read
+ * through the call's resize filter, clipped to the image.  Returns PREP_OK, the image's own status if
  * it was refused, or PREP_E_INVALID_ARG.                                      */
 int prep_debug_last_region(prep_handle *h, int32_t image, int32_t rect[4]);
 

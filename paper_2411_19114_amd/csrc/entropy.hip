@@ -45,8 +45,10 @@ static_assert(kSubseqBytes == 64 && (kSubseqBytes / 4) == (1 << kPadShift), "one
 
 // Lookup entry of a Huffman code (16 bits):
 //   bits 15..11 code length + number of appended bits (1..31); 0 = not a code entry
-//   bit 10      the symbol's coefficient index must lie inside the block (all but EOB)
-//   bits 9..4   zig-zag advance - 1 (DC 1, AC run+1, ZRL 16, EOB 64)
+//   bits 10..4  zig-zag advance - 1 (DC 1, AC run+1, ZRL 16, EOB 128).  Added to the zig-zag
+//               index it gives the index k of the symbol's coefficient, which must not exceed
+//               63 except for EOB, whose coefficient is the block's last: k <= 63 is in order,
+//               64 <= k < 128 is a run past the block's end, k >= 128 is EOB (bit 6 of k tells)
 //   bits 3..0   number of appended bits
 // A first-level entry that is not a code entry refers to the table's second-level pool:
 // bits 10..8 = extra index bits (0..6), bits 7..0 = offset of its block.  Two pool entries are
@@ -55,7 +57,7 @@ static_assert(kSubseqBytes == 64 && (kSubseqBytes / 4) == (1 << kPadShift), "one
 // not fit the pool: search the canonical code lists instead).
 constexpr uint32_t kUseLoop = 0x07FFu;
 constexpr uint32_t kPoolReserved = 2, kPoolSearchRef = 1;
-constexpr uint32_t kInvalidEntry = (16u << 11) | (63u << 4);  // 16 bits, ends the block
+constexpr uint32_t kInvalidEntry = (16u << 11) | (127u << 4);  // 16 bits, ends the block
 
 struct alignas(16) HuffTables {
     alignas(8) uint16_t lut[4 << kLutBits];  // first level, indexed by the next kLutBits bits
@@ -190,20 +192,16 @@ __device__ inline bool canonical_lookup(const HuffTables &T, int t, uint32_t pee
 
 __device__ inline uint32_t make_entry(bool ac, uint32_t sym, uint32_t len)
 {
-    uint32_t s = sym & 15u, inc, store;
+    uint32_t s = sym & 15u, inc;
     if (!ac) {
         if (sym > 11u) return 0u;  // no such DC category in baseline
         inc = 1;
-        store = 1;
     } else if (s == 0) {
-        const bool zrl = (sym >> 4) == 15u;
-        inc = zrl ? 16u : 64u;  // ZRL, otherwise end of block
-        store = zrl ? 1u : 0u;
+        inc = (sym >> 4) == 15u ? 16u : 128u;  // ZRL, otherwise end of block
     } else {
         inc = (sym >> 4) + 1u;
-        store = 1;
     }
-    return ((len + s) << 11) | (store << 10) | ((inc - 1u) << 4) | s;
+    return ((len + s) << 11) | ((inc - 1u) << 4) | s;
 }
 
 // The first level is filled code by code: canonical codes of one table are consecutive when
@@ -376,10 +374,11 @@ __device__ __forceinline__ uint32_t clean_index(uint32_t w)
 // (F.2.2.1 EXTEND); adv = code length + s
 __device__ __forceinline__ int32_t coefficient_value(uint32_t win, uint32_t adv, uint32_t s)
 {
-    const uint32_t mag = __builtin_amdgcn_ubfe(win, 32u - adv, s);  // RECEIVE(s): the s bits after the code; 0 for s = 0
-    const int32_t lower = (int32_t)((0xFFFFFFFFu << s) + 1u);       // -(2^s - 1)
-    // EXTEND: a value whose first appended bit is 0 (2 mag < 2^s) lies 2^s - 1 lower
-    return (int32_t)mag + ((int32_t)(mag << 1) + lower > 0 ? 0 : lower);
+    // RECEIVE(s) read as a signed field: t < 0 where the first appended bit is 1; 0 for s = 0
+    const int32_t t = __builtin_amdgcn_sbfe((int32_t)win, 32u - adv, s);
+    // EXTEND: first bit 1: the bits are the value, t + 2^s; first bit 0: 2^s - 1 below them.
+    // With m = t >> 31 both are t + ((-2^s) ^ m) + 1.
+    return t + (int32_t)((0xFFFFFFFFu << s) ^ (uint32_t)(t >> 31)) + 1;
 }
 
 // Decode from packed state `st` until the bit position reaches end_bit.
@@ -479,7 +478,7 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                     ahead = S.clean[clean_index(w + 2)];
                 }
             } else {
-                const uint32_t k = zz + ((e >> 4) & 63u);  // index of the symbol's coefficient
+                const uint32_t k = zz + ((e >> 4) & 127u);  // index of the symbol's coefficient
                 if (kWrite) {
                     // Every symbol stores.  ZRL and EOB carry no appended bits, so their value
                     // is 0, and it lands on a coefficient that they declare to be zero: the
@@ -487,7 +486,7 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                     // past the image keeps overwriting the image's last coefficient; the block
                     // count then gives it away.
                     wc->coef[min(boff + min(k, 63u), last)] = (int16_t)coefficient_value(win, adv, e & 15u);
-                    over |= (e >> 4) & k;
+                    over |= k;
                     late |= iv_rem - 1;
                 }
                 p += adv;
@@ -567,12 +566,12 @@ __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const
     // is padding, or nothing at all
     while (p + (e >> 11) <= end_bit) {
         const uint32_t adv = e >> 11;
-        const uint32_t k = (at & 63u) + ((e >> 4) & 63u);  // index of the symbol's coefficient
+        const uint32_t k = (at & 63u) + ((e >> 4) & 127u);  // index of the symbol's coefficient
         // every symbol stores (see decode_span)
         const uint32_t here = (at & ~63u) | min(k, 63u);
         wc->coef[min(here, last)] = (int16_t)coefficient_value(win, adv, e & 15u);
         at = here + 1u;
-        over |= (e >> 4) & k;
+        over |= k;
         p += adv;
         {
             const bool moved = (p >> 5) != w;

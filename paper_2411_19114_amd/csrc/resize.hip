@@ -1,4 +1,5 @@
-// Bilinear resize + centre crop + mean/std normalize -> planar NCHW, fused (gfx950).
+// Resize (two-tap bilinear or antialiased) + centre crop + mean/std normalize -> planar NCHW,
+// or without normalize -> 8-bit NHWC, fused (gfx950).
 //
 // The Resize, Crop and Normalize functional units of the image CU (PREBA
 // section 4.2, Table 1), streamed through one kernel as the paper streams them
@@ -42,18 +43,17 @@ __device__ inline void store_row(__half *p, const float v[kPx])
     *reinterpret_cast<uint2 *>(p) = u;
 }
 static_assert(kPx == 4, "store_row writes four values");
-__device__ inline void store1(float *p, float v) { *p = v; }
-__device__ inline void store1(__half *p, float v) { *p = __float2half_rn(v); }
-__device__ inline void store1(uint8_t *p, float v);
-
 // 8-bit output: a resized sample (0 .. 255, no Normalize) to the nearest integer, halves
 // upwards, where a sample within 1/1024 below a half counts as a half (far more than the
 // interpolation's rounding error, far less than matters)
 __device__ inline uint32_t to_byte(float v) { return min((uint32_t)(v + (0.5f + 1.0f / 1024.0f)), 255u); }
+
+__device__ inline void store1(float *p, float v) { *p = v; }
+__device__ inline void store1(__half *p, float v) { *p = __float2half_rn(v); }
 __device__ inline void store1(uint8_t *p, float v) { *p = (uint8_t)to_byte(v); }
 
-// Where output (img, y, x) of plane c goes: planar [n][3][h][w], or interleaved [n][h][w][3]
-// for the 8-bit output.
+// Where channel 0 of output (img, y, x) goes and how far apart its channels are (*plane):
+// planar [n][3][h][w], or interleaved [n][h][w][3] for the 8-bit output.
 template <typename OutT>
 __device__ inline OutT *output_at(OutT *out, int img, int y, int x, int crop_h, int crop_w, size_t *plane)
 {

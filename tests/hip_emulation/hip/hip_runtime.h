@@ -162,6 +162,14 @@ inline uint32_t __builtin_amdgcn_ubfe(uint32_t v, uint32_t offset, uint32_t widt
     width &= 31u;
     return width == 0 ? 0u : (v >> offset) & ((1u << width) - 1u);
 }
+inline int32_t __builtin_amdgcn_sbfe(int32_t v, uint32_t offset, uint32_t width)
+{
+    offset &= 31u;
+    width &= 31u;
+    if (width == 0) return 0;
+    const uint32_t field = ((uint32_t)v >> offset) & ((1u << width) - 1u);
+    return (field >> (width - 1)) ? (int32_t)(field | ~((1u << width) - 1u)) : (int32_t)field;
+}
 inline int __mul24(int a, int b) { return a * b; }
 inline int __popcll(unsigned long long v) { return __builtin_popcountll(v); }
 
