@@ -313,7 +313,24 @@ struct Geometry {
     uint32_t n_luma;     // luma blocks per MCU (blocks >= n_luma use the chroma tables)
     uint32_t ri_blocks;  // blocks per restart interval, 0 = none
     uint32_t n_blocks;   // blocks in the image
+    // The symbol loops keep the block's place in the MCU as slot = 5 * block, so that one field
+    // extract gives the next block's slot (wrapping at the MCU's end) and another whether a
+    // block uses the chroma tables:
+    uint32_t next_slot;  // bits [slot, slot + 5): slot of the block after the one at slot
+    uint32_t chroma_at;  // bit slot: the block at slot uses the chroma tables
+    __device__ void set_slots()
+    {
+        next_slot = chroma_at = 0;
+        for (uint32_t b = 0; b < bpm; b++) {
+            next_slot |= (5u * ((b + 1u) % bpm)) << (5u * b);
+            chroma_at |= (b >= n_luma ? 1u : 0u) << (5u * b);
+        }
+    }
 };
+// (an MCU holds at most six blocks, luma 2 x 2 and two chroma: six 5-bit fields fit a word)
+
+__device__ __forceinline__ uint32_t slot_of_block(uint32_t blk) { return 5u * blk; }
+__device__ __forceinline__ uint32_t block_of_slot(uint32_t slot) { return (slot * 13u) >> 6; }  // slot / 5 for slot <= 25
 
 __device__ inline uint32_t comp_of_block(const Geometry &g, uint32_t blk_in_mcu)
 {
@@ -403,7 +420,7 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                                                 bool after_boundary, uint32_t end_bit,
                                                 uint32_t limit_bits, uint32_t *nblk, WriteCtx *wc)
 {
-    uint32_t p = st >> 9, blk = (st >> 6) & 7u, zz = st & 63u;
+    uint32_t p = st >> 9, slot = slot_of_block((st >> 6) & 7u), zz = st & 63u;
     uint32_t done = 0;
     // write mode: first coefficient of the current block, the image's last coefficient,
     // blocks left in the restart interval
@@ -419,7 +436,7 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
     const uint16_t *lut = S.tab.lut;
     const uint32_t chroma_tb = 2u << kLutBits, ac_bit = 1u << kLutBits;
     // tb: first entry of the current table (DC luma 0, AC luma 1024, DC chroma 2048, AC 3072)
-    uint32_t tb = (blk >= g.n_luma ? chroma_tb : 0u) | (zz ? ac_bit : 0u);
+    uint32_t tb = (__builtin_amdgcn_ubfe(g.chroma_at, slot, 1u) * chroma_tb) | (zz ? ac_bit : 0u);
     // what a writing pass has to refuse is gathered without branches in the loop: bit 6 of
     // over = a coefficient index past its block; sign of late = a symbol where a restart marker
     // had to come; broken = what the rare branches find
@@ -456,19 +473,19 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
             if (__builtin_expect(p + adv > nb, 0)) {
                 // the symbol does not fit before the next restart boundary / the end of the data
                 if (nb >= limit_bits) {
-                    if (kWrite && (blk != 0 || zz != 0 || limit_bits - p >= 8)) broken = 1;
+                    if (kWrite && (slot != 0 || zz != 0 || limit_bits - p >= 8)) broken = 1;
                     p = limit_bits;  // >= end_bit: the lane is done
                 } else {
                     if (kWrite) {
                         // a boundary comes between MCUs, behind fewer than eight padding bits,
                         // and after a whole interval (or right where one has just begun)
-                        if (blk != 0 || zz != 0 || nb - p >= 8 || g.ri_blocks == 0 ||
+                        if (slot != 0 || zz != 0 || nb - p >= 8 || g.ri_blocks == 0 ||
                             (iv_rem != 0 && iv_rem != (int32_t)g.ri_blocks))
                             broken = 1;
                         iv_rem = (int32_t)g.ri_blocks;
                     }
                     p = nb;
-                    blk = 0;
+                    slot = 0;
                     zz = 0;
                     tb = 0;
                     nb = boundary_from(S, (p >> 3) + 1u, limit_bits);
@@ -498,11 +515,11 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                     ahead = S.clean[clean_index(w + 2)];
                 }
                 const bool endb = k >= 63u;  // zz = k + 1 reaches 64
-                const uint32_t blk1 = blk + 1u == g.bpm ? 0u : blk + 1u;
+                const uint32_t slot1 = __builtin_amdgcn_ubfe(g.next_slot, slot, 5u);
                 zz = endb ? 0u : k + 1u;
-                blk = endb ? blk1 : blk;
+                slot = endb ? slot1 : slot;
                 done += endb ? 1u : 0u;
-                tb = endb ? (blk1 >= g.n_luma ? chroma_tb : 0u) : tb | ac_bit;
+                tb = endb ? __builtin_amdgcn_ubfe(g.chroma_at, slot1, 1u) * chroma_tb : tb | ac_bit;
                 if (kWrite) {
                     boff += endb ? 64u : 0u;
                     iv_rem -= endb ? 1 : 0;
@@ -515,7 +532,7 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
     }
     if (kWrite) wc->bad |= broken | (late < 0 ? 1 : 0) | (int32_t)((over >> 6) & 1u);
     *nblk = done;
-    return pack_state(p, blk, zz);
+    return pack_state(p, block_of_slot(slot), zz);
 }
 
 // The short-interval pass: one lane decodes one restart interval from its start state to
@@ -528,7 +545,7 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
 __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const Geometry &g, uint32_t st,
                                                     uint32_t end_bit, uint32_t *nblk, WriteCtx *wc)
 {
-    uint32_t p = st >> 9, blk = (st >> 6) & 7u;
+    uint32_t p = st >> 9, slot = slot_of_block((st >> 6) & 7u);
     // Where the next symbol starts counting, as one number: 64 * (block of the image) + zig-zag
     // index.  A symbol's coefficient index is clamped to 63, so one past the coefficient of a
     // symbol that ends its block is the first coefficient of the next block by itself.  The
@@ -538,7 +555,7 @@ __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const
     const uint32_t last = g.n_blocks * 64u - 1u;
     const uint16_t *lut = S.tab.lut;
     const uint32_t chroma_tb = 2u << kLutBits, ac_bit = 1u << kLutBits;
-    uint32_t tb = (blk >= g.n_luma ? chroma_tb : 0u) | ((st & 63u) ? ac_bit : 0u);
+    uint32_t tb = (__builtin_amdgcn_ubfe(g.chroma_at, slot, 1u) * chroma_tb) | ((st & 63u) ? ac_bit : 0u);
     int32_t broken = 0;
     uint32_t over = 0;
     uint32_t w = p >> 5;
@@ -581,19 +598,19 @@ __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const
             ahead = S.clean[w + 2];
         }
         const bool endb = k >= 63u;  // the zig-zag index reaches 64
-        const uint32_t blk1 = blk + 1u == g.bpm ? 0u : blk + 1u;
-        blk = endb ? blk1 : blk;
-        tb = endb ? (blk1 >= g.n_luma ? chroma_tb : 0u) : tb | ac_bit;
+        const uint32_t slot1 = __builtin_amdgcn_ubfe(g.next_slot, slot, 5u);
+        slot = endb ? slot1 : slot;
+        tb = endb ? __builtin_amdgcn_ubfe(g.chroma_at, slot1, 1u) * chroma_tb : tb | ac_bit;
         win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
         e = lookup(win);
     }
     // the lane must stand between MCUs, fewer than eight (padding) bits before the end
     const uint32_t zz = at & 63u;
-    if (blk != 0 || zz != 0 || end_bit - p >= 8) broken = 1;
+    if (slot != 0 || zz != 0 || end_bit - p >= 8) broken = 1;
     else p = end_bit;
     wc->bad |= broken | (int32_t)((over >> 6) & 1u);
     *nblk = (at >> 6) - first_block;
-    return pack_state(p, blk, zz);
+    return pack_state(p, block_of_slot(slot), zz);
 }
 
 // DC differences -> DC values (T.81 F.2.2.1) for blocks [lo, hi) of the image, by the whole
@@ -839,6 +856,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     g.bpm = R.blocks_per_mcu;
     g.n_luma = (uint32_t)(luma_h(R.sampling) * luma_v(R.sampling));
     g.ri_blocks = (uint32_t)R.restart_interval * g.bpm;
+    g.set_slots();
     g.n_blocks = R.n_blocks;
 
     // ---- which part of the stream is ours -------------------------------------
