@@ -46,12 +46,12 @@ N_STREAMS, STREAM_BATCH = 7, 8
 # scaled by what the same counters read for a plain 256 MiB copy (FETCH_SIZE x 2, WRITE_SIZE x 1).
 # They describe the kernels whose sources hash to MEASURED_SOURCES; for any other sources the
 # figure is reported as null.
-MEASURED_SOURCES = "1e8c7af8b0182a7ee26a9f5479cedb43235bb1a51f47f7baaedb4ecff8c165df"
+MEASURED_SOURCES = "00d2a1d66b5913eb850a3185435b4d6fd705428c9672106294b4cfa8c3ff29b1"
 MEASURED_TRAFFIC = {
-    2: {"scan": (5425 * 2 + 139046) * 1024, "decode": (120520 * 2 + 147214) * 1024,
-        "reconstruct": (50645 * 2 + 104369) * 1024, "resize": (49117 * 2 + 75264) * 1024},
-    4: {"scan": (23830 * 2 + 392764) * 1024, "decode": (220663 * 2 + 418602) * 1024,
-        "reconstruct": (114437 * 2 + 241116) * 1024, "resize": (91745 * 2 + 55296) * 1024},
+    2: {"scan": (5424 * 2 + 139051) * 1024, "decode": (120026 * 2 + 147225) * 1024,
+        "reconstruct": (50644 * 2 + 104405) * 1024, "resize": (49117 * 2 + 75264) * 1024},
+    4: {"scan": (23831 * 2 + 392698) * 1024, "decode": (220620 * 2 + 411698) * 1024,
+        "reconstruct": (114438 * 2 + 241278) * 1024, "resize": (91721 * 2 + 55296) * 1024},
 }
 
 
