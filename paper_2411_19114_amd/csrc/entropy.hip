@@ -33,8 +33,8 @@ namespace prep {
 namespace {
 
 constexpr int kT = kDecodeThreads;
-constexpr int kPadShift = 4;                        // one pad word after every 16 words (= one subsequence)
-constexpr int kCleanWords = kChunkRaw / 4 + kT + 16;  // destuffed stream, pad words, zero tail
+constexpr int kPadShift = 4;                        // rows of 16 words (= one subsequence) + 1 (copy of the next)
+constexpr int kCleanWords = kChunkRaw / 4 + kT + 16;  // destuffed stream, the rows' last words, zero tail
 constexpr int kMaskWords = kChunkRaw / 32 + 2;      // one bit per clean byte
 constexpr int kSubEntries = 256;                    // second-level lookup entries per table
 constexpr int kMaxBoundaries = 1024;                // listed interval starts per chunk
@@ -70,9 +70,10 @@ struct alignas(16) HuffTables {
 };
 
 struct DecodeShared {
-    // The destuffed stream, big-endian packed (bit 31 of a word is the earliest bit), with one
-    // unused word after every 16 words: lanes that read at similar offsets of their
-    // subsequences then hit different LDS banks instead of all the same one.
+    // The destuffed stream, big-endian packed (bit 31 of a word is the earliest bit).  In the
+    // subsequence passes every 16 words (a subsequence) are followed by a copy of the next
+    // word: rows of 17, so that lanes that read at similar offsets of their subsequences hit
+    // different LDS banks, and a lane's reads stay in its row (see clean_row_of_bit).
     uint32_t clean[kCleanWords];
     uint32_t bmask[kMaskWords];      // bit q set: a restart interval begins at clean byte q
     uint32_t next_boundary[kT + 1];  // first interval start at or after the lane's subsequence
@@ -381,10 +382,17 @@ __device__ __forceinline__ uint32_t second_level(const HuffTables &T, uint32_t e
     return T.sub[(tb >> 2) + (e & 0xFFu) + idx];
 }
 
-// word w of the destuffed stream lives at this index of DecodeShared::clean
-__device__ __forceinline__ uint32_t clean_index(uint32_t w)
+// Word w of the destuffed stream lives at index w + (w >> kPadShift) of DecodeShared::clean in
+// the subsequence passes: rows of seventeen words, a subsequence's sixteen and a copy of the
+// first word of the next.  A lane that decodes subsequence r (from wherever in it to the first
+// symbol boundary at or past its end) uses no word beyond that copy, so all its reads are at
+// index w + r with r fixed: one add instead of the row arithmetic, and lanes that are equally
+// far into their subsequences still read from different banks.  (The words it merely
+// prefetches, up to two further, lie in the next row at the wrong place and are never used.)
+__device__ __forceinline__ uint32_t clean_row_of_bit(uint32_t p)
 {
-    return w + (w >> kPadShift);
+    static_assert(kSubseqBytes * 8 == 1 << 9 && kPadShift == 4, "bit >> 9 = subsequence = row");
+    return p >> 9;
 }
 
 // value of a stored coefficient: appended bits (T.81 F.2.2.4 RECEIVE) and sign extension
@@ -446,8 +454,9 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
     // registers: a symbol is shorter than a word, so at most one new word is needed per
     // symbol, and it is fetched one symbol ahead of its use
     uint32_t w = p >> 5;
-    uint32_t hi = S.clean[clean_index(w)], lo = S.clean[clean_index(w + 1)];
-    uint32_t ahead = S.clean[clean_index(w + 2)];
+    const uint32_t *row = S.clean + clean_row_of_bit(p);  // the span lies in one subsequence
+    uint32_t hi = row[w], lo = row[w + 1];
+    uint32_t ahead = row[w + 2];
     // look a symbol up: its table entry, or the invalid entry for bits that are no code word
     // (an error unless they are the padding before a boundary, which the invalid entry is too
     // long to fit before)
@@ -459,7 +468,9 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                 if (e == kUseLoop) e = lookup_by_search(S.tab, tb >> kLutBits, win);
                 if ((e >> 11) == 0) {
                     e = kInvalidEntry;
-                    if (kWrite && p + (kInvalidEntry >> 11) <= nb) broken = 1;
+                    // (a lookup at or past the span's end is the next span's to judge: this
+                    // one's row holds only part of those bits)
+                    if (kWrite && p < end_bit && p + (kInvalidEntry >> 11) <= nb) broken = 1;
                 }
             }
         }
@@ -490,9 +501,9 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                     tb = 0;
                     nb = boundary_from(S, (p >> 3) + 1u, limit_bits);
                     w = p >> 5;
-                    hi = S.clean[clean_index(w)];
-                    lo = S.clean[clean_index(w + 1)];
-                    ahead = S.clean[clean_index(w + 2)];
+                    hi = row[w];
+                    lo = row[w + 1];
+                    ahead = row[w + 2];
                 }
             } else {
                 const uint32_t k = zz + ((e >> 4) & 127u);  // index of the symbol's coefficient
@@ -512,7 +523,7 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                     hi = moved ? lo : hi;
                     lo = moved ? ahead : lo;
                     w += moved ? 1u : 0u;
-                    ahead = S.clean[clean_index(w + 2)];
+                    ahead = row[w + 2];
                 }
                 const bool endb = k >= 63u;  // zz = k + 1 reaches 64
                 const uint32_t slot1 = __builtin_amdgcn_ubfe(g.next_slot, slot, 5u);
@@ -1001,9 +1012,12 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         const uint32_t pad_shift = short_intervals ? 31u : (uint32_t)kPadShift;
         // zeros behind the data: the last word is written byte by byte, and lookups near the
         // end read a few words past it
-        if (tid < 12) {
-            const uint32_t wd = (clean_len >> 2) + (uint32_t)tid;
-            S.clean[wd + (wd >> pad_shift)] = 0;
+        {
+            // (a run of array entries: in the subsequence passes it takes in the rows' last words,
+            // the copies, among them the copy of the data's last, partly written word)
+            const uint32_t wd = clean_len >> 2, first = wd + (wd >> pad_shift);
+            const uint32_t from = !short_intervals && (wd & 15u) == 0 && wd != 0 ? first - 1u : first;
+            if (tid < 14) S.clean[from + (uint32_t)tid] = 0;
         }
         __syncthreads();  // zero fill done before bytes are written
         {
@@ -1026,8 +1040,11 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
                         rank++;
                     }
                     if ((kp >> i) & 1u) {
-                        cb[(((o >> 2) + ((o >> 2) >> pad_shift)) << 2) | ((o & 3u) ^ 3u)] =
-                            (uint8_t)((wv[i >> 2] >> (8 * (i & 3))) & 255u);
+                        const uint32_t wq = o >> 2, at = ((wq + (wq >> pad_shift)) << 2) | ((o & 3u) ^ 3u);
+                        const uint8_t byte = (uint8_t)((wv[i >> 2] >> (8 * (i & 3))) & 255u);
+                        cb[at] = byte;
+                        // the first word of a subsequence is also the last of the row before
+                        if (!short_intervals && (wq & 15u) == 0 && wq != 0) cb[at - 4] = byte;
                         o++;
                     }
                 }
