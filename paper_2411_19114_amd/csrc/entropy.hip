@@ -60,7 +60,10 @@ constexpr uint32_t kPoolReserved = 2, kPoolSearchRef = 1;
 constexpr uint32_t kInvalidEntry = (16u << 11) | (127u << 4);  // 16 bits, ends the block
 
 struct alignas(16) HuffTables {
-    alignas(8) uint16_t lut[4 << kLutBits];  // first level, indexed by the next kLutBits bits
+    // first level: entry (prefix << 2) | table for the next kLutBits bits, the four tables
+    // (DC luma, AC luma, DC chroma, AC chroma) interleaved, so that a decoder forms an entry's
+    // address from the bits and its table number with one AND-OR
+    alignas(8) uint16_t lut[4 << kLutBits];
     uint16_t sub[4 * kSubEntries];   // second level
     int32_t first[4][17];            // first code of each length
     int32_t count[4][17];            // BITS
@@ -250,13 +253,7 @@ __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const Im
             const uint32_t e = make_entry(t & 1, T.huffval[t][i], (uint32_t)l);
             const uint32_t span = 1u << (kLutBits - l), base = c << (kLutBits - l);
             if (base + span > (1u << kLutBits)) continue;  // not a prefix code; the parser refuses these
-            uint16_t *dst = &T.lut[(t << kLutBits) + base];
-            if (span >= 4u) {
-                const unsigned long long four = 0x0001000100010001ull * e;
-                for (uint32_t j = 0; j < span; j += 4) *reinterpret_cast<unsigned long long *>(dst + j) = four;
-            } else {
-                for (uint32_t j = 0; j < span; j++) dst[j] = (uint16_t)e;
-            }
+            for (uint32_t j = 0; j < span; j++) T.lut[((base + j) << 2) | (uint32_t)t] = (uint16_t)e;
         }
         // the rest of the first level: beginnings of longer codes, or of none
         const uint32_t x_lo = min((uint32_t)(T.first[t][kLutBits] + T.count[t][kLutBits]), 1u << kLutBits);
@@ -283,7 +280,7 @@ __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const Im
                     e = kPoolSearchRef;
                 }
             }
-            T.lut[(t << kLutBits) + x] = (uint16_t)e;
+            T.lut[(x << 2) | (uint32_t)t] = (uint16_t)e;
         }
     }
     __syncthreads();
@@ -295,7 +292,7 @@ __device__ inline void build_tables(HuffTables &T, const uint8_t *file, const Im
             uint32_t e = i == kPoolSearchRef ? kUseLoop : 0u;
             if (note) {
                 const uint32_t nb = note >> 11, x = note & ((1u << kLutBits) - 1u);
-                const uint32_t off = T.lut[(t << kLutBits) + x] & 0xFFu;
+                const uint32_t off = T.lut[(x << 2) | (uint32_t)t] & 0xFFu;
                 const uint32_t peek = (x << (16 - kLutBits)) | ((i - off) << (16 - kLutBits - nb));
                 uint32_t len, sym;
                 if (canonical_lookup(T, t, peek, kLutBits + 1, kLutBits + (int)nb, &len, &sym))
@@ -318,13 +315,14 @@ struct Geometry {
     // extract gives the next block's slot (wrapping at the MCU's end) and another whether a
     // block uses the chroma tables:
     uint32_t next_slot;  // bits [slot, slot + 5): slot of the block after the one at slot
-    uint32_t chroma_at;  // bit slot: the block at slot uses the chroma tables
+    uint32_t chroma_at;  // bits [slot, slot + 3): 4 if the block at slot uses the chroma tables, else 0
+                         // (twice the number of its DC table)
     __device__ void set_slots()
     {
         next_slot = chroma_at = 0;
         for (uint32_t b = 0; b < bpm; b++) {
             next_slot |= (5u * ((b + 1u) % bpm)) << (5u * b);
-            chroma_at |= (b >= n_luma ? 1u : 0u) << (5u * b);
+            chroma_at |= (b >= n_luma ? 4u : 0u) << (5u * b);
         }
     }
 };
@@ -371,15 +369,21 @@ __device__ __attribute__((noinline)) uint32_t lookup_by_search(const HuffTables 
 }
 
 // Codes longer than the first level covers: e is the first-level entry (not a code entry),
-// win = the next 32 bits of the stream, tb = first entry of the table in the first level.
+// win = the next 32 bits of the stream, ts2 = twice the table's number.
 // Returns the second-level entry: a code entry, 0, or kUseLoop.
-__device__ __forceinline__ uint32_t second_level(const HuffTables &T, uint32_t e, uint32_t tb, uint32_t win)
+__device__ __forceinline__ uint32_t second_level(const HuffTables &T, uint32_t e, uint32_t ts2, uint32_t win)
 {
-    static_assert((1 << kLutBits) == 4 * kSubEntries, "tb / 4 is the table's first pool entry");
     const uint32_t nbits = e >> 8;
     // the nbits bits after the first kLutBits; none for nbits = 0
     const uint32_t idx = __builtin_amdgcn_ubfe(win, 32u - kLutBits - nbits, nbits);
-    return T.sub[(tb >> 2) + (e & 0xFFu) + idx];
+    return T.sub[(ts2 >> 1) * kSubEntries + (e & 0xFFu) + idx];
+}
+
+// First-level entry for the next bits `win` in table ts2 / 2: byte offset (prefix << 3) | ts2.
+__device__ __forceinline__ uint32_t first_level(const uint16_t *lut, uint32_t ts2, uint32_t win)
+{
+    const uint32_t at = ((win >> (32 - kLutBits - 3)) & (((1u << kLutBits) - 1u) << 3)) | ts2;
+    return *reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(lut) + at);
 }
 
 // Word w of the destuffed stream lives at index w + (w >> kPadShift) of DecodeShared::clean in
@@ -442,9 +446,9 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
     // next restart boundary ahead (bit position), limit_bits if none
     uint32_t nb = boundary_from(S, after_boundary ? (p >> 3) + 1u : (p + 7u) >> 3, limit_bits);
     const uint16_t *lut = S.tab.lut;
-    const uint32_t chroma_tb = 2u << kLutBits, ac_bit = 1u << kLutBits;
-    // tb: first entry of the current table (DC luma 0, AC luma 1024, DC chroma 2048, AC 3072)
-    uint32_t tb = (__builtin_amdgcn_ubfe(g.chroma_at, slot, 1u) * chroma_tb) | (zz ? ac_bit : 0u);
+    // tb: twice the number of the current table (DC luma 0, AC luma 2, DC chroma 4, AC chroma 6)
+    const uint32_t ac_bit = 2u;
+    uint32_t tb = __builtin_amdgcn_ubfe(g.chroma_at, slot, 3u) | (zz ? ac_bit : 0u);
     // what a writing pass has to refuse is gathered without branches in the loop: bit 6 of
     // over = a coefficient index past its block; sign of late = a symbol where a restart marker
     // had to come; broken = what the rare branches find
@@ -461,11 +465,11 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
     // (an error unless they are the padding before a boundary, which the invalid entry is too
     // long to fit before)
     auto lookup = [&](uint32_t win) {
-        uint32_t e = lut[tb + (win >> (32 - kLutBits))];
+        uint32_t e = first_level(lut, tb, win);
         if (__builtin_expect((e >> 11) == 0, 0)) {
             e = second_level(S.tab, e, tb, win);
             if (__builtin_expect((e >> 11) == 0, 0)) {
-                if (e == kUseLoop) e = lookup_by_search(S.tab, tb >> kLutBits, win);
+                if (e == kUseLoop) e = lookup_by_search(S.tab, tb >> 1, win);
                 if ((e >> 11) == 0) {
                     e = kInvalidEntry;
                     // (a lookup at or past the span's end is the next span's to judge: this
@@ -530,7 +534,7 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                 zz = endb ? 0u : k + 1u;
                 slot = endb ? slot1 : slot;
                 done += endb ? 1u : 0u;
-                tb = endb ? __builtin_amdgcn_ubfe(g.chroma_at, slot1, 1u) * chroma_tb : tb | ac_bit;
+                tb = endb ? __builtin_amdgcn_ubfe(g.chroma_at, slot1, 3u) : tb | ac_bit;
                 if (kWrite) {
                     boff += endb ? 64u : 0u;
                     iv_rem -= endb ? 1 : 0;
@@ -565,8 +569,8 @@ __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const
     uint32_t at = (first_block << 6) | (st & 63u);
     const uint32_t last = g.n_blocks * 64u - 1u;
     const uint16_t *lut = S.tab.lut;
-    const uint32_t chroma_tb = 2u << kLutBits, ac_bit = 1u << kLutBits;
-    uint32_t tb = (__builtin_amdgcn_ubfe(g.chroma_at, slot, 1u) * chroma_tb) | ((st & 63u) ? ac_bit : 0u);
+    const uint32_t ac_bit = 2u;  // tb: twice the number of the current table, see decode_span
+    uint32_t tb = __builtin_amdgcn_ubfe(g.chroma_at, slot, 3u) | ((st & 63u) ? ac_bit : 0u);
     int32_t broken = 0;
     uint32_t over = 0;
     uint32_t w = p >> 5;
@@ -575,11 +579,11 @@ __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const
     // (an error unless they are the padding before the boundary, which the invalid entry is too
     // long to fit before)
     auto lookup = [&](uint32_t win) {
-        uint32_t e = lut[tb + (win >> (32 - kLutBits))];
+        uint32_t e = first_level(lut, tb, win);
         if (__builtin_expect((e >> 11) == 0, 0)) {
             e = second_level(S.tab, e, tb, win);
             if (__builtin_expect((e >> 11) == 0, 0)) {
-                if (e == kUseLoop) e = lookup_by_search(S.tab, tb >> kLutBits, win);
+                if (e == kUseLoop) e = lookup_by_search(S.tab, tb >> 1, win);
                 if ((e >> 11) == 0) {
                     e = kInvalidEntry;
                     if (p + (kInvalidEntry >> 11) <= end_bit) broken = 1;
@@ -611,7 +615,7 @@ __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const
         const bool endb = k >= 63u;  // the zig-zag index reaches 64
         const uint32_t slot1 = __builtin_amdgcn_ubfe(g.next_slot, slot, 5u);
         slot = endb ? slot1 : slot;
-        tb = endb ? __builtin_amdgcn_ubfe(g.chroma_at, slot1, 1u) * chroma_tb : tb | ac_bit;
+        tb = endb ? __builtin_amdgcn_ubfe(g.chroma_at, slot1, 3u) : tb | ac_bit;
         win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
         e = lookup(win);
     }
@@ -778,8 +782,11 @@ __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
         const uint32_t *src = reinterpret_cast<const uint32_t *>(&tab);
         uint32_t *dst = reinterpret_cast<uint32_t *>(tables) + (size_t)slot * (sizeof(HuffTables) / 4);
         // the members of table t, as 32-bit words of the struct
-        const uint32_t part[7][2] = {
-            {(uint32_t)offsetof(HuffTables, lut) + (uint32_t)t * (2u << kLutBits), 2u << kLutBits},
+        // (its first-level entries lie among the other tables': they go one by one)
+        uint16_t *dst_lut = reinterpret_cast<uint16_t *>(dst + offsetof(HuffTables, lut) / 4);
+        for (uint32_t i = threadIdx.x; i < (1u << kLutBits); i += kT)
+            dst_lut[(i << 2) | (uint32_t)t] = tab.lut[(i << 2) | (uint32_t)t];
+        const uint32_t part[6][2] = {
             {(uint32_t)offsetof(HuffTables, sub) + (uint32_t)t * 2u * kSubEntries, 2u * kSubEntries},
             {(uint32_t)offsetof(HuffTables, first) + (uint32_t)t * 68u, 68u},
             {(uint32_t)offsetof(HuffTables, count) + (uint32_t)t * 68u, 68u},
@@ -787,7 +794,7 @@ __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
             {(uint32_t)offsetof(HuffTables, huffval) + (uint32_t)t * 256u, 256u},
             {(uint32_t)offsetof(HuffTables, sub_used) + (uint32_t)t * 4u, 4u}};
 #pragma unroll
-        for (int m = 0; m < 7; m++)
+        for (int m = 0; m < 6; m++)
             for (uint32_t i = threadIdx.x; i < part[m][1] / 4; i += kT)
                 dst[part[m][0] / 4 + i] = src[part[m][0] / 4 + i];
         return;
