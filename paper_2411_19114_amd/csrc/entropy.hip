@@ -399,6 +399,14 @@ __device__ __forceinline__ uint32_t clean_row_of_bit(uint32_t p)
     return p >> 9;
 }
 
+// the 32 stream bits from bit position p on, of the two words that hold them and the next:
+// the upper half of the pair shifted left (one instruction less than shifting it right by
+// 32 minus the offset)
+__device__ __forceinline__ uint32_t window_at(uint32_t hi, uint32_t lo, uint32_t p)
+{
+    return (uint32_t)(((((unsigned long long)hi << 32) | lo) << (p & 31u)) >> 32);
+}
+
 // value of a stored coefficient: appended bits (T.81 F.2.2.4 RECEIVE) and sign extension
 // (F.2.2.1 EXTEND); adv = code length + s
 __device__ __forceinline__ int32_t coefficient_value(uint32_t win, uint32_t adv, uint32_t s)
@@ -481,7 +489,7 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
         return e;
     };
     if (p < end_bit) {
-        uint32_t win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
+        uint32_t win = window_at(hi, lo, p);
         uint32_t e = lookup(win);
         do {
             const uint32_t adv = e >> 11;
@@ -541,7 +549,7 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                 }
             }
             // the next symbol's lookup, issued before the loop test
-            win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
+            win = window_at(hi, lo, p);
             e = lookup(win);
         } while (p < end_bit);
     }
@@ -592,7 +600,7 @@ __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const
         }
         return e;
     };
-    uint32_t win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
+    uint32_t win = window_at(hi, lo, p);
     uint32_t e = lookup(win);
     // the loop runs while the symbol that was looked up fits before the end: what does not fit
     // is padding, or nothing at all
@@ -616,7 +624,7 @@ __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const
         const uint32_t slot1 = __builtin_amdgcn_ubfe(g.next_slot, slot, 5u);
         slot = endb ? slot1 : slot;
         tb = endb ? __builtin_amdgcn_ubfe(g.chroma_at, slot1, 3u) : tb | ac_bit;
-        win = (uint32_t)((((unsigned long long)hi << 32) | lo) >> (32 - (p & 31u)));
+        win = window_at(hi, lo, p);
         e = lookup(win);
     }
     // the lane must stand between MCUs, fewer than eight (padding) bits before the end
