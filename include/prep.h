@@ -199,6 +199,26 @@ int prep_resize_normalize(prep_handle *h, const uint8_t *rgb, const uint64_t *rg
                           int32_t n, const prep_params *params, void *out, void *stream);
 
 /*
+ * prep_resize_normalize for callers that cannot allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments without a handle (device = HIP device ordinal), same kernels, same
+ * results.  The per-image mapping records that the kernels read, which
+ * prep_resize_normalize keeps in buffers of its handle, live in a device array
+ * of fixed size inside the library (PREP_STATIC_MAX_IMAGES records, 56 KiB per
+ * GPU, held until the process ends); the records reach it as kernel arguments.
+ * The call makes no hipMalloc, hipFree or other allocating call.
+ * n > PREP_STATIC_MAX_IMAGES returns PREP_E_TOO_LARGE and enqueues nothing.
+ * Every call on a GPU uses that GPU's one array: calls that may overlap on one
+ * GPU (two streams, two threads) race and must be serialised by the caller;
+ * calls on one stream are ordered by the stream.
+ */
+#define PREP_STATIC_MAX_IMAGES 1024
+int prep_resize_normalize_static(int32_t device, const uint8_t *rgb, const uint64_t *rgb_offsets,
+                                 const int32_t *widths, const int32_t *heights,
+                                 const int32_t *pitches, int32_t n, const prep_params *params,
+                                 void *out, void *stream);
+
+/*
  * Dequantise + inverse DCT + chroma upsampling + colour conversion (the second
  * half of the Decode unit), then resize/crop/normalize, from coefficients the
  * caller supplies instead of the entropy decoder's: the files' headers give

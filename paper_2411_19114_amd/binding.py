@@ -7,7 +7,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
-_SOURCES = ["entropy.hip", "reconstruct.hip", "resize.hip", "api.cpp", "parser.cpp", "batcher.cpp", "audio.hip"]
+_SOURCES = ["entropy.hip", "reconstruct.hip", "resize.hip", "static_entry.hip", "api.cpp", "parser.cpp", "batcher.cpp", "audio.hip"]
 
 OK, E_INVALID_ARG, E_TOO_LARGE, E_HIP, E_UNSUPPORTED, E_CORRUPT, E_NOMEM = 0, -1, -2, -3, -4, -5, -6
 F32, F16, U8_NHWC = 0, 1, 2
@@ -85,7 +85,7 @@ class IntervalDesc(C.Structure):
 EXPORTS = [
     "prep_create", "prep_destroy", "prep_decode_resize_batch", "prep_decode_resize_batch_resident",
     "prep_get_status", "prep_strerror", "prep_parse_headers", "prep_interval_descriptors",
-    "prep_resize_normalize", "prep_reconstruct_from_coefficients", "prep_debug_last_coefficients",
+    "prep_resize_normalize", "prep_resize_normalize_static", "prep_reconstruct_from_coefficients", "prep_debug_last_coefficients",
     "prep_debug_last_rgb", "prep_debug_last_region", "prep_stage_ms", "prep_set_timing",
     "prep_policy_create", "prep_policy_destroy", "prep_policy_arrive", "prep_policy_deadline",
     "prep_policy_take", "prep_policy_pending", "prep_server_create", "prep_server_destroy",
@@ -126,6 +126,8 @@ def lib():
         L.prep_interval_descriptors.restype = C.c_int64
         L.prep_resize_normalize.argtypes = [vp, vp, u64p, i32p, i32p, i32p, C.c_int32,
                                             C.POINTER(Params), vp, vp]
+        L.prep_resize_normalize_static.argtypes = [C.c_int32, vp, u64p, i32p, i32p, i32p, C.c_int32,
+                                                   C.POINTER(Params), vp, vp]
         L.prep_reconstruct_from_coefficients.argtypes = [vp, u8p, u64p, C.c_int32, vp, C.c_uint64,
                                                          C.POINTER(Params), vp, vp]
         L.prep_debug_last_coefficients.argtypes = [vp, C.c_int32, vp, C.c_uint64]
@@ -209,6 +211,20 @@ def interval_descriptors(infos):
     desc = (IntervalDesc * max(total, 1))()
     lib().prep_interval_descriptors(arr, n, desc, total)
     return list(desc)[:total]
+
+
+def resize_normalize_static(device, rgb_ptr, rgb_offsets, widths, heights, pitches, params, out_ptr,
+                            stream=0):
+    """prep_resize_normalize_static: the resize stage without a handle, allocating nothing."""
+    o, op = _u64(rgb_offsets)
+    w = np.ascontiguousarray(widths, dtype=np.int32)
+    h = np.ascontiguousarray(heights, dtype=np.int32)
+    p = np.ascontiguousarray(pitches, dtype=np.int32)
+    i32p = C.POINTER(C.c_int32)
+    _check(lib().prep_resize_normalize_static(
+        int(device), C.c_void_p(rgb_ptr), op, w.ctypes.data_as(i32p), h.ctypes.data_as(i32p),
+        p.ctypes.data_as(i32p), len(w), C.byref(params), C.c_void_p(out_ptr), C.c_void_p(stream)),
+        "prep_resize_normalize_static")
 
 
 class Preprocessor:

@@ -17,6 +17,53 @@
 
 using namespace prep;
 
+namespace prep {
+
+bool params_ok(const prep_params *p)
+{
+    if (!p) return false;
+    if (p->resize_short < 0 || p->resize_short > 65535) return false;
+    if (p->crop_h < 1 || p->crop_w < 1 || p->crop_h > 65535 || p->crop_w > 65535) return false;
+    if (p->out_dtype != PREP_F32 && p->out_dtype != PREP_F16 && p->out_dtype != PREP_U8_NHWC) return false;
+    if (p->filter != PREP_FILTER_BILINEAR && p->filter != PREP_FILTER_ANTIALIAS) return false;
+    if (p->out_dtype == PREP_U8_NHWC) return true;  // no Normalize: mean and std are not looked at
+    for (int c = 0; c < 3; c++)
+        if (!(p->std[c] > 0.0f) || !isfinite(p->std[c]) || !isfinite(p->mean[c])) return false;
+    return true;
+}
+
+// Resized size: the short side becomes s, the long side floor(s * long / short).
+static void resized_size(int w, int h, int s, int *ow, int *oh)
+{
+    if (s <= 0) { *ow = w; *oh = h; return; }
+    if (w <= h) { *ow = s; *oh = (int)(((int64_t)s * h) / w); }
+    else { *oh = s; *ow = (int)(((int64_t)s * w) / h); }
+}
+
+// Mapping constants of one image; false when the crop does not fit.
+bool make_resize_rec(int w, int h, const prep_params *p, uint64_t src_off, uint32_t pitch,
+                     ResizeRec *r)
+{
+    int ow, oh;
+    resized_size(w, h, p->resize_short, &ow, &oh);
+    if (p->crop_w > ow || p->crop_h > oh) return false;
+    const int top = (oh - p->crop_h) / 2, left = (ow - p->crop_w) / 2;
+    const double sx = (double)w / (double)ow, sy = (double)h / (double)oh;
+    const double one = (double)(1ull << kCoordFrac);
+    r->scale_x = (uint64_t)llround(sx * one);
+    r->scale_y = (uint64_t)llround(sy * one);
+    r->off_x = (uint64_t)llround(((left + 0.5) * sx - 0.5 + kCoordBias) * one);
+    r->off_y = (uint64_t)llround(((top + 0.5) * sy - 0.5 + kCoordBias) * one);
+    r->src_w = w;
+    r->src_h = h;
+    r->src_pitch = pitch;
+    r->pad_ = 0;
+    r->src_off = src_off;
+    return true;
+}
+
+}  // namespace prep
+
 namespace {
 
 constexpr int kSlots = 2;            // pinned staging is double buffered
@@ -91,49 +138,6 @@ namespace {
             return PREP_E_HIP;              \
         }                                   \
     } while (0)
-
-bool params_ok(const prep_params *p)
-{
-    if (!p) return false;
-    if (p->resize_short < 0 || p->resize_short > 65535) return false;
-    if (p->crop_h < 1 || p->crop_w < 1 || p->crop_h > 65535 || p->crop_w > 65535) return false;
-    if (p->out_dtype != PREP_F32 && p->out_dtype != PREP_F16 && p->out_dtype != PREP_U8_NHWC) return false;
-    if (p->filter != PREP_FILTER_BILINEAR && p->filter != PREP_FILTER_ANTIALIAS) return false;
-    if (p->out_dtype == PREP_U8_NHWC) return true;  // no Normalize: mean and std are not looked at
-    for (int c = 0; c < 3; c++)
-        if (!(p->std[c] > 0.0f) || !isfinite(p->std[c]) || !isfinite(p->mean[c])) return false;
-    return true;
-}
-
-// Resized size: the short side becomes s, the long side floor(s * long / short).
-void resized_size(int w, int h, int s, int *ow, int *oh)
-{
-    if (s <= 0) { *ow = w; *oh = h; return; }
-    if (w <= h) { *ow = s; *oh = (int)(((int64_t)s * h) / w); }
-    else { *oh = s; *ow = (int)(((int64_t)s * w) / h); }
-}
-
-// Mapping constants of one image; false when the crop does not fit.
-bool make_resize_rec(int w, int h, const prep_params *p, uint64_t src_off, uint32_t pitch,
-                     ResizeRec *r)
-{
-    int ow, oh;
-    resized_size(w, h, p->resize_short, &ow, &oh);
-    if (p->crop_w > ow || p->crop_h > oh) return false;
-    const int top = (oh - p->crop_h) / 2, left = (ow - p->crop_w) / 2;
-    const double sx = (double)w / (double)ow, sy = (double)h / (double)oh;
-    const double one = (double)(1ull << kCoordFrac);
-    r->scale_x = (uint64_t)llround(sx * one);
-    r->scale_y = (uint64_t)llround(sy * one);
-    r->off_x = (uint64_t)llround(((left + 0.5) * sx - 0.5 + kCoordBias) * one);
-    r->off_y = (uint64_t)llround(((top + 0.5) * sy - 0.5 + kCoordBias) * one);
-    r->src_w = w;
-    r->src_h = h;
-    r->src_pitch = pitch;
-    r->pad_ = 0;
-    r->src_off = src_off;
-    return true;
-}
 
 // First and last source row (or column) whose pixels count in n_out outputs: the same
 // fixed-point mapping as the resize kernel's, taps i and i + 1 clamped to the image; the

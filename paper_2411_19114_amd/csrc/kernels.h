@@ -4,6 +4,7 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "../../include/prep.h"
 #include "prep_internal.h"
 
 namespace prep {
@@ -33,5 +34,11 @@ void launch_resize_normalize(const uint8_t *rgb, const ResizeRec *rr, const int3
                              int n_images, int crop_h, int crop_w, int out_dtype, int filter,
                              const ResizeRec *host_rr, const float mean[3], const float std[3], void *out,
                              bool wide_reads, hipStream_t stream);
+
+// api.cpp: host-side checks and geometry shared by the entry points
+bool params_ok(const prep_params *p);
+// Mapping constants of one image (source offset and row pitch in bytes); false when the crop
+// does not fit the resized image.
+bool make_resize_rec(int w, int h, const prep_params *p, uint64_t src_off, uint32_t pitch, ResizeRec *r);
 
 }  // namespace prep
