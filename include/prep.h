@@ -257,7 +257,7 @@ int prep_debug_last_region(prep_handle *h, int32_t image, int32_t rect[4]);
  * events on the call's stream (calls that enqueue no decode are not counted).
  * prep_stage_ms waits for the call made `calls_back` timed calls ago (0 = the
  * last one; at most the last 256 are kept) and returns the milliseconds of
- * [0] restart-marker scan (with clearing the coefficient workspace), [1] entropy
+ * [0] restart-marker scan (with expanding the batch's Huffman tables), [1] entropy
  * decode, [2] reconstruct RGB, [3] resize/crop/normalize.  prep_set_timing
  * forgets earlier timings.                                                    */
 int prep_set_timing(prep_handle *h, int32_t enabled);

@@ -363,14 +363,13 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
             HIP_TRY(hipMemcpyAsync(h->d_coef, coef_host, P.n_blocks * 128, hipMemcpyHostToDevice, stream));
         if (timing) { HIP_TRY(hipEventRecord(ev[1], stream)); HIP_TRY(hipEventRecord(ev[2], stream)); }
     } else {
-        // the scan also clears the coefficients of the batch (P.n_windows >= n > 0)
+        // (P.n_windows >= n > 0: the scan also sets every image's status)
         launch_scan_restart_markers(d_bits, s->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
-                                    h->d_status, h->d_coef, P.n_blocks,
-                                    reinterpret_cast<const uint32_t *>(s->d_recs + n) + n, P.n_tables,
-                                    h->d_tables, stream);
+                                    h->d_status, reinterpret_cast<const uint32_t *>(s->d_recs + n) + n,
+                                    P.n_tables, h->d_tables, stream);
         if (timing) HIP_TRY(hipEventRecord(ev[1], stream));
         launch_decode_entropy(d_bits, s->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
-                              h->d_coef, h->d_status, h->d_tables, stream);
+                              h->d_coef, (uint32_t)(h->cap_blocks * 64), h->d_status, h->d_tables, stream);
         if (timing) HIP_TRY(hipEventRecord(ev[2], stream));
     }
     launch_reconstruct(d_bits, s->d_recs, reinterpret_cast<const uint32_t *>(s->d_recs + n), n, P.recon_wgs,
@@ -420,11 +419,14 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     h->cap_rgb = padded * 3 + (kRgbAlign + kRgbSlack) * n;
     h->cap_windows = cfg->max_bitstream_bytes / kWindowBytes + n + 1;
     h->cap_bits = cfg->max_bitstream_bytes + kBitsPad;
-    if (h->cap_blocks > 0xFFFFFFFFull) { delete h; return PREP_E_TOO_LARGE; }
+    // (the kernels index the workspace and its side array with 32-bit element offsets)
+    if (h->cap_blocks * 65 > 0xFFFFFFFFull) { delete h; return PREP_E_TOO_LARGE; }
 
     bool ok = hipSetDevice(cfg->device) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&h->copy_stream, hipStreamNonBlocking) == hipSuccess;
-    ok = ok && hipMalloc((void **)&h->d_coef, h->cap_blocks * 128) == hipSuccess;
+    // 64 coefficients per block, and behind them one more int16 per block: the DC differences
+    // between the decoder's two steps
+    ok = ok && hipMalloc((void **)&h->d_coef, h->cap_blocks * 130 + 16) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_rgb, h->cap_rgb) == hipSuccess;
     h->table_slots = (cfg->flags & PREP_FLAG_TABLES_PER_WORKGROUP) ? 0u : std::min<uint32_t>((uint32_t)n, kMaxTableSlots);
     h->table_rep.reserve(h->table_slots);

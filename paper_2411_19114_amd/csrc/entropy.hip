@@ -353,6 +353,7 @@ __device__ inline uint32_t boundary_from(const DecodeShared &S, uint32_t q, uint
 // iteration of the decode loop wait for its coefficient stores).
 struct WriteCtx {
     int16_t *coef;         // this image's first block
+    uint32_t side_rel;     // coef + side_rel = this image's DC differences, one int16 per block
     uint32_t block;        // absolute index of the block being decoded
     int32_t iv_rem;        // blocks left before a restart boundary has to come (0: it comes next)
     int32_t bad;
@@ -525,7 +526,10 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
                     // last of ZRL's sixteen, the last of the block for EOB.  A stream that runs
                     // past the image keeps overwriting the image's last coefficient; the block
                     // count then gives it away.
-                    wc->coef[min(boff + min(k, 63u), last)] = (int16_t)coefficient_value(win, adv, e & 15u);
+                    // A DC difference goes to the block's entry of the side array (dc_prefix turns
+                    // the differences into values and puts those into the blocks).
+                    const uint32_t ci = min(boff + min(k, 63u), last);
+                    wc->coef[zz == 0 ? wc->side_rel + (ci >> 6) : ci] = (int16_t)coefficient_value(win, adv, e & 15u);
                     over |= k;
                     late |= iv_rem - 1;
                 }
@@ -556,6 +560,19 @@ __device__ __forceinline__ uint32_t decode_span(const DecodeShared &S, const Geo
     if (kWrite) wc->bad |= broken | (late < 0 ? 1 : 0) | (int32_t)((over >> 6) & 1u);
     *nblk = done;
     return pack_state(p, block_of_slot(slot), zz);
+}
+
+// Zeros over the blocks [lo, hi) of an image whose coefficients begin at coef, in 16-byte units
+// first, first + step, ... of the range's eight per block.  Nothing clears the coefficient
+// workspace before the decoder runs, and the writing passes store only the coefficients that
+// symbols name: the blocks that a pass is about to decode get their zeros from here first, in
+// whole 128-byte lines.  Out of line: it runs a few times per chunk and must not add to the
+// registers of the symbol loops.
+__device__ __attribute__((noinline)) void zero_blocks(int16_t *coef, uint32_t lo, uint32_t hi, uint32_t first,
+                                                      uint32_t step)
+{
+    uint4 *units = reinterpret_cast<uint4 *>(coef);  // eight to a block
+    for (uint32_t u = lo * 8u + first; u < hi * 8u; u += step) units[u] = make_uint4(0, 0, 0, 0);
 }
 
 // The short-interval pass: one lane decodes one restart interval from its start state to
@@ -608,8 +625,10 @@ __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const
         const uint32_t adv = e >> 11;
         const uint32_t k = (at & 63u) + ((e >> 4) & 127u);  // index of the symbol's coefficient
         // every symbol stores (see decode_span)
+        // (k = 0 is a DC difference: it goes to the side array)
         const uint32_t here = (at & ~63u) | min(k, 63u);
-        wc->coef[min(here, last)] = (int16_t)coefficient_value(win, adv, e & 15u);
+        const uint32_t ci = min(here, last);
+        wc->coef[k == 0 ? wc->side_rel + (ci >> 6) : ci] = (int16_t)coefficient_value(win, adv, e & 15u);
         at = here + 1u;
         over |= k;
         p += adv;
@@ -637,7 +656,9 @@ __device__ __forceinline__ uint32_t decode_interval(const DecodeShared &S, const
 }
 
 // DC differences -> DC values (T.81 F.2.2.1) for blocks [lo, hi) of the image, by the whole
-// workgroup: each lane takes a contiguous run of blocks, sums its differences per component (a
+// workgroup.  The writing passes leave the differences in the image's side array (one int16 per
+// block, so both walks below read a few cache lines instead of one line per block); the values go
+// into the blocks.  Each lane takes a contiguous run of blocks, sums its differences per component (a
 // sum restarts where a restart interval begins), a segmented scan over the lanes carries the
 // running values in, and a second walk writes them.  carry[] = running value of each
 // component before block lo; on return, after block hi - 1.  All lanes must call.
@@ -663,10 +684,10 @@ struct DcWalk {
     }
 };
 
-__device__ inline void dc_prefix(DecodeShared &S, const Geometry &g, int16_t *coef, uint32_t lo,
-                                 uint32_t hi, int32_t carry[3])
+__device__ inline void dc_prefix(DecodeShared &S, const Geometry &g, int16_t *coef, const int16_t *side,
+                                 uint32_t lo, uint32_t hi, int32_t carry[3])
 {
-    __syncthreads();  // the coefficient stores of every lane are done and visible
+    __syncthreads();  // the stores of every lane (zeros, coefficients, differences) are done and visible
     const uint32_t n = hi > lo ? hi - lo : 0u;
     const uint32_t per = (n + kT - 1) / kT;
     const uint32_t a = min(lo + threadIdx.x * per, hi), b = min(a + per, hi);
@@ -676,7 +697,7 @@ __device__ inline void dc_prefix(DecodeShared &S, const Geometry &g, int16_t *co
     for (uint32_t i = a; i < b; i += 8) {
         int32_t d[8];
 #pragma unroll
-        for (uint32_t u = 0; u < 8; u++) d[u] = coef[(size_t)min(i + u, b - 1) * 64];
+        for (uint32_t u = 0; u < 8; u++) d[u] = side[min(i + u, b - 1)];
 #pragma unroll
         for (uint32_t u = 0; u < 8; u++) {
             if (i + u < b) {
@@ -700,7 +721,7 @@ __device__ inline void dc_prefix(DecodeShared &S, const Geometry &g, int16_t *co
     for (uint32_t i = a; i < b; i += 8) {
         int32_t d[8];
 #pragma unroll
-        for (uint32_t u = 0; u < 8; u++) d[u] = coef[(size_t)min(i + u, b - 1) * 64];
+        for (uint32_t u = 0; u < 8; u++) d[u] = side[min(i + u, b - 1)];
 #pragma unroll
         for (uint32_t u = 0; u < 8; u++) {
             if (i + u < b) {
@@ -766,16 +787,12 @@ __device__ inline void classify16(const uint4 v, uint32_t prev, uint32_t nextb, 
 // window w of an image = raw bytes [w*kWindowBytes, (w+1)*kWindowBytes) of its
 // entropy-coded segment.  cnt = RSTn markers whose FF byte lies in the window,
 // first = offset (from the segment start) of the first such FF byte.
-// The workgroups also clear the coefficient workspace between them (the decoder stores only
-// the coefficients that symbols name): workgroup wg clears 16-byte units [wg, wg + 1) *
-// clear_per_wg of the clear_units that the batch uses.
 // Workgroups from n_windows on do something else: workgroup n_windows + 4 s + t expands
 // Huffman table t of image table_rep[s] into slot s of `tables`.
 __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
     const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
     uint32_t n_windows, uint32_t *__restrict__ win_count, uint32_t *__restrict__ win_first,
-    int32_t *__restrict__ status, uint4 *__restrict__ clear, uint64_t clear_units,
-    uint64_t clear_per_wg, const uint32_t *__restrict__ table_rep, uint4 *__restrict__ tables)
+    int32_t *__restrict__ status, const uint32_t *__restrict__ table_rep, uint4 *__restrict__ tables)
 {
     __shared__ uint32_t s_cnt[kT / 64], s_first[kT / 64];
     const uint32_t wg = blockIdx.x;
@@ -806,18 +823,6 @@ __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
             for (uint32_t i = threadIdx.x; i < part[m][1] / 4; i += kT)
                 dst[part[m][0] / 4 + i] = src[part[m][0] / 4 + i];
         return;
-    }
-    {
-        const uint64_t lo = (uint64_t)wg * clear_per_wg;
-        const uint64_t hi = lo + clear_per_wg < clear_units ? lo + clear_per_wg : clear_units;
-        uint64_t i = lo + threadIdx.x;
-        for (; i + 3 * kT < hi; i += 4 * kT) {
-            clear[i] = make_uint4(0, 0, 0, 0);
-            clear[i + kT] = make_uint4(0, 0, 0, 0);
-            clear[i + 2 * kT] = make_uint4(0, 0, 0, 0);
-            clear[i + 3 * kT] = make_uint4(0, 0, 0, 0);
-        }
-        for (; i < hi; i += kT) clear[i] = make_uint4(0, 0, 0, 0);
     }
     const int img = find_image(n_images, wg, [&](int i) { return recs[i].window0; });
     const ImageRec &R = recs[img];
@@ -868,7 +873,8 @@ __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
 __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
     const uint32_t *__restrict__ win_count, const uint32_t *__restrict__ win_first,
-    int16_t *__restrict__ coef_all, int32_t *__restrict__ status, const uint4 *__restrict__ tables)
+    int16_t *__restrict__ coef_all, uint32_t side_off, int32_t *__restrict__ status,
+    const uint4 *__restrict__ tables)
 {
     __shared__ DecodeShared S;
     const int tid = threadIdx.x;
@@ -890,6 +896,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     // marker of its window, if it has one, and runs to the first marker of the
     // next window that has one.
     uint32_t range_lo = 0, range_hi = R.entropy_len, block0 = 0, block_end = R.n_blocks;
+    uint32_t marker_base = 0;  // number, within the image, of the first restart marker at or after cs
+    bool first_marker_ok = true;
     {
         const uint32_t *wc = win_count + R.window0, *wf = win_first + R.window0;
         uint32_t my_first = w == 0 ? 0u : wf[w];
@@ -922,6 +930,10 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         if (w != 0) {
             range_lo = my_first + 2;
             block0 = (before + 1) * g.ri_blocks;  // markers before ours + ours = intervals done
+            marker_base = before + 1;
+            // our marker is number `before` of the image, and markers count modulo 8 from RST0
+            // (T.81 E.2.4, B.2.1); the markers inside the run are checked where they are staged
+            first_marker_ok = ((load_byte(bits + R.file_off + R.entropy_rel + my_first + 1) ^ before) & 7u) == 0;
         }
         if (next_w != kNoMarker) {
             range_hi = next_first;
@@ -932,7 +944,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             block_end = (upto + 1) * g.ri_blocks;
         }
     }
-    if (block0 >= R.n_blocks || block_end > R.n_blocks || range_lo > range_hi) {
+    if (block0 >= R.n_blocks || block_end > R.n_blocks || range_lo > range_hi || !first_marker_ok) {
         if (tid == 0) atomicMin(&status[img], (int32_t)PREP_E_CORRUPT);
         return;
     }
@@ -950,6 +962,9 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
 
     const uint8_t *seg = file + R.entropy_rel;
     int16_t *coef = coef_all + (size_t)R.coef_block0 * 64;
+    // DC differences of this image's blocks: the side array begins side_off elements after the
+    // first coefficient of the workspace, one entry per block
+    const uint32_t side_rel = side_off + R.coef_block0 - R.coef_block0 * 64u;
     // raw offsets are signed: the aligned span of the first chunk may begin a few bytes
     // before the segment (inside the file's headers)
     const int32_t seg_len = (int32_t)R.entropy_len;
@@ -1047,6 +1062,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
 #pragma unroll
                 for (int i = 0; i < 16; i++) {
                     if ((bd >> i) & 1u) {
+                        // marker number marker_base + rank of the image must be RST((that) mod 8)
+                        if ((((wv[i >> 2] >> (8 * (i & 3))) ^ (marker_base + rank)) & 7u) != 0) bad = 1;
                         atomicOr(&S.bmask[o >> 5], 1u << (o & 31));
                         if (rank < (uint32_t)kMaxBoundaries) S.bpos[rank] = (uint16_t)o;
                         // raw offset just after the last marker of the chunk: where a chunk of
@@ -1087,6 +1104,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         const uint32_t limit_bits = clean_len * 8u;
         WriteCtx wc;
         wc.coef = coef;
+        wc.side_rel = side_rel;
         wc.bad = 0;
 
         // ---- short intervals: one lane per restart interval, one pass -----------------
@@ -1096,6 +1114,14 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         // possible and the other waves of the workgroup leave their SIMDs to other workgroups.
         if (short_intervals) {
             const uint32_t rem0 = g.ri_blocks - block_base % g.ri_blocks;  // blocks left in interval 0
+            {
+                // zeros over the blocks of the chunk's intervals: [z_lo, z_hi) of the image (a block
+                // that is under way when the chunk begins was begun, and zeroed, in the chunk before)
+                const uint32_t z_lo = min(block_base + ((st0 & 63u) ? 1u : 0u), g.n_blocks);
+                const uint32_t z_hi = min(min(block_base + rem0 + (n_iv - 1) * g.ri_blocks, block_end), g.n_blocks);
+                zero_blocks(coef, z_lo, z_hi, (uint32_t)tid, kT);
+                __syncthreads();  // (and only then does any lane store a coefficient)
+            }
             for (uint32_t k = (uint32_t)tid; k < n_iv; k += kT) {
                 const uint32_t start = k ? pack_state((uint32_t)S.bpos[k - 1] * 8u, 0, 0) : st0;
                 const uint32_t end_bit = k < nbnd ? (uint32_t)S.bpos[k] * 8u : limit_bits;
@@ -1112,7 +1138,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
                 // DC values of the blocks whose DC was decoded here (the chunk may begin inside a block)
                 const uint32_t dc_lo = block_base + ((st0 & 63u) ? 1u : 0u);
                 block_base = min(block_base + rem0 + (n_iv - 1) * g.ri_blocks, block_end);
-                dc_prefix(S, g, coef, dc_lo, min(block_base, g.n_blocks), dc_carry);
+                dc_prefix(S, g, coef, coef + side_rel, dc_lo, min(block_base, g.n_blocks), dc_carry);
             }
             st0 = pack_state(0, 0, 0);
             dc_carry[0] = dc_carry[1] = dc_carry[2] = 0;
@@ -1121,6 +1147,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             const int32_t next_cs = (int32_t)S.bcast[2];
             if (next_cs <= cs || next_cs > rhi) { bad = 1; cs = rhi; break; }
             cs = next_cs;
+            marker_base += nbnd;  // the next chunk starts just after the last marker of this one
             continue;
         }
 
@@ -1164,6 +1191,15 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         const bool boundary_due = (in_state & 511u) == 0 && g.ri_blocks != 0 && my_block % g.ri_blocks == 0 &&
                                   my_block < g.n_blocks && tid != 0;
         wc.iv_rem = boundary_due ? 0 : g.ri_blocks ? (int32_t)(g.ri_blocks - my_block % g.ri_blocks) : 0x7FFFFFFF;
+        // Nothing has cleared the blocks: every lane stores zeros over the blocks whose first
+        // coefficient it will decode (a block that is under way when the lane begins was begun,
+        // and zeroed, by an earlier lane or chunk), and only then does any lane store a coefficient.
+        if (active && (in_state >> 9) < end_bit) {
+            const uint32_t z_lo = my_block + ((in_state & 63u) ? 1u : 0u);
+            const uint32_t z_hi = min(my_block + nblk + ((out_state & 63u) ? 1u : 0u), g.n_blocks);
+            zero_blocks(coef, z_lo, max(z_lo, z_hi), 0, 1);
+        }
+        __syncthreads();
         uint32_t final_state = out_state;
         if (active && (in_state >> 9) < end_bit) {
             uint32_t nb2;
@@ -1180,7 +1216,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             // a block (DC decoded earlier) and end inside one (DC decoded here)
             const uint32_t dc_lo = block_base + ((st0 & 63u) ? 1u : 0u);
             const uint32_t dc_hi = block_base + total_blocks + ((fs & 63u) ? 1u : 0u);
-            dc_prefix(S, g, coef, dc_lo, min(dc_hi, g.n_blocks), dc_carry);
+            dc_prefix(S, g, coef, coef + side_rel, dc_lo, min(dc_hi, g.n_blocks), dc_carry);
         }
 
         // carry the true end state into the next chunk
@@ -1195,8 +1231,17 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             cs = rhi;
             break;
         }
-        if (tid == 0) S.bcast[1] = 0;
+        if (tid == 0) S.bcast[1] = S.bcast[3] = 0;
         __syncthreads();
+        {
+            // restart markers of this chunk that the next chunk will not stage again: those whose
+            // interval begins at or before the clean byte the next chunk starts with
+            const unsigned long long m = ((unsigned long long)S.bmask[2 * tid + 1] << 32) | S.bmask[2 * tid];
+            const uint32_t first = (uint32_t)tid * 64u;
+            if (m != 0 && qc >= first)
+                atomicAdd(&S.bcast[3], qc - first >= 63u ? (uint32_t)__popcll(m)
+                                                         : (uint32_t)__popcll(m & ((2ull << (qc - first)) - 1ull)));
+        }
         if (S.keep_off[tid] <= qc && qc < S.keep_off[tid] + (uint32_t)__popcll(S.keep[tid])) {
             unsigned long long m = S.keep[tid];
             const uint32_t skip = qc - S.keep_off[tid];
@@ -1208,6 +1253,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         if (next_cs <= cs || next_cs >= rhi) { bad = 1; cs = rhi; break; }  // no progress: refuse to spin
         cs = next_cs;
         st0 = pack_state(pbit & 7u, (fs >> 6) & 7u, fs & 63u);
+        marker_base += S.bcast[3];
     }
 
     // the run must end on an MCU boundary with exactly the blocks it should hold
@@ -1222,26 +1268,23 @@ static_assert(sizeof(HuffTables) % 16 == 0, "table slots are copied in 16-byte u
 
 void launch_scan_restart_markers(const uint8_t *bits, const ImageRec *recs, int n_images,
                                  uint32_t n_windows, uint32_t *win_count, uint32_t *win_first,
-                                 int32_t *status, int16_t *coef, uint64_t n_blocks,
-                                 const uint32_t *table_rep, uint32_t n_tables, uint8_t *tables,
-                                 hipStream_t stream)
+                                 int32_t *status, const uint32_t *table_rep, uint32_t n_tables,
+                                 uint8_t *tables, hipStream_t stream)
 {
     if (n_windows == 0) return;
-    const uint64_t clear_units = n_blocks * 8;  // 128 bytes per block, 16 per unit
-    const uint64_t clear_per_wg = (clear_units + n_windows - 1) / n_windows;
     hipLaunchKernelGGL(scan_restart_markers, dim3(n_windows + 4 * n_tables), dim3(kDecodeThreads), 0, stream,
-                       bits, recs, n_images, n_windows, win_count, win_first, status,
-                       reinterpret_cast<uint4 *>(coef), clear_units, clear_per_wg, table_rep,
+                       bits, recs, n_images, n_windows, win_count, win_first, status, table_rep,
                        reinterpret_cast<uint4 *>(tables));
 }
 
 void launch_decode_entropy(const uint8_t *bits, const ImageRec *recs, int n_images,
                            uint32_t n_windows, const uint32_t *win_count, const uint32_t *win_first,
-                           int16_t *coef, int32_t *status, const uint8_t *tables, hipStream_t stream)
+                           int16_t *coef, uint32_t side_off, int32_t *status, const uint8_t *tables,
+                           hipStream_t stream)
 {
     if (n_windows == 0) return;
     hipLaunchKernelGGL(decode_entropy, dim3(n_windows), dim3(kDecodeThreads), 0, stream, bits, recs,
-                       n_images, win_count, win_first, coef, status,
+                       n_images, win_count, win_first, coef, side_off, status,
                        reinterpret_cast<const uint4 *>(tables));
 }
 

@@ -131,7 +131,8 @@ DAMAGE_BASES = [(96, 64, oracle.MODE_420, 2, 85), (96, 64, oracle.MODE_420, 0, 9
 
 def damaged_streams(seed, per_base, n_bases=len(DAMAGE_BASES)):
     """Sound oracle-encoded files whose entropy-coded segment is then damaged at random: bit
-    flips, inserted marker bytes, deleted runs, garbage runs, truncation, runs of FF.
+    flips, inserted marker bytes, deleted runs, garbage runs, truncation, runs of FF, restart
+    markers with a wrong number or two of them swapped.
     Headers stay intact, so every file reaches the decoder kernels."""
     rng = np.random.default_rng(seed)
     out = []
@@ -142,8 +143,11 @@ def damaged_streams(seed, per_base, n_bases=len(DAMAGE_BASES)):
         start, end = sos + 2 + int.from_bytes(b[sos + 2:sos + 4], "big"), len(b) - 2
         for _ in range(per_base):
             a = bytearray(b)
-            kind = int(rng.integers(0, 6))
+            kind = int(rng.integers(0, 7))
             pos = int(rng.integers(start, end))
+            marks = [m for m in range(start, end - 1) if b[m] == 0xFF and 0xD0 <= b[m + 1] <= 0xD7]
+            if kind == 6 and not marks:
+                kind = 0
             if kind == 0:
                 for _ in range(int(rng.integers(1, 4))):
                     a[int(rng.integers(start, end))] ^= 1 << int(rng.integers(0, 8))
@@ -156,9 +160,15 @@ def damaged_streams(seed, per_base, n_bases=len(DAMAGE_BASES)):
                 a[pos:pos + n] = rng.integers(0, 256, n, dtype=np.uint8).tobytes()
             elif kind == 4:
                 a = a[:pos] + b"\xff\xd9"
-            else:
+            elif kind == 5:
                 n = int(rng.integers(1, 30))
                 a[pos:pos + n] = b"\xff" * n
+            elif len(marks) >= 2 and rng.random() < 0.5:
+                m1, m2 = (int(x) for x in rng.choice(len(marks), 2, replace=False))
+                a[marks[m1] + 1], a[marks[m2] + 1] = a[marks[m2] + 1], a[marks[m1] + 1]
+            else:
+                m = marks[int(rng.integers(0, len(marks)))]
+                a[m + 1] = 0xD0 + (a[m + 1] - 0xD0 + int(rng.integers(1, 8))) % 8
             out.append(bytes(a))
     return out
 

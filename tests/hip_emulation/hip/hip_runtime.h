@@ -170,6 +170,8 @@ inline int32_t __builtin_amdgcn_sbfe(int32_t v, uint32_t offset, uint32_t width)
     const uint32_t field = ((uint32_t)v >> offset) & ((1u << width) - 1u);
     return (field >> (width - 1)) ? (int32_t)(field | ~((1u << width) - 1u)) : (int32_t)field;
 }
+// the value of the wave's first active lane; used only where all lanes hold the same value
+inline int __builtin_amdgcn_readfirstlane(int v) { return v; }
 inline int __mul24(int a, int b) { return a * b; }
 inline int __popcll(unsigned long long v) { return __builtin_popcountll(v); }
 

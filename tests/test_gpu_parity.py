@@ -222,7 +222,7 @@ def test_corrupt_and_unsupported_images_do_not_poison_the_batch(pp, prep):
     sos = good[0].index(b"\xff\xda")
     i = good[0].index(b"\xff\xd1", sos)
     i2 = good[2].index(b"\xff\xd3", good[2].index(b"\xff\xda"))
-    wrong_rst = good[0][:i + 1] + b"\xd5" + good[0][i + 2:]  # RST5 where RST1 belongs: the index is not validated
+    wrong_rst = good[0][:i + 1] + b"\xd5" + good[0][i + 2:]  # RST5 where RST1 belongs (T.81 E.2.4: they count modulo 8)
     dropped = good[2][:i2] + good[2][i2 + 2:]               # a restart marker removed
     garbage = good[0][:sos + 40] + bytes(200) + good[0][sos + 240:]  # zeros inside the scan
     streams = [good[0], cut, good[1], prog, dropped, good[2], garbage, wrong_rst]
@@ -235,7 +235,9 @@ def test_corrupt_and_unsupported_images_do_not_poison_the_batch(pp, prep):
     ref = oracle_batch(good, 256, 224, 224)
     for j, i in ((0, 0), (2, 1), (5, 2)):
         assert np.abs(got[j] - ref[i][3]).max() <= 0.02
-    assert status[7] == 0 and np.array_equal(got[7], got[0])
+    assert status[7] == prep.E_CORRUPT and (got[7] == 0).all()
+    with pytest.raises(oracle.OracleError):
+        oracle.decode(wrong_rst)
 
 
 def test_argument_errors(pp, prep):
