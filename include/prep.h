@@ -23,6 +23,12 @@
  *   output    : planar NCHW, RGB channel order, fp32 or fp16; or, without normalize,
  *               the resized crop as interleaved 8-bit RGB (PREP_U8_NHWC).
  *
+ * Two restrictions inside the baseline subset: the two chroma components must name the same
+ * Huffman tables (the decoder holds one DC/AC pair for luma and one for chroma; a file that
+ * gives Cb and Cr different tables is reported PREP_E_UNSUPPORTED), and the entropy-coded
+ * segment is taken to end at the LAST EOI marker of a file (a sound image followed by data
+ * that holds another FF D9, such as an appended preview, is reported PREP_E_CORRUPT).
+ *
  * All entry points are plain C.  "HOST" pointers are ordinary process memory,
  * "DEVICE" pointers are HIP device memory of the handle's GPU.  A handle may be
  * used by one thread and one stream at a time; use several handles for
@@ -50,10 +56,11 @@ enum {
 
 /* Output element type and layout.  PREP_F32, PREP_F16: the normalized tensor, planar
  * [n][3][crop_h][crop_w].  PREP_U8_NHWC: Resize and Crop without Normalize (mean and std are
- * not looked at), the resized samples rounded to the nearest integer, halves upwards (a
- * sample within 1/1024 below a half counts as a half: rational scales produce exact halves
- * all the time, and they must not depend on the last bit of the interpolation), as
- * interleaved RGB bytes [n][crop_h][crop_w][3]. */
+ * not looked at), the resized samples rounded to the nearest integer, halves upwards, as
+ * interleaved RGB bytes [n][crop_h][crop_w][3].  The kernels interpolate in fp32: a sample
+ * that lies within 2^-12 below a half is taken for the half (rational scales produce exact
+ * halves all the time, and fp32 lands on either side of them), so a result may be one level
+ * above the exactly rounded one there. */
 enum { PREP_F32 = 0, PREP_F16 = 1, PREP_U8_NHWC = 2 };
 
 /* The Resize unit's filter (PREBA section 4.2, Table 1 names the unit, not the filter).
@@ -225,6 +232,8 @@ int prep_resize_normalize_static(int32_t device, const uint8_t *rgb, const uint6
  * geometry and quantisation tables.
  *   coefficients HOST  for each image in turn, its blocks in scan order, 64
  *                int16 per block in zig-zag order with absolute DC values
+ * Unlike the batch calls this one waits for `stream` before it returns (the
+ * coefficients are copied from pageable host memory): it is a checking aid.
  */
 int prep_reconstruct_from_coefficients(prep_handle *h, const uint8_t *bitstreams,
                                        const uint64_t *offsets, int32_t n,
@@ -336,7 +345,7 @@ int prep_server_release_many(prep_server *s, const prep_server_result *r, int32_
  * configured dtype) to host_out (HOST); for checks, while the slab is valid.  */
 int prep_server_copy_tensor(prep_server *s, const prep_server_result *r, void *host_out);
 
-/* ---- audio path (PREBA section 2.3 item b; section 4.2, Fig. 11(b), Table 2) ----
+/* ---- audio path (PREBA section 2.3 item b; section 4.2, Fig. 11(b), Table 1) ----
  *
  * Resample -> log-Mel spectrogram -> per-feature normalize, the three units of
  * the paper's audio compute units.  Definitions: band-limited interpolation
@@ -373,7 +382,8 @@ int64_t prep_audio_frames(const prep_audio_config *cfg, uint64_t samples_in, int
  * in elements) as [n_mels][frames_i], frames innermost.  Every utterance must
  * be longer than n_fft/2 samples after resampling.  Enqueues on `stream` (a
  * hipStream_t, NULL = the default stream) and
- * returns; allocates nothing except when the rate pair changes.                 */
+ * returns; allocates nothing (the interpolation taps of a new rate pair are built on
+ * the host and uploaded on `stream`; the last two pairs are kept).              */
 int prep_audio_features(prep_audio *h, const float *waveforms, const uint64_t *offsets, int32_t n,
                         int32_t rate_in, float *out, uint64_t *out_offsets, void *stream);
 

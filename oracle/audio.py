@@ -1,6 +1,6 @@
 """CPU oracle (test infrastructure): the audio preprocessing path of PREBA (section 2.3 item
 b and Fig. 4(b): resampling, Fourier transform, Mel filters; section 4.2, Fig. 11(b) and
-Table 2: the Resample, Mel spectrogram and Normalize units) in plain numpy, float64.
+Table 1: the Resample, Mel spectrogram and Normalize units) in plain numpy, float64.
 
 The paper names the operations and nothing else.  The definitions taken here (listed as
 readings in the design notes):

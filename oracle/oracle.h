@@ -155,10 +155,12 @@ int oracle_preprocess_antialias(const uint8_t *rgb, int w, int h, int resize_sho
                                 double *out);
 
 /* Resize (either filter) and centre crop without Normalize: the resized samples rounded to
- * the nearest integer, halves upwards (a sample within 1/1024 below a half counts as a
- * half), as interleaved RGB8 out[y][x][c].
- * pinned by: the source pixels themselves at scale 1, integer means of a 2:1 reduction with
- * their halves, Pillow's 8-bit resize within one level.                                   */
+ * the nearest integer, halves upwards, floor(v + 1/2), evaluated in exact integer arithmetic
+ * (both filters' weights are rationals), as interleaved RGB8 out[y][x][c].
+ * pinned by: the source pixels themselves at scale 1, integer means of 2:1 and 8:1 reductions
+ * with their halves, both filters at scales with weights in sixths and fifteenths against the
+ * definition in exact fractions (images built so that many samples lie exactly half way),
+ * Pillow's 8-bit resize within one level.                                                 */
 int oracle_resize_crop_u8(const uint8_t *rgb, int w, int h, int resize_short, int crop_h, int crop_w,
                           int antialias, uint8_t *out);
 

@@ -273,25 +273,108 @@ int oracle_preprocess_antialias(const uint8_t *rgb, int w, int h, int resize_sho
     return rc ? rc : normalize_planes(out, crop_h, crop_w, mean, std);
 }
 
+/* ---- 8-bit output: the resized sample rounded to the nearest integer, halves upwards ------
+ * Computed in exact integers, not from the double-precision planes above: the weights of both
+ * filters are rationals with small denominators (2 * out size for the two-tap filter, the
+ * window's weight sum for the antialiased one), rational scales put samples exactly half way
+ * between two integers all the time, and floor(v + 1/2) must not depend on which side of such
+ * a point a floating-point evaluation happens to land.                                      */
+
+typedef __int128 wide_t;
+
+static int64_t floor_div(int64_t a, int64_t b) /* b > 0 */
+{
+    int64_t q = a / b;
+    return (a % b != 0 && a < 0) ? q - 1 : q;
+}
+
+/* Two-tap weights along one axis for output index i (crop offset included): source
+ * coordinate (2 i + 1) in / (2 out) - 1/2 = n / d with d = 2 out; taps floor and floor + 1,
+ * clamped, with weights (d - a) / d and a / d.                                             */
+static void two_taps(int i, int in_size, int out_size, int *t0, int *t1, int64_t *a, int64_t *d)
+{
+    int64_t n = (int64_t)(2 * (int64_t)i + 1) * in_size - out_size;
+    *d = 2 * (int64_t)out_size;
+    int64_t f = floor_div(n, *d);
+    *a = n - f * *d;
+    *t0 = clampi((int)f, 0, in_size - 1);
+    *t1 = clampi((int)f + 1, 0, in_size - 1);
+}
+
+/* Triangle weights along one axis for output index i, as integers u[j - first] >= 0 whose sum
+ * is the normalising denominator.  With scale = in / out and support = max(scale, 1) = s / out,
+ * s = max(in, out): the centre is (2 i + 1) in / (2 out), the window is
+ * [floor(centre - support + 1/2), floor(centre + support + 1/2)) cut to the image, and
+ * 1 - |j + 1/2 - centre| / support = (2 s - |(2 j + 1) out - (2 i + 1) in|) / (2 s).          */
+static int triangle_units(int i, int in_size, int out_size, int64_t *u, int *count)
+{
+    int64_t s = in_size > out_size ? in_size : out_size;
+    int64_t c2 = (int64_t)(2 * (int64_t)i + 1) * in_size;            /* centre * 2 out */
+    int64_t first = floor_div(c2 - 2 * s + out_size, 2 * (int64_t)out_size);
+    int64_t end = floor_div(c2 + 2 * s + out_size, 2 * (int64_t)out_size);
+    if (first < 0) first = 0;
+    if (end > in_size) end = in_size;
+    for (int64_t j = first; j < end; j++) {
+        int64_t dist = (2 * j + 1) * out_size - c2;
+        if (dist < 0) dist = -dist;
+        u[j - first] = 2 * s > dist ? 2 * s - dist : 0;
+    }
+    *count = (int)(end - first);
+    return (int)first;
+}
+
 int oracle_resize_crop_u8(const uint8_t *rgb, int w, int h, int resize_short, int crop_h, int crop_w,
                           int antialias, uint8_t *out)
 {
-    if (!rgb || !out || crop_h < 1 || crop_w < 1) return ORACLE_E_ARG;
-    double *planes = malloc((size_t)3 * crop_h * crop_w * sizeof *planes);
-    if (!planes) return ORACLE_E_ARG;
-    int rc = antialias ? resample_antialias(rgb, w, h, resize_short, crop_h, crop_w, planes)
-                       : resample_plain(rgb, w, h, resize_short, crop_h, crop_w, planes);
-    if (rc == ORACLE_OK)
-        for (int y = 0; y < crop_h; y++)
-            for (int x = 0; x < crop_w; x++)
+    if (!rgb || !out || w < 1 || h < 1 || crop_h < 1 || crop_w < 1) return ORACLE_E_ARG;
+    int ow, oh;
+    oracle_resized_size(w, h, resize_short, &ow, &oh);
+    if (crop_w > ow || crop_h > oh) return ORACLE_E_ARG;
+    int top = (oh - crop_h) / 2, left = (ow - crop_w) / 2;
+    if (!antialias) {
+        for (int y = 0; y < crop_h; y++) {
+            int ya, yb;
+            int64_t b, e;
+            two_taps(y + top, h, oh, &ya, &yb, &b, &e);
+            for (int x = 0; x < crop_w; x++) {
+                int xa, xb;
+                int64_t a, d;
+                two_taps(x + left, w, ow, &xa, &xb, &a, &d);
                 for (int c = 0; c < 3; c++) {
-                    /* the resized sample itself to the nearest integer, halves upwards; a sample
-                     * within 1/1024 below a half counts as a half, so that the halves that rational
-                     * scales produce all the time (weights k/42 and the like) do not depend on the
-                     * last bit of the arithmetic that formed them */
-                    double v = floor(planes[((size_t)c * crop_h + y) * crop_w + x] + 0.5 + 1.0 / 1024.0);
-                    out[((size_t)y * crop_w + x) * 3 + c] = (uint8_t)(v < 0.0 ? 0.0 : (v > 255.0 ? 255.0 : v));
+                    int64_t p00 = rgb[((size_t)ya * w + xa) * 3 + c], p01 = rgb[((size_t)ya * w + xb) * 3 + c];
+                    int64_t p10 = rgb[((size_t)yb * w + xa) * 3 + c], p11 = rgb[((size_t)yb * w + xb) * 3 + c];
+                    /* v = num / (d e); floor(v + 1/2) = floor((2 num + d e) / (2 d e)) */
+                    int64_t num = (e - b) * ((d - a) * p00 + a * p01) + b * ((d - a) * p10 + a * p11);
+                    out[((size_t)y * crop_w + x) * 3 + c] = (uint8_t)((2 * num + d * e) / (2 * d * e));
                 }
-    free(planes);
-    return rc;
+            }
+        }
+        return ORACLE_OK;
+    }
+    size_t cap_x = 2 * (size_t)(w > ow ? w / ow + 1 : 1) + 4, cap_y = 2 * (size_t)(h > oh ? h / oh + 1 : 1) + 4;
+    int64_t *ux = malloc(cap_x * sizeof *ux), *uy = malloc(cap_y * sizeof *uy);
+    if (!ux || !uy) { free(ux); free(uy); return ORACLE_E_ARG; }
+    for (int y = 0; y < crop_h; y++) {
+        int ny, y0 = triangle_units(y + top, h, oh, uy, &ny);
+        wide_t sum_y = 0;
+        for (int r = 0; r < ny; r++) sum_y += uy[r];
+        for (int x = 0; x < crop_w; x++) {
+            int nx, x0 = triangle_units(x + left, w, ow, ux, &nx);
+            wide_t sum_x = 0;
+            for (int k = 0; k < nx; k++) sum_x += ux[k];
+            for (int c = 0; c < 3; c++) {
+                wide_t num = 0;
+                for (int r = 0; r < ny; r++) {
+                    wide_t row = 0;
+                    for (int k = 0; k < nx; k++) row += (wide_t)ux[k] * rgb[((size_t)(y0 + r) * w + (x0 + k)) * 3 + c];
+                    num += (wide_t)uy[r] * row;
+                }
+                wide_t den = sum_x * sum_y;
+                out[((size_t)y * crop_w + x) * 3 + c] = (uint8_t)((2 * num + den) / (2 * den));
+            }
+        }
+    }
+    free(ux);
+    free(uy);
+    return ORACLE_OK;
 }

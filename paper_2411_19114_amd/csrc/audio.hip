@@ -1,6 +1,6 @@
 // Audio preprocessing for gfx950: resample -> log-Mel spectrogram -> per-feature normalize.
 //
-// The audio compute units of PREBA's DPU (section 2.3 item b; section 4.2, Fig. 11(b), Table 2:
+// The audio compute units of PREBA's DPU (section 2.3 item b; section 4.2, Fig. 11(b), Table 1:
 // Resample, Mel spectrogram, Normalize).  The paper names the operations only; the definitions
 // are: band-limited interpolation with a Hann-windowed sinc (six zero crossings, cut-off at
 // 0.99 of the lower Nyquist rate); frames of n_fft samples every hop samples, centred by
@@ -88,6 +88,10 @@ __global__ __launch_bounds__(256) void resample_kernel(const float *__restrict__
 // taps are loaded once and only the signal is read in the loop.  tile_start[u] = first
 // workgroup of utterance u; a workgroup makes kTilesPerWg * blockDim.x consecutive outputs.
 constexpr int kMaxTaps = 40;
+// A rate pair p : q (reduced) is accepted up to this size of either term; its tap table has q
+// rows of at most 2 * 6 / 0.99 * max(p / q, 1) + 2 taps, fewer than 14 * max(p, q) + 2 q entries.
+constexpr int kMaxRateTerm = 4096;
+constexpr size_t kMaxTapEntries = 16 * (size_t)kMaxRateTerm;
 constexpr int kTilesPerWg = 8;
 
 __global__ __launch_bounds__(512) void resample_phase_kernel(
@@ -330,11 +334,17 @@ struct prep_audio {
     double2 *d_twiddle = nullptr;
     double *d_mel_weights = nullptr;
     MelTable mel;
-    // interpolation taps of the rate pair seen last
-    int taps_p = 0, taps_q = 0, n_taps = 0;
-    double *d_taps = nullptr;
-    int32_t *d_first = nullptr;
-    size_t taps_cap = 0;
+    // interpolation taps of the two rate pairs seen last, in buffers of the largest size a rate
+    // pair can need (reserved in prep_audio_create: a call never allocates or frees)
+    struct TapSlot {
+        int p = 0, q = 0, n_taps = 0;
+        double *d_taps = nullptr;
+        int32_t *d_first = nullptr;
+        uint64_t used = 0;       // call counter when the slot served last
+    } slot[2];
+    double *h_taps_pinned = nullptr;   // staging of an upload, free again once `done` has passed
+    int32_t *h_first_pinned = nullptr;
+    uint64_t calls = 0;
     // per call
     Utterance *h_utt = nullptr, *d_utt = nullptr;
     uint64_t *h_starts = nullptr, *d_starts = nullptr;  // [mid_start n][frame_start n][tile_start n]
@@ -456,6 +466,12 @@ int prep_audio_create(prep_audio **out, const prep_audio_config *cfg)
     ok = ok && hipHostMalloc((void **)&h->h_starts, sizeof(uint64_t) * 3 * n, hipHostMallocDefault) == hipSuccess;
     // the resampled signal is never longer than max_total_samples scaled by the largest ratio accepted
     ok = ok && hipMalloc((void **)&h->d_mid, sizeof(double) * (cfg->max_total_samples + n)) == hipSuccess;
+    for (auto &ts : h->slot) {
+        ok = ok && hipMalloc((void **)&ts.d_taps, sizeof(double) * kMaxTapEntries) == hipSuccess;
+        ok = ok && hipMalloc((void **)&ts.d_first, sizeof(int32_t) * kMaxRateTerm) == hipSuccess;
+    }
+    ok = ok && hipHostMalloc((void **)&h->h_taps_pinned, sizeof(double) * kMaxTapEntries, hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipHostMalloc((void **)&h->h_first_pinned, sizeof(int32_t) * kMaxRateTerm, hipHostMallocDefault) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&h->done, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipMemcpy(h->d_window, window.data(), sizeof(double) * kFft, hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(h->d_twiddle, tw.data(), sizeof(double2) * kFft, hipMemcpyHostToDevice) == hipSuccess;
@@ -480,8 +496,12 @@ int prep_audio_destroy(prep_audio *h)
     (void)hipFree(h->d_utt);
     (void)hipFree(h->d_starts);
     (void)hipFree(h->d_mid);
-    (void)hipFree(h->d_taps);
-    (void)hipFree(h->d_first);
+    for (auto &ts : h->slot) {
+        (void)hipFree(ts.d_taps);
+        (void)hipFree(ts.d_first);
+    }
+    if (h->h_taps_pinned) (void)hipHostFree(h->h_taps_pinned);
+    if (h->h_first_pinned) (void)hipHostFree(h->h_first_pinned);
     if (h->h_utt) (void)hipHostFree(h->h_utt);
     if (h->h_starts) (void)hipHostFree(h->h_starts);
     if (h->done) (void)hipEventDestroy(h->done);
@@ -499,7 +519,7 @@ int prep_audio_features(prep_audio *h, const float *waveforms, const uint64_t *o
     if (n == 0) return PREP_OK;
     const int g = std::gcd(rate_in, h->cfg.rate);
     const int p = rate_in / g, q = h->cfg.rate / g;
-    if (p > 4096 || q > 4096) return PREP_E_INVALID_ARG;  // the tap table has q rows
+    if (p > kMaxRateTerm || q > kMaxRateTerm) return PREP_E_INVALID_ARG;  // the tap table has q rows
     AUDIO_TRY(hipSetDevice(h->cfg.device));
     if (h->pending) {  // the pinned records of the call before are still being read
         AUDIO_TRY(hipEventSynchronize(h->done));
@@ -533,28 +553,30 @@ int prep_audio_features(prep_audio *h, const float *waveforms, const uint64_t *o
     }
     if (offsets[n] - offsets[0] > h->cfg.max_total_samples || mid_total > h->cfg.max_total_samples + (uint64_t)n)
         return PREP_E_TOO_LARGE;
-    if (p != q && (p != h->taps_p || q != h->taps_q)) {
-        // a new rate pair: build its taps (the stream is drained so that the old ones are free)
-        AUDIO_TRY(hipStreamSynchronize(stream));
-        make_taps(p, q, &h->h_taps, &h->h_first, &h->n_taps);
-        const size_t need = h->h_taps.size();
-        if (need > h->taps_cap) {
-            (void)hipFree(h->d_taps);
-            (void)hipFree(h->d_first);
-            h->d_taps = nullptr;
-            h->d_first = nullptr;
-            h->taps_cap = 0;
-            if (hipMalloc((void **)&h->d_taps, sizeof(double) * need) != hipSuccess ||
-                hipMalloc((void **)&h->d_first, sizeof(int32_t) * 4096) != hipSuccess) {
-                (void)hipGetLastError();
-                return PREP_E_NOMEM;
+    prep_audio::TapSlot *taps = &h->slot[0];
+    if (p != q) {
+        h->calls++;
+        if (!(taps->p == p && taps->q == q)) {
+            if (h->slot[1].p == p && h->slot[1].q == q) {
+                taps = &h->slot[1];
+            } else {
+                // a new rate pair: build its taps into the slot that served longest ago and upload
+                // them on the caller's stream, ahead of the kernels that read them (the pinned
+                // staging is free: the call before has been waited for above; so is the slot)
+                if (h->slot[1].used < taps->used) taps = &h->slot[1];
+                make_taps(p, q, &h->h_taps, &h->h_first, &taps->n_taps);
+                if (h->h_taps.size() > kMaxTapEntries) return PREP_E_TOO_LARGE;
+                memcpy(h->h_taps_pinned, h->h_taps.data(), sizeof(double) * h->h_taps.size());
+                memcpy(h->h_first_pinned, h->h_first.data(), sizeof(int32_t) * (size_t)q);
+                AUDIO_TRY(hipMemcpyAsync(taps->d_taps, h->h_taps_pinned, sizeof(double) * h->h_taps.size(),
+                                         hipMemcpyHostToDevice, stream));
+                AUDIO_TRY(hipMemcpyAsync(taps->d_first, h->h_first_pinned, sizeof(int32_t) * (size_t)q,
+                                         hipMemcpyHostToDevice, stream));
+                taps->p = p;
+                taps->q = q;
             }
-            h->taps_cap = need;
         }
-        AUDIO_TRY(hipMemcpy(h->d_taps, h->h_taps.data(), sizeof(double) * need, hipMemcpyHostToDevice));
-        AUDIO_TRY(hipMemcpy(h->d_first, h->h_first.data(), sizeof(int32_t) * (size_t)q, hipMemcpyHostToDevice));
-        h->taps_p = p;
-        h->taps_q = q;
+        taps->used = h->calls;
     }
     if (p == q) {
         // same rate: the frames read the input itself; utterance offsets are the input's
@@ -562,12 +584,12 @@ int prep_audio_features(prep_audio *h, const float *waveforms, const uint64_t *o
     }
     AUDIO_TRY(hipMemcpyAsync(h->d_utt, h->h_utt, sizeof(Utterance) * (size_t)n, hipMemcpyHostToDevice, stream));
     AUDIO_TRY(hipMemcpyAsync(h->d_starts, h->h_starts, sizeof(uint64_t) * 3 * (size_t)n, hipMemcpyHostToDevice, stream));
-    if (p != q && phase_threads && h->n_taps <= kMaxTaps && tiles_total <= 0x7FFFFFFFull) {
+    if (p != q && phase_threads && taps->n_taps <= kMaxTaps && tiles_total <= 0x7FFFFFFFull) {
         hipLaunchKernelGGL(resample_phase_kernel, dim3((unsigned)tiles_total), dim3(phase_threads), 0, stream, waveforms,
-                           h->d_utt, h->d_starts + 2 * n, n, h->d_taps, h->d_first, p, q, h->n_taps, h->d_mid);
+                           h->d_utt, h->d_starts + 2 * n, n, taps->d_taps, taps->d_first, p, q, taps->n_taps, h->d_mid);
     } else if (p != q) {
         hipLaunchKernelGGL(resample_kernel, dim3((unsigned)((mid_total + 255) / 256)), dim3(256), 0, stream, waveforms,
-                           h->d_utt, h->d_starts, n, h->d_taps, h->d_first, p, q, h->n_taps, h->d_mid, mid_total);
+                           h->d_utt, h->d_starts, n, taps->d_taps, taps->d_first, p, q, taps->n_taps, h->d_mid, mid_total);
     }
     const dim3 frame_grid((unsigned)((frames_total + 3) / 4));
     if (p == q)

@@ -44,9 +44,9 @@ __device__ inline void store_row(__half *p, const float v[kPx])
 }
 static_assert(kPx == 4, "store_row writes four values");
 // 8-bit output: a resized sample (0 .. 255, no Normalize) to the nearest integer, halves
-// upwards, where a sample within 1/1024 below a half counts as a half (far more than the
-// interpolation's rounding error, far less than matters)
-__device__ inline uint32_t to_byte(float v) { return min((uint32_t)(v + (0.5f + 1.0f / 1024.0f)), 255u); }
+// upwards.  Exact halves are common (rational scales) and fp32 interpolation lands up to a few
+// 1e-5 to either side of them, so a sample within 2^-12 below a half is taken for the half.
+__device__ inline uint32_t to_byte(float v) { return min((uint32_t)(v + (0.5f + 1.0f / 4096.0f)), 255u); }
 
 __device__ inline void store1(float *p, float v) { *p = v; }
 __device__ inline void store1(__half *p, float v) { *p = __float2half_rn(v); }

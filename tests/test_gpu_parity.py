@@ -327,12 +327,12 @@ def test_medium_restart_intervals_cross_subsequences(pp):
 
 
 def test_concurrent_handles_and_streams(prep):
-    # the serving pattern of workload 3: several host threads, each with its own handle and
-    # stream, decode different batches at the same time
+    # the serving pattern of workload 3 as it is stated: seven host threads, each with its own
+    # handle and stream, decode different batches of eight at the same time
     import threading
     import torch
     from paper_2411_19114_amd.binding import make_params
-    n_workers, per_batch, rounds = 4, 6, 3
+    n_workers, per_batch, rounds = 7, 8, 3
     pool = synth.make_batch(3, n_workers * per_batch)
     blob, offsets = synth.pack(pool)
     dev_bits = torch.from_numpy(blob).to("cuda:0")
@@ -459,7 +459,7 @@ def _full_batch_sampled(prep, config, sample):
         h.close()
 
 
-@pytest.mark.parametrize("config,sample", [(1, 8), (2, 16), (5, 16)])
+@pytest.mark.parametrize("config,sample", [(1, 8), (2, 16), (5, 16), (4, 4)])
 def test_full_batch_as_benchmarked(prep, config, sample):
     _full_batch_sampled(prep, config, sample)
 

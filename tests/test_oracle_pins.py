@@ -622,6 +622,62 @@ def test_eight_bit_output_is_the_rounded_resized_sample():
     assert np.abs(mine - theirs).max() <= 1 and (mine == theirs).mean() > 0.75
 
 
+def _exact_resize_u8(rgb, resize_short, crop_h, crop_w, antialias):
+    """The resize definitions in exact fractions, rounded half up: the two-tap filter (taps
+    floor(s), floor(s) + 1 of s = (i + 1/2) in/out - 1/2, clamped) and the triangle of
+    half-width max(in/out, 1) around (i + 1/2) in/out over the window
+    [floor(c - support + 1/2), floor(c + support + 1/2)) cut at the edge, weights scaled to sum 1."""
+    from fractions import Fraction as F
+    import math
+    h, w, _ = rgb.shape
+    ow, oh = oracle.resized_size(w, h, resize_short)
+    top, left = (oh - crop_h) // 2, (ow - crop_w) // 2
+
+    def taps(i, n_in, n_out):
+        scale = F(n_in, n_out)
+        if not antialias:
+            s_ = (i + F(1, 2)) * scale - F(1, 2)
+            f = math.floor(s_)
+            t = s_ - f
+            return [(min(max(f, 0), n_in - 1), 1 - t), (min(max(f + 1, 0), n_in - 1), t)]
+        support, c = max(scale, F(1)), (i + F(1, 2)) * scale
+        first, end = max(math.floor(c - support + F(1, 2)), 0), min(math.floor(c + support + F(1, 2)), n_in)
+        wt = [max(1 - abs(j + F(1, 2) - c) / support, F(0)) for j in range(first, end)]
+        return [(j, x / sum(wt)) for j, x in zip(range(first, end), wt)]
+
+    out = np.zeros((crop_h, crop_w, 3), dtype=np.int64)
+    halves = 0
+    for y in range(crop_h):
+        ty = taps(y + top, h, oh)
+        for x in range(crop_w):
+            tx = taps(x + left, w, ow)
+            for c in range(3):
+                v = sum(wy * wx * int(rgb[j, i, c]) for j, wy in ty for i, wx in tx)
+                halves += (v - math.floor(v)) == F(1, 2)
+                out[y, x, c] = math.floor(v + F(1, 2))
+    return out, halves
+
+
+@pytest.mark.parametrize("antialias", [False, True])
+def test_eight_bit_output_at_exact_halves_of_rational_scales(antialias):
+    # 4 -> 3 (two-tap weights in sixths) and 5 -> 3 (thirds; fifteenths under the triangle), on
+    # pixels that are multiples of 3 plus a few others: many samples lie exactly half way between
+    # two integers, where a floating-point evaluation falls on either side
+    rng = np.random.default_rng(35)
+    total = 0
+    for (h, w, short, ch, cw) in ((32, 24, 18, 22, 18), (35, 25, 15, 21, 14)):
+        rgb = (3 * rng.integers(0, 86, size=(h, w, 3))).astype(np.uint8)
+        rgb[::4, ::3] += 1
+        want, halves = _exact_resize_u8(rgb, short, ch, cw, antialias)
+        total += halves
+        assert np.array_equal(oracle.resize_crop_u8(rgb, short, ch, cw, antialias), want)
+    assert total >= 20, "too few half-way samples: the pin lost its point"
+    # an enlargement (2 -> 3: sixths again), where the triangle filter is the two-tap one
+    small = rgb[:6, :8]
+    want, _ = _exact_resize_u8(small, 9, 9, 12, antialias)
+    assert np.array_equal(oracle.resize_crop_u8(small, 9, 9, 12, antialias), want)
+
+
 def test_preprocess_rejects_bad_arguments():
     rgb = np.zeros((10, 10, 3), dtype=np.uint8)
     with pytest.raises(oracle.OracleError):
