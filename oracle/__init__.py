@@ -81,6 +81,11 @@ def lib():
         L.oracle_jpeg_decode.argtypes = [u8p, C.c_size_t, i16p, C.c_size_t, u8p, C.c_size_t,
                                          C.POINTER(Info)]
         L.oracle_jpeg_decode.restype = C.c_int
+        L.oracle_jpeg_decode_smooth.argtypes = L.oracle_jpeg_decode.argtypes
+        L.oracle_jpeg_decode_smooth.restype = C.c_int
+        L.oracle_upsample_triangle.argtypes = [u8p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                               C.c_int, C.c_int, u8p]
+        L.oracle_upsample_triangle.restype = C.c_int
         L.oracle_resized_size.argtypes = [C.c_int, C.c_int, C.c_int,
                                           C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.oracle_resized_size.restype = None
@@ -221,13 +226,27 @@ def jpeg_info(data):
     return info
 
 
-def decode(data, want_coef=True, want_rgb=True):
-    """JPEG bytes -> (coefficients [nblocks,64] or None, rgb [H,W,3] or None, Info)."""
+def upsample_triangle(plane, fx, fy, w, h):
+    """Subsampled plane [ch, cw] uint8 -> [h, w] by the centred triangle (oracle_upsample_triangle)."""
+    plane = np.ascontiguousarray(plane, dtype=np.uint8)
+    ch, cw = plane.shape
+    out = np.empty((h, w), dtype=np.uint8)
+    rc = lib().oracle_upsample_triangle(_p(plane, C.c_uint8), cw, cw, ch, fx, fy, w, h, _p(out, C.c_uint8))
+    if rc:
+        raise OracleError(rc, "upsample_triangle")
+    return out
+
+
+def decode(data, want_coef=True, want_rgb=True, smooth_chroma=False):
+    """JPEG bytes -> (coefficients [nblocks,64] or None, rgb [H,W,3] or None, Info).
+
+    smooth_chroma: subsampled chroma is interpolated (centred triangle) instead of replicated."""
     a = _bytes_arr(data)
     info = jpeg_info(a)
     coef = np.zeros((info.nblocks, 64), dtype=np.int16) if want_coef else None
     rgb = np.zeros((info.height, info.width, 3), dtype=np.uint8) if want_rgb else None
-    rc = lib().oracle_jpeg_decode(
+    fn = lib().oracle_jpeg_decode_smooth if smooth_chroma else lib().oracle_jpeg_decode
+    rc = fn(
         _p(a, C.c_uint8), a.size,
         _p(coef, C.c_int16) if want_coef else None, coef.size if want_coef else 0,
         _p(rgb, C.c_uint8) if want_rgb else None, rgb.size if want_rgb else 0,

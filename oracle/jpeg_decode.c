@@ -4,7 +4,8 @@
  * C and F.2.2.3 (Huffman decode by MINCODE/MAXCODE/VALPTR), F.2.2.1/2 (DC
  * differences, AC run/size), F.1.2.3 (byte stuffing), E.2.4 (restart
  * intervals), A.3.4 + A.3.3 (dequantise, IDCT), level shift and clamp;
- * chroma upsampling by sample replication; JFIF colour transform.
+ * chroma upsampling by sample replication, or by the centred triangle
+ * (oracle_upsample_triangle); JFIF colour transform.
  */
 #include "oracle.h"
 #include <math.h>
@@ -239,8 +240,41 @@ static uint8_t clamp_sample(double v)
     return (uint8_t)r;
 }
 
-int oracle_jpeg_decode(const uint8_t *data, size_t len, int16_t *coef, size_t coef_cap,
-                       uint8_t *rgb, size_t rgb_cap, oracle_info *info)
+/* A subsampled plane brought to full resolution by linear interpolation between sample
+ * centres.  With fx = 2 a sample sits between output columns 2i and 2i + 1, so column 2i
+ * is a quarter of a sample spacing left of sample i and three quarters right of sample
+ * i - 1: weights 3/4 and 1/4; column 2i + 1 takes 3/4 of sample i and 1/4 of sample
+ * i + 1.  Rows likewise with fy = 2, the two axes multiplied (9, 3, 3, 1 sixteenths).  A
+ * neighbour outside the cw x ch samples that the image owns is the sample at the edge.
+ * The result is rounded to the nearest integer, halves upwards.  fx = 1 or fy = 1 leaves
+ * that axis as it is.                                                                   */
+int oracle_upsample_triangle(const uint8_t *plane, int pitch, int cw, int ch, int fx, int fy,
+                             int w, int h, uint8_t *out)
+{
+    if (!plane || !out || cw < 1 || ch < 1 || w < 1 || h < 1) return ORACLE_E_ARG;
+    if ((fx != 1 && fx != 2) || (fy != 1 && fy != 2)) return ORACLE_E_ARG;
+    if ((w + fx - 1) / fx > cw || (h + fy - 1) / fy > ch) return ORACLE_E_ARG;
+    for (int y = 0; y < h; y++)
+        for (int x = 0; x < w; x++) {
+            /* nearer sample, the farther one, and the nearer one's weight in quarters */
+            int x_near = x / fx, x_far = x_near, wx = 4;
+            if (fx == 2) { x_far = (x & 1) ? x_near + 1 : x_near - 1; wx = 3; }
+            int y_near = y / fy, y_far = y_near, wy = 4;
+            if (fy == 2) { y_far = (y & 1) ? y_near + 1 : y_near - 1; wy = 3; }
+            if (x_far < 0) x_far = 0;
+            if (x_far > cw - 1) x_far = cw - 1;
+            if (y_far < 0) y_far = 0;
+            if (y_far > ch - 1) y_far = ch - 1;
+            int nn = plane[(size_t)y_near * pitch + x_near], nf = plane[(size_t)y_near * pitch + x_far];
+            int fn = plane[(size_t)y_far * pitch + x_near], ff = plane[(size_t)y_far * pitch + x_far];
+            int sum = wy * (wx * nn + (4 - wx) * nf) + (4 - wy) * (wx * fn + (4 - wx) * ff); /* sixteenths */
+            out[(size_t)y * w + x] = (uint8_t)((sum + 8) >> 4);
+        }
+    return ORACLE_OK;
+}
+
+static int decode_with(const uint8_t *data, size_t len, int16_t *coef, size_t coef_cap,
+                       uint8_t *rgb, size_t rgb_cap, oracle_info *info, int triangle)
 {
     if (!data) return ORACLE_E_ARG;
     header H;
@@ -336,12 +370,25 @@ int oracle_jpeg_decode(const uint8_t *data, size_t len, int16_t *coef, size_t co
                                         clamp_sample(f[y * 8 + x]);
                         }
                 }
-        for (int y = 0; y < g->height; y++)
+        uint8_t *full[3] = {0, 0, 0};
+        if (triangle && g->ncomp == 3) {
+            /* chroma at full resolution first; the image owns ceil(size * factor share) samples */
+            for (int c = 1; c < 3; c++) {
+                int fx = g->hmax / g->hs[c], fy = g->vmax / g->vs[c];
+                full[c] = (uint8_t *)malloc((size_t)g->width * g->height);
+                rc = oracle_upsample_triangle(plane[c], cw[c], (g->width + fx - 1) / fx,
+                                              (g->height + fy - 1) / fy, fx, fy, g->width, g->height, full[c]);
+                if (rc) break;
+            }
+        }
+        for (int y = 0; y < g->height && !rc; y++)
             for (int x = 0; x < g->width; x++) {
                 uint8_t *o = rgb + ((size_t)y * g->width + x) * 3;
                 int Y = plane[0][(size_t)y * cw[0] + x];
                 if (g->ncomp == 1) {
                     o[0] = o[1] = o[2] = (uint8_t)Y;
+                } else if (full[1]) {
+                    oracle_ycc_to_rgb(Y, full[1][(size_t)y * g->width + x], full[2][(size_t)y * g->width + x], o);
                 } else {
                     /* replicate each chroma sample over the pixels it covers */
                     int cx1 = x * g->hs[1] / g->hmax, cy1 = y * g->vs[1] / g->vmax;
@@ -351,9 +398,22 @@ int oracle_jpeg_decode(const uint8_t *data, size_t len, int16_t *coef, size_t co
                     oracle_ycc_to_rgb(Y, Cb, Cr, o);
                 }
             }
-        for (int c = 0; c < 3; c++) free(plane[c]);
+        for (int c = 0; c < 3; c++) { free(plane[c]); free(full[c]); }
+        if (rc) { free(zz); return rc; }
     }
     free(zz);
     if (info) *info = *g;
     return ORACLE_OK;
+}
+
+int oracle_jpeg_decode(const uint8_t *data, size_t len, int16_t *coef, size_t coef_cap,
+                       uint8_t *rgb, size_t rgb_cap, oracle_info *info)
+{
+    return decode_with(data, len, coef, coef_cap, rgb, rgb_cap, info, 0);
+}
+
+int oracle_jpeg_decode_smooth(const uint8_t *data, size_t len, int16_t *coef, size_t coef_cap,
+                              uint8_t *rgb, size_t rgb_cap, oracle_info *info)
+{
+    return decode_with(data, len, coef, coef_cap, rgb, rgb_cap, info, 1);
 }

@@ -125,6 +125,24 @@ int oracle_jpeg_info(const uint8_t *data, size_t len, oracle_info *info);
 int oracle_jpeg_decode(const uint8_t *data, size_t len, int16_t *coef, size_t coef_cap,
                        uint8_t *rgb, size_t rgb_cap, oracle_info *info);
 
+/* Centred-triangle upsampling of one subsampled plane (a decode variant in the sense of the
+ * flexibility objective of PREBA section 4.2): the cw x ch samples of `plane` (rows `pitch`
+ * apart), subsampled fx : 1 across and fy : 1 down (each 1 or 2), to w x h samples in `out`.
+ * A sample of a 2 : 1 axis lies midway between two output samples, and an output sample is
+ * the linear interpolation between the two input samples nearest to it (weights 3/4, 1/4;
+ * 9, 3, 3, 1 sixteenths for 2 x 2), the edge sample standing in for a neighbour outside,
+ * rounded to the nearest integer with halves upwards.
+ * pinned by: an impulse (90, 30, 30, 10 of 160 and where they land), a ramp reproduced at the
+ * quarter positions, the edge columns, the rounding of sums of 8 and 7 sixteenths, and the
+ * decoder of an image library on smooth chroma.                                          */
+int oracle_upsample_triangle(const uint8_t *plane, int pitch, int cw, int ch, int fx, int fy,
+                             int w, int h, uint8_t *out);
+
+/* oracle_jpeg_decode with the chroma planes of a subsampled image brought to full
+ * resolution by oracle_upsample_triangle instead of sample replication.                 */
+int oracle_jpeg_decode_smooth(const uint8_t *data, size_t len, int16_t *coef, size_t coef_cap,
+                              uint8_t *rgb, size_t rgb_cap, oracle_info *info);
+
 /* ---- resize + centre crop + normalize ---------------------------------- */
 
 /* Resized size for "short side -> s" (s = 0 keeps the size): the short side

@@ -420,6 +420,75 @@ def test_pillow_decodes_oracle_420_file():
     assert np.abs(mine.astype(int) - rgb.astype(int)).mean() < 6.0
 
 
+# ---------------------------------------------------------------- centred-triangle upsampling
+
+def test_triangle_upsampling_of_an_impulse_has_weights_9_3_3_1():
+    plane = np.zeros((5, 6), dtype=np.uint8)
+    plane[2, 3] = 160
+    out = oracle.upsample_triangle(plane, 2, 2, 12, 10).astype(int)
+    # sample (2, 3) lies between rows 4, 5 and columns 6, 7: nine sixteenths there, three
+    # sixteenths one step away along an axis, one sixteenth at the diagonal
+    expect = np.zeros((10, 12), dtype=int)
+    expect[3:7, 5:9] = np.outer([1, 3, 3, 1], [1, 3, 3, 1]) * 10
+    assert np.array_equal(out, expect)
+    # one axis only: 3/4 and 1/4
+    across = oracle.upsample_triangle(plane, 2, 1, 12, 5).astype(int)
+    assert across[2, 5:9].tolist() == [40, 120, 120, 40] and across.sum() == 320
+    down = oracle.upsample_triangle(plane, 1, 2, 6, 10).astype(int)
+    assert down[3:7, 3].tolist() == [40, 120, 120, 40] and down.sum() == 320
+
+
+def test_triangle_upsampling_reproduces_a_ramp_at_quarter_positions_and_clamps_at_the_edge():
+    # samples 16, 24, 32, ... sit at pixel coordinates 0.5, 2.5, 4.5, ...: slope 4 per pixel
+    ramp = (16 + 8 * np.arange(9)).astype(np.uint8)
+    out = oracle.upsample_triangle(np.tile(ramp, (3, 1)), 2, 1, 18, 3).astype(int)
+    x = np.arange(18)
+    inside = 16 + 4 * (x - 0.5)
+    assert np.array_equal(out[1, 1:17], inside[1:17].astype(int)) and (inside[1:17] % 1 == 0).all()
+    assert out[1, 0] == 16 and out[1, 17] == 80      # beyond the first and last sample: the sample
+    # an odd width owns ceil(w / 2) samples; the last column is a left-hand one
+    odd = oracle.upsample_triangle(np.tile(ramp, (3, 1)), 2, 1, 17, 3).astype(int)
+    assert np.array_equal(odd[1], out[1, :17])
+    # the same down the rows
+    rows = oracle.upsample_triangle(np.tile(ramp[:, None], (1, 4)), 1, 2, 4, 18).astype(int)
+    assert np.array_equal(rows[:, 2], out[1])
+    # constants stay
+    assert (oracle.upsample_triangle(np.full((4, 4), 77, np.uint8), 2, 2, 7, 8) == 77).all()
+
+
+def test_triangle_upsampling_rounds_halves_up():
+    # one sample of 8 among zeros: 72, 24, 8 sixteenths -> 4.5 -> 5, 1.5 -> 2, 0.5 -> 1
+    plane = np.zeros((3, 3), dtype=np.uint8)
+    plane[1, 1] = 8
+    out = oracle.upsample_triangle(plane, 2, 2, 6, 6).astype(int)
+    assert out[1:5, 1:5].tolist() == [[1, 2, 2, 1], [2, 5, 5, 2], [2, 5, 5, 2], [1, 2, 2, 1]]
+    # 7 sixteenths stay below: a sample of 7 gives 63/16 -> 4, 21/16 -> 1, 7/16 -> 0
+    plane[1, 1] = 7
+    out = oracle.upsample_triangle(plane, 2, 2, 6, 6).astype(int)
+    assert out[1:5, 1:5].tolist() == [[0, 1, 1, 0], [1, 4, 4, 1], [1, 4, 4, 1], [0, 1, 1, 0]]
+
+
+@pytest.mark.parametrize("mode", [MODE_420, MODE_422, MODE_440])
+def test_smooth_chroma_decode_is_what_an_image_library_decodes(mode):
+    # an image library interpolates subsampled chroma with the same triangle (its two rounding
+    # offsets alternate, and its IDCT is an integer one): on smooth colour the interpolating
+    # decoder is within a few levels of it everywhere and much closer than the replicating one
+    yy, xx = np.mgrid[0:72, 0:88]
+    rgb = np.stack([40 + 2 * xx, 200 - 2 * yy, 60 + xx + yy], axis=-1).astype(np.uint8)
+    data, _ = oracle.encode(rgb, quality=95, mode=mode, dri=0)
+    theirs = _pil_decode(data).astype(int)
+    coef_s, smooth, _ = oracle.decode(data, smooth_chroma=True)
+    coef_r, plain, _ = oracle.decode(data)
+    assert np.array_equal(coef_s, coef_r)
+    d_smooth, d_plain = np.abs(smooth.astype(int) - theirs), np.abs(plain.astype(int) - theirs)
+    assert d_smooth.max() <= 3 and d_smooth.mean() < 0.5
+    assert d_plain.mean() > 2 * d_smooth.mean()
+    # full-resolution chroma and gray have nothing to interpolate
+    for m in (MODE_444, MODE_GRAY):
+        data, _ = oracle.encode(rgb, quality=90, mode=m, dri=3)
+        assert np.array_equal(oracle.decode(data, smooth_chroma=True)[1], oracle.decode(data)[1])
+
+
 @pytest.mark.parametrize("mode", [MODE_444, MODE_420, MODE_GRAY, MODE_422])
 def test_oracle_decodes_pillow_files(mode):
     import synth
