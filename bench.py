@@ -699,6 +699,7 @@ def main():
         pp.set_timing(True)
         torch.cuda.synchronize()
         host_s[0] = 0.0
+        turn[0] = 0   # handle 0, whose stage times are read, takes the first step
         t0 = time.perf_counter()
         for _ in range(args.steps):
             step(host_input)

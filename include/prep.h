@@ -11,7 +11,7 @@
  *   decode    : ITU-T T.81 baseline sequential DCT, Huffman coded, 8 bit,
  *               1 or 3 components in one interleaved scan, sampling gray /
  *               4:4:4 / 4:2:0 / 4:2:2 / 4:4:0, optional restart intervals; chroma upsampled by
- *               sample replication; JFIF YCbCr -> RGB; samples and RGB values
+ *               sample replication (or interpolated, PREP_FLAG_SMOOTH_CHROMA); JFIF YCbCr -> RGB; samples and RGB values
  *               rounded half up and clamped to 0..255;
  *   resize    : short side -> resize_short, long side floor(resize_short *
  *               long / short); bilinear, pixel centres at half-integers,
@@ -81,8 +81,16 @@ enum { PREP_FILTER_BILINEAR = 0, PREP_FILTER_ANTIALIAS = 1 };
  *   the samples under the triangles of the antialiased one) are converted (the output tensor is the
  *   same; the paper's image unit streams decode into resize and crop without keeping a
  *   decoded image either, section 4.2), and prep_debug_last_rgb returns what the workspace
- *   holds outside those MCUs. */
-enum { PREP_FLAG_TABLES_PER_WORKGROUP = 1, PREP_FLAG_FULL_RGB = 2 };
+ *   holds outside those MCUs.
+ * PREP_FLAG_SMOOTH_CHROMA: a decode variant (flexibility objective of section 4.2).  Subsampled
+ *   chroma (4:2:0, 4:2:2, 4:4:0) is brought to full resolution by linear interpolation between
+ *   sample centres (a centred triangle: a pixel takes 3/4 of the chroma sample it belongs to and
+ *   1/4 of the next one on its side, per subsampled axis; the sample at the image's edge stands
+ *   in for a neighbour outside; rounded to the nearest integer, halves upwards) instead of
+ *   sample replication.  Reconstruction then takes two kernels and a chroma workspace a third
+ *   of the RGB workspace's size; prep_debug_last_region leaves out the outermost chroma sample
+ *   of the converted region where that does not end with the image. */
+enum { PREP_FLAG_TABLES_PER_WORKGROUP = 1, PREP_FLAG_FULL_RGB = 2, PREP_FLAG_SMOOTH_CHROMA = 4 };
 /* luma sampling factors H x V (chroma is 1 x 1): 4:4:4 = 1 x 1, 4:2:0 = 2 x 2, 4:2:2 = 2 x 1,
  * 4:4:0 = 1 x 2; GRAY = one component */
 enum { PREP_SAMPLING_444 = 0, PREP_SAMPLING_420 = 1, PREP_SAMPLING_GRAY = 2, PREP_SAMPLING_422 = 3,

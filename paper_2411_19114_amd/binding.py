@@ -13,6 +13,7 @@ OK, E_INVALID_ARG, E_TOO_LARGE, E_HIP, E_UNSUPPORTED, E_CORRUPT, E_NOMEM = 0, -1
 F32, F16, U8_NHWC = 0, 1, 2
 FLAG_TABLES_PER_WORKGROUP = 1
 FLAG_FULL_RGB = 2
+FLAG_SMOOTH_CHROMA = 4
 FILTER_BILINEAR, FILTER_ANTIALIAS = 0, 1
 
 

@@ -98,6 +98,7 @@ struct Plan {                         // what one call will run
     uint32_t n_tables = 0;     // distinct sets of Huffman tables (<= the handle's table slots)
     uint64_t n_blocks = 0;
     uint64_t rgb_bytes = 0;
+    uint32_t max_region_pixels = 0;  // most pixels in the reconstructed region of one image
 };
 
 }  // namespace
@@ -108,6 +109,7 @@ struct prep_handle {
     hipStream_t copy_stream = nullptr;
     int16_t *d_coef = nullptr;
     uint8_t *d_rgb = nullptr;
+    uint8_t *d_chroma = nullptr;  // PREP_FLAG_SMOOTH_CHROMA: chroma planes between the two reconstruction kernels
     uint8_t *d_tables = nullptr;  // table_slots expanded Huffman table sets
     uint32_t table_slots = 0;
     std::vector<uint32_t> table_rep;   // image that owns each slot of this call
@@ -259,6 +261,13 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
                 const auto span = params->filter == PREP_FILTER_ANTIALIAS ? window_span : tap_span;
                 span(Z.off_x, Z.scale_x, params->crop_w, I.width, &x_lo, &x_hi);
                 span(Z.off_y, Z.scale_y, params->crop_h, I.height, &y_lo, &y_hi);
+                if (h->cfg.flags & PREP_FLAG_SMOOTH_CHROMA) {
+                    // an interpolated pixel also reads the chroma sample next to its own
+                    x_lo = std::max(x_lo - luma_h(I.sampling), 0);
+                    x_hi = std::min(x_hi + luma_h(I.sampling), (int)I.width - 1);
+                    y_lo = std::max(y_lo - luma_v(I.sampling), 0);
+                    y_hi = std::min(y_hi + luma_v(I.sampling), (int)I.height - 1);
+                }
             }
             R.roi_row0 = (uint16_t)(y_lo / mcu_h);
             R.roi_rows = (uint16_t)(y_hi / mcu_h - y_lo / mcu_h + 1);
@@ -270,6 +279,10 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
             P.n_blocks += R.n_blocks;
             P.rgb_bytes += ((uint64_t)R.rgb_pitch * rows + kRgbSlack + kRgbAlign - 1) / kRgbAlign * kRgbAlign;
             P.n_groups += (uint32_t)R.roi_gcols * R.roi_rows;
+            const uint32_t region_cols = std::min<uint32_t>((uint32_t)(R.roi_gcol0 + R.roi_gcols) * (uint32_t)recon_mcus_per_group(R.sampling), R.mcu_cols) -
+                                         (uint32_t)R.roi_gcol0 * (uint32_t)recon_mcus_per_group(R.sampling);
+            P.max_region_pixels = std::max<uint32_t>(P.max_region_pixels,
+                                                     region_cols * 8u * (uint32_t)luma_h(R.sampling) * (uint32_t)R.roi_rows * 8u * (uint32_t)luma_v(R.sampling));
         }
         P.n_windows += R.n_windows;
     }
@@ -373,7 +386,7 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
         if (timing) HIP_TRY(hipEventRecord(ev[2], stream));
     }
     launch_reconstruct(d_bits, s->d_recs, reinterpret_cast<const uint32_t *>(s->d_recs + n), n, P.recon_wgs,
-                       P.groups_per_wg, h->d_coef, h->d_rgb, stream);
+                       P.groups_per_wg, h->d_coef, h->d_rgb, h->d_chroma, P.max_region_pixels, stream);
     if (timing) HIP_TRY(hipEventRecord(ev[3], stream));
     launch_resize_normalize(h->d_rgb, s->d_rr, h->d_status, n, params->crop_h, params->crop_w,
                             params->out_dtype, params->filter, s->h_rr, params->mean,
@@ -399,7 +412,7 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     if (!cfg || cfg->max_batch < 1 || cfg->max_batch > 65535 || cfg->max_width < 1 ||
         cfg->max_height < 1 || cfg->max_width > 65535 || cfg->max_height > 65535 ||
         cfg->max_bitstream_bytes < 1 || cfg->max_bitstream_bytes > 0x7FFF0000ull ||
-        (cfg->flags & ~(uint32_t)(PREP_FLAG_TABLES_PER_WORKGROUP | PREP_FLAG_FULL_RGB)) != 0)
+        (cfg->flags & ~(uint32_t)(PREP_FLAG_TABLES_PER_WORKGROUP | PREP_FLAG_FULL_RGB | PREP_FLAG_SMOOTH_CHROMA)) != 0)
         return PREP_E_INVALID_ARG;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) {
@@ -428,6 +441,8 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     // between the decoder's two steps
     ok = ok && hipMalloc((void **)&h->d_coef, h->cap_blocks * 130 + 16) == hipSuccess;
     ok = ok && hipMalloc((void **)&h->d_rgb, h->cap_rgb) == hipSuccess;
+    if (cfg->flags & PREP_FLAG_SMOOTH_CHROMA)
+        ok = ok && hipMalloc((void **)&h->d_chroma, h->cap_rgb / 3 + 16) == hipSuccess;
     h->table_slots = (cfg->flags & PREP_FLAG_TABLES_PER_WORKGROUP) ? 0u : std::min<uint32_t>((uint32_t)n, kMaxTableSlots);
     h->table_rep.reserve(h->table_slots);
     h->table_hash.assign(2 * (size_t)kMaxTableSlots, 0u);
@@ -466,6 +481,7 @@ int prep_destroy(prep_handle *h)
     (void)hipDeviceSynchronize();
     (void)hipFree(h->d_coef);
     (void)hipFree(h->d_rgb);
+    (void)hipFree(h->d_chroma);
     (void)hipFree(h->d_tables);
     (void)hipFree(h->d_status);
     (void)hipFree(h->d_win_count);
@@ -645,6 +661,15 @@ int prep_debug_last_region(prep_handle *h, int32_t image, int32_t rect[4])
     rect[1] = std::min<int>(R.roi_row0 * mcu_h, R.height);
     rect[2] = std::min<int>((R.roi_gcol0 + R.roi_gcols) * group_px, R.width);
     rect[3] = std::min<int>((R.roi_row0 + R.roi_rows) * mcu_h, R.height);
+    if ((h->cfg.flags & PREP_FLAG_SMOOTH_CHROMA) && R.sampling != PREP_SAMPLING_GRAY) {
+        // interpolated chroma is exact up to the last chroma sample but one of the region,
+        // except where the region ends with the image
+        const int fx = luma_h(R.sampling) > 1 ? luma_h(R.sampling) : 0, fy = luma_v(R.sampling) > 1 ? luma_v(R.sampling) : 0;
+        if (rect[0] > 0) rect[0] += fx;
+        if (rect[1] > 0) rect[1] += fy;
+        if ((R.roi_gcol0 + R.roi_gcols) * recon_mcus_per_group(R.sampling) < R.mcu_cols) rect[2] -= fx;
+        if (R.roi_row0 + R.roi_rows < R.mcu_rows) rect[3] -= fy;
+    }
     return PREP_OK;
 }
 

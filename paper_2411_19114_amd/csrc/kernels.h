@@ -26,9 +26,12 @@ void launch_decode_entropy(const uint8_t *bits, const ImageRec *recs, int n_imag
                            hipStream_t stream);
 
 // reconstruct.hip
+// chroma: nullptr = subsampled chroma is replicated; else the workspace of the interpolating
+// variant (a third of the RGB workspace's size), and max_region_pixels = the most pixels that
+// the reconstructed region of one image holds (a multiple of four).
 void launch_reconstruct(const uint8_t *bits, const ImageRec *recs, const uint32_t *group0, int n_images,
                         uint32_t n_workgroups, uint32_t groups_per_wg, const int16_t *coef, uint8_t *rgb,
-                        hipStream_t stream);
+                        uint8_t *chroma, uint32_t max_region_pixels, hipStream_t stream);
 
 // resize.hip
 // host_rr: the host's copy of rr (the records of all n_images must be initialised); read for

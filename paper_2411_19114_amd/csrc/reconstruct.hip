@@ -2,7 +2,8 @@
 //
 // The second half of the "Decode" functional unit (PREBA section 4.2, Table 1):
 // T.81 A.3.4 (dequantisation, zig-zag), A.3.3 (IDCT), A.3.1 (level shift),
-// sample replication for subsampled chroma, JFIF colour transform.  One
+// sample replication for subsampled chroma (or, as a variant, interpolation under a centred
+// triangle by a second kernel), JFIF colour transform.  One
 // workgroup handles a run of MCUs of one MCU row: coefficients are read once
 // (128 B per block), everything else lives in LDS, and RGB leaves as aligned
 // 32-bit stores covering the whole MCU grid (the row pitch includes padding).
@@ -169,6 +170,23 @@ static_assert(kReconBlocks * kRawPitch * sizeof(int16_t) <=
                   sizeof(uint32_t) * (16 * kLumaPitch / 4 + 2 * 8 * kChromaPitch / 4),
               "the raw coefficients fit in the sample planes");
 
+// Where the interpolating variant keeps an image's chroma samples between its two kernels:
+// two planes of (8 mcu_cols) x (8 mcu_rows) bytes, Cb then Cr, in a workspace that mirrors the
+// RGB workspace at a third of its offsets (a subsampled image has at most half as many chroma
+// samples as pixels, and its RGB rows take three bytes per pixel).
+struct ChromaPlanes {
+    size_t off, plane;
+    uint32_t pitch;
+};
+__device__ inline ChromaPlanes chroma_planes_of(const ImageRec &R)
+{
+    ChromaPlanes c;
+    c.off = (size_t)(R.rgb_off / 12u) * 4u;
+    c.pitch = (uint32_t)R.mcu_cols * 8u;
+    c.plane = (size_t)c.pitch * R.mcu_rows * 8u;
+    return c;
+}
+
 // The work of one workgroup: groups gi0 .. gi0 + n_groups - 1 of one image (a group is a run
 // of MCUs of one MCU row, numbered row by row), one after the other.  The sampling mode is
 // a compile-time constant so that every block / pixel index is divided by constants.
@@ -176,11 +194,16 @@ static_assert(kReconBlocks * kRawPitch * sizeof(int16_t) <=
 // A group's time is mostly the latency of its coefficient loads, and LDS limits a compute
 // unit to six workgroups, so the coefficients of the next group are fetched into registers
 // while the current one is transformed and converted.
-template <int sampling>
+//
+// kPlanes (the interpolating variant, subsampled images only): the colour step is left to
+// interpolate_chroma_rgb.  The group writes its luma as gray pixels and its chroma samples
+// into the image's two chroma planes in chroma_all.
+template <int sampling, bool kPlanes>
 __device__ __forceinline__ void reconstruct_groups(ReconShared &S, const uint8_t *__restrict__ bits,
                                                    const ImageRec &R, uint32_t gi0, uint32_t n_groups,
                                                    const int16_t *__restrict__ coef_all,
-                                                   uint8_t *__restrict__ rgb_all)
+                                                   uint8_t *__restrict__ rgb_all,
+                                                   uint8_t *__restrict__ chroma_all)
 {
     double *tile = S.tile;
     int32_t (*qi)[64] = S.qi;
@@ -278,12 +301,23 @@ __device__ __forceinline__ void reconstruct_groups(ReconShared &S, const uint8_t
         const int rows = 8 * vs, width = gcount * 8 * hs, quads = width >> 2;
         uint8_t *dst0 = rgb_all + R.rgb_off + (size_t)mrow * rows * R.rgb_pitch +
                         (size_t)mcu_x0 * 8 * hs * 3;
-        if (sampling == PREP_SAMPLING_GRAY) {
+        if (sampling == PREP_SAMPLING_GRAY || kPlanes) {
             // an item is 4 pixels of one row
             const int items = rows * quads;
             for (int it = tid; it < items; it += kReconThreads) {
                 const int row = it / quads, q = it - row * quads;
                 store_gray4(dst0 + (size_t)row * R.rgb_pitch + q * 12, luma[(row * kLumaPitch) / 4 + q]);
+            }
+            if (kPlanes) {
+                // the group's 8 rows of gcount * 8 samples of each chroma plane, a word per item
+                const ChromaPlanes cp = chroma_planes_of(R);
+                const int words = gcount * 2;
+                for (int it = tid; it < 2 * 8 * words; it += kReconThreads) {
+                    const int c = it / (8 * words), r = (it / words) & 7, wd = it % words;
+                    uint8_t *dst = chroma_all + cp.off + (size_t)c * cp.plane +
+                                   (size_t)(mrow * 8u + (uint32_t)r) * cp.pitch + mcu_x0 * 8u + (uint32_t)wd * 4u;
+                    *reinterpret_cast<uint32_t *>(dst) = chroma[c][(r * kChromaPitch) / 4 + wd];
+                }
             }
         } else {
             // an item is 4 pixels of vs rows: the pixels that 4 / hs chroma samples of one chroma
@@ -321,10 +355,11 @@ __device__ __forceinline__ void reconstruct_groups(ReconShared &S, const uint8_t
 // group0[i] = first workgroup of image i (ascending); a workgroup takes groups_per_wg
 // consecutive groups of its image.  The image of workgroup wg is the last one whose entry
 // does not exceed wg: every lane tests one entry and the hits are counted.
+template <bool kPlanes>
 __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
     const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs,
     const uint32_t *__restrict__ group0, int n_images, uint32_t groups_per_wg,
-    const int16_t *__restrict__ coef_all, uint8_t *__restrict__ rgb_all)
+    const int16_t *__restrict__ coef_all, uint8_t *__restrict__ rgb_all, uint8_t *__restrict__ chroma_all)
 {
     __shared__ ReconShared S;
     __shared__ uint32_t s_hits[kReconThreads / 64];
@@ -346,24 +381,104 @@ __global__ __launch_bounds__(kReconThreads) void reconstruct_rgb(
     if (gi0 >= total) return;
     const uint32_t n = min(groups_per_wg, total - gi0);
     if (R.sampling == PREP_SAMPLING_420)
-        reconstruct_groups<PREP_SAMPLING_420>(S, bits, R, gi0, n, coef_all, rgb_all);
+        reconstruct_groups<PREP_SAMPLING_420, kPlanes>(S, bits, R, gi0, n, coef_all, rgb_all, chroma_all);
     else if (R.sampling == PREP_SAMPLING_444)
-        reconstruct_groups<PREP_SAMPLING_444>(S, bits, R, gi0, n, coef_all, rgb_all);
+        reconstruct_groups<PREP_SAMPLING_444, false>(S, bits, R, gi0, n, coef_all, rgb_all, chroma_all);
     else if (R.sampling == PREP_SAMPLING_422)
-        reconstruct_groups<PREP_SAMPLING_422>(S, bits, R, gi0, n, coef_all, rgb_all);
+        reconstruct_groups<PREP_SAMPLING_422, kPlanes>(S, bits, R, gi0, n, coef_all, rgb_all, chroma_all);
     else if (R.sampling == PREP_SAMPLING_440)
-        reconstruct_groups<PREP_SAMPLING_440>(S, bits, R, gi0, n, coef_all, rgb_all);
+        reconstruct_groups<PREP_SAMPLING_440, kPlanes>(S, bits, R, gi0, n, coef_all, rgb_all, chroma_all);
     else
-        reconstruct_groups<PREP_SAMPLING_GRAY>(S, bits, R, gi0, n, coef_all, rgb_all);
+        reconstruct_groups<PREP_SAMPLING_GRAY, false>(S, bits, R, gi0, n, coef_all, rgb_all, chroma_all);
+}
+
+// The second kernel of the interpolating variant (a decode variant under the flexibility
+// objective of PREBA section 4.2): subsampled chroma brought to full resolution under a centred
+// triangle, then the colour transform.  A chroma sample of a 2:1 axis lies midway between two
+// pixels; a pixel takes 3/4 of the sample it belongs to and 1/4 of the next one on its side
+// (9, 3, 3, 1 sixteenths over two axes), rounded to the nearest integer with halves upwards,
+// and a neighbour outside the image's samples is the sample at the edge.  Reads the gray
+// pixels and the chroma planes that reconstruct_rgb<true> left, and writes the pixels in
+// place.  A thread takes four adjacent pixels of one row of the image's reconstructed region;
+// neighbours outside that region are clamped to it, so its outermost pixels are exact only
+// where the region ends with the image.
+__global__ __launch_bounds__(kReconThreads) void interpolate_chroma_rgb(
+    const ImageRec *__restrict__ recs, const uint8_t *__restrict__ chroma_all, uint8_t *__restrict__ rgb_all)
+{
+    const ImageRec &R = recs[blockIdx.y];
+    if (R.status != PREP_OK) return;
+    const int fx = luma_h(R.sampling), fy = luma_v(R.sampling);
+    if (R.sampling == PREP_SAMPLING_GRAY || fx * fy == 1) return;
+    const int per_group = recon_mcus_per_group(R.sampling);
+    // the region in pixels and in chroma samples
+    const int x_lo = R.roi_gcol0 * per_group * 8 * fx;
+    const int x_hi = min((R.roi_gcol0 + R.roi_gcols) * per_group, (int)R.mcu_cols) * 8 * fx;
+    const int y_lo = R.roi_row0 * 8 * fy, y_hi = (R.roi_row0 + R.roi_rows) * 8 * fy;
+    const int quads = (x_hi - x_lo) >> 2;
+    const int item = blockIdx.x * kReconThreads + threadIdx.x;
+    if (item >= quads * (y_hi - y_lo)) return;
+    const int y = y_lo + item / quads, x0 = x_lo + (item % quads) * 4;
+    const int cx_lo = x_lo / fx, cx_hi = min(x_hi / fx, ((int)R.width + fx - 1) / fx) - 1;
+    const int cy_lo = y_lo / fy, cy_hi = min(y_hi / fy, ((int)R.height + fy - 1) / fy) - 1;
+    const ChromaPlanes cp = chroma_planes_of(R);
+    // rows: the sample row the pixel belongs to, the next one on its side, and the nearer row's
+    // weight in quarters
+    const int y_near = min(y / fy, cy_hi);
+    int y_far = y_near, wy = 4;
+    if (fy == 2) { y_far = min(max((y & 1) ? y / 2 + 1 : y / 2 - 1, cy_lo), cy_hi); wy = 3; }
+    uint32_t up[2][4];  // the four pixels' chroma, Cb and Cr
+#pragma unroll
+    for (int c = 0; c < 2; c++) {
+        const uint8_t *near = chroma_all + cp.off + (size_t)c * cp.plane + (size_t)y_near * cp.pitch;
+        const uint8_t *far = chroma_all + cp.off + (size_t)c * cp.plane + (size_t)y_far * cp.pitch;
+        // quarters along the row, of the nearer and of the farther sample row
+        int hn[4], hf[4];
+        if (fx == 2) {
+            const int c0 = x0 / 2;
+            int sn[4], sf[4];  // samples c0 - 1 .. c0 + 2
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                const int cx = min(max(c0 - 1 + k, cx_lo), cx_hi);
+                sn[k] = near[cx];
+                sf[k] = far[cx];
+            }
+            hn[0] = 3 * sn[1] + sn[0]; hn[1] = 3 * sn[1] + sn[2]; hn[2] = 3 * sn[2] + sn[1]; hn[3] = 3 * sn[2] + sn[3];
+            hf[0] = 3 * sf[1] + sf[0]; hf[1] = 3 * sf[1] + sf[2]; hf[2] = 3 * sf[2] + sf[1]; hf[3] = 3 * sf[2] + sf[3];
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                const int cx = min(x0 + k, cx_hi);
+                hn[k] = 4 * near[cx];
+                hf[k] = 4 * far[cx];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; k++) up[c][k] = (uint32_t)(wy * hn[k] + (4 - wy) * hf[k] + 8) >> 4;
+    }
+    uint8_t *px = rgb_all + R.rgb_off + (size_t)y * R.rgb_pitch + (size_t)x0 * 3;
+    const uint32_t *g = reinterpret_cast<const uint32_t *>(px);  // gray pixels: Y Y Y Y Y Y ...
+    const uint32_t g0 = g[0], g1 = g[1], g2 = g[2];
+    const uint32_t y4 = (g0 & 255u) | ((g0 >> 24) << 8) | (((g1 >> 16) & 255u) << 16) | (((g2 >> 8) & 255u) << 24);
+    store_rgb4(px, y4, chroma_terms(up[0][0], up[1][0]), chroma_terms(up[0][1], up[1][1]),
+               chroma_terms(up[0][2], up[1][2]), chroma_terms(up[0][3], up[1][3]));
 }
 
 void launch_reconstruct(const uint8_t *bits, const ImageRec *recs, const uint32_t *group0, int n_images,
                         uint32_t n_workgroups, uint32_t groups_per_wg, const int16_t *coef, uint8_t *rgb,
-                        hipStream_t stream)
+                        uint8_t *chroma, uint32_t max_region_pixels, hipStream_t stream)
 {
     if (n_workgroups == 0) return;
-    hipLaunchKernelGGL(reconstruct_rgb, dim3(n_workgroups), dim3(kReconThreads), 0, stream, bits, recs,
-                       group0, n_images, groups_per_wg, coef, rgb);
+    if (!chroma) {
+        hipLaunchKernelGGL(reconstruct_rgb<false>, dim3(n_workgroups), dim3(kReconThreads), 0, stream, bits,
+                           recs, group0, n_images, groups_per_wg, coef, rgb, chroma);
+        return;
+    }
+    hipLaunchKernelGGL(reconstruct_rgb<true>, dim3(n_workgroups), dim3(kReconThreads), 0, stream, bits, recs,
+                       group0, n_images, groups_per_wg, coef, rgb, chroma);
+    const uint32_t items = max_region_pixels / 4;  // four pixels per thread
+    if (items)
+        hipLaunchKernelGGL(interpolate_chroma_rgb, dim3((items + kReconThreads - 1) / kReconThreads, n_images),
+                           dim3(kReconThreads), 0, stream, recs, chroma, rgb);
 }
 
 }  // namespace prep

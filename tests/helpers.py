@@ -68,10 +68,10 @@ def rgb_in_region(rect, got_rgb, ref_rgb, footprint):
     return np.abs(got_rgb[y0:y1, x0:x1].astype(np.int32) - ref_rgb[y0:y1, x0:x1].astype(np.int32))
 
 
-def oracle_batch(streams, resize_short, crop_h, crop_w, workers=8, antialias=False):
+def oracle_batch(streams, resize_short, crop_h, crop_w, workers=8, antialias=False, smooth_chroma=False):
     """[(coef, rgb, info, tensor float64)] for every stream, computed by the oracle."""
     def one(s):
-        coef, rgb, info = oracle.decode(s)
+        coef, rgb, info = oracle.decode(s, smooth_chroma=smooth_chroma)
         ten = oracle.preprocess(rgb, resize_short, crop_h, crop_w, MEAN, STD, antialias)
         return coef, rgb, info, ten
     with ThreadPoolExecutor(workers) as ex:
@@ -100,10 +100,11 @@ def run_gpu(pp, streams, resize_short, crop_h, crop_w, out_dtype, resident=False
 
 
 def check_against_oracle(pp, streams, resize_short, crop_h, crop_w, out_dtype, resident=False,
-                         check_intermediates=True, antialias=False):
+                         check_intermediates=True, antialias=False, smooth_chroma=False):
+    """smooth_chroma: pp was created with FLAG_SMOOTH_CHROMA, and the oracle interpolates too."""
     status, got = run_gpu(pp, streams, resize_short, crop_h, crop_w, out_dtype, resident, antialias)
     assert status == [0] * len(streams), status
-    ref = oracle_batch(streams, resize_short, crop_h, crop_w, antialias=antialias)
+    ref = oracle_batch(streams, resize_short, crop_h, crop_w, antialias=antialias, smooth_chroma=smooth_chroma)
     footprint = window_footprint if antialias else tap_footprint
     n_values = n_exact = 0
     for i, (coef, rgb, info, ten) in enumerate(ref):

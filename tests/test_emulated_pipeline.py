@@ -20,7 +20,7 @@ def _img(seed, w, h, sigma=12.0):
     return synth.gradient_noise_image(np.random.default_rng(seed), w, h, sigma)
 
 
-def _check(streams, rs, ch, cw, dt, expect_status=None, flags=0, antialias=False):
+def _check(streams, rs, ch, cw, dt, expect_status=None, flags=0, antialias=False, smooth_chroma=False):
     per, ten = emul.run(streams, rs, ch, cw, dt, MEAN, STD, flags=flags, antialias=antialias)
     footprint = helpers.window_footprint if antialias else helpers.tap_footprint
     for i, s in enumerate(streams):
@@ -30,7 +30,7 @@ def _check(streams, rs, ch, cw, dt, expect_status=None, flags=0, antialias=False
             assert (ten[i] == 0).all()
             continue
         assert status == 0, f"image {i}: status {status}"
-        c0, r0, info = oracle.decode(s)
+        c0, r0, info = oracle.decode(s, smooth_chroma=smooth_chroma)
         assert np.array_equal(coef, c0), f"image {i}: coefficients differ"
         if flags & 2:
             assert rect == (0, 0, info.width, info.height)
@@ -69,6 +69,16 @@ def test_antialiased_resize_reducing_enlarging_and_at_the_edges():
     _check(streams, 40, 24, 30, "f16", antialias=True)
     _check(streams[:2], 150, 120, 150, "f32", antialias=True)
     _check(streams[2:], 0, 64, 97, "f32", antialias=True)
+
+
+def test_interpolated_chroma_in_the_crop_region_and_over_whole_images():
+    streams = []
+    for k, (w, h) in enumerate([(1, 1), (17, 33), (161, 100), (75, 131)]):
+        for mode in (MODE_420, MODE_422, MODE_440, MODE_444):
+            streams.append(oracle.encode(_img(70 + k, w, h), 90, mode, dri=(0, 2)[k % 2])[0])
+    _check(streams, 0, 1, 1, "f32", flags=4 | 2, smooth_chroma=True)
+    _check(streams[8:], 60, 40, 48, "f32", flags=4, smooth_chroma=True)
+    _check(streams[8:12], 0, 100, 161, "f16", flags=4, smooth_chroma=True)
 
 
 def test_eight_bit_interleaved_output_of_both_filters():

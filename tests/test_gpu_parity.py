@@ -69,6 +69,32 @@ def test_422_and_440_files_resized_and_cropped(pp):
     check_against_oracle(pp, streams, 256, 224, 224, "f16")
 
 
+@pytest.mark.parametrize("flags", [4, 4 | 2], ids=["crop-region", "full-rgb"])
+def test_interpolated_chroma(prep, flags):
+    # the decode variant that interpolates subsampled chroma under a centred triangle: odd
+    # sizes (the last chroma sample serves one pixel), one-MCU images, crop windows inside the
+    # image (the region's edge is not the image's) and at its edge, both resize filters
+    assert prep.FLAG_SMOOTH_CHROMA == 4
+    h = prep.Preprocessor(device=0, max_batch=32, max_width=700, max_height=520,
+                          max_bitstream_bytes=8 << 20, flags=flags)
+    try:
+        small = []
+        for k, (w, ht) in enumerate([(1, 1), (7, 9), (17, 33), (64, 48), (301, 251)]):
+            for mode in (MODE_420, MODE_422, MODE_440, MODE_444, MODE_GRAY):
+                small.append(oracle.encode(_img(900 + k + mode, w, ht), 88, mode, dri=(0, 1, 3)[k % 3])[0])
+        check_against_oracle(h, small, 0, 1, 1, "f32", smooth_chroma=True)
+        photos = []
+        for k, (w, ht) in enumerate([(333, 250), (640, 427), (500, 375), (259, 480)]):
+            rgb = _img(920 + k, w, ht, sigma=10.0)
+            photos.append(synth.encode_jpeg(rgb, 90, synth.MODE_420, restart_blocks=8 if k else 0))
+            photos.append(oracle.encode(rgb, 90, (MODE_422, MODE_440)[k % 2], dri=5)[0])
+        check_against_oracle(h, photos, 256, 224, 224, "f16", smooth_chroma=True)
+        check_against_oracle(h, photos, 256, 200, 256, "f32", smooth_chroma=True, antialias=True)
+        check_against_oracle(h, photos[:4], 0, 250, 259, "f32", smooth_chroma=True)
+    finally:
+        h.close()
+
+
 def test_upscaling_small_images(pp):
     streams = [oracle.encode(_img(300 + k, w, h), 90, MODE_420, 0)[0]
                for k, (w, h) in enumerate([(1, 1), (7, 9), (40, 23), (23, 40)])]
