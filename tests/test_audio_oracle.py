@@ -43,6 +43,55 @@ def test_resampling_special_cases():
                        2 * audio.resample(a, 48000, 16000) - 3 * audio.resample(b, 48000, 16000))
 
 
+def _series_sin_cos(x, terms=40):
+    """sin and cos of the exact rational x by their power series in exact rational arithmetic."""
+    from fractions import Fraction
+    s, c, t = Fraction(0), Fraction(0), Fraction(1)
+    for k in range(terms):
+        if k % 2 == 0:
+            c += t if k % 4 == 0 else -t
+        else:
+            s += t if k % 4 == 1 else -t
+        t = t * x / (k + 1)
+    return s, c
+
+
+@pytest.mark.parametrize("rates,n0", [((44100, 16000), 300), ((8000, 16000), 40), ((48000, 16000), 123)])
+def test_resampling_an_impulse_gives_the_kernel_itself(rates, n0):
+    # a unit impulse at input sample n0 comes out as h(n0 / rate_in - m / rate_out): evaluated
+    # here in exact rational arithmetic (power series of sin and cos, pi to 40 digits), so the
+    # band edge, the gain, the time alignment of the two grids and the extent of the window
+    # are all held to rounding error
+    from fractions import Fraction
+    rin, rout = rates
+    pi = Fraction("3.1415926535897932384626433832795028841972")
+    x = np.zeros(2 * n0 + 1)
+    x[n0] = 1.0
+    y = audio.resample(x, rin, rout)
+    band = Fraction(99, 100) * min(rin, rout)      # 0.99 of the lower rate
+    zeros = 6                                        # zero crossings kept each side
+    worst, inside = 0.0, 0
+    for m in range(len(y)):
+        u = band * (Fraction(n0, rin) - Fraction(m, rout))
+        if abs(u) >= zeros:
+            assert y[m] == 0.0
+            continue
+        inside += 1
+        if u == 0:
+            sinc = Fraction(1)
+        else:
+            # reduce pi u to within pi of zero: sin(a + k pi) = (-1)^k sin(a)
+            k = round(u)
+            sn, _ = _series_sin_cos(pi * (u - k))
+            sinc = (-sn if k % 2 else sn) / (pi * u)
+        _, cw = _series_sin_cos(pi * u / (2 * zeros))
+        want = band / rin * sinc * cw * cw
+        worst = max(worst, abs(y[m] - float(want)))
+    assert worst < 1e-12
+    # the window spans 2 * 6 / (0.99 min(rate)) seconds of output samples
+    assert abs(inside - 2 * zeros * rout / float(band)) <= 1
+
+
 def test_resampling_agrees_with_a_polyphase_resampler_on_band_limited_noise():
     rng = np.random.default_rng(2)
     spec = np.zeros(2049, dtype=complex)
