@@ -89,8 +89,15 @@ enum { PREP_FILTER_BILINEAR = 0, PREP_FILTER_ANTIALIAS = 1 };
  *   in for a neighbour outside; rounded to the nearest integer, halves upwards) instead of
  *   sample replication.  Reconstruction then takes two kernels and a chroma workspace a third
  *   of the RGB workspace's size; prep_debug_last_region leaves out the outermost chroma sample
- *   of the converted region where that does not end with the image. */
-enum { PREP_FLAG_TABLES_PER_WORKGROUP = 1, PREP_FLAG_FULL_RGB = 2, PREP_FLAG_SMOOTH_CHROMA = 4 };
+ *   of the converted region where that does not end with the image.
+ * PREP_FLAG_LARGE_WINDOWS: a call with little entropy-coded data (1.5 MiB) is normally cut
+ *   into more and smaller pieces for the entropy decoder, which then finds the decoder states
+ *   inside restart intervals by hypotheses over the block's place in the MCU, so that the
+ *   single-input and small-batch latency (a design objective of section 4.2) is not that of
+ *   one lane walking a restart interval; with this flag such a call is decoded like a large
+ *   one (same results; kept for checking that path on small inputs). */
+enum { PREP_FLAG_TABLES_PER_WORKGROUP = 1, PREP_FLAG_FULL_RGB = 2, PREP_FLAG_SMOOTH_CHROMA = 4,
+       PREP_FLAG_LARGE_WINDOWS = 8 };
 /* luma sampling factors H x V (chroma is 1 x 1): 4:4:4 = 1 x 1, 4:2:0 = 2 x 2, 4:2:2 = 2 x 1,
  * 4:4:0 = 1 x 2; GRAY = one component */
 enum { PREP_SAMPLING_444 = 0, PREP_SAMPLING_420 = 1, PREP_SAMPLING_GRAY = 2, PREP_SAMPLING_422 = 3,

@@ -14,6 +14,7 @@ F32, F16, U8_NHWC = 0, 1, 2
 FLAG_TABLES_PER_WORKGROUP = 1
 FLAG_FULL_RGB = 2
 FLAG_SMOOTH_CHROMA = 4
+FLAG_LARGE_WINDOWS = 8
 FILTER_BILINEAR, FILTER_ANTIALIAS = 0, 1
 
 

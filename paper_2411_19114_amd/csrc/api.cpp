@@ -99,6 +99,7 @@ struct Plan {                         // what one call will run
     uint64_t n_blocks = 0;
     uint64_t rgb_bytes = 0;
     uint32_t max_region_pixels = 0;  // most pixels in the reconstructed region of one image
+    uint32_t window_bytes = kWindowBytes;  // raw bytes between the decoder's workgroup starts
 };
 
 }  // namespace
@@ -209,11 +210,18 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
     h->table_rep.clear();
     std::fill(h->table_hash.begin(), h->table_hash.end(), 0u);
     Plan P;
+    uint64_t entropy_total = 0;
     for (int32_t i = 0; i < n; i++) {
         if (offsets[i + 1] < offsets[i]) return PREP_E_INVALID_ARG;
-        const uint64_t len = offsets[i + 1] - offsets[i];
         ParsedImage &pi = h->parsed[(size_t)i];
-        parse_image(bits + offsets[i], len, &pi);
+        parse_image(bits + offsets[i], offsets[i + 1] - offsets[i], &pi);
+        if (pi.info.status == PREP_OK) entropy_total += pi.info.entropy_bytes;
+    }
+    // a call with little data is cut into small windows, for the decoder variant that fills
+    // the chip with hypotheses instead of walking whole restart intervals lane by lane
+    if (entropy_total <= kSmallCallBytes && !(h->cfg.flags & PREP_FLAG_LARGE_WINDOWS)) P.window_bytes = kSmallWindowBytes;
+    for (int32_t i = 0; i < n; i++) {
+        ParsedImage &pi = h->parsed[(size_t)i];
         prep_image_info &I = pi.info;
         ImageRec &R = h->recs[(size_t)i];
         memset(&R, 0, sizeof R);
@@ -233,7 +241,7 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
             R.entropy_rel = (uint32_t)I.entropy_offset;
             R.entropy_len = (uint32_t)I.entropy_bytes;
             R.n_blocks = (uint32_t)((uint64_t)I.mcu_cols * I.mcu_rows * I.blocks_per_mcu);
-            R.n_windows = (uint32_t)((I.entropy_bytes + kWindowBytes - 1) / kWindowBytes);
+            R.n_windows = (uint32_t)((I.entropy_bytes + P.window_bytes - 1) / P.window_bytes);
             if (R.n_windows == 0) R.n_windows = 1;
             R.rgb_pitch = (uint32_t)I.mcu_cols * 8u * hs * 3u;
             for (int t = 0; t < 4; t++) { R.dht_off[t] = pi.dht_off[t]; R.dht_nval[t] = pi.dht_nval[t]; }
@@ -377,12 +385,13 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
         if (timing) { HIP_TRY(hipEventRecord(ev[1], stream)); HIP_TRY(hipEventRecord(ev[2], stream)); }
     } else {
         // (P.n_windows >= n > 0: the scan also sets every image's status)
-        launch_scan_restart_markers(d_bits, s->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
+        launch_scan_restart_markers(d_bits, s->d_recs, n, P.n_windows, P.window_bytes, h->d_win_count, h->d_win_first,
                                     h->d_status, reinterpret_cast<const uint32_t *>(s->d_recs + n) + n,
                                     P.n_tables, h->d_tables, stream);
         if (timing) HIP_TRY(hipEventRecord(ev[1], stream));
         launch_decode_entropy(d_bits, s->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
-                              h->d_coef, (uint32_t)(h->cap_blocks * 64), h->d_status, h->d_tables, stream);
+                              h->d_coef, (uint32_t)(h->cap_blocks * 64), h->d_status, h->d_tables,
+                              P.window_bytes == (uint32_t)kSmallWindowBytes, stream);
         if (timing) HIP_TRY(hipEventRecord(ev[2], stream));
     }
     launch_reconstruct(d_bits, s->d_recs, reinterpret_cast<const uint32_t *>(s->d_recs + n), n, P.recon_wgs,
@@ -412,7 +421,7 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     if (!cfg || cfg->max_batch < 1 || cfg->max_batch > 65535 || cfg->max_width < 1 ||
         cfg->max_height < 1 || cfg->max_width > 65535 || cfg->max_height > 65535 ||
         cfg->max_bitstream_bytes < 1 || cfg->max_bitstream_bytes > 0x7FFF0000ull ||
-        (cfg->flags & ~(uint32_t)(PREP_FLAG_TABLES_PER_WORKGROUP | PREP_FLAG_FULL_RGB | PREP_FLAG_SMOOTH_CHROMA)) != 0)
+        (cfg->flags & ~(uint32_t)(PREP_FLAG_TABLES_PER_WORKGROUP | PREP_FLAG_FULL_RGB | PREP_FLAG_SMOOTH_CHROMA | PREP_FLAG_LARGE_WINDOWS)) != 0)
         return PREP_E_INVALID_ARG;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) {
@@ -430,7 +439,9 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     const uint64_t padded = px + 15ull * n * ((uint64_t)cfg->max_width + cfg->max_height) + 225ull * n;
     h->cap_blocks = padded * 3 / 64 + 6 * n;       // 4:4:4 worst case: 3 blocks per 64 pixels
     h->cap_rgb = padded * 3 + (kRgbAlign + kRgbSlack) * n;
-    h->cap_windows = cfg->max_bitstream_bytes / kWindowBytes + n + 1;
+    // (windows of either size: a call cut into small ones holds at most kSmallCallBytes)
+    h->cap_windows = std::max<uint64_t>(cfg->max_bitstream_bytes / kWindowBytes,
+                                        std::min<uint64_t>(cfg->max_bitstream_bytes, kSmallCallBytes) / kSmallWindowBytes) + n + 1;
     h->cap_bits = cfg->max_bitstream_bytes + kBitsPad;
     // (the kernels index the workspace and its side array with 32-bit element offsets)
     if (h->cap_blocks * 65 > 0xFFFFFFFFull) { delete h; return PREP_E_TOO_LARGE; }

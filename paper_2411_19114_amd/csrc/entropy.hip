@@ -20,6 +20,9 @@
 //        fixed point is the sequential decode, exactly.  A prefix sum of completed
 //        blocks gives every lane its block index, a last pass writes coefficients,
 //        and a segmented scan turns DC differences into absolute values.
+//      - calls with little data (small windows, kHyp): the states at the subsequence
+//        borders inside restart intervals are found by phase hypotheses in two passes
+//        (resolve_by_hypotheses) instead of by iteration, then written as above.
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -784,15 +787,16 @@ __device__ inline void classify16(const uint4 v, uint32_t prev, uint32_t nextb, 
 }  // namespace
 
 // ---- kernel 1: restart markers per window -----------------------------------
-// window w of an image = raw bytes [w*kWindowBytes, (w+1)*kWindowBytes) of its
+// window w of an image = raw bytes [w*window_bytes, (w+1)*window_bytes) of its
 // entropy-coded segment.  cnt = RSTn markers whose FF byte lies in the window,
 // first = offset (from the segment start) of the first such FF byte.
 // Workgroups from n_windows on do something else: workgroup n_windows + 4 s + t expands
 // Huffman table t of image table_rep[s] into slot s of `tables`.
 __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
     const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
-    uint32_t n_windows, uint32_t *__restrict__ win_count, uint32_t *__restrict__ win_first,
-    int32_t *__restrict__ status, const uint32_t *__restrict__ table_rep, uint4 *__restrict__ tables)
+    uint32_t n_windows, uint32_t window_bytes, uint32_t *__restrict__ win_count,
+    uint32_t *__restrict__ win_first, int32_t *__restrict__ status,
+    const uint32_t *__restrict__ table_rep, uint4 *__restrict__ tables)
 {
     __shared__ uint32_t s_cnt[kT / 64], s_first[kT / 64];
     const uint32_t wg = blockIdx.x;
@@ -832,8 +836,8 @@ __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
     uint32_t cnt = 0, first = kNoMarker;
     if (R.status == PREP_OK && R.restart_interval != 0 && w < R.n_windows) {
         const uint8_t *seg = bits + R.file_off + R.entropy_rel;
-        const int32_t lo = (int32_t)(w * (uint32_t)kWindowBytes);
-        const int32_t hi = (int32_t)min(w * (uint32_t)kWindowBytes + (uint32_t)kWindowBytes, R.entropy_len);
+        const int32_t lo = (int32_t)(w * window_bytes);
+        const int32_t hi = (int32_t)min(w * window_bytes + window_bytes, R.entropy_len);
         // 16-byte aligned parts that cover [lo, hi), dealt to the lanes in turn; a part that
         // begins before lo reaches at most 15 bytes back, into the file's headers
         const int32_t a0 = lo - (int32_t)((uintptr_t)(seg + lo) & 15u);
@@ -870,6 +874,14 @@ __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
 }
 
 // ---- kernel 2: the decoder -----------------------------------------------------
+// kHyp: the variant for calls with little data, whose workgroups own a few restart intervals
+// each (small windows).  Inside a restart interval the state at a subsequence border is not
+// known; what keeps iteration slow there is the block's place in the MCU (which tables come
+// next), while bit position and zig-zag index fall into step within a block or two.  So every
+// subsequence is decoded once from each place-in-MCU hypothesis by a lane of its own (the chip
+// is idle otherwise), and once more from the end states those lanes reached in the subsequence
+// before; the true chain then only picks, link by link, the candidate that it equals.
+template <bool kHyp>
 __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
     const uint32_t *__restrict__ win_count, const uint32_t *__restrict__ win_first,
@@ -1036,8 +1048,10 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         // listed start, interval k > 0 between listed starts k-1 and k, and in the last chunk
         // one more runs to the end of the data.
         const uint32_t n_iv = last ? nbnd + 1 : nbnd;
-        const bool short_intervals = g.ri_blocks != 0 && n_iv >= 1 && nbnd <= (uint32_t)kMaxBoundaries &&
-                                     clean_len <= kShortInterval * (nbnd + 1);
+        // (the variant for small calls finds the states inside restart intervals by hypotheses)
+        const bool by_hypotheses = kHyp && g.ri_blocks != 0;
+        const bool short_intervals = !by_hypotheses && g.ri_blocks != 0 && n_iv >= 1 &&
+                                     nbnd <= (uint32_t)kMaxBoundaries && clean_len <= kShortInterval * (nbnd + 1);
         // the short-interval pass reads the stream without pad words (its lanes start anywhere)
         const uint32_t pad_shift = short_intervals ? 31u : (uint32_t)kPadShift;
         // zeros behind the data: the last word is written byte by byte, and lookups near the
@@ -1159,9 +1173,103 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         const bool active = (uint32_t)tid < nsub;
         const uint32_t end_bit = min(((uint32_t)tid + 1u) * kSubBits, own_bits);
 
-        // synchronise: iterate end states to their fixed point
         uint32_t in_state = tid == 0 ? st0 : pack_state((uint32_t)tid * kSubBits, 0, 0);
         uint32_t out_state = in_state, nblk = 0;
+        if (by_hypotheses) {
+            // ---- the true states by place-in-MCU hypotheses ------------------------------
+            // Subsequences [0, first) are settled; x = true state where subsequence `first`
+            // begins.  A region is the next kT / H subsequences (H = blocks per MCU), lane
+            // tid = j H + h working on subsequence first + j (row j) under hypothesis h.
+            //   pass 0: decode from (first bit of the subsequence, block h of an MCU, DC), no
+            //           matter where a symbol really begins there; the lanes of row 0 know the
+            //           true state and decode from it.  End states -> cand[].
+            //   pass 1: decode again from cand[] of the row before: these are the candidates
+            //           for the true state at the row's start.  End states -> next[].
+            //   link[] of a lane: which candidate of its own row its end state next[] equals.
+            //   Lane 0 then follows the links from row to row.  Where the true state is none
+            //   of the candidates (the true decoder had not fallen into step with any
+            //   hypothesis by the end of the row before), the lanes of that row decode it
+            //   once more from the true state, as row 0 did, and the walk goes on from there.
+            __shared__ uint16_t hyp_blocks[kT];
+            __shared__ uint8_t link[kT], chosen[kT];
+            uint32_t *cand = reinterpret_cast<uint32_t *>(S.bpos);  // (the list of interval starts
+            uint32_t *next = cand + kT;                             // is of no use to these passes)
+            static_assert(sizeof(S.bpos) >= 2 * kT * sizeof(uint32_t), "cand[] and next[] fit");
+            constexpr uint32_t kNoLink = 255;
+            const uint32_t H = g.bpm, per = (uint32_t)kT / H;
+            const uint32_t j = (uint32_t)tid / H, h = (uint32_t)tid - j * H;
+            uint32_t first = 0, x = st0;
+            for (uint32_t region = 0; region < nsub && first < nsub; region++) {
+                const uint32_t cnt = min(per, nsub - first);
+                const bool mine = j < cnt;
+                const uint32_t s_end = min((first + j + 1u) * kSubBits, own_bits);
+                // which candidate of my row my end state equals (rows link to themselves: the
+                // state where row j + 1 begins is looked up among the ends of row j)
+                auto find_link = [&]() {
+                    uint32_t hit = kNoLink;
+                    for (uint32_t k = 0; k < H; k++)
+                        if (cand[j * H + k] == next[tid]) { hit = k; break; }
+                    link[tid] = (uint8_t)hit;
+                };
+                for (int pass = 0; pass < 2; pass++) {
+                    const bool run = mine && (pass == 0 || j != 0);
+                    if (run) {
+                        const uint32_t from = pass == 0 ? (j == 0 ? x : pack_state((first + j) * kSubBits, h, 0))
+                                                        : cand[(uint32_t)tid - H];
+                        uint32_t to = from, nb = 0;
+                        // (a state past the subsequence's end: the lane before ran through it)
+                        if ((from >> 9) < s_end) to = decode_span<false>(S, g, from, false, s_end, limit_bits, &nb, nullptr);
+                        if (pass == 0) cand[tid] = to;
+                        if (pass == 1 || j == 0) { next[tid] = to; hyp_blocks[tid] = (uint16_t)nb; }
+                    }
+                    __syncthreads();
+                }
+                // (row 0's own candidates are all the true end state: it links to candidate 0)
+                if (mine) find_link();
+                if (tid == 0) S.bcast[5] = 0;
+                __syncthreads();
+                // rows [0, walked) are settled; chosen[r] = the lane of row r that decoded from
+                // the true state
+                for (uint32_t walk = 0; walk < cnt; walk++) {
+                    if (tid == 0) {
+                        uint32_t r = S.bcast[5], k = 0;  // row r holds the true state in every lane
+                        chosen[r] = 0;
+                        for (r++; r < cnt; r++) {
+                            k = link[(r - 1u) * H + k];
+                            if (k == kNoLink) break;
+                            chosen[r] = (uint8_t)k;
+                        }
+                        S.bcast[5] = r;
+                    }
+                    __syncthreads();
+                    const uint32_t r = S.bcast[5];
+                    if (r >= cnt) break;
+                    // row r begins in a state that is no candidate: decode it from that state
+                    if (j == r) {
+                        const uint32_t from = next[(r - 1u) * H + chosen[r - 1u]];
+                        uint32_t to = from, nb = 0;
+                        if ((from >> 9) < s_end) to = decode_span<false>(S, g, from, false, s_end, limit_bits, &nb, nullptr);
+                        next[tid] = to;
+                        hyp_blocks[tid] = (uint16_t)nb;
+                    }
+                    __syncthreads();
+                    if (j == r) find_link();
+                    __syncthreads();
+                }
+                if ((uint32_t)tid >= first && (uint32_t)tid < first + cnt) {
+                    const uint32_t r = (uint32_t)tid - first;
+                    in_state = r == 0 ? x : next[(r - 1u) * H + chosen[r - 1u]];
+                    out_state = next[r * H + chosen[r]];
+                    nblk = hyp_blocks[r * H + chosen[r]];
+                    S.state[tid] = out_state;
+                }
+                x = next[(cnt - 1u) * H + chosen[cnt - 1u]];
+                first += cnt;
+                __syncthreads();  // cand[], next[] and the rest are free again
+            }
+            if (!active) S.state[tid] = out_state;
+        } else {
+        // synchronise: iterate end states to their fixed point
         if (active) out_state = decode_span<false>(S, g, in_state, false, end_bit, limit_bits, &nblk, nullptr);
         S.state[tid] = out_state;
         for (uint32_t round = 0; round <= nsub; round++) {
@@ -1179,6 +1287,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
                 S.state[tid] = out_state;
             }
             if (!__syncthreads_or(changed)) break;
+        }
         }
 
         // write: decode once more from the true states
@@ -1267,25 +1376,30 @@ size_t huff_tables_bytes() { return sizeof(HuffTables); }
 static_assert(sizeof(HuffTables) % 16 == 0, "table slots are copied in 16-byte units");
 
 void launch_scan_restart_markers(const uint8_t *bits, const ImageRec *recs, int n_images,
-                                 uint32_t n_windows, uint32_t *win_count, uint32_t *win_first,
+                                 uint32_t n_windows, uint32_t window_bytes, uint32_t *win_count, uint32_t *win_first,
                                  int32_t *status, const uint32_t *table_rep, uint32_t n_tables,
                                  uint8_t *tables, hipStream_t stream)
 {
     if (n_windows == 0) return;
     hipLaunchKernelGGL(scan_restart_markers, dim3(n_windows + 4 * n_tables), dim3(kDecodeThreads), 0, stream,
-                       bits, recs, n_images, n_windows, win_count, win_first, status, table_rep,
+                       bits, recs, n_images, n_windows, window_bytes, win_count, win_first, status, table_rep,
                        reinterpret_cast<uint4 *>(tables));
 }
 
 void launch_decode_entropy(const uint8_t *bits, const ImageRec *recs, int n_images,
                            uint32_t n_windows, const uint32_t *win_count, const uint32_t *win_first,
                            int16_t *coef, uint32_t side_off, int32_t *status, const uint8_t *tables,
-                           hipStream_t stream)
+                           bool small_windows, hipStream_t stream)
 {
     if (n_windows == 0) return;
-    hipLaunchKernelGGL(decode_entropy, dim3(n_windows), dim3(kDecodeThreads), 0, stream, bits, recs,
-                       n_images, win_count, win_first, coef, side_off, status,
-                       reinterpret_cast<const uint4 *>(tables));
+    if (small_windows)
+        hipLaunchKernelGGL(decode_entropy<true>, dim3(n_windows), dim3(kDecodeThreads), 0, stream, bits, recs,
+                           n_images, win_count, win_first, coef, side_off, status,
+                           reinterpret_cast<const uint4 *>(tables));
+    else
+        hipLaunchKernelGGL(decode_entropy<false>, dim3(n_windows), dim3(kDecodeThreads), 0, stream, bits, recs,
+                           n_images, win_count, win_first, coef, side_off, status,
+                           reinterpret_cast<const uint4 *>(tables));
 }
 
 }  // namespace prep

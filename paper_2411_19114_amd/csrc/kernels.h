@@ -12,18 +12,20 @@ namespace prep {
 // entropy.hip
 // bytes of one slot of expanded Huffman tables
 size_t huff_tables_bytes();
-// table_rep[s] = an image whose tables go into slot s of `tables` (n_tables slots)
+// table_rep[s] = an image whose tables go into slot s of `tables` (n_tables slots);
+// window_bytes = raw bytes between workgroup starts (the ImageRecs' n_windows count such windows)
 void launch_scan_restart_markers(const uint8_t *bits, const ImageRec *recs, int n_images,
-                                 uint32_t n_windows, uint32_t *win_count, uint32_t *win_first,
+                                 uint32_t n_windows, uint32_t window_bytes, uint32_t *win_count, uint32_t *win_first,
                                  int32_t *status, const uint32_t *table_rep, uint32_t n_tables,
                                  uint8_t *tables, hipStream_t stream);
 // coef + side_off: one int16 per block of the coefficient workspace, in the same allocation
 // behind the coefficients (the DC differences, which the decoder turns into values in a second
-// step of the same launch); side_off plus the number of blocks must stay below 2^32
+// step of the same launch); side_off plus the number of blocks must stay below 2^32;
+// small_windows: the windows are kSmallWindowBytes apart (the decoder variant for small calls)
 void launch_decode_entropy(const uint8_t *bits, const ImageRec *recs, int n_images,
                            uint32_t n_windows, const uint32_t *win_count, const uint32_t *win_first,
                            int16_t *coef, uint32_t side_off, int32_t *status, const uint8_t *tables,
-                           hipStream_t stream);
+                           bool small_windows, hipStream_t stream);
 
 // reconstruct.hip
 // chroma: nullptr = subsampled chroma is replicated; else the workspace of the interpolating

@@ -15,6 +15,12 @@ constexpr int kSubseqBytes = 64;                            // clean bytes per l
 constexpr int kChunkRaw = kDecodeThreads * kSubseqBytes;    // raw bytes staged per chunk
 constexpr int kChunkTail = 16;                              // bytes a non-final chunk keeps back
 constexpr int kWindowBytes = 12288;                         // raw bytes between workgroup starts
+// A call with little entropy-coded data would leave most of the chip idle behind a few lanes
+// that walk whole restart intervals one symbol after the other.  Such a call is cut into
+// smaller windows (more workgroups, a few restart intervals each) and its workgroups find the
+// decoder states inside an interval by phase hypotheses instead (see decode_entropy).
+constexpr int kSmallWindowBytes = 2048;
+constexpr uint64_t kSmallCallBytes = 1536 << 10;            // entropy-coded bytes of a call up to which it is cut small
 constexpr int kLutBits = 10;                                // first-level Huffman lookup width
 // Images of a batch mostly share their Huffman tables (encoders write the tables of T.81
 // Annex K unless asked to optimise): each distinct set of four tables is expanded once per

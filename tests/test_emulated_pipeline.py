@@ -41,14 +41,21 @@ def _check(streams, rs, ch, cw, dt, expect_status=None, flags=0, antialias=False
         assert np.abs(ten[i].astype(np.float64) - ref).max() <= 0.02, f"image {i}: tensor"
 
 
-def test_modes_restart_intervals_and_odd_sizes():
+# Small inputs are cut into small windows and decoded by the hypothesis passes; flag 8
+# (PREP_FLAG_LARGE_WINDOWS) sends them down the paths that large batches take: one lane per
+# short restart interval, iterated subsequences for long ones.
+BOTH_DECODERS = pytest.mark.parametrize("windows", [0, 8], ids=["small-windows", "large-windows"])
+
+
+@BOTH_DECODERS
+def test_modes_restart_intervals_and_odd_sizes(windows):
     streams = []
     for k, (w, h) in enumerate([(1, 1), (17, 33), (70, 45)]):
         for mode in (MODE_444, MODE_420, MODE_GRAY, MODE_422, MODE_440):
             cols = -(-w // (8 * oracle.MODE_GEOMETRY[mode][0]))
             for dri in (0, 1, cols):
                 streams.append(oracle.encode(_img(10 + k, w, h), 88, mode, dri, table_mode=k % 2)[0])
-    _check(streams, 0, 1, 1, "f32", flags=2)  # whole images are converted to RGB and compared
+    _check(streams, 0, 1, 1, "f32", flags=2 | windows)  # whole images are converted to RGB and compared
 
 
 def test_tables_whose_codes_are_mostly_sixteen_bits_long():
@@ -107,13 +114,14 @@ def test_pillow_streams_of_workloads_1_and_5():
     _check(streams, 256, 224, 224, "f16")
 
 
-def test_long_intervals_and_many_chunks():
+@BOTH_DECODERS
+def test_long_intervals_and_many_chunks(windows):
     rgb = _img(20, 480, 320, sigma=25.0)
     streams = [oracle.encode(rgb, 95, MODE_444, 0)[0],        # ~150 KB without markers
                oracle.encode(rgb, 95, MODE_420, 30)[0],       # one interval per MCU row, > 1 KB each
                oracle.encode(rgb, 95, MODE_420, 3)[0]]        # short intervals over many windows
     assert len(streams[0]) > 100000
-    _check(streams, 128, 112, 120, "f32")
+    _check(streams, 128, 112, 120, "f32", flags=windows)
 
 
 def test_broken_streams_are_reported_and_zero_filled():
@@ -127,7 +135,8 @@ def test_broken_streams_are_reported_and_zero_filled():
     _check(streams, 32, 24, 24, "f32", expect_status=[0, -5, 0, -4, -5, -5])
 
 
-def test_damaged_entropy_data_stays_in_bounds():
+@BOTH_DECODERS
+def test_damaged_entropy_data_stays_in_bounds(windows):
     """Random damage to the entropy-coded bytes: the sanitizers see no access out of bounds,
     every kernel loop ends, and each stream is refused or decoded as the oracle decodes it.
     PREP_DAMAGE_FULL=1 runs the larger set that the GPU test of the same name uses."""
@@ -135,6 +144,6 @@ def test_damaged_entropy_data_stays_in_bounds():
         streams = helpers.damaged_streams(11, 12) + helpers.damaged_streams(12, 12)
     else:
         streams = helpers.damaged_streams(7, 4, n_bases=4)
-    per, ten = emul.run(streams, 32, 24, 24, "f32", MEAN, STD, timeout=3000)
+    per, ten = emul.run(streams, 32, 24, 24, "f32", MEAN, STD, timeout=3000, flags=windows)
     refused = helpers.check_damaged(streams, [p[0] for p in per], lambda i, nb: per[i][1], ten)
     assert refused >= len(streams) // 2

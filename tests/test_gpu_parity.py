@@ -19,10 +19,12 @@ def prep():
 
 
 # every test that takes `pp` runs twice: with the default handle, which converts to RGB only
-# the MCUs that the crop window reads, and with one that converts whole images
-@pytest.fixture(scope="module", params=[0, 2], ids=["crop-region", "full-rgb"])
+# the MCUs that the crop window reads and cuts small calls into small windows for the
+# hypothesis passes of the entropy decoder, and with one that converts whole images and sends
+# small calls down the decoder paths of large batches
+@pytest.fixture(scope="module", params=[0, 2 | 8], ids=["crop-region", "full-rgb-large-windows"])
 def pp(prep, request):
-    assert prep.FLAG_FULL_RGB == 2
+    assert prep.FLAG_FULL_RGB == 2 and prep.FLAG_LARGE_WINDOWS == 8
     h = prep.Preprocessor(device=0, max_batch=64, max_width=2048, max_height=1200,
                           max_bitstream_bytes=48 << 20, max_total_pixels=24 << 20, flags=request.param)
     yield h
