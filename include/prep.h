@@ -131,7 +131,7 @@ typedef struct {
     int32_t width, height;
     int32_t sampling;          /* PREP_SAMPLING_*                                   */
     int32_t mcu_cols, mcu_rows;
-    int32_t blocks_per_mcu;    /* 1, 3 or 6                                         */
+    int32_t blocks_per_mcu;    /* 1, 3, 4 or 6                                      */
     int32_t restart_interval;  /* MCUs per restart interval, 0 = none               */
     int32_t n_intervals;       /* restart-interval work descriptors of this image   */
     int32_t reserved;

@@ -119,8 +119,9 @@ def test_long_intervals_and_many_chunks(windows):
     rgb = _img(20, 480, 320, sigma=25.0)
     streams = [oracle.encode(rgb, 95, MODE_444, 0)[0],        # ~150 KB without markers
                oracle.encode(rgb, 95, MODE_420, 30)[0],       # one interval per MCU row, > 1 KB each
-               oracle.encode(rgb, 95, MODE_420, 3)[0]]        # short intervals over many windows
-    assert len(streams[0]) > 100000
+               oracle.encode(rgb, 95, MODE_420, 3)[0],        # short intervals over many windows
+               oracle.encode(rgb[:160, :240], 95, MODE_420, 0)[0]]   # no markers, six blocks per MCU, two chunks
+    assert len(streams[0]) > 100000 and len(streams[3]) > 20000
     _check(streams, 128, 112, 120, "f32", flags=windows)
 
 
