@@ -166,7 +166,11 @@ constexpr int32_t kCopyStreamMinImages = 128;       // and so do the records of 
 // call before it (on the caller's stream).
 struct Slot {
     uint8_t *h_bits = nullptr;
-    ImageRec *h_recs = nullptr;   // n records, then n first-workgroup indices, then <= n table owners
+    // One block, host side and device side, holds what a call uploads besides the bitstreams,
+    // so that it goes up in one copy: n ResizeRecs, then n ImageRecs, then n first-workgroup
+    // indices, then <= n table owners.  The four pointers below are set per call.
+    uint8_t *h_block = nullptr, *d_block = nullptr;
+    ImageRec *h_recs = nullptr;
     ResizeRec *h_rr = nullptr;
     int32_t *h_status = nullptr;
     uint8_t *d_bits = nullptr;
@@ -176,6 +180,17 @@ struct Slot {
     hipEvent_t done = nullptr;    // kernels of the slot's call are done
     bool pending = false;
 };
+
+// bytes of a slot's block for n images, and the pointers into it
+inline size_t block_bytes(size_t n) { return (sizeof(ResizeRec) + sizeof(ImageRec) + 2 * sizeof(uint32_t)) * n; }
+inline void place_block(Slot *s, size_t n)
+{
+    static_assert(sizeof(ResizeRec) % 8 == 0, "the ImageRecs behind the ResizeRecs stay 8-byte aligned");
+    s->h_rr = reinterpret_cast<ResizeRec *>(s->h_block);
+    s->d_rr = reinterpret_cast<ResizeRec *>(s->d_block);
+    s->h_recs = reinterpret_cast<ImageRec *>(s->h_block + sizeof(ResizeRec) * n);
+    s->d_recs = reinterpret_cast<ImageRec *>(s->d_block + sizeof(ResizeRec) * n);
+}
 
 struct Plan {                         // what one call will run
     uint32_t n_windows = 0;
@@ -439,6 +454,7 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
     if (rc == PREP_OK && coef_host && n_coef != P.n_blocks * 64) rc = PREP_E_INVALID_ARG;
     if (pooled) pool->wait();
     if (rc != PREP_OK) return rc;
+    place_block(s, (size_t)n);
     memcpy(s->h_recs, h->recs.data(), sizeof(ImageRec) * (size_t)n);
     // the first reconstruction workgroup of every image, packed behind the records: the
     // kernel finds its image by counting the entries that do not exceed its index
@@ -457,9 +473,7 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
         if (!pooled) memcpy(s->h_bits, base_host, total);
         HIP_TRY(hipMemcpyAsync(s->d_bits, s->h_bits, total, hipMemcpyHostToDevice, up));
     }
-    HIP_TRY(hipMemcpyAsync(s->d_recs, s->h_recs, (sizeof(ImageRec) + 2 * sizeof(uint32_t)) * (size_t)n,
-                           hipMemcpyHostToDevice, up));
-    HIP_TRY(hipMemcpyAsync(s->d_rr, s->h_rr, sizeof(ResizeRec) * (size_t)n, hipMemcpyHostToDevice, up));
+    HIP_TRY(hipMemcpyAsync(s->d_block, s->h_block, block_bytes((size_t)n), hipMemcpyHostToDevice, up));
     if (aside) {
         HIP_TRY(hipEventRecord(s->copied, h->copy_stream));
         HIP_TRY(hipStreamWaitEvent(stream, s->copied, 0));
@@ -554,12 +568,10 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     for (int i = 0; ok && i < kSlots; i++) {
         Slot &s = h->slot[i];
         ok = ok && hipHostMalloc((void **)&s.h_bits, h->cap_bits, hipHostMallocDefault) == hipSuccess;
-        ok = ok && hipHostMalloc((void **)&s.h_recs, (sizeof(ImageRec) + 2 * sizeof(uint32_t)) * n, hipHostMallocDefault) == hipSuccess;
-        ok = ok && hipHostMalloc((void **)&s.h_rr, sizeof(ResizeRec) * n, hipHostMallocDefault) == hipSuccess;
+        ok = ok && hipHostMalloc((void **)&s.h_block, block_bytes(n), hipHostMallocDefault) == hipSuccess;
         ok = ok && hipHostMalloc((void **)&s.h_status, sizeof(int32_t) * n, hipHostMallocDefault) == hipSuccess;
         ok = ok && hipMalloc((void **)&s.d_bits, h->cap_bits) == hipSuccess;
-        ok = ok && hipMalloc((void **)&s.d_recs, (sizeof(ImageRec) + 2 * sizeof(uint32_t)) * n) == hipSuccess;
-        ok = ok && hipMalloc((void **)&s.d_rr, sizeof(ResizeRec) * n) == hipSuccess;
+        ok = ok && hipMalloc((void **)&s.d_block, block_bytes(n)) == hipSuccess;
         ok = ok && hipEventCreateWithFlags(&s.copied, hipEventDisableTiming) == hipSuccess;
         ok = ok && hipEventCreateWithFlags(&s.done, hipEventDisableTiming) == hipSuccess;
     }
@@ -590,12 +602,10 @@ int prep_destroy(prep_handle *h)
     for (int i = 0; i < kSlots; i++) {
         Slot &s = h->slot[i];
         if (s.h_bits) (void)hipHostFree(s.h_bits);
-        if (s.h_recs) (void)hipHostFree(s.h_recs);
-        if (s.h_rr) (void)hipHostFree(s.h_rr);
+        if (s.h_block) (void)hipHostFree(s.h_block);
         if (s.h_status) (void)hipHostFree(s.h_status);
         (void)hipFree(s.d_bits);
-        (void)hipFree(s.d_recs);
-        (void)hipFree(s.d_rr);
+        (void)hipFree(s.d_block);
         if (s.copied) (void)hipEventDestroy(s.copied);
         if (s.done) (void)hipEventDestroy(s.done);
     }
@@ -708,6 +718,7 @@ int prep_resize_normalize(prep_handle *h, const uint8_t *rgb, const uint64_t *rg
     Slot *s;
     int rc = take_slot(h, &s);
     if (rc != PREP_OK) return rc;
+    place_block(s, (size_t)n);
     for (int32_t i = 0; i < n; i++) {
         if (widths[i] < 1 || heights[i] < 1 || pitches[i] < widths[i] * 3) return PREP_E_INVALID_ARG;
         if (!make_resize_rec(widths[i], heights[i], params, rgb_offsets[i], (uint32_t)pitches[i], &s->h_rr[i]))
