@@ -97,6 +97,25 @@ def test_interpolated_chroma(prep, flags):
         h.close()
 
 
+def test_random_small_batches(pp):
+    # seeded batches of 1 to 16 images of random size, sampling, quality, noise and restart
+    # interval (from one MCU to two MCU rows, and none): calls with little data, whose restart
+    # intervals the default handle decodes by hypotheses over the block's place in the MCU
+    rng = np.random.default_rng(2024)
+    modes = [MODE_420, MODE_420, MODE_422, MODE_440, MODE_444, MODE_GRAY]
+    for _ in range(24):
+        streams = []
+        for _ in range(int(rng.integers(1, 17))):
+            w, h = int(rng.integers(16, 640)), int(rng.integers(16, 500))
+            mode = modes[int(rng.integers(0, len(modes)))]
+            cols = -(-w // (8 * oracle.MODE_GEOMETRY[mode][0]))
+            dri = int(rng.choice([1, 2, 3, 5, 8, cols, 2 * cols, 0]))
+            rgb = synth.gradient_noise_image(rng, w, h, float(rng.uniform(2, 30)))
+            streams.append(oracle.encode(rgb, int(rng.integers(40, 98)), mode, dri,
+                                         table_mode=int(rng.integers(0, 2)))[0])
+        check_against_oracle(pp, streams, 0, 16, 16, "f32")
+
+
 def test_upscaling_small_images(pp):
     streams = [oracle.encode(_img(300 + k, w, h), 90, MODE_420, 0)[0]
                for k, (w, h) in enumerate([(1, 1), (7, 9), (40, 23), (23, 40)])]
