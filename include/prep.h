@@ -164,7 +164,8 @@ int prep_destroy(prep_handle *h);
  *              PREP_U8_NHWC);
  *              must stay valid until `stream` has run the enqueued work
  *   stream     a hipStream_t (NULL = the default stream)
- * The call copies what it needs from the host buffers before it returns and
+ * The call copies what it needs from the host buffers before it returns (copies of 1 MiB
+ * or more with the help of three threads that the library starts once per process) and
  * returns as soon as the GPU work is enqueued on `stream` (uploads of large
  * batches run on a stream of the handle that `stream` is made to wait for).  Whole-call errors
  * (INVALID_ARG, TOO_LARGE, HIP) enqueue nothing.  A file that cannot be decoded
