@@ -23,11 +23,12 @@
  *   output    : planar NCHW, RGB channel order, fp32 or fp16; or, without normalize,
  *               the resized crop as interleaved 8-bit RGB (PREP_U8_NHWC).
  *
- * Two restrictions inside the baseline subset: the two chroma components must name the same
+ * One restriction inside the baseline subset: the two chroma components must name the same
  * Huffman tables (the decoder holds one DC/AC pair for luma and one for chroma; a file that
- * gives Cb and Cr different tables is reported PREP_E_UNSUPPORTED), and the entropy-coded
- * segment is taken to end at the LAST EOI marker of a file (a sound image followed by data
- * that holds another FF D9, such as an appended preview, is reported PREP_E_CORRUPT).
+ * gives Cb and Cr different tables is reported PREP_E_UNSUPPORTED).  A file may go on after
+ * its image (a second image, a preview, padding): the host, which does not read the
+ * entropy-coded bytes, takes them to run up to the file's last EOI marker, and the GPU ends
+ * them at the first FF D9 inside (which cannot occur in entropy-coded data, T.81 F.1.2.3).
  *
  * All entry points are plain C.  "HOST" pointers are ordinary process memory,
  * "DEVICE" pointers are HIP device memory of the handle's GPU.  A handle may be
@@ -136,7 +137,7 @@ typedef struct {
     int32_t n_intervals;       /* restart-interval work descriptors of this image   */
     int32_t reserved;
     uint64_t entropy_offset;   /* first entropy-coded byte, from the file start     */
-    uint64_t entropy_bytes;    /* up to, not including, the EOI marker              */
+    uint64_t entropy_bytes;    /* up to, not including, the file's last EOI marker  */
 } prep_image_info;
 
 /* One restart-interval work descriptor: the unit of independent entropy

@@ -168,7 +168,8 @@ struct Slot {
     uint8_t *h_bits = nullptr;
     // One block, host side and device side, holds what a call uploads besides the bitstreams,
     // so that it goes up in one copy: n ResizeRecs, then n ImageRecs, then n first-workgroup
-    // indices, then <= n table owners.  The four pointers below are set per call.
+    // indices, then <= n table owners, then n lengths of the entropy-coded data (which the scan
+    // kernel lowers to the first EOI marker).  The pointers below are set per call.
     uint8_t *h_block = nullptr, *d_block = nullptr;
     ImageRec *h_recs = nullptr;
     ResizeRec *h_rr = nullptr;
@@ -176,13 +177,14 @@ struct Slot {
     uint8_t *d_bits = nullptr;
     ImageRec *d_recs = nullptr;
     ResizeRec *d_rr = nullptr;
+    uint32_t *h_data_end = nullptr, *d_data_end = nullptr;
     hipEvent_t copied = nullptr;  // uploads of the slot's call are done
     hipEvent_t done = nullptr;    // kernels of the slot's call are done
     bool pending = false;
 };
 
 // bytes of a slot's block for n images, and the pointers into it
-inline size_t block_bytes(size_t n) { return (sizeof(ResizeRec) + sizeof(ImageRec) + 2 * sizeof(uint32_t)) * n; }
+inline size_t block_bytes(size_t n) { return (sizeof(ResizeRec) + sizeof(ImageRec) + 3 * sizeof(uint32_t)) * n; }
 inline void place_block(Slot *s, size_t n)
 {
     static_assert(sizeof(ResizeRec) % 8 == 0, "the ImageRecs behind the ResizeRecs stay 8-byte aligned");
@@ -190,6 +192,9 @@ inline void place_block(Slot *s, size_t n)
     s->d_rr = reinterpret_cast<ResizeRec *>(s->d_block);
     s->h_recs = reinterpret_cast<ImageRec *>(s->h_block + sizeof(ResizeRec) * n);
     s->d_recs = reinterpret_cast<ImageRec *>(s->d_block + sizeof(ResizeRec) * n);
+    const size_t before = (sizeof(ResizeRec) + sizeof(ImageRec) + 2 * sizeof(uint32_t)) * n;
+    s->h_data_end = reinterpret_cast<uint32_t *>(s->h_block + before);
+    s->d_data_end = reinterpret_cast<uint32_t *>(s->d_block + before);
 }
 
 struct Plan {                         // what one call will run
@@ -461,6 +466,7 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
     uint32_t *h_group0 = reinterpret_cast<uint32_t *>(s->h_recs + n);
     for (int32_t i = 0; i < n; i++) h_group0[i] = h->recs[(size_t)i].group0;
     for (uint32_t t = 0; t < P.n_tables; t++) h_group0[n + (int32_t)t] = h->table_rep[t];
+    for (int32_t i = 0; i < n; i++) s->h_data_end[i] = h->recs[(size_t)i].entropy_len;
     memcpy(s->h_rr, h->rr.data(), sizeof(ResizeRec) * (size_t)n);
     // Large uploads go on the handle's copy stream and the caller's stream waits for them, so
     // that they overlap the kernels of the call before.  Small ones stay on the caller's
@@ -490,10 +496,11 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
     } else {
         // (P.n_windows >= n > 0: the scan also sets every image's status)
         launch_scan_restart_markers(d_bits, s->d_recs, n, P.n_windows, P.window_bytes, h->d_win_count, h->d_win_first,
+                                    s->d_data_end,
                                     h->d_status, reinterpret_cast<const uint32_t *>(s->d_recs + n) + n,
                                     P.n_tables, h->d_tables, stream);
         if (timing) HIP_TRY(hipEventRecord(ev[1], stream));
-        launch_decode_entropy(d_bits, s->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first,
+        launch_decode_entropy(d_bits, s->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first, s->d_data_end,
                               h->d_coef, (uint32_t)(h->cap_blocks * 64), h->d_status, h->d_tables,
                               P.window_bytes == (uint32_t)kSmallWindowBytes, stream);
         if (timing) HIP_TRY(hipEventRecord(ev[2], stream));

@@ -790,12 +790,16 @@ __device__ inline void classify16(const uint4 v, uint32_t prev, uint32_t nextb, 
 // window w of an image = raw bytes [w*window_bytes, (w+1)*window_bytes) of its
 // entropy-coded segment.  cnt = RSTn markers whose FF byte lies in the window,
 // first = offset (from the segment start) of the first such FF byte.
+// data_end[image] arrives as the length that the host gave the segment (up to the file's last
+// EOI marker, which it finds from the file's end) and leaves as the offset of the first EOI
+// marker in it: FF D9 cannot occur inside entropy-coded data (T.81 F.1.2.3), so where a file
+// goes on after its image (a second image, a preview) the data end there.
 // Workgroups from n_windows on do something else: workgroup n_windows + 4 s + t expands
 // Huffman table t of image table_rep[s] into slot s of `tables`.
 __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
     const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
     uint32_t n_windows, uint32_t window_bytes, uint32_t *__restrict__ win_count,
-    uint32_t *__restrict__ win_first, int32_t *__restrict__ status,
+    uint32_t *__restrict__ win_first, uint32_t *__restrict__ data_end, int32_t *__restrict__ status,
     const uint32_t *__restrict__ table_rep, uint4 *__restrict__ tables)
 {
     __shared__ uint32_t s_cnt[kT / 64], s_first[kT / 64];
@@ -833,8 +837,9 @@ __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
     const uint32_t w = wg - R.window0;
     // the per-image verdict starts as the host parser's; the decoder may lower it
     if (w == 0 && threadIdx.x == 0) status[img] = R.status;
-    uint32_t cnt = 0, first = kNoMarker;
-    if (R.status == PREP_OK && R.restart_interval != 0 && w < R.n_windows) {
+    uint32_t cnt = 0, first = kNoMarker, eoi = kNoMarker;
+    if (R.status == PREP_OK && w < R.n_windows) {
+        const bool count_rst = R.restart_interval != 0;
         const uint8_t *seg = bits + R.file_off + R.entropy_rel;
         const int32_t lo = (int32_t)(w * window_bytes);
         const int32_t hi = (int32_t)min(w * window_bytes + window_bytes, R.entropy_len);
@@ -851,12 +856,17 @@ __global__ __launch_bounds__(kDecodeThreads) void scan_restart_markers(
                 const uint32_t cur = (wv[i >> 2] >> (8 * (i & 3))) & 255u;
                 const uint32_t nxt = (wv[(i + 1) >> 2] >> (8 * ((i + 1) & 3))) & 255u;
                 const int32_t pos = plo + i;
-                if (cur == 0xFFu && nxt >= 0xD0u && nxt <= 0xD7u && pos >= lo && pos < hi) {
-                    cnt++;
-                    first = min(first, (uint32_t)pos);
+                if (cur == 0xFFu && nxt >= 0xD0u && nxt <= 0xD9u && nxt != 0xD8u && pos >= lo && pos < hi) {
+                    if (nxt == 0xD9u) {
+                        eoi = min(eoi, (uint32_t)pos);
+                    } else if (count_rst) {
+                        cnt++;
+                        first = min(first, (uint32_t)pos);
+                    }
                 }
             }
         }
+        if (eoi != kNoMarker) atomicMin(&data_end[img], eoi);
     }
     // workgroup reduction
     for (int d = 32; d >= 1; d >>= 1) {
@@ -885,8 +895,8 @@ template <bool kHyp>
 __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
     const uint32_t *__restrict__ win_count, const uint32_t *__restrict__ win_first,
-    int16_t *__restrict__ coef_all, uint32_t side_off, int32_t *__restrict__ status,
-    const uint4 *__restrict__ tables)
+    const uint32_t *__restrict__ data_end, int16_t *__restrict__ coef_all, uint32_t side_off,
+    int32_t *__restrict__ status, const uint4 *__restrict__ tables)
 {
     __shared__ DecodeShared S;
     const int tid = threadIdx.x;
@@ -907,13 +917,15 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     // window 0 starts at the segment start; window w > 0 starts after the first
     // marker of its window, if it has one, and runs to the first marker of the
     // next window that has one.
-    uint32_t range_lo = 0, range_hi = R.entropy_len, block0 = 0, block_end = R.n_blocks;
+    // the entropy-coded data end at the segment's first EOI marker (found by the scan kernel)
+    const uint32_t data_len = min(R.entropy_len, data_end[img]);
+    uint32_t range_lo = 0, range_hi = data_len, block0 = 0, block_end = R.n_blocks;
     uint32_t marker_base = 0;  // number, within the image, of the first restart marker at or after cs
     bool first_marker_ok = true;
     {
         const uint32_t *wc = win_count + R.window0, *wf = win_first + R.window0;
         uint32_t my_first = w == 0 ? 0u : wf[w];
-        if (w != 0 && my_first == kNoMarker) return;  // uniform over the workgroup
+        if (w != 0 && (my_first == kNoMarker || my_first >= data_len)) return;  // uniform over the workgroup
         uint32_t before = 0, next_first = kNoMarker, next_w = kNoMarker;
         for (uint32_t i = tid; i < w; i += kT) before += wc[i];
         for (uint32_t i = w + 1 + tid; i < R.n_windows; i += kT)
@@ -939,6 +951,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             }
         }
         __syncthreads();
+        if (next_w != kNoMarker && next_first >= data_len) next_w = kNoMarker;  // (a marker of what follows the image)
         if (w != 0) {
             range_lo = my_first + 2;
             block0 = (before + 1) * g.ri_blocks;  // markers before ours + ours = intervals done
@@ -979,7 +992,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     const uint32_t side_rel = side_off + R.coef_block0 - R.coef_block0 * 64u;
     // raw offsets are signed: the aligned span of the first chunk may begin a few bytes
     // before the segment (inside the file's headers)
-    const int32_t seg_len = (int32_t)R.entropy_len;
+    const int32_t seg_len = (int32_t)data_len;
     const int32_t rhi = (int32_t)range_hi;
     int32_t cs = (int32_t)range_lo;      // raw offset where the next chunk starts
     uint32_t st0 = pack_state(0, 0, 0);  // true state at the start of the chunk
@@ -1377,28 +1390,29 @@ static_assert(sizeof(HuffTables) % 16 == 0, "table slots are copied in 16-byte u
 
 void launch_scan_restart_markers(const uint8_t *bits, const ImageRec *recs, int n_images,
                                  uint32_t n_windows, uint32_t window_bytes, uint32_t *win_count, uint32_t *win_first,
+                                 uint32_t *data_end,
                                  int32_t *status, const uint32_t *table_rep, uint32_t n_tables,
                                  uint8_t *tables, hipStream_t stream)
 {
     if (n_windows == 0) return;
     hipLaunchKernelGGL(scan_restart_markers, dim3(n_windows + 4 * n_tables), dim3(kDecodeThreads), 0, stream,
-                       bits, recs, n_images, n_windows, window_bytes, win_count, win_first, status, table_rep,
+                       bits, recs, n_images, n_windows, window_bytes, win_count, win_first, data_end, status, table_rep,
                        reinterpret_cast<uint4 *>(tables));
 }
 
 void launch_decode_entropy(const uint8_t *bits, const ImageRec *recs, int n_images,
                            uint32_t n_windows, const uint32_t *win_count, const uint32_t *win_first,
-                           int16_t *coef, uint32_t side_off, int32_t *status, const uint8_t *tables,
-                           bool small_windows, hipStream_t stream)
+                           const uint32_t *data_end, int16_t *coef, uint32_t side_off, int32_t *status,
+                           const uint8_t *tables, bool small_windows, hipStream_t stream)
 {
     if (n_windows == 0) return;
     if (small_windows)
         hipLaunchKernelGGL(decode_entropy<true>, dim3(n_windows), dim3(kDecodeThreads), 0, stream, bits, recs,
-                           n_images, win_count, win_first, coef, side_off, status,
+                           n_images, win_count, win_first, data_end, coef, side_off, status,
                            reinterpret_cast<const uint4 *>(tables));
     else
         hipLaunchKernelGGL(decode_entropy<false>, dim3(n_windows), dim3(kDecodeThreads), 0, stream, bits, recs,
-                           n_images, win_count, win_first, coef, side_off, status,
+                           n_images, win_count, win_first, data_end, coef, side_off, status,
                            reinterpret_cast<const uint4 *>(tables));
 }
 

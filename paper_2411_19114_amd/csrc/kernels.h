@@ -13,9 +13,12 @@ namespace prep {
 // bytes of one slot of expanded Huffman tables
 size_t huff_tables_bytes();
 // table_rep[s] = an image whose tables go into slot s of `tables` (n_tables slots);
-// window_bytes = raw bytes between workgroup starts (the ImageRecs' n_windows count such windows)
+// window_bytes = raw bytes between workgroup starts (the ImageRecs' n_windows count such windows);
+// data_end[i] = length of image i's entropy-coded segment as the host found it, lowered by the
+// kernel to the offset of the first EOI marker inside it
 void launch_scan_restart_markers(const uint8_t *bits, const ImageRec *recs, int n_images,
                                  uint32_t n_windows, uint32_t window_bytes, uint32_t *win_count, uint32_t *win_first,
+                                 uint32_t *data_end,
                                  int32_t *status, const uint32_t *table_rep, uint32_t n_tables,
                                  uint8_t *tables, hipStream_t stream);
 // coef + side_off: one int16 per block of the coefficient workspace, in the same allocation
@@ -24,8 +27,8 @@ void launch_scan_restart_markers(const uint8_t *bits, const ImageRec *recs, int 
 // small_windows: the windows are kSmallWindowBytes apart (the decoder variant for small calls)
 void launch_decode_entropy(const uint8_t *bits, const ImageRec *recs, int n_images,
                            uint32_t n_windows, const uint32_t *win_count, const uint32_t *win_first,
-                           int16_t *coef, uint32_t side_off, int32_t *status, const uint8_t *tables,
-                           bool small_windows, hipStream_t stream);
+                           const uint32_t *data_end, int16_t *coef, uint32_t side_off, int32_t *status,
+                           const uint8_t *tables, bool small_windows, hipStream_t stream);
 
 // reconstruct.hip
 // chroma: nullptr = subsampled chroma is replicated; else the workspace of the interpolating

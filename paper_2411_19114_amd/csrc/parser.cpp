@@ -158,7 +158,9 @@ int parse_image(const uint8_t *d, uint64_t len, ParsedImage *out)
                 return I.status;
             }
             const uint64_t start = i + L;
-            // the entropy-coded segment ends at the last EOI marker of the file
+            // The entropy-coded segment is taken up to the last EOI marker of the file, found from
+            // the back without reading the data; if the file goes on after its image, the scan
+            // kernel finds the first EOI marker inside and the decoder stops there.
             uint64_t e = len;
             while (e >= start + 2 && !(d[e - 2] == 0xFF && d[e - 1] == 0xD9)) e--;
             if (e < start + 2) return I.status;  // truncated: no EOI

@@ -141,6 +141,12 @@ inline int32_t atomicMin(int32_t *p, int32_t v)
     while (old > v && !__atomic_compare_exchange_n(p, &old, v, false, __ATOMIC_SEQ_CST, __ATOMIC_SEQ_CST)) {}
     return old;
 }
+inline uint32_t atomicMin(uint32_t *p, uint32_t v)
+{
+    uint32_t old = __atomic_load_n(p, __ATOMIC_SEQ_CST);
+    while (old > v && !__atomic_compare_exchange_n(p, &old, v, false, __ATOMIC_SEQ_CST, __ATOMIC_SEQ_CST)) {}
+    return old;
+}
 // ({hi,lo} >> (shift & 31)) truncated to 32 bits, as V_ALIGNBIT_B32 computes it
 inline uint32_t __builtin_amdgcn_alignbit(uint32_t hi, uint32_t lo, uint32_t shift)
 {

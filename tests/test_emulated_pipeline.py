@@ -126,6 +126,20 @@ def test_long_intervals_and_many_chunks(windows):
     _check(streams if windows else streams[1:3], 128, 112, 120, "f32", flags=windows)
 
 
+@BOTH_DECODERS
+def test_files_that_go_on_after_their_image(windows):
+    # a second image (with restart markers of its own) or noise ending in another EOI marker
+    # behind a sound file: the entropy-coded data end at the first EOI marker
+    rng = np.random.default_rng(77)
+    tail_image = oracle.encode(_img(78, 96, 80), 85, MODE_420, 2)[0]
+    noise = bytes(rng.integers(0, 256, 300, dtype=np.uint8)).replace(b"\xff\xd9", b"\xff\x00") + b"\xff\xd9"
+    streams = []
+    for k, (w, h, mode, dri) in enumerate([(120, 90, MODE_420, 4), (77, 65, MODE_444, 0), (200, 160, MODE_420, 13)]):
+        sound = oracle.encode(_img(80 + k, w, h, sigma=20.0), 92, mode, dri)[0]
+        streams += [sound + tail_image, sound + noise]
+    _check(streams, 0, 40, 48, "f32", flags=windows)
+
+
 def test_broken_streams_are_reported_and_zero_filled():
     good = [oracle.encode(_img(30 + k, 64, 48), 85, MODE_420, 2)[0] for k in range(3)]
     sos = good[0].index(b"\xff\xda")

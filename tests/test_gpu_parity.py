@@ -97,6 +97,30 @@ def test_interpolated_chroma(prep, flags):
         h.close()
 
 
+def _files_with_trailing_data():
+    """Sound files that go on after their EOI marker: a second image (with restart markers of its
+    own, as multi-picture files of cameras have), noise that ends in another EOI, both for
+    images with and without restart markers and for one of several decoder windows."""
+    rng = np.random.default_rng(77)
+    tail_image = oracle.encode(_img(78, 96, 80), 85, MODE_420, dri=2)[0]
+    noise = bytes(rng.integers(0, 256, 700, dtype=np.uint8)).replace(b"\xff\xd9", b"\xff\x00") + b"\xff\xd9"
+    out = []
+    for k, (w, h, mode, dri, q) in enumerate([(120, 90, MODE_420, 4, 90), (120, 90, MODE_420, 0, 90),
+                                              (77, 65, MODE_444, 1, 80), (90, 70, MODE_GRAY, 0, 85),
+                                              (480, 320, MODE_420, 30, 95), (480, 320, MODE_422, 0, 95)]):
+        sound = oracle.encode(_img(80 + k, w, h, sigma=20.0), q, mode, dri)[0]
+        out += [sound + tail_image, sound + noise]
+    return out
+
+
+def test_files_that_go_on_after_their_image(pp):
+    # the entropy-coded data end at the first EOI marker, whatever follows it
+    streams = _files_with_trailing_data()
+    assert max(len(s) for s in streams) > 40000
+    check_against_oracle(pp, streams, 0, 48, 64, "f32")
+    check_against_oracle(pp, streams, 0, 48, 64, "f32", resident=True)
+
+
 def test_random_small_batches(pp):
     # seeded batches of 1 to 16 images of random size, sampling, quality, noise and restart
     # interval (from one MCU to two MCU rows, and none): calls with little data, whose restart
