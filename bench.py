@@ -50,12 +50,12 @@ N_STREAMS, STREAM_BATCH = 7, 8
 # scaled by what the same counters read for a plain 256 MiB copy (FETCH_SIZE x 2, WRITE_SIZE x 1).
 # They describe the kernels whose sources hash to MEASURED_SOURCES; for any other sources the
 # figure is reported as null.
-MEASURED_SOURCES = "26196791df6a78b5479857db717c016fc55635ec0aefae4a0f5b6d4867c335db"
+MEASURED_SOURCES = "b8ddaae0ea25bdcd3f067d92810d64535505ccb30adf604f3e9e13de29cc69f8"
 MEASURED_TRAFFIC = {
-    2: {"scan": (5411 * 2 + 1265) * 1024, "decode": (7715 * 2 + 289802) * 1024,
-        "reconstruct": (50642 * 2 + 104439) * 1024, "resize": (49116 * 2 + 75264) * 1024},
-    4: {"scan": (23806 * 2 + 575) * 1024, "decode": (28218 * 2 + 625043) * 1024,
-        "reconstruct": (114439 * 2 + 241163) * 1024, "resize": (91533 * 2 + 55296) * 1024},
+    2: {"scan": (5419 * 2 + 1265) * 1024, "decode": (7708 * 2 + 289820) * 1024,
+        "reconstruct": (50642 * 2 + 104419) * 1024, "resize": (49116 * 2 + 75264) * 1024},
+    4: {"scan": (23814 * 2 + 575) * 1024, "decode": (28130 * 2 + 621096) * 1024,
+        "reconstruct": (114440 * 2 + 241116) * 1024, "resize": (91715 * 2 + 55296) * 1024},
 }
 
 
