@@ -326,7 +326,8 @@ int plan_batch(prep_handle *h, const uint8_t *bits, const uint64_t *offsets, int
     }
     // a call with little data is cut into small windows, for the decoder variant that fills
     // the chip with hypotheses instead of walking whole restart intervals lane by lane
-    if (entropy_total <= kSmallCallBytes && !(h->cfg.flags & PREP_FLAG_LARGE_WINDOWS)) P.window_bytes = kSmallWindowBytes;
+    if (entropy_total <= kSmallCallBytes && !(h->cfg.flags & PREP_FLAG_LARGE_WINDOWS))
+        P.window_bytes = entropy_total <= kTinyCallBytes ? kTinyWindowBytes : kSmallWindowBytes;
     for (int32_t i = 0; i < n; i++) {
         ParsedImage &pi = h->parsed[(size_t)i];
         prep_image_info &I = pi.info;
@@ -502,7 +503,8 @@ int run_batch(prep_handle *h, const uint8_t *bits_host, const uint8_t *bits_dev,
         if (timing) HIP_TRY(hipEventRecord(ev[1], stream));
         launch_decode_entropy(d_bits, s->d_recs, n, P.n_windows, h->d_win_count, h->d_win_first, s->d_data_end,
                               h->d_coef, (uint32_t)(h->cap_blocks * 64), h->d_status, h->d_tables,
-                              P.window_bytes == (uint32_t)kSmallWindowBytes, stream);
+                              P.window_bytes != (uint32_t)kWindowBytes,
+                              P.window_bytes == (uint32_t)kTinyWindowBytes ? 256u : 512u, stream);
         if (timing) HIP_TRY(hipEventRecord(ev[2], stream));
     }
     launch_reconstruct(d_bits, s->d_recs, reinterpret_cast<const uint32_t *>(s->d_recs + n), n, P.recon_wgs,
@@ -552,7 +554,8 @@ int prep_create(prep_handle **out, const prep_config *cfg)
     h->cap_rgb = padded * 3 + (kRgbAlign + kRgbSlack) * n;
     // (windows of either size: a call cut into small ones holds at most kSmallCallBytes)
     h->cap_windows = std::max<uint64_t>(cfg->max_bitstream_bytes / kWindowBytes,
-                                        std::min<uint64_t>(cfg->max_bitstream_bytes, kSmallCallBytes) / kSmallWindowBytes) + n + 1;
+                                        std::max<uint64_t>(std::min<uint64_t>(cfg->max_bitstream_bytes, kSmallCallBytes) / kSmallWindowBytes,
+                                                           std::min<uint64_t>(cfg->max_bitstream_bytes, kTinyCallBytes) / kTinyWindowBytes)) + n + 1;
     h->cap_bits = cfg->max_bitstream_bytes + kBitsPad;
     // (the kernels index the workspace and its side array with 32-bit element offsets)
     if (h->cap_blocks * 65 > 0xFFFFFFFFull) { delete h; return PREP_E_TOO_LARGE; }

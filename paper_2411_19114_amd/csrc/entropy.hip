@@ -896,7 +896,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
     const uint8_t *__restrict__ bits, const ImageRec *__restrict__ recs, int n_images,
     const uint32_t *__restrict__ win_count, const uint32_t *__restrict__ win_first,
     const uint32_t *__restrict__ data_end, int16_t *__restrict__ coef_all, uint32_t side_off,
-    int32_t *__restrict__ status, const uint4 *__restrict__ tables)
+    int32_t *__restrict__ status, const uint4 *__restrict__ tables, uint32_t hyp_span_bits)
 {
     __shared__ DecodeShared S;
     const int tid = threadIdx.x;
@@ -1182,11 +1182,15 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
         // a chunk that is not the last keeps a tail back so that no symbol straddles its end
         const uint32_t own_bits = last ? limit_bits
                                        : (clean_len > (uint32_t)kChunkTail ? (clean_len - kChunkTail) * 8u : 0u);
-        const uint32_t nsub = (own_bits + kSubBits - 1) / kSubBits;  // <= kT
+        // What a lane takes: a subsequence, or, in the hypothesis passes of the smallest calls,
+        // half of one (the passes are shorter, and a chunk of a small window has the lanes for
+        // twice the rows); a lane's reads stay inside its subsequence's row either way.
+        const uint32_t span_bits = kHyp && by_hypotheses && own_bits <= (uint32_t)kT * hyp_span_bits ? hyp_span_bits : kSubBits;
+        const uint32_t nsub = (own_bits + span_bits - 1) / span_bits;  // <= kT
         const bool active = (uint32_t)tid < nsub;
-        const uint32_t end_bit = min(((uint32_t)tid + 1u) * kSubBits, own_bits);
+        const uint32_t end_bit = min(((uint32_t)tid + 1u) * span_bits, own_bits);
 
-        uint32_t in_state = tid == 0 ? st0 : pack_state((uint32_t)tid * kSubBits, 0, 0);
+        uint32_t in_state = tid == 0 ? st0 : pack_state((uint32_t)tid * span_bits, 0, 0);
         uint32_t out_state = in_state, nblk = 0;
         if (by_hypotheses) {
             // ---- the true states by place-in-MCU hypotheses ------------------------------
@@ -1215,7 +1219,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
             for (uint32_t region = 0; region < nsub && first < nsub; region++) {
                 const uint32_t cnt = min(per, nsub - first);
                 const bool mine = j < cnt;
-                const uint32_t s_end = min((first + j + 1u) * kSubBits, own_bits);
+                const uint32_t s_end = min((first + j + 1u) * span_bits, own_bits);
                 // which candidate of my row my end state equals (rows link to themselves: the
                 // state where row j + 1 begins is looked up among the ends of row j)
                 auto find_link = [&]() {
@@ -1227,7 +1231,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_entropy(
                 for (int pass = 0; pass < 2; pass++) {
                     const bool run = mine && (pass == 0 || j != 0);
                     if (run) {
-                        const uint32_t from = pass == 0 ? (j == 0 ? x : pack_state((first + j) * kSubBits, h, 0))
+                        const uint32_t from = pass == 0 ? (j == 0 ? x : pack_state((first + j) * span_bits, h, 0))
                                                         : cand[(uint32_t)tid - H];
                         uint32_t to = from, nb = 0;
                         // (a state past the subsequence's end: the lane before ran through it)
@@ -1403,17 +1407,17 @@ void launch_scan_restart_markers(const uint8_t *bits, const ImageRec *recs, int 
 void launch_decode_entropy(const uint8_t *bits, const ImageRec *recs, int n_images,
                            uint32_t n_windows, const uint32_t *win_count, const uint32_t *win_first,
                            const uint32_t *data_end, int16_t *coef, uint32_t side_off, int32_t *status,
-                           const uint8_t *tables, bool small_windows, hipStream_t stream)
+                           const uint8_t *tables, bool small_windows, uint32_t hyp_span_bits, hipStream_t stream)
 {
     if (n_windows == 0) return;
     if (small_windows)
         hipLaunchKernelGGL(decode_entropy<true>, dim3(n_windows), dim3(kDecodeThreads), 0, stream, bits, recs,
                            n_images, win_count, win_first, data_end, coef, side_off, status,
-                           reinterpret_cast<const uint4 *>(tables));
+                           reinterpret_cast<const uint4 *>(tables), hyp_span_bits);
     else
         hipLaunchKernelGGL(decode_entropy<false>, dim3(n_windows), dim3(kDecodeThreads), 0, stream, bits, recs,
                            n_images, win_count, win_first, data_end, coef, side_off, status,
-                           reinterpret_cast<const uint4 *>(tables));
+                           reinterpret_cast<const uint4 *>(tables), hyp_span_bits);
 }
 
 }  // namespace prep

@@ -24,11 +24,12 @@ void launch_scan_restart_markers(const uint8_t *bits, const ImageRec *recs, int 
 // coef + side_off: one int16 per block of the coefficient workspace, in the same allocation
 // behind the coefficients (the DC differences, which the decoder turns into values in a second
 // step of the same launch); side_off plus the number of blocks must stay below 2^32;
-// small_windows: the windows are kSmallWindowBytes apart (the decoder variant for small calls)
+// small_windows: the windows are small (the decoder variant for small calls), and
+// hyp_span_bits = what a lane of its hypothesis passes takes, 512 or 256 bits
 void launch_decode_entropy(const uint8_t *bits, const ImageRec *recs, int n_images,
                            uint32_t n_windows, const uint32_t *win_count, const uint32_t *win_first,
                            const uint32_t *data_end, int16_t *coef, uint32_t side_off, int32_t *status,
-                           const uint8_t *tables, bool small_windows, hipStream_t stream);
+                           const uint8_t *tables, bool small_windows, uint32_t hyp_span_bits, hipStream_t stream);
 
 // reconstruct.hip
 // chroma: nullptr = subsampled chroma is replicated; else the workspace of the interpolating

@@ -21,6 +21,13 @@ constexpr int kWindowBytes = 12288;                         // raw bytes between
 // decoder states inside an interval by phase hypotheses instead (see decode_entropy).
 constexpr int kSmallWindowBytes = 2048;
 constexpr uint64_t kSmallCallBytes = 1536 << 10;            // entropy-coded bytes of a call up to which it is cut small
+// The smallest calls (a single image, a batch of a few dozen small ones) still leave most
+// compute units idle with 2 KiB windows: they are cut into windows of about one restart
+// interval of a small image, and a lane of the hypothesis passes takes half a subsequence
+// (measured on batches of 256 x 256 images: 86 against 142 us up to 16 images, 96 against 140
+// at 32 = 375 KB, even at 48 = 562 KB, worse from there on).
+constexpr int kTinyWindowBytes = 512;
+constexpr uint64_t kTinyCallBytes = 448 << 10;
 constexpr int kLutBits = 10;                                // first-level Huffman lookup width
 // Images of a batch mostly share their Huffman tables (encoders write the tables of T.81
 // Annex K unless asked to optimise): each distinct set of four tables is expanded once per

@@ -140,6 +140,25 @@ def test_random_small_batches(pp):
         check_against_oracle(pp, streams, 0, 16, 16, "f32")
 
 
+def test_batches_between_the_two_small_call_limits(pp):
+    # 0.45 to 1.5 MB of entropy-coded data: small windows of 2 KiB, whole subsequences per lane
+    # (smaller calls take 512-byte windows and half subsequences, larger ones one lane per
+    # restart interval)
+    rng = np.random.default_rng(4242)
+    modes = [MODE_420, MODE_420, MODE_422, MODE_440, MODE_444, MODE_GRAY]
+    streams, total = [], 0
+    while total < 700000 and len(streams) < 60:
+        w, h = int(rng.integers(200, 640)), int(rng.integers(150, 500))
+        mode = modes[int(rng.integers(0, len(modes)))]
+        cols = -(-w // (8 * oracle.MODE_GEOMETRY[mode][0]))
+        dri = int(rng.choice([1, 4, 8, cols, 3 * cols]))
+        rgb = synth.gradient_noise_image(rng, w, h, float(rng.uniform(4, 20)))
+        streams.append(oracle.encode(rgb, int(rng.integers(60, 95)), mode, dri)[0])
+        total += len(streams[-1])
+    assert 500000 < total < 1400000
+    check_against_oracle(pp, streams, 128, 112, 112, "f16")
+
+
 def test_upscaling_small_images(pp):
     streams = [oracle.encode(_img(300 + k, w, h), 90, MODE_420, 0)[0]
                for k, (w, h) in enumerate([(1, 1), (7, 9), (40, 23), (23, 40)])]
