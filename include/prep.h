@@ -91,8 +91,9 @@ enum { PREP_FILTER_BILINEAR = 0, PREP_FILTER_ANTIALIAS = 1 };
  *   sample replication.  Reconstruction then takes two kernels and a chroma workspace a third
  *   of the RGB workspace's size; prep_debug_last_region leaves out the outermost chroma sample
  *   of the converted region where that does not end with the image.
- * PREP_FLAG_LARGE_WINDOWS: a call with little entropy-coded data (1.5 MiB) is normally cut
- *   into more and smaller pieces for the entropy decoder, which then finds the decoder states
+ * PREP_FLAG_LARGE_WINDOWS: a call with little entropy-coded data (up to 1.5 MiB, and in
+ *   smaller pieces still up to 448 KiB) is normally cut into more and smaller pieces for the
+ *   entropy decoder, which then finds the decoder states
  *   inside restart intervals by hypotheses over the block's place in the MCU, so that the
  *   single-input and small-batch latency (a design objective of section 4.2) is not that of
  *   one lane walking a restart interval; with this flag such a call is decoded like a large
