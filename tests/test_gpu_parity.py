@@ -140,6 +140,19 @@ def test_random_small_batches(pp):
         check_against_oracle(pp, streams, 0, 16, 16, "f32")
 
 
+def test_small_calls_with_long_restart_intervals(pp):
+    # restart intervals of tens of kilobytes in calls small enough for the smallest windows: a
+    # workgroup's run then spans several chunks and more rows than it has lanes for half
+    # subsequences, and it falls back to whole ones
+    rgb = _img(555, 640, 480, sigma=18.0)
+    streams = [oracle.encode(rgb, 92, MODE_420, dri)[0] for dri in (600, 200)]
+    streams.append(oracle.encode(rgb[:240, :320], 92, MODE_444, 150)[0])
+    assert all(len(s) > 60000 for s in streams[:2]) and sum(len(s) for s in streams) < 440000
+    for s in streams:
+        check_against_oracle(pp, [s], 256, 224, 224, "f16")
+    check_against_oracle(pp, streams, 256, 224, 224, "f32")
+
+
 def test_batches_between_the_two_small_call_limits(pp):
     # 0.45 to 1.5 MB of entropy-coded data: small windows of 2 KiB, whole subsequences per lane
     # (smaller calls take 512-byte windows and half subsequences, larger ones one lane per
